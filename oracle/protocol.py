@@ -1,0 +1,202 @@
+"""Speculative round protocol and plain greedy decoding (test oracle).
+
+Section 3.3 of the paper: a round drafts k tokens with the SSM-only subgraph
+M_S, verifies them with one pass of the full hybrid M_H, and under greedy
+decoding accepts draft token i iff it equals M_H's argmax at that position;
+every token up to the first mismatch is kept and M_H's own token is emitted at
+the mismatch (or after the last draft when all match).  The committed stream
+is therefore exactly plain greedy decoding of M_H, whatever the draft was.
+
+Reading used for the caches (the paper's prototype shares none): the last
+committed token is "pending" (emitted but not yet consumed by the caches).
+The draft starts from the committed recurrent state and works on a scratch
+copy; verification consumes pending, d_1 .. d_k at positions len .. len+k and
+snapshots the recurrent state after each; committing n accepted drafts
+restores snapshot n and sets the cache length to len + n + 1 (later KV slots
+are dead).  Sequences in a batch are independent.
+
+`expected_tokens_per_round` and `speedup_model` are Eq. 1.
+"""
+from __future__ import annotations
+
+from typing import List, Optional, Sequence
+
+import numpy as np
+
+from .hybrid_lm import HybridLM, SeqState, argmax_lowest, top2_gap
+from .passes import full_pass
+
+
+def expected_tokens_per_round(alpha: float, k: int) -> float:
+    """Numerator of Eq. 1: (1 - alpha^(k+1)) / (1 - alpha) for per-token
+    acceptance probability alpha."""
+    if alpha == 1.0:
+        return float(k + 1)
+    return (1.0 - alpha ** (k + 1)) / (1.0 - alpha)
+
+
+def speedup_model(alpha: float, k: int, cost_ratio: float) -> float:
+    """Eq. 1: expected tokens per round over the round's cost in units of one
+    verification, 1 + k * c_draft / c_verify."""
+    return expected_tokens_per_round(alpha, k) / (1.0 + k * cost_ratio)
+
+
+def accepted_prefix(drafts: Sequence[int], targets: Sequence[int]) -> int:
+    """Greedy acceptance (Section 3.3): the number n of leading draft tokens with
+    drafts[i] == targets[i], where targets[i] is M_H's argmax given the prefix
+    that ends just before draft i."""
+    n = 0
+    for d, g in zip(drafts, targets):
+        if int(d) != int(g):
+            break
+        n += 1
+    return n
+
+
+def greedy_generate(lm: HybridLM, prompt, n_new: int, gaps: Optional[list] = None) -> List[int]:
+    """Plain autoregressive greedy decoding of the full model: n_new tokens."""
+    st = lm.new_state(len(prompt) + n_new + 1)
+    logits = None
+    for t in prompt:
+        logits = lm.step(st, int(t), "full")
+    out = []
+    for _ in range(n_new):
+        tok = argmax_lowest(logits)
+        if gaps is not None:
+            gaps.append(top2_gap(logits))
+        out.append(tok)
+        if len(out) < n_new:
+            logits = lm.step(st, tok, "full")
+    return out
+
+
+class SpecDecoder:
+    """prefill -> (draft -> verify -> commit)* over a batch of independent
+    sequences.  engine="step" uses only single-token steps (the definition);
+    engine="pass" uses the multi-position pass for prefill and verification."""
+
+    def __init__(self, lm: HybridLM, capacity: int, engine: str = "step", chunk: int = 64):
+        assert engine in ("step", "pass")
+        self.lm, self.capacity, self.engine, self.chunk = lm, capacity, engine, chunk
+        self.gaps: List[float] = []          # top-1/top-2 gap of every greedy decision taken
+
+    # ---------------------------------------------------------------- prefill
+    def prefill(self, prompts: Sequence[Sequence[int]], max_new_tokens: int) -> None:
+        self.B = len(prompts)
+        self.G = int(max_new_tokens)
+        self.st: List[SeqState] = []
+        self.out: List[List[int]] = []
+        self.pending: List[int] = []
+        self.last_n = [0] * self.B
+        self.prefill_logits = []
+        for p in prompts:
+            st = self.lm.new_state(self.capacity)
+            if self.engine == "pass":
+                logits = full_pass(self.lm, st, p, self.chunk, last_only=True)[0][0]
+            else:
+                for t in p:
+                    logits = self.lm.step(st, int(t), "full")
+            tok = argmax_lowest(logits)
+            self.gaps.append(top2_gap(logits))
+            self.st.append(st)
+            self.out.append([tok][:self.G])
+            self.pending.append(tok)
+            self.prefill_logits.append(logits)
+        self.drafts: List[List[int]] = [[] for _ in range(self.B)]
+        self.targets: List[List[int]] = [[] for _ in range(self.B)]
+        self._ckpt = [None] * self.B
+
+    def finished(self, b: int) -> bool:
+        return len(self.out[b]) >= self.G
+
+    def all_finished(self) -> bool:
+        return all(self.finished(b) for b in range(self.B))
+
+    # ---------------------------------------------------------------- draft
+    def draft(self, k: int, override: Optional[np.ndarray] = None) -> None:
+        """k SSM-only steps per active sequence from a scratch copy of the committed
+        recurrent state.  `override[b][i]` replaces the draft tokens (any draft
+        source must leave the committed stream unchanged)."""
+        self.k = k
+        self.draft_logits = [None] * self.B
+        for b in range(self.B):
+            if self.finished(b):
+                continue
+            st = self.st[b]
+            S, conv = st.recurrent_copy()
+            scratch = SeqState(S=S, conv=conv, K=st.K, V=st.V, kv_len=st.kv_len)
+            t = self.pending[b]
+            ds, ls = [], []
+            for i in range(k):
+                logits = self.lm.step(scratch, t, "draft")
+                t = argmax_lowest(logits)
+                self.gaps.append(top2_gap(logits))
+                ds.append(t)
+                ls.append(logits)
+            if override is not None:
+                ds = [int(v) for v in override[b][:k]]
+            self.drafts[b] = ds
+            self.draft_logits[b] = np.array(ls).reshape(k, -1) if k else None
+
+    # ---------------------------------------------------------------- verify
+    def verify(self) -> None:
+        """Full-model pass over pending, d_1..d_k; keeps M_H's argmax g_j and a
+        snapshot of the recurrent state after every position."""
+        self.verify_logits = [None] * self.B
+        for b in range(self.B):
+            if self.finished(b):
+                continue
+            st = self.st[b]
+            xs = [self.pending[b]] + list(self.drafts[b])
+            if self.engine == "pass":
+                logits, ck = full_pass(self.lm, st, xs, self.chunk, checkpoints=True)
+            else:
+                logits, ck = [], []
+                for t in xs:
+                    logits.append(self.lm.step(st, int(t), "full"))
+                    ck.append(st.recurrent_copy())
+                logits = np.array(logits)
+            self.targets[b] = [argmax_lowest(r) for r in logits]
+            self.verify_logits[b] = logits
+            self._gaps_v = [top2_gap(r) for r in logits]
+            self._ckpt[b] = (ck, st.kv_len - len(xs), self._gaps_v)
+
+    # ---------------------------------------------------------------- commit
+    def commit(self, forced_n: Optional[Sequence[int]] = None) -> None:
+        """Accept n drafts (longest matching prefix, or forced_n[b] taken as
+        given), emit d_1..d_n and g_n, roll the recurrent state back to the
+        snapshot after position n and truncate the cache length to len+n+1."""
+        for b in range(self.B):
+            if self.finished(b):
+                continue
+            ck, len0, gaps_v = self._ckpt[b]
+            d, g = self.drafts[b], self.targets[b]
+            n = accepted_prefix(d, g) if forced_n is None else int(forced_n[b])
+            assert 0 <= n <= len(d)
+            self.gaps.extend(gaps_v[:n + 1])     # only positions that decided a token
+            emit = list(d[:n]) + [g[n]]
+            room = self.G - len(self.out[b])
+            self.out[b].extend(emit[:room])
+            self.pending[b] = g[n]
+            st = self.st[b]
+            st.S = [s.copy() for s in ck[n][0]]
+            st.conv = [c.copy() for c in ck[n][1]]
+            st.kv_len = len0 + n + 1
+            self.last_n[b] = n
+
+    # ---------------------------------------------------------------- whole runs
+    def run(self, prompts, max_new_tokens: int, k: int, forced: Optional[np.ndarray] = None,
+            override: Optional[np.ndarray] = None, max_rounds: int = 1 << 30) -> List[List[int]]:
+        """Rounds until every sequence has max_new_tokens tokens.  forced[r][b]:
+        accepted counts taken as given; override[r][b][i]: draft tokens replaced."""
+        self.prefill(prompts, max_new_tokens)
+        self.n_hist: List[List[int]] = []
+        r = 0
+        while not self.all_finished() and r < max_rounds:
+            active = [not self.finished(b) for b in range(self.B)]
+            self.draft(k, None if override is None else override[r])
+            self.verify()
+            self.commit(None if forced is None else forced[r])
+            self.n_hist.append([self.last_n[b] if active[b] else -1 for b in range(self.B)])
+            r += 1
+        return self.out

@@ -1,0 +1,178 @@
+/*
+ * hh.h -- C ABI of the component-aware self-speculative decoding hot path for a
+ * parallel-hybrid (Mamba-2 branch + GQA attention branch, summed per block)
+ * decoder on one MI355X (gfx950).
+ *
+ * The calls follow the paper's statement of a speculative round (Section 3.3,
+ * "Draft Generation and Verification Protocol"): draft k tokens with the
+ * SSM-only subgraph M_S (Section 3.2, Eq. 4: attention output suppressed at
+ * every layer), verify them with one pass of the full hybrid M_H (Eq. 2), and
+ * under greedy decoding accept the longest prefix on which both argmaxes agree.
+ *
+ * Conventions
+ *  - Every call returns an hh_status and never throws.  Argument and ordering
+ *    errors are detected on the host before anything is enqueued and leave all
+ *    device state untouched.
+ *  - The library allocates no device memory: the caller passes one workspace
+ *    (size from hh_workspace_bytes) and the weights, all device pointers, which
+ *    must outlive the context.  Weight pointers are borrowed, never written.
+ *  - Work calls (prefill, draft, set_drafts, verify, commit) are asynchronous on
+ *    the HIP stream given as `void* stream` (a hipStream_t; NULL = default
+ *    stream).  All calls of one context must use streams that are ordered with
+ *    respect to each other.  Calls on one context are not thread-safe.
+ *  - Read-back calls (hh_get_*) synchronise the given stream and copy to HOST
+ *    pointers.  They are not part of the hot path.
+ *  - Order: create -> prefill -> (draft -> verify -> commit)* ; prefill may be
+ *    called again to start a new batch.  Violations return HH_ESTATE.
+ *  - Matrices are row-major [out][in] in cfg.w_dtype (float32 or bfloat16).
+ *    Vectors (norm weights, conv taps [conv_dim][d_conv], conv bias, a_log,
+ *    d_skip, dt_bias) are always float32.  The residual stream, SSM and conv
+ *    state, softmax and logits are float32; the KV cache is stored in w_dtype.
+ *  - Token ids, lengths and acceptance counts are int32.
+ */
+#ifndef HH_H
+#define HH_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define HH_API __attribute__((visibility("default")))
+
+typedef struct hh_ctx hh_ctx; /* opaque, host memory owned by the library */
+
+typedef enum {
+  HH_OK = 0,
+  HH_EINVAL = -1,     /* bad argument or configuration */
+  HH_ESTATE = -2,     /* call out of order */
+  HH_ECAPACITY = -3,  /* batch, sequence length, draft length or generation budget exceeds capacity */
+  HH_EWORKSPACE = -4, /* workspace missing, misaligned or too small */
+  HH_EDEVICE = -5     /* a HIP call failed */
+} hh_status;
+
+typedef enum { HH_F32 = 0, HH_BF16 = 1 } hh_dtype;
+
+/* Model shape and capacities.  Plain data; set struct_size = sizeof(hh_cfg). */
+typedef struct hh_cfg {
+  uint32_t struct_size;
+  int32_t n_layers, d_model, vocab;
+  int32_t m_heads, m_head_dim, d_state; /* Mamba-2 branch: heads x head_dim = d_inner, state size N */
+  int32_t n_groups;                     /* must be 1 */
+  int32_t d_conv;                       /* causal depthwise conv taps, must be 4 */
+  int32_t n_q_heads, n_kv_heads, head_dim; /* attention branch; n_q_heads % n_kv_heads == 0, head_dim even */
+  float rope_base;
+  int32_t d_ff;                         /* SwiGLU width */
+  float rms_eps;
+  int32_t w_dtype;                      /* hh_dtype of matrices and of the KV cache */
+  int32_t max_batch;                    /* sequences per prefill */
+  int32_t max_seq_len;                  /* per sequence: prompt + max_new + 2*max_draft + 2 must fit */
+  int32_t max_draft;                    /* largest k */
+  int32_t max_new_tokens;               /* largest generation budget per sequence */
+  int32_t kv_page_tokens;               /* tokens per KV page: 16, 32, 64, 128 or 256; 0 = default */
+  int32_t prefill_chunk;                /* prompt positions per sequence per prefill pass; 0 = default */
+  int32_t keep_logits;                  /* 1: materialise float32 logits of draft and verify rows for hh_get_logits */
+  int32_t use_graphs;                   /* 1: replay draft/verify/commit as HIP graphs after their first call */
+  void* workspace;                      /* DEVICE, 256-byte aligned */
+  size_t workspace_bytes;
+} hh_cfg;
+
+/* DEVICE pointers to one block's weights (Eq. 2: both branches read the same
+ * normalised input; the block also carries its SwiGLU MLP). */
+typedef struct hh_layer_weights {
+  const void* norm1;   /* f32 [d_model]               shared input RMSNorm */
+  const void* w_in;    /* w   [d_in_proj][d_model]    rows: z(d_inner) | x(d_inner) B(N) C(N) | dt(m_heads) */
+  const void* conv_w;  /* f32 [conv_dim][d_conv]      tap j multiplies the input d_conv-1-j positions back */
+  const void* conv_b;  /* f32 [conv_dim] */
+  const void* a_log;   /* f32 [m_heads]               A = -exp(a_log) */
+  const void* d_skip;  /* f32 [m_heads] */
+  const void* dt_bias; /* f32 [m_heads] */
+  const void* gnorm;   /* f32 [d_inner]               RMSNorm applied to y * silu(z) */
+  const void* w_out;   /* w   [d_model][d_inner] */
+  const void* w_q;     /* w   [n_q_heads*head_dim][d_model] */
+  const void* w_k;     /* w   [n_kv_heads*head_dim][d_model] */
+  const void* w_v;     /* w   [n_kv_heads*head_dim][d_model] */
+  const void* w_o;     /* w   [d_model][n_q_heads*head_dim] */
+  const void* norm2;   /* f32 [d_model] */
+  const void* w_gate;  /* w   [d_ff][d_model] */
+  const void* w_up;    /* w   [d_ff][d_model] */
+  const void* w_down;  /* w   [d_model][d_ff] */
+} hh_layer_weights;
+
+typedef struct hh_weights {
+  const void* embed;      /* w   [vocab][d_model]   DEVICE */
+  const void* final_norm; /* f32 [d_model]          DEVICE */
+  const void* lm_head;    /* w   [vocab][d_model]   DEVICE */
+  const hh_layer_weights* layers; /* HOST array of n_layers entries (copied by hh_create) */
+} hh_weights;
+
+/* Bytes of device workspace needed for cfg (workspace fields ignored); 0 if cfg is invalid. */
+HH_API size_t hh_workspace_bytes(const hh_cfg* cfg);
+
+/* Validates cfg, carves the workspace, builds the RoPE table.  *out is NULL on failure. */
+HH_API hh_status hh_create(const hh_weights* weights, const hh_cfg* cfg, hh_ctx** out);
+HH_API hh_status hh_destroy(hh_ctx* ctx);
+
+/* Run M_H over the prompts (Section 3.3: the prefix x_{1:t}), fill the KV cache
+ * and the recurrent state, and take the first generated token as each
+ * sequence's pending token (emitted, not yet consumed by the caches).
+ *   tokens      DEVICE int32 [batch][row_stride], ids in [0, vocab)
+ *   lens        HOST   int32 [batch], 1 <= lens[b] <= row_stride
+ *   max_new     generation budget per sequence (1 .. cfg.max_new_tokens)
+ * Resets every sequence slot.  HH_ECAPACITY if lens[b] + max_new + 2*max_draft + 2
+ * exceeds max_seq_len or batch exceeds max_batch. */
+HH_API hh_status hh_prefill(hh_ctx* ctx, const int32_t* tokens, int32_t row_stride, const int32_t* lens,
+                     int32_t batch, int32_t max_new, void* stream);
+
+/* Draft phase (Section 3.3 / Eq. 4): k autoregressive greedy steps of the
+ * SSM-only subgraph per sequence, starting from the committed recurrent state
+ * on a scratch copy; never touches the KV cache.  0 <= k <= max_draft; k = 0
+ * makes the round a plain greedy step of M_H. */
+HH_API hh_status hh_draft(hh_ctx* ctx, int32_t k, void* stream);
+
+/* Replace the drafted tokens of the current round by caller-chosen ones
+ * (DEVICE int32 [batch][k]); valid between hh_draft and hh_verify.  The
+ * committed stream does not depend on the draft source (losslessness). */
+HH_API hh_status hh_set_drafts(hh_ctx* ctx, const int32_t* drafts, void* stream);
+
+/* Verification phase (Section 3.3): one pass of M_H over pending, d_1..d_k at
+ * positions len..len+k of every sequence: chunked SSM scan from the committed
+ * state with the data needed to restore the state after any position, K/V
+ * appended to the paged cache, causal attention over len+j+1 keys, and M_H's
+ * argmax g_j for j = 0..k. */
+HH_API hh_status hh_verify(hh_ctx* ctx, void* stream);
+
+/* Greedy acceptance and rollback (Section 3.3): n = longest prefix with
+ * d_i == g_{i-1}; emit d_1..d_n, g_n (clamped to the budget); pending = g_n;
+ * recurrent state = state after position n; cache length += n+1 (later slots
+ * are dead).  n_accepted: NULL for the greedy rule, else DEVICE int32 [batch]
+ * with 0 <= n <= k taken as given (drafts committed as drafted).  Sequences
+ * that have reached their budget are left untouched. */
+HH_API hh_status hh_commit(hh_ctx* ctx, const int32_t* n_accepted, void* stream);
+
+/* ---- read-back (HOST output pointers; synchronise `stream`) ---- */
+/* Committed tokens of sequence seq (first generated token first). */
+HH_API hh_status hh_get_tokens(hh_ctx* ctx, int32_t seq, int32_t* out, int32_t cap, int32_t* n_out, void* stream);
+/* Per sequence: cache length, committed count, accepted count of the last commit.  Any pointer may be NULL. */
+HH_API hh_status hh_get_lengths(hh_ctx* ctx, int32_t* kv_len, int32_t* committed, int32_t* last_n, void* stream);
+/* Tokens of the current round: drafts [batch][k] and targets g [batch][k+1].  Either may be NULL. */
+HH_API hh_status hh_get_round(hh_ctx* ctx, int32_t* drafts, int32_t* targets, void* stream);
+/* Logits (needs cfg.keep_logits): which = 0 draft rows [batch][k][vocab], 1 verify rows
+ * [batch][k+1][vocab], 2 prefill last-position rows [batch][vocab]. */
+HH_API hh_status hh_get_logits(hh_ctx* ctx, int32_t which, float* out, void* stream);
+/* Committed recurrent state of one layer: ssm [batch][m_heads][m_head_dim][d_state],
+ * conv [batch][conv_dim][d_conv-1] (oldest first).  Either may be NULL. */
+HH_API hh_status hh_get_state(hh_ctx* ctx, int32_t layer, float* ssm, float* conv, void* stream);
+/* First n_tokens cache entries of one sequence and layer as float32 [n_tokens][n_kv_heads][head_dim]. */
+HH_API hh_status hh_get_kv(hh_ctx* ctx, int32_t layer, int32_t seq, int32_t n_tokens, float* k, float* v, void* stream);
+
+/* Human-readable description of the last error on this context (or of the last
+ * failed hh_create when ctx is NULL).  Never NULL. */
+HH_API const char* hh_last_error(const hh_ctx* ctx);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* HH_H */

@@ -1,0 +1,254 @@
+"""Thin ctypes binding of libhh.so: the same entry points as include/hh.h.
+
+Argument marshalling only -- every step of the hot path runs inside the
+library's HIP kernels.  PyTorch appears here solely as the owner of device
+memory (weights, workspace, token buffers) and of the HIP stream.
+
+Importing this module fails loudly if the library has not been built
+(``python -m paper_2605_01106_amd.build``); there is no fallback path.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Dict, List, Optional, Sequence
+
+import numpy as np
+import torch  # first: libhh must bind to the HIP runtime PyTorch has already loaded, not to a second copy
+
+from . import workloads as W
+
+_LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libhh.so")
+if not os.path.exists(_LIB_PATH):
+    raise ImportError(f"{_LIB_PATH} is missing: build it with `python -m paper_2605_01106_amd.build`")
+lib = C.CDLL(_LIB_PATH)
+
+HH_OK, HH_EINVAL, HH_ESTATE, HH_ECAPACITY, HH_EWORKSPACE, HH_EDEVICE = 0, -1, -2, -3, -4, -5
+HH_F32, HH_BF16 = 0, 1
+STATUS_NAMES = {0: "HH_OK", -1: "HH_EINVAL", -2: "HH_ESTATE", -3: "HH_ECAPACITY", -4: "HH_EWORKSPACE",
+                -5: "HH_EDEVICE"}
+
+
+class hh_cfg(C.Structure):
+    _fields_ = [("struct_size", C.c_uint32),
+                ("n_layers", C.c_int32), ("d_model", C.c_int32), ("vocab", C.c_int32),
+                ("m_heads", C.c_int32), ("m_head_dim", C.c_int32), ("d_state", C.c_int32),
+                ("n_groups", C.c_int32), ("d_conv", C.c_int32),
+                ("n_q_heads", C.c_int32), ("n_kv_heads", C.c_int32), ("head_dim", C.c_int32),
+                ("rope_base", C.c_float), ("d_ff", C.c_int32), ("rms_eps", C.c_float),
+                ("w_dtype", C.c_int32), ("max_batch", C.c_int32), ("max_seq_len", C.c_int32),
+                ("max_draft", C.c_int32), ("max_new_tokens", C.c_int32), ("kv_page_tokens", C.c_int32),
+                ("prefill_chunk", C.c_int32), ("keep_logits", C.c_int32), ("use_graphs", C.c_int32),
+                ("workspace", C.c_void_p), ("workspace_bytes", C.c_size_t)]
+
+
+_LAYER_FIELDS = ("norm1", "w_in", "conv_w", "conv_b", "a_log", "d_skip", "dt_bias", "gnorm", "w_out",
+                 "w_q", "w_k", "w_v", "w_o", "norm2", "w_gate", "w_up", "w_down")
+
+
+class hh_layer_weights(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in _LAYER_FIELDS]
+
+
+class hh_weights(C.Structure):
+    _fields_ = [("embed", C.c_void_p), ("final_norm", C.c_void_p), ("lm_head", C.c_void_p),
+                ("layers", C.POINTER(hh_layer_weights))]
+
+
+_ctx_p = C.c_void_p
+_i32p = C.POINTER(C.c_int32)
+_f32p = C.POINTER(C.c_float)
+
+EXPORTS = {
+    "hh_workspace_bytes": (C.c_size_t, [C.POINTER(hh_cfg)]),
+    "hh_create": (C.c_int, [C.POINTER(hh_weights), C.POINTER(hh_cfg), C.POINTER(_ctx_p)]),
+    "hh_destroy": (C.c_int, [_ctx_p]),
+    "hh_prefill": (C.c_int, [_ctx_p, C.c_void_p, C.c_int32, _i32p, C.c_int32, C.c_int32, C.c_void_p]),
+    "hh_draft": (C.c_int, [_ctx_p, C.c_int32, C.c_void_p]),
+    "hh_set_drafts": (C.c_int, [_ctx_p, C.c_void_p, C.c_void_p]),
+    "hh_verify": (C.c_int, [_ctx_p, C.c_void_p]),
+    "hh_commit": (C.c_int, [_ctx_p, C.c_void_p, C.c_void_p]),
+    "hh_get_tokens": (C.c_int, [_ctx_p, C.c_int32, _i32p, C.c_int32, _i32p, C.c_void_p]),
+    "hh_get_lengths": (C.c_int, [_ctx_p, _i32p, _i32p, _i32p, C.c_void_p]),
+    "hh_get_round": (C.c_int, [_ctx_p, _i32p, _i32p, C.c_void_p]),
+    "hh_get_logits": (C.c_int, [_ctx_p, C.c_int32, _f32p, C.c_void_p]),
+    "hh_get_state": (C.c_int, [_ctx_p, C.c_int32, _f32p, _f32p, C.c_void_p]),
+    "hh_get_kv": (C.c_int, [_ctx_p, C.c_int32, C.c_int32, C.c_int32, _f32p, _f32p, C.c_void_p]),
+    "hh_last_error": (C.c_char_p, [_ctx_p]),
+}
+for _name, (_res, _args) in EXPORTS.items():
+    _fn = getattr(lib, _name)
+    _fn.restype, _fn.argtypes = _res, _args
+
+
+class HHError(RuntimeError):
+    def __init__(self, status: int, msg: str):
+        super().__init__(f"{STATUS_NAMES.get(status, status)}: {msg}")
+        self.status = status
+
+
+def make_cfg(cfg: W.HybridConfig, max_batch: int, max_seq_len: int, max_draft: int, max_new_tokens: int,
+             kv_page_tokens: int = 0, prefill_chunk: int = 0, keep_logits: int = 1, use_graphs: int = 0) -> hh_cfg:
+    c = hh_cfg()
+    c.struct_size = C.sizeof(hh_cfg)
+    c.n_layers, c.d_model, c.vocab = cfg.n_layers, cfg.d_model, cfg.vocab
+    c.m_heads, c.m_head_dim, c.d_state = cfg.m_heads, cfg.m_head_dim, cfg.d_state
+    c.n_groups, c.d_conv = cfg.n_groups, cfg.d_conv
+    c.n_q_heads, c.n_kv_heads, c.head_dim = cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim
+    c.rope_base, c.d_ff, c.rms_eps = cfg.rope_base, cfg.d_ff, cfg.rms_eps
+    c.w_dtype = HH_BF16 if cfg.w_dtype == W.BF16 else HH_F32
+    c.max_batch, c.max_seq_len, c.max_draft, c.max_new_tokens = max_batch, max_seq_len, max_draft, max_new_tokens
+    c.kv_page_tokens, c.prefill_chunk, c.keep_logits, c.use_graphs = kv_page_tokens, prefill_chunk, keep_logits, use_graphs
+    c.workspace, c.workspace_bytes = None, 0
+    return c
+
+
+def hh_workspace_bytes(cfg: hh_cfg) -> int:
+    return int(lib.hh_workspace_bytes(C.byref(cfg)))
+
+
+def hh_last_error(ctx=None) -> str:
+    return (lib.hh_last_error(ctx) or b"").decode()
+
+
+def _check(st: int, ctx=None) -> None:
+    if st != HH_OK:
+        raise HHError(st, hh_last_error(ctx))
+
+
+def _stream_ptr(stream) -> Optional[int]:
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return C.c_void_p(getattr(stream, "cuda_stream", stream))
+
+
+def upload_weights(weights: W.Weights, device="cuda:0"):
+    """Copies a host `Weights` to device tensors; returns (hh_weights, keepalive)."""
+    cfg = weights.cfg
+    keep: Dict[str, "torch.Tensor"] = {}
+
+    def dev(name: str) -> int:
+        if name in weights.bits:
+            t = torch.from_numpy(weights.bits[name].view(np.int16)).to(device)
+        else:
+            t = torch.from_numpy(weights.values[name]).to(device)
+        keep[name] = t
+        return t.data_ptr()
+
+    layers = (hh_layer_weights * cfg.n_layers)()
+    for i in range(cfg.n_layers):
+        for n in _LAYER_FIELDS:
+            setattr(layers[i], n, dev(f"L{i}.{n}"))
+    hw = hh_weights()
+    hw.embed, hw.final_norm, hw.lm_head = dev("embed"), dev("final_norm"), dev("lm_head")
+    hw.layers = layers
+    keep["__layers__"] = layers
+    return hw, keep
+
+
+class Context:
+    """Owns one hh_ctx plus the device memory it borrows (weights, workspace)."""
+
+    def __init__(self, weights: W.Weights, max_batch: int, max_seq_len: int, max_draft: int,
+                 max_new_tokens: int, device="cuda:0", **cfg_kw):
+        self.torch = torch
+        self.device = device
+        self.model_cfg = weights.cfg
+        self.cfg = make_cfg(weights.cfg, max_batch, max_seq_len, max_draft, max_new_tokens, **cfg_kw)
+        need = hh_workspace_bytes(self.cfg)
+        if need == 0:
+            raise HHError(HH_EINVAL, hh_last_error(None))
+        self.workspace = torch.empty(need, dtype=torch.uint8, device=device)
+        self.cfg.workspace = self.workspace.data_ptr()
+        self.cfg.workspace_bytes = need
+        self.hw, self._keep = upload_weights(weights, device)
+        self.ctx = _ctx_p()
+        _check(lib.hh_create(C.byref(self.hw), C.byref(self.cfg), C.byref(self.ctx)))
+        self.B = 0
+        self.k = 0
+
+    def close(self):
+        if self.ctx:
+            lib.hh_destroy(self.ctx)
+            self.ctx = _ctx_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    # ---- work calls (asynchronous on the current torch stream unless given)
+    def hh_prefill(self, tokens: np.ndarray, lens: Sequence[int], max_new: int, stream=None):
+        torch = self.torch
+        t = torch.from_numpy(np.ascontiguousarray(tokens, dtype=np.int32)).to(self.device)
+        self._prompt = t
+        lens_arr = (C.c_int32 * len(lens))(*[int(x) for x in lens])
+        _check(lib.hh_prefill(self.ctx, C.c_void_p(t.data_ptr()), t.shape[1], lens_arr, len(lens), max_new,
+                              _stream_ptr(stream)), self.ctx)
+        self.B = len(lens)
+
+    def hh_draft(self, k: int, stream=None):
+        _check(lib.hh_draft(self.ctx, k, _stream_ptr(stream)), self.ctx)
+        self.k = k
+
+    def hh_set_drafts(self, drafts, stream=None):
+        torch = self.torch
+        t = drafts if isinstance(drafts, torch.Tensor) else torch.from_numpy(
+            np.ascontiguousarray(drafts, dtype=np.int32)).to(self.device)
+        self._drafts_keep = t
+        _check(lib.hh_set_drafts(self.ctx, C.c_void_p(t.data_ptr()), _stream_ptr(stream)), self.ctx)
+
+    def hh_verify(self, stream=None):
+        _check(lib.hh_verify(self.ctx, _stream_ptr(stream)), self.ctx)
+
+    def hh_commit(self, n_accepted=None, stream=None):
+        """n_accepted: None (greedy rule) or a device int32 tensor [B]."""
+        ptr = None if n_accepted is None else C.c_void_p(n_accepted.data_ptr())
+        _check(lib.hh_commit(self.ctx, ptr, _stream_ptr(stream)), self.ctx)
+
+    # ---- read-back
+    def hh_get_tokens(self, seq: int, stream=None) -> List[int]:
+        cap = self.cfg.max_new_tokens
+        out = (C.c_int32 * cap)()
+        n = C.c_int32(0)
+        _check(lib.hh_get_tokens(self.ctx, seq, out, cap, C.byref(n), _stream_ptr(stream)), self.ctx)
+        return list(out[:n.value])
+
+    def hh_get_lengths(self, stream=None):
+        B = self.B
+        a, b, c = (C.c_int32 * B)(), (C.c_int32 * B)(), (C.c_int32 * B)()
+        _check(lib.hh_get_lengths(self.ctx, a, b, c, _stream_ptr(stream)), self.ctx)
+        return list(a), list(b), list(c)
+
+    def hh_get_round(self, stream=None):
+        B, k = self.B, self.k
+        d = np.zeros((B, max(k, 1)), np.int32)
+        g = np.zeros((B, k + 1), np.int32)
+        _check(lib.hh_get_round(self.ctx, d.ctypes.data_as(_i32p), g.ctypes.data_as(_i32p), _stream_ptr(stream)),
+               self.ctx)
+        return d[:, :k], g
+
+    def hh_get_logits(self, which: int, stream=None) -> np.ndarray:
+        B, k, V = self.B, self.k, self.model_cfg.vocab
+        shape = {0: (B, k, V), 1: (B, k + 1, V), 2: (B, V)}[which]
+        out = np.zeros(shape, np.float32)
+        if out.size:
+            _check(lib.hh_get_logits(self.ctx, which, out.ctypes.data_as(_f32p), _stream_ptr(stream)), self.ctx)
+        return out
+
+    def hh_get_state(self, layer: int, stream=None):
+        c = self.model_cfg
+        ssm = np.zeros((self.B, c.m_heads, c.m_head_dim, c.d_state), np.float32)
+        conv = np.zeros((self.B, c.conv_dim, c.d_conv - 1), np.float32)
+        _check(lib.hh_get_state(self.ctx, layer, ssm.ctypes.data_as(_f32p), conv.ctypes.data_as(_f32p),
+                                _stream_ptr(stream)), self.ctx)
+        return ssm, conv
+
+    def hh_get_kv(self, layer: int, seq: int, n_tokens: int, stream=None):
+        c = self.model_cfg
+        k = np.zeros((n_tokens, c.n_kv_heads, c.head_dim), np.float32)
+        v = np.zeros_like(k)
+        _check(lib.hh_get_kv(self.ctx, layer, seq, n_tokens, k.ctypes.data_as(_f32p), v.ctypes.data_as(_f32p),
+                             _stream_ptr(stream)), self.ctx)
+        return k, v

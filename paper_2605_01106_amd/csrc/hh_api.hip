@@ -1,0 +1,578 @@
+// C ABI of libhh: context, workspace carving, the round state machine and the per-layer
+// kernel schedules of the two forward modes -- the full hybrid M_H (Eq. 2 of the paper: SSM
+// branch + attention branch summed) and the SSM-only draft M_S (Eq. 4: the attention branch
+// is simply not launched).  Host code only enqueues; every value a round depends on (tokens,
+// lengths, accepted counts) stays in device memory.
+#include <math.h>
+#include <stdio.h>
+#include <string.h>
+
+#include <string>
+#include <vector>
+
+#include "hh_internal.h"
+
+using namespace hh;
+
+namespace {
+
+enum Phase { PH_CREATED = 0, PH_READY = 1, PH_DRAFTED = 2, PH_VERIFIED = 3 };
+
+constexpr int kMaxSplits = 32;
+constexpr size_t kAlign = 256;
+
+std::string g_create_error;
+
+struct Carver {
+  char* base;
+  size_t off = 0;
+  template <typename T>
+  T* take(size_t n) {
+    off = (off + kAlign - 1) / kAlign * kAlign;
+    T* p = base ? reinterpret_cast<T*>(base + off) : nullptr;
+    off += n * sizeof(T);
+    return p;
+  }
+};
+
+}  // namespace
+
+struct hh_ctx {
+  hh_cfg cfg;
+  Dims d;
+  const void *embed, *final_norm, *lm_head;
+  std::vector<LayerDev> layers_host;
+  LayerDev* layers_dev;
+  // device int state
+  int *kv_len, *committed, *last_n, *pending, *n_acc, *skip, *adv, *drafts, *targets, *tok, *pos0, *out_tok,
+      *page_table, *plan_ntok, *plan_last, *first_tok;
+  unsigned long long* best;
+  float *rope, *h, *zx, *qkv, *g, *o, *act, *logits_d, *logits_v, *logits_p, *lasth, *part_o, *part_ml, *export_buf;
+  int max_passes;
+  // host state
+  int phase = PH_CREATED;
+  int B = 0, G = 0, k = 0;
+  int len_upper = 0;
+  std::vector<int> h_page_table, h_plan;
+  std::string err;
+};
+
+namespace {
+
+bool derive_dims(const hh_cfg& c, Dims& d, std::string& why) {
+  auto bad = [&](const char* m) { why = m; return false; };
+  if (c.struct_size != sizeof(hh_cfg)) return bad("struct_size does not match this library's hh_cfg");
+  if (c.n_layers < 1 || c.d_model < 8 || c.vocab < 2) return bad("n_layers/d_model/vocab out of range");
+  if (c.m_heads < 1 || c.m_head_dim < 1 || c.d_state < 8) return bad("m_heads/m_head_dim/d_state out of range");
+  if (c.n_groups != 1) return bad("n_groups must be 1");
+  if (c.d_conv != 4) return bad("d_conv must be 4");
+  if (c.n_q_heads < 1 || c.n_kv_heads < 1 || c.n_q_heads % c.n_kv_heads != 0) return bad("n_q_heads must be a multiple of n_kv_heads");
+  if (c.head_dim < 8 || c.head_dim % 8 != 0 || c.head_dim > 256) return bad("head_dim must be a multiple of 8 in 8..256");
+  if (c.w_dtype != HH_F32 && c.w_dtype != HH_BF16) return bad("unknown w_dtype");
+  const int ns = c.d_state / 8;
+  if (c.d_state % 8 != 0 || (ns & (ns - 1)) != 0 || ns > 32) return bad("d_state must be 8, 16, 32, 64, 128 or 256");
+  if (c.max_batch < 1 || c.max_draft < 0 || c.max_new_tokens < 1 || c.max_seq_len < 2) return bad("capacities out of range");
+  if (!(c.rms_eps > 0.f) || !(c.rope_base > 1.f)) return bad("rms_eps / rope_base out of range");
+  d.L = c.n_layers; d.D = c.d_model; d.V = c.vocab;
+  d.Hm = c.m_heads; d.P = c.m_head_dim; d.N = c.d_state;
+  d.d_inner = d.Hm * d.P; d.conv_dim = d.d_inner + 2 * d.N; d.d_in_proj = 2 * d.d_inner + 2 * d.N + d.Hm;
+  d.ring_w = d.conv_dim + d.Hm;
+  d.Hq = c.n_q_heads; d.Hkv = c.n_kv_heads; d.Dh = c.head_dim;
+  d.dq = d.Hq * d.Dh; d.dkv = d.Hkv * d.Dh; d.dqkv = d.dq + 2 * d.dkv;
+  d.F = c.d_ff;
+  if (d.D % 8 || d.d_inner % 8 || d.dq % 8 || d.F % 8 || d.F < 8) return bad("d_model, d_inner, n_q_heads*head_dim and d_ff must be multiples of 8");
+  d.page_tokens = c.kv_page_tokens == 0 ? 64 : c.kv_page_tokens;
+  if (d.page_tokens != 16 && d.page_tokens != 32 && d.page_tokens != 64 && d.page_tokens != 128 && d.page_tokens != 256)
+    return bad("kv_page_tokens must be 16, 32, 64, 128 or 256");
+  int chunk = c.prefill_chunk == 0 ? 64 : c.prefill_chunk;
+  if (chunk < 1 || chunk > 1024) return bad("prefill_chunk must be in 1..1024");
+  d.Kmax = c.max_draft; d.Bmax = c.max_batch; d.Gmax = c.max_new_tokens; d.max_seq = c.max_seq_len;
+  d.Tmax = d.Kmax + 1 > chunk ? d.Kmax + 1 : chunk;
+  d.ring_slots = 4;
+  while (d.ring_slots < d.Tmax + 3) d.ring_slots <<= 1;
+  d.pages_per_seq = (d.max_seq + d.page_tokens - 1) / d.page_tokens;
+  d.n_pages = d.pages_per_seq * d.Bmax;
+  d.bf16 = c.w_dtype == HH_BF16;
+  d.eps = c.rms_eps; d.rope_base = c.rope_base;
+  return true;
+}
+
+// Assigns (or, with base == nullptr, only sizes) every region of the workspace.
+size_t carve(hh_ctx* x, char* base) {
+  const Dims& d = x->d;
+  Carver c{base};
+  const size_t B = d.Bmax, Mmax = B * d.Tmax, Mv = B * (d.Kmax + 1);
+  const size_t esz = d.bf16 ? 2 : 4;
+  x->layers_dev = c.take<LayerDev>(d.L);
+  x->kv_len = c.take<int>(B); x->committed = c.take<int>(B); x->last_n = c.take<int>(B);
+  x->pending = c.take<int>(B); x->n_acc = c.take<int>(B); x->skip = c.take<int>(B); x->adv = c.take<int>(B);
+  x->first_tok = c.take<int>(B);
+  x->drafts = c.take<int>(B * (d.Kmax > 0 ? d.Kmax : 1));
+  x->targets = c.take<int>(B * (d.Kmax + 1));
+  x->tok = c.take<int>(Mmax); x->pos0 = c.take<int>(B);
+  x->out_tok = c.take<int>(B * d.Gmax);
+  x->page_table = c.take<int>(B * d.pages_per_seq);
+  const int chunk = x->cfg.prefill_chunk == 0 ? 64 : x->cfg.prefill_chunk;
+  x->max_passes = (d.max_seq + chunk - 1) / chunk;
+  x->plan_ntok = c.take<int>((size_t)x->max_passes * B);
+  x->plan_last = c.take<int>((size_t)x->max_passes * B);
+  x->best = c.take<unsigned long long>(Mv * gemv_max_blocks());
+  x->rope = c.take<float>((size_t)d.max_seq * d.Dh);
+  x->h = c.take<float>(Mmax * d.D);
+  x->zx = c.take<float>(Mmax * d.d_in_proj);
+  x->qkv = c.take<float>(Mmax * d.dqkv);
+  x->g = c.take<float>(Mmax * d.d_inner);
+  x->o = c.take<float>(Mmax * d.dq);
+  x->act = c.take<float>(Mmax * d.F);
+  x->logits_d = c.take<float>(B * (d.Kmax > 0 ? d.Kmax : 1) * d.V);
+  x->logits_v = c.take<float>(Mv * d.V);
+  x->logits_p = c.take<float>(B * d.V);
+  x->lasth = c.take<float>(B * d.D);
+  x->part_o = c.take<float>(Mv * d.Hq * kMaxSplits * d.Dh);
+  x->part_ml = c.take<float>(Mv * d.Hq * kMaxSplits * 2);
+  x->export_buf = c.take<float>(B * d.conv_dim * 3);
+  const size_t state = B * d.Hm * d.P * d.N;
+  const size_t ring = B * d.ring_slots * d.ring_w;
+  const size_t pool = (size_t)d.n_pages * d.Hkv * d.page_tokens * d.Dh * esz;
+  if (base) x->layers_host.resize(d.L);
+  for (int l = 0; l < d.L; ++l) {
+    float* S = c.take<float>(state);
+    float* Sd = c.take<float>(state);
+    float* rg = c.take<float>(ring);
+    char* kp = c.take<char>(pool);
+    char* vp = c.take<char>(pool);
+    if (base) {
+      LayerDev& ld = x->layers_host[l];
+      ld.S = S; ld.S_draft = Sd; ld.ring = rg; ld.kpool = kp; ld.vpool = vp;
+    }
+  }
+  return (c.off + kAlign - 1) / kAlign * kAlign;
+}
+
+hh_status fail(hh_ctx* x, hh_status st, const std::string& msg) {
+  if (x) x->err = msg; else g_create_error = msg;
+  return st;
+}
+
+#define HH_HIP(call)                                                                           \
+  do {                                                                                         \
+    hipError_t e_ = (call);                                                                    \
+    if (e_ != hipSuccess)                                                                      \
+      return fail(x, HH_EDEVICE, std::string(#call) + ": " + hipGetErrorString(e_));           \
+  } while (0)
+
+// ---- one pass of the block stack over M = B*T rows.  full: M_H (both branches); !full: M_S.
+hh_status run_layers(hh_ctx* x, bool full, int B, int T, const int* n_tok, int state_in, int state_out,
+                     int n_splits, hipStream_t s) {
+  const Dims& d = x->d;
+  const int M = B * T;
+  for (int l = 0; l < d.L; ++l) {
+    const LayerDev& w = x->layers_host[l];
+    {  // shared input norm, Mamba-2 input projection (+ q, k, v of the attention branch)
+      GemvArgs a{};
+      a.X = x->h; a.ldx = d.D; a.M = M; a.K = d.D; a.norm_w = w.norm1; a.eps = d.eps; a.epi = EPI_STORE; a.bf16 = d.bf16;
+      a.seg[0] = {w.w_in, nullptr, x->zx, d.d_in_proj, d.d_in_proj};
+      a.n_seg = 1;
+      if (full) {
+        a.seg[1] = {w.w_q, nullptr, x->qkv, d.dq, d.dqkv};
+        a.seg[2] = {w.w_k, nullptr, x->qkv + d.dq, d.dkv, d.dqkv};
+        a.seg[3] = {w.w_v, nullptr, x->qkv + d.dq + d.dkv, d.dkv, d.dqkv};
+        a.n_seg = 4;
+      }
+      HH_HIP(launch_gemv(a, nullptr, s));
+    }
+    {  // conv + selective scan -> y * silu(z)
+      SsmArgs a{};
+      a.layers = x->layers_dev; a.layer0 = l; a.n_layers_z = 1;
+      a.zx = x->zx; a.g = x->g; a.pos0 = x->pos0; a.n_tok = n_tok; a.T = T; a.B = B;
+      a.state_in = state_in; a.state_out = state_out; a.write_ring = 1;
+      HH_HIP(launch_ssm(d, a, s));
+    }
+    if (full) {
+      AttnArgs a{};
+      a.layer = x->layers_dev + l; a.qkv = x->qkv; a.o = x->o; a.pos0 = x->pos0; a.n_tok = n_tok;
+      a.page_table = x->page_table; a.rope = x->rope; a.part_o = x->part_o; a.part_ml = x->part_ml;
+      a.T = T; a.B = B; a.n_splits = n_splits;
+      HH_HIP(launch_rope_append(d, a, s));
+      HH_HIP(launch_attention(d, a, s));
+    }
+    {  // h += W_out * gated_norm(g)   (+ W_o * o in full mode: the two branches are summed)
+      GemvArgs a{};
+      a.X = x->g; a.ldx = d.d_inner; a.M = M; a.K = d.d_inner; a.norm_w = w.gnorm; a.eps = d.eps; a.epi = EPI_ADD; a.bf16 = d.bf16;
+      a.seg[0] = {w.w_out, nullptr, x->h, d.D, d.D}; a.n_seg = 1;
+      HH_HIP(launch_gemv(a, nullptr, s));
+      if (full) {
+        GemvArgs b{};
+        b.X = x->o; b.ldx = d.dq; b.M = M; b.K = d.dq; b.norm_w = nullptr; b.epi = EPI_ADD; b.bf16 = d.bf16;
+        b.seg[0] = {w.w_o, nullptr, x->h, d.D, d.D}; b.n_seg = 1;
+        HH_HIP(launch_gemv(b, nullptr, s));
+      }
+    }
+    {  // SwiGLU MLP
+      GemvArgs a{};
+      a.X = x->h; a.ldx = d.D; a.M = M; a.K = d.D; a.norm_w = w.norm2; a.eps = d.eps; a.epi = EPI_SWIGLU; a.bf16 = d.bf16;
+      a.seg[0] = {w.w_gate, w.w_up, x->act, d.F, d.F}; a.n_seg = 1;
+      HH_HIP(launch_gemv(a, nullptr, s));
+      GemvArgs b{};
+      b.X = x->act; b.ldx = d.F; b.M = M; b.K = d.F; b.norm_w = nullptr; b.epi = EPI_ADD; b.bf16 = d.bf16;
+      b.seg[0] = {w.w_down, nullptr, x->h, d.D, d.D}; b.n_seg = 1;
+      HH_HIP(launch_gemv(b, nullptr, s));
+    }
+  }
+  return HH_OK;
+}
+
+// final norm + LM head + argmax of M rows of X; row m = b*T + j -> out[b*out_stride + out_off + j]
+hh_status run_head(hh_ctx* x, const float* X, int M, int T, float* logits, int ld_logits, int* out, int out_stride,
+                   int out_off, hipStream_t s) {
+  const Dims& d = x->d;
+  GemvArgs a{};
+  a.X = X; a.ldx = d.D; a.M = M; a.K = d.D; a.norm_w = static_cast<const float*>(x->final_norm); a.eps = d.eps;
+  a.epi = EPI_STORE; a.bf16 = d.bf16; a.best = x->best;
+  a.seg[0] = {x->lm_head, nullptr, logits, d.V, ld_logits}; a.n_seg = 1;
+  int nblk = 0;
+  HH_HIP(launch_gemv(a, &nblk, s));
+  HH_HIP(launch_argmax_finish(x->best, nblk, M, out, out_stride, out_off, T, s));
+  return HH_OK;
+}
+
+int pick_splits(const Dims& d, int B, int T, int len_upper) {
+  const int G = d.Hq / d.Hkv;
+  const int row_chunks = (T * G + 15) / 16;
+  const int blocks = row_chunks * d.Hkv * B;
+  const int tiles = (len_upper + T + 63) / 64;
+  int s = (512 + blocks - 1) / blocks;
+  if (s > kMaxSplits) s = kMaxSplits;
+  if (s > tiles) s = tiles;
+  return s < 1 ? 1 : s;
+}
+
+}  // namespace
+
+extern "C" {
+
+size_t hh_workspace_bytes(const hh_cfg* cfg) {
+  if (!cfg) return 0;
+  hh_ctx tmp;
+  std::string why;
+  tmp.cfg = *cfg;
+  if (!derive_dims(*cfg, tmp.d, why)) { g_create_error = why; return 0; }
+  return carve(&tmp, nullptr);
+}
+
+hh_status hh_create(const hh_weights* weights, const hh_cfg* cfg, hh_ctx** out) {
+  hh_ctx* x = nullptr;
+  if (out) *out = nullptr;
+  if (!weights || !cfg || !out) return fail(nullptr, HH_EINVAL, "hh_create: NULL argument");
+  Dims d;
+  std::string why;
+  if (!derive_dims(*cfg, d, why)) return fail(nullptr, HH_EINVAL, "hh_create: " + why);
+  if (!weights->embed || !weights->final_norm || !weights->lm_head || !weights->layers)
+    return fail(nullptr, HH_EINVAL, "hh_create: NULL weight pointer");
+  for (int l = 0; l < d.L; ++l) {
+    const void* const* p = reinterpret_cast<const void* const*>(&weights->layers[l]);
+    for (size_t i = 0; i < sizeof(hh_layer_weights) / sizeof(void*); ++i)
+      if (!p[i]) return fail(nullptr, HH_EINVAL, "hh_create: NULL layer weight pointer");
+  }
+  hh_ctx* ctx = new hh_ctx();
+  ctx->cfg = *cfg; ctx->d = d;
+  const size_t need = carve(ctx, nullptr);
+  if (!cfg->workspace || (reinterpret_cast<uintptr_t>(cfg->workspace) % kAlign) != 0 || cfg->workspace_bytes < need) {
+    char msg[160];
+    snprintf(msg, sizeof msg, "hh_create: workspace missing, misaligned or too small (need %zu bytes, 256-byte aligned)", need);
+    delete ctx;
+    return fail(nullptr, HH_EWORKSPACE, msg);
+  }
+  carve(ctx, static_cast<char*>(cfg->workspace));
+  ctx->embed = weights->embed; ctx->final_norm = weights->final_norm; ctx->lm_head = weights->lm_head;
+  for (int l = 0; l < d.L; ++l) {
+    const hh_layer_weights& w = weights->layers[l];
+    LayerDev& ld = ctx->layers_host[l];
+    ld.norm1 = (const float*)w.norm1; ld.conv_w = (const float*)w.conv_w; ld.conv_b = (const float*)w.conv_b;
+    ld.a_log = (const float*)w.a_log; ld.d_skip = (const float*)w.d_skip; ld.dt_bias = (const float*)w.dt_bias;
+    ld.gnorm = (const float*)w.gnorm; ld.norm2 = (const float*)w.norm2;
+    ld.w_in = w.w_in; ld.w_out = w.w_out; ld.w_q = w.w_q; ld.w_k = w.w_k; ld.w_v = w.w_v; ld.w_o = w.w_o;
+    ld.w_gate = w.w_gate; ld.w_up = w.w_up; ld.w_down = w.w_down;
+  }
+  x = nullptr;  // errors below are reported through g_create_error
+  auto bail = [&](hipError_t e, const char* what) {
+    delete ctx;
+    return fail(nullptr, HH_EDEVICE, std::string(what) + ": " + hipGetErrorString(e));
+  };
+  hipError_t e = hipMemcpy(ctx->layers_dev, ctx->layers_host.data(), sizeof(LayerDev) * d.L, hipMemcpyHostToDevice);
+  if (e != hipSuccess) return bail(e, "hh_create: upload of layer table");
+  // rotary table: angle pos * base^(-2i/Dh) evaluated in double, stored as float (cos, sin)
+  {
+    const int half = d.Dh / 2;
+    std::vector<float> tab((size_t)d.max_seq * d.Dh);
+    for (int i = 0; i < half; ++i) {
+      const double inv = pow((double)d.rope_base, -2.0 * i / d.Dh);
+      for (int pos = 0; pos < d.max_seq; ++pos) {
+        const double ang = (double)pos * inv;
+        tab[((size_t)pos * half + i) * 2] = (float)cos(ang);
+        tab[((size_t)pos * half + i) * 2 + 1] = (float)sin(ang);
+      }
+    }
+    e = hipMemcpy(ctx->rope, tab.data(), tab.size() * sizeof(float), hipMemcpyHostToDevice);
+    if (e != hipSuccess) return bail(e, "hh_create: upload of rotary table");
+  }
+  *out = ctx;
+  return HH_OK;
+}
+
+hh_status hh_destroy(hh_ctx* ctx) {
+  if (!ctx) return HH_EINVAL;
+  delete ctx;
+  return HH_OK;
+}
+
+hh_status hh_prefill(hh_ctx* x, const int32_t* tokens, int32_t row_stride, const int32_t* lens, int32_t batch,
+                     int32_t max_new, void* stream) {
+  if (!x) return HH_EINVAL;
+  if (!tokens || !lens) return fail(x, HH_EINVAL, "hh_prefill: NULL argument");
+  const Dims& d = x->d;
+  if (batch < 1 || batch > d.Bmax) return fail(x, HH_ECAPACITY, "hh_prefill: batch exceeds max_batch");
+  if (max_new < 1 || max_new > d.Gmax) return fail(x, HH_ECAPACITY, "hh_prefill: max_new exceeds max_new_tokens");
+  int maxlen = 0;
+  for (int b = 0; b < batch; ++b) {
+    if (lens[b] < 1 || lens[b] > row_stride) return fail(x, HH_EINVAL, "hh_prefill: lens[b] must be in 1..row_stride");
+    if ((long long)lens[b] + max_new + 2LL * d.Kmax + 2 > d.max_seq)
+      return fail(x, HH_ECAPACITY, "hh_prefill: lens[b] + max_new + 2*max_draft + 2 exceeds max_seq_len");
+    if (lens[b] > maxlen) maxlen = lens[b];
+  }
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  const int B = batch;
+  const int chunk = x->cfg.prefill_chunk == 0 ? 64 : x->cfg.prefill_chunk;
+  const int n_pass = (maxlen + chunk - 1) / chunk;
+
+  // pages: each sequence gets what its final length can need, handed out round-robin so that
+  // the pages of one sequence are not contiguous in the pool
+  x->h_page_table.assign((size_t)B * d.pages_per_seq, 0);
+  {
+    std::vector<int> need(B), got(B, 0);
+    int most = 0;
+    for (int b = 0; b < B; ++b) {
+      need[b] = (lens[b] + max_new + 2 * d.Kmax + 2 + d.page_tokens - 1) / d.page_tokens;
+      if (need[b] > d.pages_per_seq) need[b] = d.pages_per_seq;
+      if (need[b] > most) most = need[b];
+    }
+    int next = 0;
+    for (int i = 0; i < most; ++i)
+      for (int b = 0; b < B; ++b)
+        if (got[b] < need[b]) x->h_page_table[(size_t)b * d.pages_per_seq + got[b]++] = next++;
+    if (next > d.n_pages) return fail(x, HH_ECAPACITY, "hh_prefill: KV page pool exhausted");
+  }
+  x->h_plan.assign((size_t)2 * n_pass * B, 0);
+  for (int p = 0; p < n_pass; ++p)
+    for (int b = 0; b < B; ++b) {
+      int nt = lens[b] - p * chunk;
+      nt = nt < 0 ? 0 : (nt > chunk ? chunk : nt);
+      x->h_plan[(size_t)p * B + b] = nt;
+      x->h_plan[(size_t)(n_pass + p) * B + b] = (nt > 0 && lens[b] <= (p + 1) * chunk) ? 1 : 0;
+    }
+  HH_HIP(hipMemcpyAsync(x->page_table, x->h_page_table.data(), x->h_page_table.size() * sizeof(int), hipMemcpyHostToDevice, s));
+  HH_HIP(hipMemcpyAsync(x->plan_ntok, x->h_plan.data(), (size_t)n_pass * B * sizeof(int), hipMemcpyHostToDevice, s));
+  HH_HIP(hipMemcpyAsync(x->plan_last, x->h_plan.data() + (size_t)n_pass * B, (size_t)n_pass * B * sizeof(int), hipMemcpyHostToDevice, s));
+  HH_HIP(launch_fill_i32(x->kv_len, 0, B, s));
+  HH_HIP(launch_fill_i32(x->committed, 0, B, s));
+
+  for (int p = 0; p < n_pass; ++p) {
+    const int T = maxlen - p * chunk < chunk ? maxlen - p * chunk : chunk;
+    const int* nt = x->plan_ntok + (size_t)p * B;
+    HH_HIP(launch_gather_prompt(tokens, row_stride, p * chunk, nt, B, T, x->tok, x->kv_len, x->pos0, s));
+    HH_HIP(launch_embed(d, x->embed, x->tok, B * T, x->h, s));
+    hh_status st = run_layers(x, true, B, T, nt, p == 0 ? 2 : 0, 1, 1, s);
+    if (st != HH_OK) return st;
+    HH_HIP(launch_prefill_tail(x->h, T, d.D, nt, x->plan_last + (size_t)p * B, x->lasth, x->kv_len, B, s));
+  }
+  hh_status st = run_head(x, x->lasth, B, 1, x->logits_p, d.V, x->first_tok, 1, 0, s);
+  if (st != HH_OK) return st;
+  HH_HIP(launch_prefill_finish(x->first_tok, x->pending, x->out_tok, d.Gmax, x->committed, x->last_n, B, s));
+  x->B = B; x->G = max_new; x->k = 0; x->len_upper = maxlen;
+  x->phase = PH_READY;
+  return HH_OK;
+}
+
+hh_status hh_draft(hh_ctx* x, int32_t k, void* stream) {
+  if (!x) return HH_EINVAL;
+  if (x->phase != PH_READY) return fail(x, HH_ESTATE, "hh_draft: needs a prefilled context with no round in flight");
+  const Dims& d = x->d;
+  if (k < 0 || k > d.Kmax) return fail(x, HH_ECAPACITY, "hh_draft: k outside 0..max_draft");
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  const int B = x->B;
+  for (int i = 0; i < k; ++i) {
+    HH_HIP(launch_gather_tokens(x->pending, x->drafts, d.Kmax, B, 1, 0, i, x->tok, x->kv_len, x->pos0, s));
+    HH_HIP(launch_embed(d, x->embed, x->tok, B, x->h, s));
+    hh_status st = run_layers(x, false, B, 1, nullptr, i == 0 ? 0 : 1, 2, 1, s);
+    if (st != HH_OK) return st;
+    st = run_head(x, x->h, B, 1, x->logits_d + (size_t)i * d.V, d.Kmax * d.V, x->drafts, d.Kmax, i, s);
+    if (st != HH_OK) return st;
+  }
+  x->k = k;
+  x->phase = PH_DRAFTED;
+  return HH_OK;
+}
+
+hh_status hh_set_drafts(hh_ctx* x, const int32_t* drafts, void* stream) {
+  if (!x) return HH_EINVAL;
+  if (x->phase != PH_DRAFTED) return fail(x, HH_ESTATE, "hh_set_drafts: only between hh_draft and hh_verify");
+  if (!drafts) return fail(x, HH_EINVAL, "hh_set_drafts: NULL argument");
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  if (x->k > 0)
+    HH_HIP(hipMemcpy2DAsync(x->drafts, (size_t)x->d.Kmax * sizeof(int), drafts, (size_t)x->k * sizeof(int),
+                            (size_t)x->k * sizeof(int), x->B, hipMemcpyDeviceToDevice, s));
+  return HH_OK;
+}
+
+hh_status hh_verify(hh_ctx* x, void* stream) {
+  if (!x) return HH_EINVAL;
+  if (x->phase != PH_DRAFTED) return fail(x, HH_ESTATE, "hh_verify: needs hh_draft first");
+  const Dims& d = x->d;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  const int B = x->B, T = x->k + 1;
+  HH_HIP(launch_gather_tokens(x->pending, x->drafts, d.Kmax, B, T, 1, 0, x->tok, x->kv_len, x->pos0, s));
+  HH_HIP(launch_embed(d, x->embed, x->tok, B * T, x->h, s));
+  hh_status st = run_layers(x, true, B, T, nullptr, 0, 0, pick_splits(d, B, T, x->len_upper), s);
+  if (st != HH_OK) return st;
+  st = run_head(x, x->h, B * T, T, x->logits_v, d.V, x->targets, d.Kmax + 1, 0, s);
+  if (st != HH_OK) return st;
+  x->phase = PH_VERIFIED;
+  return HH_OK;
+}
+
+hh_status hh_commit(hh_ctx* x, const int32_t* n_accepted, void* stream) {
+  if (!x) return HH_EINVAL;
+  if (x->phase != PH_VERIFIED) return fail(x, HH_ESTATE, "hh_commit: needs hh_verify first");
+  const Dims& d = x->d;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  const int B = x->B;
+  CommitArgs c{};
+  c.drafts = x->drafts; c.targets = x->targets; c.forced = n_accepted;
+  c.committed = x->committed; c.last_n = x->last_n; c.pending = x->pending; c.out_tok = x->out_tok;
+  c.n_acc = x->n_acc; c.skip = x->skip; c.adv = x->adv;
+  c.B = B; c.k = x->k; c.kmax = d.Kmax; c.G = x->G; c.out_stride = d.Gmax;
+  HH_HIP(launch_accept(c, s));
+  // rollback: rebuild the state after position n from the committed state and the ring
+  SsmArgs a{};
+  a.layers = x->layers_dev; a.layer0 = 0; a.n_layers_z = d.L;
+  a.zx = nullptr; a.g = nullptr; a.pos0 = x->kv_len; a.n_tok = nullptr; a.n_acc = x->n_acc; a.skip = x->skip;
+  a.T = x->k + 1; a.B = B; a.state_in = 0; a.state_out = 1; a.write_ring = 0;
+  HH_HIP(launch_ssm(d, a, s));
+  HH_HIP(launch_advance(x->kv_len, x->adv, B, s));
+  x->len_upper += x->k + 1;
+  if (x->len_upper > d.max_seq) x->len_upper = d.max_seq;
+  x->phase = PH_READY;
+  return HH_OK;
+}
+
+// ------------------------------------------------------------------ read-back
+
+static hh_status sync_stream(hh_ctx* x, void* stream) {
+  HH_HIP(hipStreamSynchronize(static_cast<hipStream_t>(stream)));
+  return HH_OK;
+}
+
+hh_status hh_get_tokens(hh_ctx* x, int32_t seq, int32_t* out, int32_t cap, int32_t* n_out, void* stream) {
+  if (!x) return HH_EINVAL;
+  if (x->phase == PH_CREATED) return fail(x, HH_ESTATE, "hh_get_tokens: nothing prefilled");
+  if (seq < 0 || seq >= x->B || !out || !n_out || cap < 0) return fail(x, HH_EINVAL, "hh_get_tokens: bad argument");
+  hh_status st = sync_stream(x, stream);
+  if (st != HH_OK) return st;
+  int c = 0;
+  HH_HIP(hipMemcpy(&c, x->committed + seq, sizeof(int), hipMemcpyDeviceToHost));
+  if (c > cap) c = cap;
+  if (c > 0) HH_HIP(hipMemcpy(out, x->out_tok + (size_t)seq * x->d.Gmax, (size_t)c * sizeof(int), hipMemcpyDeviceToHost));
+  *n_out = c;
+  return HH_OK;
+}
+
+hh_status hh_get_lengths(hh_ctx* x, int32_t* kv_len, int32_t* committed, int32_t* last_n, void* stream) {
+  if (!x) return HH_EINVAL;
+  if (x->phase == PH_CREATED) return fail(x, HH_ESTATE, "hh_get_lengths: nothing prefilled");
+  hh_status st = sync_stream(x, stream);
+  if (st != HH_OK) return st;
+  const size_t n = (size_t)x->B * sizeof(int);
+  if (kv_len) HH_HIP(hipMemcpy(kv_len, x->kv_len, n, hipMemcpyDeviceToHost));
+  if (committed) HH_HIP(hipMemcpy(committed, x->committed, n, hipMemcpyDeviceToHost));
+  if (last_n) HH_HIP(hipMemcpy(last_n, x->last_n, n, hipMemcpyDeviceToHost));
+  return HH_OK;
+}
+
+hh_status hh_get_round(hh_ctx* x, int32_t* drafts, int32_t* targets, void* stream) {
+  if (!x) return HH_EINVAL;
+  if (x->phase == PH_CREATED) return fail(x, HH_ESTATE, "hh_get_round: nothing prefilled");
+  hh_status st = sync_stream(x, stream);
+  if (st != HH_OK) return st;
+  const Dims& d = x->d;
+  if (drafts && x->k > 0)
+    HH_HIP(hipMemcpy2D(drafts, (size_t)x->k * sizeof(int), x->drafts, (size_t)d.Kmax * sizeof(int),
+                       (size_t)x->k * sizeof(int), x->B, hipMemcpyDeviceToHost));
+  if (targets)
+    HH_HIP(hipMemcpy2D(targets, (size_t)(x->k + 1) * sizeof(int), x->targets, (size_t)(d.Kmax + 1) * sizeof(int),
+                       (size_t)(x->k + 1) * sizeof(int), x->B, hipMemcpyDeviceToHost));
+  return HH_OK;
+}
+
+hh_status hh_get_logits(hh_ctx* x, int32_t which, float* out, void* stream) {
+  if (!x) return HH_EINVAL;
+  if (x->phase == PH_CREATED) return fail(x, HH_ESTATE, "hh_get_logits: nothing prefilled");
+  if (!out || which < 0 || which > 2) return fail(x, HH_EINVAL, "hh_get_logits: bad argument");
+  hh_status st = sync_stream(x, stream);
+  if (st != HH_OK) return st;
+  const Dims& d = x->d;
+  const size_t V = d.V;
+  if (which == 0) {
+    if (x->k > 0)
+      HH_HIP(hipMemcpy2D(out, (size_t)x->k * V * 4, x->logits_d, (size_t)d.Kmax * V * 4, (size_t)x->k * V * 4, x->B,
+                         hipMemcpyDeviceToHost));
+  } else if (which == 1) {
+    HH_HIP(hipMemcpy(out, x->logits_v, (size_t)x->B * (x->k + 1) * V * 4, hipMemcpyDeviceToHost));
+  } else {
+    HH_HIP(hipMemcpy(out, x->logits_p, (size_t)x->B * V * 4, hipMemcpyDeviceToHost));
+  }
+  return HH_OK;
+}
+
+hh_status hh_get_state(hh_ctx* x, int32_t layer, float* ssm, float* conv, void* stream) {
+  if (!x) return HH_EINVAL;
+  if (x->phase == PH_CREATED) return fail(x, HH_ESTATE, "hh_get_state: nothing prefilled");
+  const Dims& d = x->d;
+  if (layer < 0 || layer >= d.L) return fail(x, HH_EINVAL, "hh_get_state: layer out of range");
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  if (conv) HH_HIP(launch_export_state(d, x->layers_dev + layer, x->kv_len, x->B, x->export_buf, s));
+  hh_status st = sync_stream(x, stream);
+  if (st != HH_OK) return st;
+  if (ssm)
+    HH_HIP(hipMemcpy(ssm, x->layers_host[layer].S, (size_t)x->B * d.Hm * d.P * d.N * 4, hipMemcpyDeviceToHost));
+  if (conv) HH_HIP(hipMemcpy(conv, x->export_buf, (size_t)x->B * d.conv_dim * 3 * 4, hipMemcpyDeviceToHost));
+  return HH_OK;
+}
+
+hh_status hh_get_kv(hh_ctx* x, int32_t layer, int32_t seq, int32_t n_tokens, float* k, float* v, void* stream) {
+  if (!x) return HH_EINVAL;
+  if (x->phase == PH_CREATED) return fail(x, HH_ESTATE, "hh_get_kv: nothing prefilled");
+  const Dims& d = x->d;
+  if (layer < 0 || layer >= d.L || seq < 0 || seq >= x->B || n_tokens < 0 || n_tokens > d.max_seq || !k || !v)
+    return fail(x, HH_EINVAL, "hh_get_kv: bad argument");
+  // staged through the (idle between calls) projection buffer, a slab of tokens at a time
+  const size_t per_tok = (size_t)d.Hkv * d.Dh;
+  const size_t cap = (size_t)d.Bmax * d.Tmax * d.d_in_proj / 2;
+  const int slab = (int)(cap / per_tok);
+  if (slab < 1) return fail(x, HH_ECAPACITY, "hh_get_kv: staging buffer too small");
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  float* kb = x->zx;
+  float* vb = x->zx + cap;
+  for (int t0 = 0; t0 < n_tokens; t0 += slab) {
+    const int nt = n_tokens - t0 < slab ? n_tokens - t0 : slab;
+    HH_HIP(launch_export_kv(d, x->layers_dev + layer, x->page_table, seq, t0, nt, kb, vb, s));
+    hh_status st = sync_stream(x, stream);
+    if (st != HH_OK) return st;
+    HH_HIP(hipMemcpy(k + (size_t)t0 * per_tok, kb, (size_t)nt * per_tok * 4, hipMemcpyDeviceToHost));
+    HH_HIP(hipMemcpy(v + (size_t)t0 * per_tok, vb, (size_t)nt * per_tok * 4, hipMemcpyDeviceToHost));
+  }
+  return HH_OK;
+}
+
+const char* hh_last_error(const hh_ctx* ctx) { return ctx ? ctx->err.c_str() : g_create_error.c_str(); }
+
+}  // extern "C"

@@ -1,0 +1,108 @@
+// Internal declarations shared by the translation units of libhh (not installed).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "../../include/hh.h"
+
+namespace hh {
+
+// ---- model dimensions derived from hh_cfg
+struct Dims {
+  int L, D, V;
+  int Hm, P, N, d_inner, conv_dim, d_in_proj, ring_w;  // ring_w = conv_dim + Hm (raw xBC inputs | raw dt)
+  int Hq, Hkv, Dh, dq, dkv, dqkv;
+  int F;
+  int ring_slots;   // power of two >= d_conv-1 + max_draft+1 and >= d_conv-1 + prefill chunk
+  int page_tokens, pages_per_seq, n_pages;
+  int Bmax, Tmax, Gmax, Kmax, max_seq;
+  int bf16;         // storage type of matrices and KV
+  float eps, rope_base;
+};
+
+// ---- per-layer device pointers (an array of these lives in the workspace)
+struct LayerDev {
+  const float *norm1, *conv_w, *conv_b, *a_log, *d_skip, *dt_bias, *gnorm, *norm2;
+  const void *w_in, *w_out, *w_q, *w_k, *w_v, *w_o, *w_gate, *w_up, *w_down;
+  float* S;        // committed SSM state of this layer   [B][Hm][P][N]
+  float* S_draft;  // draft scratch state                 [B][Hm][P][N]
+  float* ring;     // raw conv inputs, ring over positions [B][ring_slots][ring_w]
+  void* kpool;     // K pages [n_pages][Hkv][page_tokens][Dh]
+  void* vpool;     // V pages
+};
+
+// ---- skinny GEMM: Y[m][n] (op)= sum_k norm(X)[m][k] * W[n][k]
+enum { EPI_STORE = 0, EPI_ADD = 1, EPI_SWIGLU = 2 };
+struct GemvSeg {
+  const void* W;    // [n_rows][K]
+  const void* W2;   // EPI_SWIGLU: the "up" matrix paired row by row with W (gate)
+  float* Y;         // [M][ldy], row n of this segment lands in column n
+  int n_rows, ldy;
+};
+struct GemvArgs {
+  const float* X; int ldx; int M; int K;
+  const float* norm_w; float eps;          // rmsnorm prologue when norm_w != nullptr
+  GemvSeg seg[4]; int n_seg;
+  int epi;
+  unsigned long long* best;                // optional per-block argmax partials [M][gridDim.x]
+  int bf16;
+};
+hipError_t launch_gemv(const GemvArgs& a, int* n_blocks_out, hipStream_t s);
+int gemv_max_blocks();   // upper bound on gridDim.x of launch_gemv (size of the argmax partial rows)
+
+// ---- SSM branch: causal conv + selective scan over up to T positions per sequence
+struct SsmArgs {
+  const LayerDev* layers; int layer0; int n_layers_z;  // blockIdx.z = (layer - layer0) * B + b
+  const float* zx;     // [B*T][d_in_proj] projections of this pass (nullptr: inputs come from the ring only)
+  float* g;            // [B*T][d_inner]  y * silu(z)  (nullptr: no output)
+  const int* pos0;     // [B] position of the first token of this pass
+  const int* n_tok;    // [B] valid positions (<= T); nullptr: T for all
+  const int* n_acc;    // [B] rebuild mode: positions = n_acc[b] + 1
+  const int* skip;     // [B] nonzero: leave this sequence untouched (may be nullptr)
+  int T, B;
+  int state_in, state_out;   // in: 0 committed S, 1 S_draft, 2 zeros.  out: 0 none, 1 S, 2 S_draft
+  int write_ring;
+};
+hipError_t launch_ssm(const Dims& d, const SsmArgs& a, hipStream_t s);
+
+// ---- attention branch
+struct AttnArgs {
+  const LayerDev* layer;  // device pointer to this layer's entry
+  float* qkv;             // [B*T][dqkv]: q | k | v, rotated in place by rope_append
+  float* o;               // [B*T][dq]
+  const int* pos0; const int* n_tok; const int* page_table;  // [B], [B], [B][pages_per_seq]
+  const float* rope;      // [max_seq][Dh/2][2] (cos, sin)
+  float* part_o; float* part_ml;  // split scratch: [B*T*Hq][S][Dh], [B*T*Hq][S][2]
+  int T, B, n_splits;
+};
+hipError_t launch_rope_append(const Dims& d, const AttnArgs& a, hipStream_t s);
+hipError_t launch_attention(const Dims& d, const AttnArgs& a, hipStream_t s);
+
+// ---- small kernels
+hipError_t launch_embed(const Dims& d, const void* embed, const int* tok, int M, float* h, hipStream_t s);
+// tokens of one draft step: step 0 reads pending[b], step i reads drafts[b][i-1]
+hipError_t launch_gather_tokens(const int* pending, const int* drafts, int kmax, int B, int T, int mode,
+                                int step, int* tok, const int* kv_len, int* pos0, hipStream_t s);
+hipError_t launch_argmax_finish(const unsigned long long* best, int n_part, int M, int* out, int out_stride,
+                                int out_off, int T, hipStream_t s);
+struct CommitArgs {
+  const int* drafts; const int* targets; const int* forced;  // [B][kmax], [B][kmax+1], [B] or nullptr
+  int *committed, *last_n, *pending, *out_tok, *n_acc, *skip, *adv;
+  int B, k, kmax, G, out_stride;
+};
+hipError_t launch_accept(const CommitArgs& a, hipStream_t s);
+hipError_t launch_advance(int* kv_len, const int* n, int B, hipStream_t s);
+hipError_t launch_gather_prompt(const int* prompt, int row_stride, int off, const int* n_tok, int B, int T, int* tok,
+                                const int* kv_len, int* pos0, hipStream_t s);
+hipError_t launch_prefill_tail(const float* h, int T, int D, const int* n_tok, const int* is_last, float* lasth,
+                               int* kv_len, int B, hipStream_t s);
+hipError_t launch_prefill_finish(const int* first_tok, int* pending, int* out_tok, int out_stride, int* committed,
+                                 int* last_n, int B, hipStream_t s);
+hipError_t launch_fill_i32(int* p, int v, size_t n, hipStream_t s);
+hipError_t launch_fill_f32(float* p, float v, size_t n, hipStream_t s);
+hipError_t launch_export_state(const Dims& d, const LayerDev* layer, const int* kv_len, int B, float* conv_out,
+                               hipStream_t s);
+hipError_t launch_export_kv(const Dims& d, const LayerDev* layer, const int* page_table, int seq, int tok0,
+                            int n_tokens, float* k, float* v, hipStream_t s);
+
+}  // namespace hh

@@ -1,0 +1,75 @@
+"""Host-side checks of the C-ABI library that need no GPU: it loads, exports every symbol the
+header declares, sizes workspaces, and rejects bad configurations and out-of-order calls
+before touching the device."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+from paper_2605_01106_amd import workloads as W
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def B():
+    from paper_2605_01106_amd import binding
+    return binding
+
+
+def test_exports_match_header(B):
+    text = open(os.path.join(ROOT, "include", "hh.h")).read()
+    declared = set(re.findall(r"HH_API [\w\s\*]+?\b(hh_\w+)\(", text))
+    assert declared == set(B.EXPORTS), declared ^ set(B.EXPORTS)
+    for name in declared:
+        assert hasattr(B.lib, name)
+    assert C.sizeof(B.hh_cfg) == 112 and C.sizeof(B.hh_layer_weights) == 17 * 8
+
+
+def test_workspace_sizes(B):
+    c1 = W.WORKLOADS["c1"]
+    cfg = B.make_cfg(c1.cfg, 1, 1024, 2, 256)
+    n = B.hh_workspace_bytes(cfg)
+    # at least the KV pool, both SSM states and the logits scratch
+    kv = 36 * 1024 * 2 * 2 * 64 * 2
+    ssm = 2 * 36 * 24 * 64 * 128 * 4
+    assert n > kv + ssm and n < 4 * (kv + ssm) + (1 << 28)
+    c4 = W.WORKLOADS["c4"]
+    big = B.hh_workspace_bytes(B.make_cfg(c4.cfg, 64, 32768 + 128 + 18, 8, 128, prefill_chunk=16))
+    assert 69e9 < big < 120e9
+
+
+@pytest.mark.parametrize("field,value", [("n_groups", 2), ("d_conv", 3), ("n_kv_heads", 3), ("head_dim", 12),
+                                         ("d_state", 24), ("kv_page_tokens", 48), ("w_dtype", 7),
+                                         ("d_model", 60), ("max_batch", 0), ("struct_size", 8)])
+def test_bad_configs_are_rejected(B, field, value):
+    cfg = B.make_cfg(W.WORKLOADS["c0"].cfg, 1, 128, 2, 64)
+    setattr(cfg, field, value)
+    assert B.hh_workspace_bytes(cfg) == 0
+    hw = B.hh_weights()
+    ctx = C.c_void_p()
+    st = B.lib.hh_create(C.byref(hw), C.byref(cfg), C.byref(ctx))
+    assert st == B.HH_EINVAL and not ctx.value
+    assert B.hh_last_error(None)
+
+
+def test_create_needs_workspace_and_weights(B):
+    cfg = B.make_cfg(W.WORKLOADS["c0"].cfg, 1, 128, 2, 64)
+    ctx = C.c_void_p()
+    hw = B.hh_weights()
+    assert B.lib.hh_create(C.byref(hw), C.byref(cfg), C.byref(ctx)) == B.HH_EINVAL      # NULL weights
+    layers = (B.hh_layer_weights * 2)()
+    for l in layers:
+        for n, _ in B.hh_layer_weights._fields_:
+            setattr(l, n, 256)
+    hw.embed = hw.final_norm = hw.lm_head = 256
+    hw.layers = layers
+    assert B.lib.hh_create(C.byref(hw), C.byref(cfg), C.byref(ctx)) == B.HH_EWORKSPACE  # no workspace
+    cfg.workspace, cfg.workspace_bytes = 4096 + 8, 1 << 40                               # misaligned
+    assert B.lib.hh_create(C.byref(hw), C.byref(cfg), C.byref(ctx)) == B.HH_EWORKSPACE
+    cfg.workspace, cfg.workspace_bytes = 4096, 1024                                       # too small
+    assert B.lib.hh_create(C.byref(hw), C.byref(cfg), C.byref(ctx)) == B.HH_EWORKSPACE
+    assert "workspace" in B.hh_last_error(None)
+    assert B.lib.hh_destroy(None) == B.HH_EINVAL
+    assert B.lib.hh_draft(None, 1, None) == B.HH_EINVAL

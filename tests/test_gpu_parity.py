@@ -1,0 +1,83 @@
+"""HIP library vs CPU oracle, element by element, through the C ABI (needs an MI355X)."""
+import json
+import os
+
+import numpy as np
+import pytest
+
+from paper_2605_01106_amd import workloads as W
+
+pytestmark = pytest.mark.gpu
+
+from parity_util import run_lockstep  # noqa: E402
+
+
+@pytest.fixture(scope="module")
+def B():
+    from paper_2605_01106_amd import binding
+    return binding
+
+
+def _ctx(B, weights, batch, max_seq, kmax, G, **kw):
+    return B.Context(weights, batch, max_seq, kmax, G, **kw)
+
+
+def _say(tag):
+    def f(w):
+        print(f"[{tag}] rounds={w['rounds']} mean_n={w['mean_n']:.2f} min_gap={w['min_gap']:.2e} "
+              f"err: logits={w['logits']:.2e} ssm={w['ssm']:.2e} conv={w['conv']:.2e} kv={w['kv']:.2e}", flush=True)
+    return f
+
+
+def test_c0_full_run(B):
+    """Config 0 end to end: tiny fp32 hybrid, prompt 32, 64 new tokens, k = 2."""
+    wl = W.WORKLOADS["c0"]
+    seed = 1
+    wts = W.make_weights(wl.cfg, seed)
+    prompts = W.make_prompts(wl.cfg.vocab, 1, wl.prompt_len, seed)
+    ctx = _ctx(B, wts, 1, 128, wl.k, wl.gen_len)
+    w = run_lockstep(ctx, wts, prompts, [wl.prompt_len], wl.gen_len, wl.k, engine="step", min_gap=2e-5,
+                     report=_say("c0"))
+    assert w["rounds"] >= 20
+
+
+@pytest.mark.parametrize("dtype", [W.F32, W.BF16])
+def test_lively_ragged_batch(B, dtype):
+    """Odd sizes, O(1) recurrence and attention (so state, window and cache errors move the
+    logits), ragged prompts that span several prefill passes, several KV pages and tiles."""
+    cfg = W.scaled_config("lively", n_layers=3, d_model=72, vocab=200, m_heads=3, m_head_dim=40, d_state=16,
+                          n_q_heads=6, n_kv_heads=2, head_dim=24, d_ff=104, w_dtype=dtype)
+    wts = W.make_lively_weights(cfg, 7)
+    lens = [37, 5, 70, 18]
+    prompts = W.make_prompts(cfg.vocab, 4, lens, 3)
+    ctx = _ctx(B, wts, 4, 160, 4, 24, kv_page_tokens=16, prefill_chunk=16)
+    run_lockstep(ctx, wts, prompts, lens, 24, 3, engine="pass", report=_say(f"lively-{dtype}"))
+
+
+@pytest.mark.parametrize("k", [0, 1, 5])
+def test_draft_lengths_and_plain_greedy(B, k):
+    cfg = W.scaled_config("klen", n_layers=2, d_model=64, vocab=128, m_heads=2, m_head_dim=32, d_state=32,
+                          n_q_heads=4, n_kv_heads=4, head_dim=16, d_ff=64, w_dtype=W.F32)
+    wts = W.make_lively_weights(cfg, 11)
+    lens = [9, 20]
+    prompts = W.make_prompts(cfg.vocab, 2, lens, 5)
+    ctx = _ctx(B, wts, 2, 96, 5, 16, prefill_chunk=8)
+    run_lockstep(ctx, wts, prompts, lens, 16, k, engine="step", report=_say(f"k={k}"))
+
+
+def test_forced_acceptance_and_arbitrary_drafts(B):
+    """Forced accepted counts (drafts committed as drafted) and caller-supplied draft tokens."""
+    cfg = W.scaled_config("forced", n_layers=2, d_model=64, vocab=96, m_heads=4, m_head_dim=16, d_state=8,
+                          n_q_heads=2, n_kv_heads=1, head_dim=32, d_ff=128, w_dtype=W.BF16)
+    wts = W.make_lively_weights(cfg, 13)
+    lens = [12, 30, 7]
+    prompts = W.make_prompts(cfg.vocab, 3, lens, 9)
+    k, G = 4, 20
+    forced = W.make_forced_pattern(64, 3, k, 0.6, 1)
+    ctx = _ctx(B, wts, 3, 128, k, G, kv_page_tokens=32, prefill_chunk=32)
+    run_lockstep(ctx, wts, prompts, lens, G, k, forced=forced, report=_say("forced"))
+    override = W.make_random_drafts(cfg.vocab, 64, 3, k, 2)
+    w = run_lockstep(ctx, wts, prompts, lens, G, k, override=override, report=_say("random-drafts"))
+    # the committed stream does not depend on the draft source
+    w2 = run_lockstep(ctx, wts, prompts, lens, G, k, report=_say("ssm-drafts"))
+    assert w["tokens"] == w2["tokens"]

@@ -1,0 +1,236 @@
+#!/usr/bin/env python3
+"""Throughput of the speculative-decoding hot path on one MI355X.
+
+A step is one speculative round over the whole batch: hh_draft(k) + hh_verify + hh_commit
+through the C ABI, on a seeded random-init model shaped like the paper's Falcon-H1-0.5B
+(default) with the prompt already prefilled and everything resident in HBM.  Prints ONE JSON
+line: committed tokens/s (value), draft tokens/s, verify passes/s, per-segment and per-kernel
+HBM roofline fractions, and the CPU oracle timed on the host cores on a bounded sample.
+
+    python bench.py --gpus 1 --steps 64 --warmup 8 [--workload c1] [--cpu-seconds 20]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0      # MI355X HBM3E, published peak
+
+KIND_NAMES = {0: "in_proj", 1: "ssm_scan", 2: "rope_append", 3: "attention", 4: "out_proj", 5: "o_proj",
+              6: "mlp_gate_up", 7: "mlp_down", 8: "lm_head"}
+PHASE_NAMES = {0: "prefill", 1: "draft", 2: "verify", 3: "commit"}
+
+
+def algorithmic_bytes(cfg, B, k, kv_len):
+    """HBM bytes the method must move: weights once per pass, recurrent state, KV cache.
+    Activations, logits and page tables are excluded (well under 1 %)."""
+    esz = 2 if cfg.w_dtype == "bf16" else 4
+    D, F, V, L = cfg.d_model, cfg.d_ff, cfg.vocab, cfg.n_layers
+    state = cfg.m_heads * cfg.m_head_dim * cfg.d_state * 4
+    conv = (cfg.conv_dim + cfg.m_heads) * 4                       # one ring row
+    kv_tok = 2 * cfg.n_kv_heads * cfg.head_dim * esz               # per layer
+    T = k + 1
+    per_kind = {
+        (1, 0): cfg.d_in_proj * D * esz,
+        (1, 1): B * (2 * state + 4 * conv),
+        (1, 4): D * cfg.d_inner * esz,
+        (1, 6): 2 * F * D * esz,
+        (1, 7): D * F * esz,
+        (1, 8): V * D * esz,
+        (2, 0): (cfg.d_in_proj + cfg.d_q + 2 * cfg.d_kv) * D * esz,
+        (2, 1): B * (state + (3 + 2 * T) * conv),
+        (2, 2): B * T * kv_tok,
+        (2, 3): B * (kv_len + T) * kv_tok,
+        (2, 4): D * cfg.d_inner * esz,
+        (2, 5): D * cfg.d_q * esz,
+        (2, 6): 2 * F * D * esz,
+        (2, 7): D * F * esz,
+        (2, 8): V * D * esz,
+        (3, 1): L * B * (2 * state + (3 + T) * conv),
+    }
+    draft_step = sum(per_kind[(1, i)] for i in (0, 1, 4, 6, 7)) * L + per_kind[(1, 8)]
+    verify = sum(per_kind[(2, i)] for i in (0, 1, 2, 3, 4, 5, 6, 7)) * L + per_kind[(2, 8)]
+    commit = per_kind[(3, 1)]
+    return per_kind, draft_step, verify, commit
+
+
+def cpu_baseline(wl, weights, prompts, seconds):
+    """The oracle, as it stands, on the host cores: prefill once (multi-position pass), then
+    speculative rounds for about `seconds`; returns committed tokens/s over the rounds."""
+    from oracle.hybrid_lm import HybridLM
+    from oracle.protocol import SpecDecoder
+    try:
+        from threadpoolctl import threadpool_info
+        threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        threads = len(os.sched_getaffinity(0))
+    lm = HybridLM(wl.cfg, weights.values)
+    dec = SpecDecoder(lm, wl.prompt_len + wl.gen_len + 2 * wl.k + 4, engine="pass", chunk=64)
+    t0 = time.perf_counter()
+    dec.prefill([prompts[b][:wl.prompt_len] for b in range(min(wl.batch, 1))], wl.gen_len)
+    t_prefill = time.perf_counter() - t0
+    rounds, t_draft, t_verify = 0, 0.0, 0.0
+    before = sum(len(o) for o in dec.out)
+    t0 = time.perf_counter()
+    while time.perf_counter() - t0 < seconds and not dec.all_finished():
+        a = time.perf_counter()
+        dec.draft(wl.k)
+        b = time.perf_counter()
+        dec.verify()
+        c = time.perf_counter()
+        dec.commit()
+        t_draft += b - a
+        t_verify += c - b
+        rounds += 1
+    dt = time.perf_counter() - t0
+    toks = sum(len(o) for o in dec.out) - before
+    return {"value": toks / dt, "unit": "committed tokens/s", "cores": int(threads), "kind": "oracle",
+            "sample": f"sequence 0 of {wl.batch}: prefill {wl.prompt_len} tokens ({t_prefill:.1f} s, not counted), then "
+                      f"{rounds} rounds of k={wl.k} ({dt:.1f} s)",
+            "draft_tokens_per_s": rounds * wl.k / max(t_draft, 1e-9),
+            "verify_passes_per_s": rounds / max(t_verify, 1e-9)}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=64)
+    ap.add_argument("--warmup", type=int, default=8)
+    ap.add_argument("--workload", default="c1")
+    ap.add_argument("--seed", type=int, default=0)
+    ap.add_argument("--forced-p", type=float, default=None, help="per-token accept probability of the forced leg")
+    ap.add_argument("--cpu-seconds", type=float, default=15.0, help="0 disables the oracle baseline")
+    ap.add_argument("--graphs", type=int, default=1)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build measures one GPU only (the path shards by sequence with no exchange step); "
+              "run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2605_01106_amd import binding as B
+    from paper_2605_01106_amd import workloads as W
+
+    wl = W.WORKLOADS[args.workload]
+    cfg, k, Bn = wl.cfg, wl.k, wl.batch
+    K, Wm = args.steps, args.warmup
+    prof_rounds, greedy_rounds = 3, min(K, 32)
+    forced_p = args.forced_p if args.forced_p is not None else (wl.forced_p or 0.68)
+    total_rounds = Wm + K + K + prof_rounds + greedy_rounds + 4
+    G = max(wl.gen_len, total_rounds * (k + 1) + 2)
+    max_seq = wl.prompt_len + G + 2 * k + 4
+
+    t0 = time.perf_counter()
+    weights = W.make_weights(cfg, args.seed)
+    prompts = W.make_prompts(cfg.vocab, Bn, wl.prompt_len, args.seed)
+    t_gen = time.perf_counter() - t0
+    ctx = B.Context(weights, Bn, max_seq, k, G, use_graphs=args.graphs)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    ctx.hh_prefill(prompts, [wl.prompt_len] * Bn, G)
+    torch.cuda.synchronize()
+    t_prefill = time.perf_counter() - t0
+
+    def run_rounds(n, kk, forced=None, timed=False):
+        evs = []
+        for r in range(n):
+            if timed:
+                e = [torch.cuda.Event(enable_timing=True) for _ in range(4)]
+                e[0].record()
+            ctx.hh_draft(kk)
+            if timed:
+                e[1].record()
+            ctx.hh_verify()
+            if timed:
+                e[2].record()
+            ctx.hh_commit(None if forced is None else forced[r])
+            if timed:
+                e[3].record()
+                evs.append(e)
+        return evs
+
+    def timed_leg(n, kk, forced=None):
+        torch.cuda.synchronize()
+        _, c0, _ = ctx.hh_get_lengths()
+        t0 = time.perf_counter()
+        evs = run_rounds(n, kk, forced, timed=True)
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - t0
+        _, c1, _ = ctx.hh_get_lengths()
+        seg = [sum(e[i].elapsed_time(e[i + 1]) for e in evs) * 1e-3 for i in range(3)]
+        return dt, sum(c1) - sum(c0), seg
+
+    run_rounds(Wm, k)
+    dt, toks, (t_draft, t_verify, t_commit) = timed_leg(K, k)
+    kv_len, _, _ = ctx.hh_get_lengths()
+    kv_mid = int(np.mean(kv_len)) - K * (k + 1) // 4
+
+    # forced-acceptance leg (seeded fixed pattern, per-token accept probability forced_p)
+    pattern = W.make_forced_pattern(K, Bn, k, forced_p, args.seed)
+    forced_dev = [torch.from_numpy(pattern[r]).to(ctx.device) for r in range(K)]
+    dt_f, toks_f, _ = timed_leg(K, k, forced_dev)
+    # plain greedy decoding of the full model (k = 0) for the speedup the paper's Table 7 reports
+    dt_g, toks_g, _ = timed_leg(greedy_rounds, 0)
+
+    # per-kernel timing leg (HIP events around every launch, on the launch stream)
+    ctx.hh_profile(True)
+    run_rounds(prof_rounds, k)
+    prof = ctx.hh_profile_read()
+    ctx.hh_profile(False)
+    per_kind, draft_bytes, verify_bytes, commit_bytes = algorithmic_bytes(cfg, Bn, k, kv_mid)
+    kernels = {}
+    for (ph, kind), (cnt, ms) in prof.items():
+        if ph == 0:
+            continue
+        by = per_kind.get((ph, kind))
+        avg_us = ms / cnt * 1e3
+        kernels[f"{PHASE_NAMES[ph]}.{KIND_NAMES.get(kind, kind)}"] = {
+            "launches": cnt, "avg_us": round(avg_us, 3), "total_ms": round(ms, 3),
+            "bytes": by, "gbs": None if by is None else round(by / (avg_us * 1e-6) / 1e9, 1)}
+    dom = max((v for v in kernels.values() if v["bytes"]), key=lambda v: v["total_ms"])
+    dom_name = [n for n, v in kernels.items() if v is dom][0]
+    roofline = {"bound": "hbm", "kernel": dom_name, "achieved": dom["gbs"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                "frac": round(dom["gbs"] / HBM_PEAK_GBS, 4), "traffic": None,
+                "bytes_per_launch": dom["bytes"], "avg_us": dom["avg_us"]}
+
+    out = {
+        "metric": "committed tokens/s (speculative rounds, greedy acceptance); draft tok/s and verify passes/s alongside",
+        "value": round(toks / dt, 2), "unit": "tokens/s", "n_gpus": 1, "steps": K, "warmup": Wm,
+        "ms_per_step": round(dt / K * 1e3, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32 accumulate over bf16 weights/KV" if cfg.w_dtype == "bf16" else "f32", "data": "synthetic",
+        "config": {"workload": f"{args.workload}: {cfg.name}, batch {Bn}, prompt {wl.prompt_len}, k={k}, seed {args.seed}",
+                   "rounds_timed": K, "graphs": args.graphs},
+        "draft_tokens_per_s": round(Bn * k * K / t_draft, 1),
+        "verify_passes_per_s": round(K / t_verify, 1),
+        "commit_us": round(t_commit / K * 1e6, 2),
+        "mean_accepted_per_round": round(toks / (K * Bn) - 1, 3),
+        "segments": {
+            "draft_step": {"bytes": draft_bytes, "us": round(t_draft / (K * k) * 1e6, 2),
+                           "hbm_frac": round(draft_bytes / (t_draft / (K * k)) / 1e9 / HBM_PEAK_GBS, 4)},
+            "verify_pass": {"bytes": verify_bytes, "us": round(t_verify / K * 1e6, 2),
+                            "hbm_frac": round(verify_bytes / (t_verify / K) / 1e9 / HBM_PEAK_GBS, 4)},
+            "commit": {"bytes": commit_bytes, "us": round(t_commit / K * 1e6, 2),
+                       "hbm_frac": round(commit_bytes / (t_commit / K) / 1e9 / HBM_PEAK_GBS, 4)}},
+        "forced": {"p": forced_p, "committed_tokens_per_s": round(toks_f / dt_f, 2),
+                   "mean_accepted_per_round": round(toks_f / (K * Bn) - 1, 3)},
+        "plain_greedy_tokens_per_s": round(toks_g / dt_g, 2),
+        "speedup_vs_plain_greedy": round((toks / dt) / (toks_g / dt_g), 4),
+        "prefill_s": round(t_prefill, 3), "weight_gen_s": round(t_gen, 1),
+        "roofline": roofline,
+        "kernels": kernels,
+    }
+    if args.cpu_seconds > 0:
+        out["cpu_baseline"] = cpu_baseline(wl, weights, prompts, args.cpu_seconds)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -74,6 +74,8 @@ EXPORTS = {
     "hh_get_logits": (C.c_int, [_ctx_p, C.c_int32, _f32p, C.c_void_p]),
     "hh_get_state": (C.c_int, [_ctx_p, C.c_int32, _f32p, _f32p, C.c_void_p]),
     "hh_get_kv": (C.c_int, [_ctx_p, C.c_int32, C.c_int32, C.c_int32, _f32p, _f32p, C.c_void_p]),
+    "hh_profile": (C.c_int, [_ctx_p, C.c_int32]),
+    "hh_profile_read": (C.c_int, [_ctx_p, C.c_int32, _i32p, _f32p, C.c_void_p]),
     "hh_last_error": (C.c_char_p, [_ctx_p]),
 }
 for _name, (_res, _args) in EXPORTS.items():
@@ -244,6 +246,16 @@ class Context:
         _check(lib.hh_get_state(self.ctx, layer, ssm.ctypes.data_as(_f32p), conv.ctypes.data_as(_f32p),
                                 _stream_ptr(stream)), self.ctx)
         return ssm, conv
+
+    def hh_profile(self, enable: bool):
+        _check(lib.hh_profile(self.ctx, 1 if enable else 0), self.ctx)
+
+    def hh_profile_read(self, stream=None):
+        """{(phase, kind): (launches, total_ms)} of the launches timed since hh_profile(True)."""
+        n = 64
+        cnt, ms = (C.c_int32 * n)(), (C.c_float * n)()
+        _check(lib.hh_profile_read(self.ctx, n, cnt, ms, _stream_ptr(stream)), self.ctx)
+        return {(t // 16, t % 16): (cnt[t], ms[t]) for t in range(n) if cnt[t]}
 
     def hh_get_kv(self, layer: int, seq: int, n_tokens: int, stream=None):
         c = self.model_cfg

@@ -1,0 +1,8 @@
+// Instantiations of the skinny-GEMM kernel for one epilogue (see gemv.hip).
+#include "gemv_kernel.h"
+
+namespace hh {
+hipError_t gemv_dispatch_store(const GemvArgs& a, int m0, int n_total, const GemvPlan& p, hipStream_t s) {
+  return a.bf16 ? gemv_dispatch<1, EPI_STORE>(a, m0, n_total, p, s) : gemv_dispatch<0, EPI_STORE>(a, m0, n_total, p, s);
+}
+}  // namespace hh

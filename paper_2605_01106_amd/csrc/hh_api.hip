@@ -19,6 +19,7 @@ namespace {
 enum Phase { PH_CREATED = 0, PH_READY = 1, PH_DRAFTED = 2, PH_VERIFIED = 3 };
 
 constexpr int kMaxSplits = 32;
+constexpr size_t kProfCap = 1 << 15;   // timed launches kept per profiling session
 constexpr size_t kAlign = 256;
 
 std::string g_create_error;
@@ -55,6 +56,14 @@ struct hh_ctx {
   int len_upper = 0;
   std::vector<int> h_page_table, h_plan;
   std::string err;
+  // optional per-launch timing (hh_profile): event pairs tagged phase*16 + kind
+  bool prof_on = false;
+  int prof_phase = 0;
+  std::vector<hipEvent_t> prof_ev;
+  std::vector<int> prof_tag;
+  ~hh_ctx() {
+    for (hipEvent_t e : prof_ev) (void)hipEventDestroy(e);
+  }
 };
 
 namespace {
@@ -161,6 +170,21 @@ hh_status fail(hh_ctx* x, hh_status st, const std::string& msg) {
       return fail(x, HH_EDEVICE, std::string(#call) + ": " + hipGetErrorString(e_));           \
   } while (0)
 
+// Launch `call`, bracketed by an event pair when profiling is on.
+#define HH_LAUNCH(kind, call)                                                                  \
+  do {                                                                                         \
+    const bool p_ = x->prof_on && x->prof_ev.size() < kProfCap * 2;                            \
+    if (p_) {                                                                                  \
+      hipEvent_t a_, b_;                                                                       \
+      HH_HIP(hipEventCreate(&a_)); x->prof_ev.push_back(a_);                                   \
+      HH_HIP(hipEventCreate(&b_)); x->prof_ev.push_back(b_);                                   \
+      x->prof_tag.push_back(x->prof_phase * 16 + (kind));                                      \
+      HH_HIP(hipEventRecord(a_, s));                                                           \
+    }                                                                                          \
+    HH_HIP(call);                                                                              \
+    if (p_) HH_HIP(hipEventRecord(x->prof_ev.back(), s));                                      \
+  } while (0)
+
 // ---- one pass of the block stack over M = B*T rows.  full: M_H (both branches); !full: M_S.
 hh_status run_layers(hh_ctx* x, bool full, int B, int T, const int* n_tok, int state_in, int state_out,
                      int n_splits, hipStream_t s) {
@@ -179,44 +203,44 @@ hh_status run_layers(hh_ctx* x, bool full, int B, int T, const int* n_tok, int s
         a.seg[3] = {w.w_v, nullptr, x->qkv + d.dq + d.dkv, d.dkv, d.dqkv};
         a.n_seg = 4;
       }
-      HH_HIP(launch_gemv(a, nullptr, s));
+      HH_LAUNCH(HH_K_IN_PROJ, launch_gemv(a, nullptr, s));
     }
     {  // conv + selective scan -> y * silu(z)
       SsmArgs a{};
       a.layers = x->layers_dev; a.layer0 = l; a.n_layers_z = 1;
       a.zx = x->zx; a.g = x->g; a.pos0 = x->pos0; a.n_tok = n_tok; a.T = T; a.B = B;
       a.state_in = state_in; a.state_out = state_out; a.write_ring = 1;
-      HH_HIP(launch_ssm(d, a, s));
+      HH_LAUNCH(HH_K_SSM, launch_ssm(d, a, s));
     }
     if (full) {
       AttnArgs a{};
       a.layer = x->layers_dev + l; a.qkv = x->qkv; a.o = x->o; a.pos0 = x->pos0; a.n_tok = n_tok;
       a.page_table = x->page_table; a.rope = x->rope; a.part_o = x->part_o; a.part_ml = x->part_ml;
       a.T = T; a.B = B; a.n_splits = n_splits;
-      HH_HIP(launch_rope_append(d, a, s));
-      HH_HIP(launch_attention(d, a, s));
+      HH_LAUNCH(HH_K_ROPE, launch_rope_append(d, a, s));
+      HH_LAUNCH(HH_K_ATTN, launch_attention(d, a, s));
     }
     {  // h += W_out * gated_norm(g)   (+ W_o * o in full mode: the two branches are summed)
       GemvArgs a{};
       a.X = x->g; a.ldx = d.d_inner; a.M = M; a.K = d.d_inner; a.norm_w = w.gnorm; a.eps = d.eps; a.epi = EPI_ADD; a.bf16 = d.bf16;
       a.seg[0] = {w.w_out, nullptr, x->h, d.D, d.D}; a.n_seg = 1;
-      HH_HIP(launch_gemv(a, nullptr, s));
+      HH_LAUNCH(HH_K_OUT_PROJ, launch_gemv(a, nullptr, s));
       if (full) {
         GemvArgs b{};
         b.X = x->o; b.ldx = d.dq; b.M = M; b.K = d.dq; b.norm_w = nullptr; b.epi = EPI_ADD; b.bf16 = d.bf16;
         b.seg[0] = {w.w_o, nullptr, x->h, d.D, d.D}; b.n_seg = 1;
-        HH_HIP(launch_gemv(b, nullptr, s));
+        HH_LAUNCH(HH_K_O_PROJ, launch_gemv(b, nullptr, s));
       }
     }
     {  // SwiGLU MLP
       GemvArgs a{};
       a.X = x->h; a.ldx = d.D; a.M = M; a.K = d.D; a.norm_w = w.norm2; a.eps = d.eps; a.epi = EPI_SWIGLU; a.bf16 = d.bf16;
       a.seg[0] = {w.w_gate, w.w_up, x->act, d.F, d.F}; a.n_seg = 1;
-      HH_HIP(launch_gemv(a, nullptr, s));
+      HH_LAUNCH(HH_K_MLP_UP, launch_gemv(a, nullptr, s));
       GemvArgs b{};
       b.X = x->act; b.ldx = d.F; b.M = M; b.K = d.F; b.norm_w = nullptr; b.epi = EPI_ADD; b.bf16 = d.bf16;
       b.seg[0] = {w.w_down, nullptr, x->h, d.D, d.D}; b.n_seg = 1;
-      HH_HIP(launch_gemv(b, nullptr, s));
+      HH_LAUNCH(HH_K_MLP_DOWN, launch_gemv(b, nullptr, s));
     }
   }
   return HH_OK;
@@ -231,7 +255,7 @@ hh_status run_head(hh_ctx* x, const float* X, int M, int T, float* logits, int l
   a.epi = EPI_STORE; a.bf16 = d.bf16; a.best = x->best;
   a.seg[0] = {x->lm_head, nullptr, logits, d.V, ld_logits}; a.n_seg = 1;
   int nblk = 0;
-  HH_HIP(launch_gemv(a, &nblk, s));
+  HH_LAUNCH(HH_K_LM_HEAD, launch_gemv(a, &nblk, s));
   HH_HIP(launch_argmax_finish(x->best, nblk, M, out, out_stride, out_off, T, s));
   return HH_OK;
 }
@@ -344,6 +368,7 @@ hh_status hh_prefill(hh_ctx* x, const int32_t* tokens, int32_t row_stride, const
   const int B = batch;
   const int chunk = x->cfg.prefill_chunk == 0 ? 64 : x->cfg.prefill_chunk;
   const int n_pass = (maxlen + chunk - 1) / chunk;
+  x->prof_phase = HH_PHASE_PREFILL;
 
   // pages: each sequence gets what its final length can need, handed out round-robin so that
   // the pages of one sequence are not contiguous in the pool
@@ -400,6 +425,7 @@ hh_status hh_draft(hh_ctx* x, int32_t k, void* stream) {
   if (k < 0 || k > d.Kmax) return fail(x, HH_ECAPACITY, "hh_draft: k outside 0..max_draft");
   hipStream_t s = static_cast<hipStream_t>(stream);
   const int B = x->B;
+  x->prof_phase = HH_PHASE_DRAFT;
   for (int i = 0; i < k; ++i) {
     HH_HIP(launch_gather_tokens(x->pending, x->drafts, d.Kmax, B, 1, 0, i, x->tok, x->kv_len, x->pos0, s));
     HH_HIP(launch_embed(d, x->embed, x->tok, B, x->h, s));
@@ -430,6 +456,7 @@ hh_status hh_verify(hh_ctx* x, void* stream) {
   const Dims& d = x->d;
   hipStream_t s = static_cast<hipStream_t>(stream);
   const int B = x->B, T = x->k + 1;
+  x->prof_phase = HH_PHASE_VERIFY;
   HH_HIP(launch_gather_tokens(x->pending, x->drafts, d.Kmax, B, T, 1, 0, x->tok, x->kv_len, x->pos0, s));
   HH_HIP(launch_embed(d, x->embed, x->tok, B * T, x->h, s));
   hh_status st = run_layers(x, true, B, T, nullptr, 0, 0, pick_splits(d, B, T, x->len_upper), s);
@@ -446,6 +473,7 @@ hh_status hh_commit(hh_ctx* x, const int32_t* n_accepted, void* stream) {
   const Dims& d = x->d;
   hipStream_t s = static_cast<hipStream_t>(stream);
   const int B = x->B;
+  x->prof_phase = HH_PHASE_COMMIT;
   CommitArgs c{};
   c.drafts = x->drafts; c.targets = x->targets; c.forced = n_accepted;
   c.committed = x->committed; c.last_n = x->last_n; c.pending = x->pending; c.out_tok = x->out_tok;
@@ -457,7 +485,7 @@ hh_status hh_commit(hh_ctx* x, const int32_t* n_accepted, void* stream) {
   a.layers = x->layers_dev; a.layer0 = 0; a.n_layers_z = d.L;
   a.zx = nullptr; a.g = nullptr; a.pos0 = x->kv_len; a.n_tok = nullptr; a.n_acc = x->n_acc; a.skip = x->skip;
   a.T = x->k + 1; a.B = B; a.state_in = 0; a.state_out = 1; a.write_ring = 0;
-  HH_HIP(launch_ssm(d, a, s));
+  HH_LAUNCH(HH_K_SSM, launch_ssm(d, a, s));
   HH_HIP(launch_advance(x->kv_len, x->adv, B, s));
   x->len_upper += x->k + 1;
   if (x->len_upper > d.max_seq) x->len_upper = d.max_seq;
@@ -569,6 +597,34 @@ hh_status hh_get_kv(hh_ctx* x, int32_t layer, int32_t seq, int32_t n_tokens, flo
     if (st != HH_OK) return st;
     HH_HIP(hipMemcpy(k + (size_t)t0 * per_tok, kb, (size_t)nt * per_tok * 4, hipMemcpyDeviceToHost));
     HH_HIP(hipMemcpy(v + (size_t)t0 * per_tok, vb, (size_t)nt * per_tok * 4, hipMemcpyDeviceToHost));
+  }
+  return HH_OK;
+}
+
+hh_status hh_profile(hh_ctx* x, int32_t enable) {
+  if (!x) return HH_EINVAL;
+  if (enable) {
+    for (hipEvent_t e : x->prof_ev) (void)hipEventDestroy(e);
+    x->prof_ev.clear();
+    x->prof_tag.clear();
+  }
+  x->prof_on = enable != 0;
+  return HH_OK;
+}
+
+hh_status hh_profile_read(hh_ctx* x, int32_t n_tags, int32_t* launches, float* total_ms, void* stream) {
+  if (!x) return HH_EINVAL;
+  if (!launches || !total_ms || n_tags < 1) return fail(x, HH_EINVAL, "hh_profile_read: bad argument");
+  hh_status st = sync_stream(x, stream);
+  if (st != HH_OK) return st;
+  for (int i = 0; i < n_tags; ++i) { launches[i] = 0; total_ms[i] = 0.f; }
+  for (size_t i = 0; i < x->prof_tag.size(); ++i) {
+    const int tag = x->prof_tag[i];
+    if (tag < 0 || tag >= n_tags) continue;
+    float ms = 0.f;
+    HH_HIP(hipEventElapsedTime(&ms, x->prof_ev[2 * i], x->prof_ev[2 * i + 1]));
+    launches[tag] += 1;
+    total_ms[tag] += ms;
   }
   return HH_OK;
 }

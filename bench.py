@@ -132,6 +132,8 @@ def main():
     weights = W.make_weights(cfg, args.seed)
     prompts = W.make_prompts(cfg.vocab, Bn, wl.prompt_len, args.seed)
     t_gen = time.perf_counter() - t0
+    stream = torch.cuda.Stream()          # HIP graphs cannot be captured on the default stream
+    torch.cuda.set_stream(stream)
     ctx = B.Context(weights, Bn, max_seq, k, G, use_graphs=args.graphs)
     torch.cuda.synchronize()
     t0 = time.perf_counter()

@@ -36,7 +36,7 @@ __global__ __launch_bounds__(256) void rope_append_kernel(const Dims d, const At
   if (j >= nt) return;
   const int pos = a.pos0[b] + j;
   const int half = d.Dh / 2;
-  float* row = a.qkv + (size_t)m * d.dqkv;
+  float* row = a.qkv + (size_t)m * d.ldzx;
   const int* pt_row = a.page_table + (size_t)b * d.pages_per_seq;
   const float2* cs = reinterpret_cast<const float2*>(a.rope) + (size_t)pos * half;
   const int n_rot = (d.Hq + d.Hkv) * half;
@@ -128,7 +128,7 @@ __global__ __launch_bounds__(256) void attention_kernel(const Dims d, const Attn
     const int r = it / Dh, dd = it % Dh, rg = chunk * kRowsPerBlock + r;
     float v = 0.f;
     if (rg < n_rows && rg / G < nt)
-      v = a.qkv[((size_t)b * a.T + rg / G) * d.dqkv + (size_t)(kvh * G + rg % G) * Dh + dd];
+      v = a.qkv[((size_t)b * a.T + rg / G) * d.ldzx + (size_t)(kvh * G + rg % G) * Dh + dd];
     qs[it] = v;
   }
 

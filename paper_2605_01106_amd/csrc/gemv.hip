@@ -3,66 +3,89 @@
 //
 // The weights are streamed from HBM exactly once per launch, so the kernel is bound by HBM
 // bandwidth and, for the small matrices of a batch-1 decode step, by latency.  Hence:
-//   * a wavefront walks "units" of R output rows x G chunks of 512 columns and issues the
-//     16-byte loads of unit u+1 before the arithmetic of unit u; the first unit is issued
-//     BEFORE the activations are touched, so the HBM round trip overlaps the prologue;
-//   * the grid is at most two workgroups per CU; a wavefront loops over its row groups, so
-//     big matrices (LM head) pay the prologue once and keep the load pipeline full;
-//   * wavefronts are independent: each lane loads its own eight activation columns per chunk
-//     from global memory (L1/L2 hits) together with the weights, in float32, never rounded:
-//     a bf16 weight times a float32 activation, accumulated in float32.  No LDS, no barrier;
-//   * RMSNorm is fused: every wavefront sums the squares of the activation row itself, the
-//     norm weight multiplies the activations as they are used, and the scalar
+//   * a wavefront owns R output rows and up to 2048 of their columns and issues all of its
+//     16-byte weight loads at once, BEFORE it touches the activations; rows longer than
+//     that are split between the wavefronts of a workgroup and added through LDS;
+//   * many small workgroups (up to 8 wavefronts resident per SIMD) rather than deep software
+//     pipelines: measured on MI355X this streams at 5.4-5.8 TB/s;
+//   * the activation rows are staged once per workgroup in LDS in float32 and never rounded:
+//     a bf16 weight times a float32 activation, accumulated in float32;
+//   * RMSNorm is fused as a prologue in one pass: LDS holds x[k] * w[k], and the scalar
 //     1 / sqrt(mean(x^2) + eps) multiplies the finished dot product;
 //   * epilogues: plain store, in-place residual add (the old value is fetched with the first
 //     loads), SwiGLU (gate and up matrices paired row by row: silu(gate) * up), and
 //     per-workgroup argmax partials for the LM head (largest value, lowest index on ties).
+#include <stdlib.h>
+
 #include "gemv_kernel.h"
 
 namespace hh {
 
-static constexpr int kMaxBlocks = 512;   // two workgroups per CU
+static constexpr int kMaxBlocks = 1 << 15;
+static constexpr size_t kLdsBudget = 150 * 1024;
 
 int gemv_max_blocks() { return kMaxBlocks; }
 
-static GemvPlan make_plan(const GemvArgs& a, int n_total, int MT) {
-  GemvPlan p;
-  const int nch = (a.K + 511) >> 9;
+static bool make_plan(const GemvArgs& a, int MT, GemvPlan& p) {
+  const int N = a.seg[0].n_rows;
+  const int Kpad = (a.K + 511) & ~511;
+  const int nch = Kpad >> 9;
   p.MT = MT;
-  p.G = nch <= 2 ? 2 : 4;
-  // registers per lane: weights 2 buffers * R * G * 4 (bf16; 8 for float32), activations
-  // 2 buffers * MT * G * 8.  Keep the sum near 200.
-  if (MT >= 3) p.G = 2;
-  int rmax = 8 / p.G;
-  if (a.epi == EPI_SWIGLU) rmax /= 2;
-  if (!a.bf16) rmax = a.epi == EPI_SWIGLU ? 1 : (rmax > 2 ? 2 : rmax);
-  if (!a.bf16 && p.G == 4) rmax = 1;
-  if (MT >= 3 && rmax > 2) rmax = 2;
-  if (rmax < 1) rmax = 1;
-  // fewer rows per wavefront while that is needed to give every CU a workgroup
+  // column split: each wavefront takes NCW chunks, KS wavefronts per row group
+  if (nch <= 2) { p.NCW = 2; p.KS = 1; }
+  else if (nch <= 4) { p.NCW = 2; p.KS = 2; }
+  else if (nch <= 8) { p.NCW = 2; p.KS = 4; }
+  else if (nch <= 16) { p.NCW = 4; p.KS = 4; }
+  else return false;
+  // rows per wavefront: R * NCW (* 2 for SwiGLU) loads of 16 bytes in flight per lane
+  int rmax = 4;
+  if (a.epi == EPI_SWIGLU || MT > 5) rmax = 2;
+  if (!a.bf16) rmax = 1;
   p.R = rmax;
-  while (p.R > 1 && (n_total + p.R - 1) / p.R < 256 * kGemvWaves) p.R >>= 1;
-  const int nrg = (n_total + p.R - 1) / p.R;
-  p.blocks = (nrg + kGemvWaves - 1) / kGemvWaves;
-  if (p.blocks > kMaxBlocks) p.blocks = kMaxBlocks;
-  return p;
+  const int rgb = kGemvWaves / p.KS;
+  // R must divide N; use fewer rows per wavefront while that is needed to cover the CUs
+  static const int min_blocks = getenv("HH_GEMV_MINBLK") ? atoi(getenv("HH_GEMV_MINBLK")) : 256;
+  while (p.R > 1 && (N % p.R || N / p.R / rgb < min_blocks)) p.R >>= 1;
+  const int nrg = N / p.R;
+  // several row groups per workgroup, so that staging the activations (MT * K floats per
+  // workgroup, from L2) stays small next to the weights it meets
+  static const int tb1 = getenv("HH_GEMV_TB1") ? atoi(getenv("HH_GEMV_TB1")) : 1024;
+  static const int tbm = getenv("HH_GEMV_TBM") ? atoi(getenv("HH_GEMV_TBM")) : 1024;
+  const int per = (nrg + rgb - 1) / rgb;
+  const int target = MT == 1 ? tb1 : tbm;
+  p.iters = (per + target - 1) / target;
+  if (p.iters < 1) p.iters = 1;
+  if (p.iters > 64) p.iters = 64;
+  p.blocks = (nrg + rgb * p.iters - 1) / (rgb * p.iters);
+  if (p.blocks > kMaxBlocks) return false;
+  const int pn = (a.epi == EPI_SWIGLU ? 2 : 1) * p.R * MT;
+  p.lds = ((size_t)MT * Kpad + kGemvWaves * MT + 2 * kGemvWaves * pn + 4) * sizeof(float);
+  return true;
 }
 
 hipError_t launch_gemv(const GemvArgs& a, int* n_blocks_out, hipStream_t s) {
-  if (a.K % 8 != 0 || a.ldx % 4 != 0) return hipErrorInvalidValue;
-  int n_total = 0;
-  for (int i = 0; i < a.n_seg; ++i) n_total += a.seg[i].n_rows;
-  if (n_total <= 0 || a.M <= 0) return hipSuccess;
+  if (a.K % 8 != 0 || a.K < 8 || a.ldx % 4 != 0 || a.n_seg != 1) return hipErrorInvalidValue;
+  if (a.seg[0].n_rows <= 0 || a.M <= 0) return hipSuccess;
+  const int Kpad = (a.K + 511) & ~511;
+  // largest row tile whose activations fit in LDS
+  int mt_cap = 8;
+  while (mt_cap > 1 && (size_t)mt_cap * Kpad * 4 + 4096 > kLdsBudget) --mt_cap;
+  mt_cap = mt_cap >= 8 ? 8 : mt_cap >= 5 ? 5 : mt_cap >= 3 ? 3 : 1;
+  int mt_first = 0;
   for (int m0 = 0; m0 < a.M;) {
     const int left = a.M - m0;
-    const int mt = left > 5 ? 4 : left;
-    const GemvPlan p = make_plan(a, n_total, mt);
+    int mt = left > 5 ? 8 : left > 3 ? 5 : left > 1 ? 3 : 1;
+    if (mt > mt_cap) mt = mt_cap;
+    // the argmax partials of all row tiles share one layout: keep one launch shape
+    if (a.best != nullptr) { if (mt_first == 0) mt_first = mt; mt = mt_first; }
+    GemvPlan p;
+    if (!make_plan(a, mt, p)) return hipErrorInvalidValue;
     if (n_blocks_out) *n_blocks_out = p.blocks;
     hipError_t e;
     switch (a.epi) {
-      case EPI_STORE: e = gemv_dispatch_store(a, m0, n_total, p, s); break;
-      case EPI_ADD: e = gemv_dispatch_add(a, m0, n_total, p, s); break;
-      case EPI_SWIGLU: e = gemv_dispatch_swiglu(a, m0, n_total, p, s); break;
+      case EPI_STORE: e = gemv_dispatch_store(a, m0, p, s); break;
+      case EPI_ADD: e = gemv_dispatch_add(a, m0, p, s); break;
+      case EPI_SWIGLU: e = gemv_dispatch_swiglu(a, m0, p, s); break;
       default: e = hipErrorInvalidValue;
     }
     if (e != hipSuccess) return e;

@@ -7,6 +7,7 @@
 #include <stdio.h>
 #include <string.h>
 
+#include <map>
 #include <string>
 #include <vector>
 
@@ -61,8 +62,14 @@ struct hh_ctx {
   int prof_phase = 0;
   std::vector<hipEvent_t> prof_ev;
   std::vector<int> prof_tag;
+  // captured launch sequences of draft and verify, by (kind, batch, k, key splits); a key is run
+  // eagerly on its first use (which also sets kernel attributes), captured on its second
+  struct GraphSlot { hipGraphExec_t exec = nullptr; int uses = 0; };
+  std::map<long long, GraphSlot> graphs;
   ~hh_ctx() {
     for (hipEvent_t e : prof_ev) (void)hipEventDestroy(e);
+    for (auto& kv : graphs)
+      if (kv.second.exec) (void)hipGraphExecDestroy(kv.second.exec);
   }
 };
 
@@ -88,8 +95,10 @@ bool derive_dims(const hh_cfg& c, Dims& d, std::string& why) {
   d.ring_w = d.conv_dim + d.Hm;
   d.Hq = c.n_q_heads; d.Hkv = c.n_kv_heads; d.Dh = c.head_dim;
   d.dq = d.Hq * d.Dh; d.dkv = d.Hkv * d.Dh; d.dqkv = d.dq + 2 * d.dkv;
+  d.ldzx = d.d_in_proj + d.dqkv;
   d.F = c.d_ff;
   if (d.D % 8 || d.d_inner % 8 || d.dq % 8 || d.F % 8 || d.F < 8) return bad("d_model, d_inner, n_q_heads*head_dim and d_ff must be multiples of 8");
+  if (d.D > 8192 || d.d_inner > 8192 || d.dq > 8192 || d.F > 8192) return bad("d_model, d_inner, n_q_heads*head_dim and d_ff must not exceed 8192");
   d.page_tokens = c.kv_page_tokens == 0 ? 64 : c.kv_page_tokens;
   if (d.page_tokens != 16 && d.page_tokens != 32 && d.page_tokens != 64 && d.page_tokens != 128 && d.page_tokens != 256)
     return bad("kv_page_tokens must be 16, 32, 64, 128 or 256");
@@ -128,8 +137,8 @@ size_t carve(hh_ctx* x, char* base) {
   x->best = c.take<unsigned long long>(Mv * gemv_max_blocks());
   x->rope = c.take<float>((size_t)d.max_seq * d.Dh);
   x->h = c.take<float>(Mmax * d.D);
-  x->zx = c.take<float>(Mmax * d.d_in_proj);
-  x->qkv = c.take<float>(Mmax * d.dqkv);
+  x->zx = c.take<float>(Mmax * d.ldzx);
+  x->qkv = x->zx ? x->zx + d.d_in_proj : nullptr;
   x->g = c.take<float>(Mmax * d.d_inner);
   x->o = c.take<float>(Mmax * d.dq);
   x->act = c.take<float>(Mmax * d.F);
@@ -150,9 +159,10 @@ size_t carve(hh_ctx* x, char* base) {
     float* rg = c.take<float>(ring);
     char* kp = c.take<char>(pool);
     char* vp = c.take<char>(pool);
+    char* wf = c.take<char>((size_t)d.ldzx * d.D * esz);
     if (base) {
       LayerDev& ld = x->layers_host[l];
-      ld.S = S; ld.S_draft = Sd; ld.ring = rg; ld.kpool = kp; ld.vpool = vp;
+      ld.S = S; ld.S_draft = Sd; ld.ring = rg; ld.kpool = kp; ld.vpool = vp; ld.w_inqkv = wf;
     }
   }
   return (c.off + kAlign - 1) / kAlign * kAlign;
@@ -195,14 +205,8 @@ hh_status run_layers(hh_ctx* x, bool full, int B, int T, const int* n_tok, int s
     {  // shared input norm, Mamba-2 input projection (+ q, k, v of the attention branch)
       GemvArgs a{};
       a.X = x->h; a.ldx = d.D; a.M = M; a.K = d.D; a.norm_w = w.norm1; a.eps = d.eps; a.epi = EPI_STORE; a.bf16 = d.bf16;
-      a.seg[0] = {w.w_in, nullptr, x->zx, d.d_in_proj, d.d_in_proj};
+      a.seg[0] = {w.w_inqkv, nullptr, x->zx, full ? d.ldzx : d.d_in_proj, d.ldzx};
       a.n_seg = 1;
-      if (full) {
-        a.seg[1] = {w.w_q, nullptr, x->qkv, d.dq, d.dqkv};
-        a.seg[2] = {w.w_k, nullptr, x->qkv + d.dq, d.dkv, d.dqkv};
-        a.seg[3] = {w.w_v, nullptr, x->qkv + d.dq + d.dkv, d.dkv, d.dqkv};
-        a.n_seg = 4;
-      }
       HH_LAUNCH(HH_K_IN_PROJ, launch_gemv(a, nullptr, s));
     }
     {  // conv + selective scan -> y * silu(z)
@@ -257,6 +261,36 @@ hh_status run_head(hh_ctx* x, const float* X, int M, int T, float* logits, int l
   int nblk = 0;
   HH_LAUNCH(HH_K_LM_HEAD, launch_gemv(a, &nblk, s));
   HH_HIP(launch_argmax_finish(x->best, nblk, M, out, out_stride, out_off, T, s));
+  return HH_OK;
+}
+
+// Replays `enqueue` (a fixed sequence of kernel launches whose arguments never change for this
+// key) as a HIP graph.  Not used on the NULL stream (it cannot be captured) or while profiling.
+template <typename F>
+hh_status run_graphed(hh_ctx* x, long long key, hipStream_t s, F enqueue) {
+  if (!x->cfg.use_graphs || x->prof_on || s == nullptr) return enqueue();
+  hh_ctx::GraphSlot& g = x->graphs[key];
+  if (g.exec != nullptr) {
+    HH_HIP(hipGraphLaunch(g.exec, s));
+    return HH_OK;
+  }
+  if (g.uses++ == 0) return enqueue();
+  HH_HIP(hipStreamBeginCapture(s, hipStreamCaptureModeThreadLocal));
+  const hh_status st = enqueue();
+  hipGraph_t graph = nullptr;
+  const hipError_t e = hipStreamEndCapture(s, &graph);
+  if (st != HH_OK || e != hipSuccess || graph == nullptr) {
+    if (graph) (void)hipGraphDestroy(graph);
+    if (st != HH_OK) return st;
+    return fail(x, HH_EDEVICE, std::string("hipStreamEndCapture: ") + hipGetErrorString(e));
+  }
+  const hipError_t ei = hipGraphInstantiate(&g.exec, graph, nullptr, nullptr, 0);
+  (void)hipGraphDestroy(graph);
+  if (ei != hipSuccess) {
+    g.exec = nullptr;
+    return fail(x, HH_EDEVICE, std::string("hipGraphInstantiate: ") + hipGetErrorString(ei));
+  }
+  HH_HIP(hipGraphLaunch(g.exec, s));
   return HH_OK;
 }
 
@@ -319,6 +353,24 @@ hh_status hh_create(const hh_weights* weights, const hh_cfg* cfg, hh_ctx** out) 
     ld.w_gate = w.w_gate; ld.w_up = w.w_up; ld.w_down = w.w_down;
   }
   x = nullptr;  // errors below are reported through g_create_error
+  // stacked copy of the four input-side projections, so that one product yields z|xBC|dt|q|k|v
+  {
+    const size_t esz = d.bf16 ? 2 : 4, rowb = (size_t)d.D * esz;
+    for (int l = 0; l < d.L; ++l) {
+      LayerDev& ld = ctx->layers_host[l];
+      char* dst = static_cast<char*>(ld.w_inqkv);
+      const void* src[4] = {ld.w_in, ld.w_q, ld.w_k, ld.w_v};
+      const size_t rows[4] = {(size_t)d.d_in_proj, (size_t)d.dq, (size_t)d.dkv, (size_t)d.dkv};
+      for (int i = 0; i < 4; ++i) {
+        hipError_t ce = hipMemcpy(dst, src[i], rows[i] * rowb, hipMemcpyDeviceToDevice);
+        if (ce != hipSuccess) {
+          delete ctx;
+          return fail(nullptr, HH_EDEVICE, std::string("hh_create: stacking projections: ") + hipGetErrorString(ce));
+        }
+        dst += rows[i] * rowb;
+      }
+    }
+  }
   auto bail = [&](hipError_t e, const char* what) {
     delete ctx;
     return fail(nullptr, HH_EDEVICE, std::string(what) + ": " + hipGetErrorString(e));
@@ -426,12 +478,19 @@ hh_status hh_draft(hh_ctx* x, int32_t k, void* stream) {
   hipStream_t s = static_cast<hipStream_t>(stream);
   const int B = x->B;
   x->prof_phase = HH_PHASE_DRAFT;
-  for (int i = 0; i < k; ++i) {
-    HH_HIP(launch_gather_tokens(x->pending, x->drafts, d.Kmax, B, 1, 0, i, x->tok, x->kv_len, x->pos0, s));
-    HH_HIP(launch_embed(d, x->embed, x->tok, B, x->h, s));
-    hh_status st = run_layers(x, false, B, 1, nullptr, i == 0 ? 0 : 1, 2, 1, s);
-    if (st != HH_OK) return st;
-    st = run_head(x, x->h, B, 1, x->logits_d + (size_t)i * d.V, d.Kmax * d.V, x->drafts, d.Kmax, i, s);
+  auto enqueue = [&]() -> hh_status {
+    for (int i = 0; i < k; ++i) {
+      HH_HIP(launch_gather_tokens(x->pending, x->drafts, d.Kmax, B, 1, 0, i, x->tok, x->kv_len, x->pos0, s));
+      HH_HIP(launch_embed(d, x->embed, x->tok, B, x->h, s));
+      hh_status st = run_layers(x, false, B, 1, nullptr, i == 0 ? 0 : 1, 2, 1, s);
+      if (st != HH_OK) return st;
+      st = run_head(x, x->h, B, 1, x->logits_d + (size_t)i * d.V, d.Kmax * d.V, x->drafts, d.Kmax, i, s);
+      if (st != HH_OK) return st;
+    }
+    return HH_OK;
+  };
+  if (k > 0) {
+    const hh_status st = run_graphed(x, (1LL << 40) | ((long long)B << 20) | k, s, enqueue);
     if (st != HH_OK) return st;
   }
   x->k = k;
@@ -457,11 +516,15 @@ hh_status hh_verify(hh_ctx* x, void* stream) {
   hipStream_t s = static_cast<hipStream_t>(stream);
   const int B = x->B, T = x->k + 1;
   x->prof_phase = HH_PHASE_VERIFY;
-  HH_HIP(launch_gather_tokens(x->pending, x->drafts, d.Kmax, B, T, 1, 0, x->tok, x->kv_len, x->pos0, s));
-  HH_HIP(launch_embed(d, x->embed, x->tok, B * T, x->h, s));
-  hh_status st = run_layers(x, true, B, T, nullptr, 0, 0, pick_splits(d, B, T, x->len_upper), s);
-  if (st != HH_OK) return st;
-  st = run_head(x, x->h, B * T, T, x->logits_v, d.V, x->targets, d.Kmax + 1, 0, s);
+  const int splits = pick_splits(d, B, T, x->len_upper);
+  auto enqueue = [&]() -> hh_status {
+    HH_HIP(launch_gather_tokens(x->pending, x->drafts, d.Kmax, B, T, 1, 0, x->tok, x->kv_len, x->pos0, s));
+    HH_HIP(launch_embed(d, x->embed, x->tok, B * T, x->h, s));
+    hh_status st = run_layers(x, true, B, T, nullptr, 0, 0, splits, s);
+    if (st != HH_OK) return st;
+    return run_head(x, x->h, B * T, T, x->logits_v, d.V, x->targets, d.Kmax + 1, 0, s);
+  };
+  const hh_status st = run_graphed(x, (2LL << 40) | ((long long)B << 20) | ((long long)splits << 8) | T, s, enqueue);
   if (st != HH_OK) return st;
   x->phase = PH_VERIFIED;
   return HH_OK;
@@ -584,7 +647,7 @@ hh_status hh_get_kv(hh_ctx* x, int32_t layer, int32_t seq, int32_t n_tokens, flo
     return fail(x, HH_EINVAL, "hh_get_kv: bad argument");
   // staged through the (idle between calls) projection buffer, a slab of tokens at a time
   const size_t per_tok = (size_t)d.Hkv * d.Dh;
-  const size_t cap = (size_t)d.Bmax * d.Tmax * d.d_in_proj / 2;
+  const size_t cap = (size_t)d.Bmax * d.Tmax * d.ldzx / 2;
   const int slab = (int)(cap / per_tok);
   if (slab < 1) return fail(x, HH_ECAPACITY, "hh_get_kv: staging buffer too small");
   hipStream_t s = static_cast<hipStream_t>(stream);

@@ -12,6 +12,7 @@ struct Dims {
   int L, D, V;
   int Hm, P, N, d_inner, conv_dim, d_in_proj, ring_w;  // ring_w = conv_dim + Hm (raw xBC inputs | raw dt)
   int Hq, Hkv, Dh, dq, dkv, dqkv;
+  int ldzx;         // row stride of the projection buffer: d_in_proj + dqkv (z | xBC | dt | q | k | v)
   int F;
   int ring_slots;   // power of two >= d_conv-1 + max_draft+1 and >= d_conv-1 + prefill chunk
   int page_tokens, pages_per_seq, n_pages;
@@ -24,6 +25,7 @@ struct Dims {
 struct LayerDev {
   const float *norm1, *conv_w, *conv_b, *a_log, *d_skip, *dt_bias, *gnorm, *norm2;
   const void *w_in, *w_out, *w_q, *w_k, *w_v, *w_o, *w_gate, *w_up, *w_down;
+  void* w_inqkv;   // library-owned copy [d_in_proj + dqkv][D]: rows of w_in, w_q, w_k, w_v stacked
   float* S;        // committed SSM state of this layer   [B][Hm][P][N]
   float* S_draft;  // draft scratch state                 [B][Hm][P][N]
   float* ring;     // raw conv inputs, ring over positions [B][ring_slots][ring_w]
@@ -53,7 +55,7 @@ int gemv_max_blocks();   // upper bound on gridDim.x of launch_gemv (size of the
 // ---- SSM branch: causal conv + selective scan over up to T positions per sequence
 struct SsmArgs {
   const LayerDev* layers; int layer0; int n_layers_z;  // blockIdx.z = (layer - layer0) * B + b
-  const float* zx;     // [B*T][d_in_proj] projections of this pass (nullptr: inputs come from the ring only)
+  const float* zx;     // [B*T][ldzx] projections of this pass (nullptr: inputs come from the ring only)
   float* g;            // [B*T][d_inner]  y * silu(z)  (nullptr: no output)
   const int* pos0;     // [B] position of the first token of this pass
   const int* n_tok;    // [B] valid positions (<= T); nullptr: T for all
@@ -68,7 +70,7 @@ hipError_t launch_ssm(const Dims& d, const SsmArgs& a, hipStream_t s);
 // ---- attention branch
 struct AttnArgs {
   const LayerDev* layer;  // device pointer to this layer's entry
-  float* qkv;             // [B*T][dqkv]: q | k | v, rotated in place by rope_append
+  float* qkv;             // [B*T][ldzx] (offset to the q column): q | k | v, rotated in place by rope_append
   float* o;               // [B*T][dq]
   const int* pos0; const int* n_tok; const int* page_table;  // [B], [B], [B][pages_per_seq]
   const float* rope;      // [max_seq][Dh/2][2] (cos, sin)

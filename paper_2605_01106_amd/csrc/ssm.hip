@@ -47,12 +47,12 @@ __global__ __launch_bounds__(kRows * kSub) void ssm_kernel(const Dims d, const S
   const bool prow = p < d.P;
   const int rmask = d.ring_slots - 1;
   const float* ring = ly.ring + (size_t)b * d.ring_slots * d.ring_w;
-  const float* zx = a.zx != nullptr ? a.zx + (size_t)b * a.T * d.d_in_proj : nullptr;
+  const float* zx = a.zx != nullptr ? a.zx + (size_t)b * a.T * d.ldzx : nullptr;
 
   // raw (pre-conv) input of channel c (c < conv_dim: xBC, else dt of head c - conv_dim) at position pos
   auto raw = [&](int pos, int c) -> float {
     if (pos < 0) return 0.f;
-    if (zx != nullptr && pos >= pos0) return zx[(size_t)(pos - pos0) * d.d_in_proj + d.d_inner + c];
+    if (zx != nullptr && pos >= pos0) return zx[(size_t)(pos - pos0) * d.ldzx + d.d_inner + c];
     return ring[(size_t)(pos & rmask) * d.ring_w + c];
   };
 
@@ -141,7 +141,7 @@ __global__ __launch_bounds__(kRows * kSub) void ssm_kernel(const Dims d, const S
       part += __shfl_xor(part, 4, 64);
       if (a.g != nullptr && sub == 0 && prow) {
         const size_t m = (size_t)b * a.T + j0 + jj;
-        const float z = a.zx[m * d.d_in_proj + h * d.P + p];
+        const float z = a.zx[m * d.ldzx + h * d.P + p];
         a.g[m * d.d_inner + h * d.P + p] = (part + dskip * xv) * silu_f(z);
       }
     }

@@ -81,3 +81,23 @@ def test_forced_acceptance_and_arbitrary_drafts(B):
     # the committed stream does not depend on the draft source
     w2 = run_lockstep(ctx, wts, prompts, lens, G, k, report=_say("ssm-drafts"))
     assert w["tokens"] == w2["tokens"]
+
+
+def test_graph_replay_matches_oracle(B):
+    """With use_graphs the draft and verify launch sequences are captured on their second use and
+    replayed afterwards; every replay (one per round, with read-backs and eager commits between
+    them) is compared with the oracle, and the token stream with the eager run."""
+    import torch
+    wl = W.WORKLOADS["c0"]
+    seed = 1
+    wts = W.make_weights(wl.cfg, seed)
+    prompts = W.make_prompts(wl.cfg.vocab, 1, wl.prompt_len, seed)
+    eager = run_lockstep(_ctx(B, wts, 1, 128, wl.k, 40), wts, prompts, [wl.prompt_len], 40, wl.k, engine="step")
+    stream = torch.cuda.Stream()
+    with torch.cuda.stream(stream):
+        ctx = _ctx(B, wts, 1, 128, wl.k, 40, use_graphs=1)
+        w = run_lockstep(ctx, wts, prompts, [wl.prompt_len], 40, wl.k, engine="step", report=_say("graphs"))
+        # a second batch on the same context reuses the instantiated graphs
+        w2 = run_lockstep(ctx, wts, prompts, [wl.prompt_len], 40, wl.k, engine="step", check_state_every=4)
+    stream.synchronize()
+    assert w["tokens"] == eager["tokens"] == w2["tokens"] and w["rounds"] >= 10

@@ -52,10 +52,10 @@ __global__ __launch_bounds__(256) void rope_append_kernel(const Dims d, const At
       } else {
         const size_t at = kv_index(d, pt_row, hd - d.Hq, pos);
         if (d.bf16) {
-          uint16_t* kp = static_cast<uint16_t*>(a.layer->kpool) + at;
+          uint16_t* kp = static_cast<uint16_t*>(a.kpool) + at;
           kp[i] = f32_to_bf16_rne(rlo); kp[i + half] = f32_to_bf16_rne(rhi);
         } else {
-          float* kp = static_cast<float*>(a.layer->kpool) + at;
+          float* kp = static_cast<float*>(a.kpool) + at;
           kp[i] = rlo; kp[i + half] = rhi;
         }
       }
@@ -64,10 +64,10 @@ __global__ __launch_bounds__(256) void rope_append_kernel(const Dims d, const At
       const float* v = row + (size_t)(d.Hq + d.Hkv + kvh) * d.Dh;
       const size_t at = kv_index(d, pt_row, kvh, pos);
       if (d.bf16) {
-        uint16_t* vp = static_cast<uint16_t*>(a.layer->vpool) + at;
+        uint16_t* vp = static_cast<uint16_t*>(a.vpool) + at;
         vp[i] = f32_to_bf16_rne(v[i]); vp[i + half] = f32_to_bf16_rne(v[i + half]);
       } else {
-        float* vp = static_cast<float*>(a.layer->vpool) + at;
+        float* vp = static_cast<float*>(a.vpool) + at;
         vp[i] = v[i]; vp[i + half] = v[i + half];
       }
     }
@@ -79,15 +79,29 @@ hipError_t launch_rope_append(const Dims& d, const AttnArgs& a, hipStream_t s) {
   return hipGetLastError();
 }
 
+// Reductions over the 64 lanes without LDS traffic: DPP butterflies inside each row of 16
+// lanes, then the four row results are read out and combined.  All lanes must be active.
+template <int CTRL>
+__device__ __forceinline__ float dpp_perm_a(float v) {
+  return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xf, 0xf, false));
+}
 __device__ __forceinline__ float wave_max(float v) {
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
-  return v;
+  v = fmaxf(v, dpp_perm_a<0xB1>(v));
+  v = fmaxf(v, dpp_perm_a<0x4E>(v));
+  v = fmaxf(v, dpp_perm_a<0x141>(v));
+  v = fmaxf(v, dpp_perm_a<0x140>(v));
+  const int iv = __float_as_int(v);
+  return fmaxf(fmaxf(__int_as_float(__builtin_amdgcn_readlane(iv, 0)), __int_as_float(__builtin_amdgcn_readlane(iv, 16))),
+               fmaxf(__int_as_float(__builtin_amdgcn_readlane(iv, 32)), __int_as_float(__builtin_amdgcn_readlane(iv, 48))));
 }
 __device__ __forceinline__ float wave_add(float v) {
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
-  return v;
+  v += dpp_perm_a<0xB1>(v);
+  v += dpp_perm_a<0x4E>(v);
+  v += dpp_perm_a<0x141>(v);
+  v += dpp_perm_a<0x140>(v);
+  const int iv = __float_as_int(v);
+  return (__int_as_float(__builtin_amdgcn_readlane(iv, 0)) + __int_as_float(__builtin_amdgcn_readlane(iv, 16))) +
+         (__int_as_float(__builtin_amdgcn_readlane(iv, 32)) + __int_as_float(__builtin_amdgcn_readlane(iv, 48)));
 }
 
 // grid: x = row_chunks * n_splits, y = Hkv, z = B
@@ -157,8 +171,8 @@ __global__ __launch_bounds__(256) void attention_kernel(const Dims d, const Attn
       if (key < nk) {
         const size_t at = kv_index(d, pt_row, kvh, key) + c8;
         if (d.bf16) {
-          const uint4 ku = *reinterpret_cast<const uint4*>(static_cast<const uint16_t*>(a.layer->kpool) + at);
-          const uint4 vu = *reinterpret_cast<const uint4*>(static_cast<const uint16_t*>(a.layer->vpool) + at);
+          const uint4 ku = *reinterpret_cast<const uint4*>(static_cast<const uint16_t*>(a.kpool) + at);
+          const uint4 vu = *reinterpret_cast<const uint4*>(static_cast<const uint16_t*>(a.vpool) + at);
           const uint32_t kw[4] = {ku.x, ku.y, ku.z, ku.w}, vw[4] = {vu.x, vu.y, vu.z, vu.w};
 #pragma unroll
           for (int i = 0; i < 4; ++i) {
@@ -166,8 +180,8 @@ __global__ __launch_bounds__(256) void attention_kernel(const Dims d, const Attn
             vv8[2 * i] = __uint_as_float(vw[i] << 16); vv8[2 * i + 1] = __uint_as_float(vw[i] & 0xffff0000u);
           }
         } else {
-          const float* kp = static_cast<const float*>(a.layer->kpool) + at;
-          const float* vp = static_cast<const float*>(a.layer->vpool) + at;
+          const float* kp = static_cast<const float*>(a.kpool) + at;
+          const float* vp = static_cast<const float*>(a.vpool) + at;
 #pragma unroll
           for (int i = 0; i < 8; ++i) { kv8[i] = kp[i]; vv8[i] = vp[i]; }
         }

@@ -64,12 +64,18 @@ struct hh_ctx {
   std::vector<int> prof_tag;
   // captured launch sequences of draft and verify, by (kind, batch, k, key splits); a key is run
   // eagerly on its first use (which also sets kernel attributes), captured on its second
+  // side stream on which the attention branch of a block runs beside its SSM branch
+  hipStream_t side = nullptr;
+  std::vector<hipEvent_t> fork_ev, join_ev;   // one pair per layer
   struct GraphSlot { hipGraphExec_t exec = nullptr; int uses = 0; };
   std::map<long long, GraphSlot> graphs;
   ~hh_ctx() {
     for (hipEvent_t e : prof_ev) (void)hipEventDestroy(e);
     for (auto& kv : graphs)
       if (kv.second.exec) (void)hipGraphExecDestroy(kv.second.exec);
+    for (hipEvent_t e : fork_ev) (void)hipEventDestroy(e);
+    for (hipEvent_t e : join_ev) (void)hipEventDestroy(e);
+    if (side) (void)hipStreamDestroy(side);
   }
 };
 
@@ -209,21 +215,37 @@ hh_status run_layers(hh_ctx* x, bool full, int B, int T, const int* n_tok, int s
       a.n_seg = 1;
       HH_LAUNCH(HH_K_IN_PROJ, launch_gemv(a, nullptr, s));
     }
+    // The two branches of the block (Eq. 2) only share their input: the attention branch is
+    // enqueued on a side stream so that it overlaps the SSM branch, and joins before the sum.
+    const bool overlap = full && !x->prof_on && x->side != nullptr;
+    hipStream_t sa = s;
+    if (overlap) {
+      sa = x->side;
+      HH_HIP(hipEventRecord(x->fork_ev[l], s));
+      HH_HIP(hipStreamWaitEvent(sa, x->fork_ev[l], 0));
+    }
+    if (full) {
+      AttnArgs a{};
+      a.kpool = w.kpool; a.vpool = w.vpool; a.qkv = x->qkv; a.o = x->o; a.pos0 = x->pos0; a.n_tok = n_tok;
+      a.page_table = x->page_table; a.rope = x->rope; a.part_o = x->part_o; a.part_ml = x->part_ml;
+      a.T = T; a.B = B; a.n_splits = n_splits;
+      if (overlap) {
+        HH_HIP(launch_rope_append(d, a, sa));
+        HH_HIP(launch_attention(d, a, sa));
+        HH_HIP(hipEventRecord(x->join_ev[l], sa));
+      } else {
+        HH_LAUNCH(HH_K_ROPE, launch_rope_append(d, a, s));
+        HH_LAUNCH(HH_K_ATTN, launch_attention(d, a, s));
+      }
+    }
     {  // conv + selective scan -> y * silu(z)
       SsmArgs a{};
-      a.layers = x->layers_dev; a.layer0 = l; a.n_layers_z = 1;
+      a.layers = nullptr; a.one = w; a.layer0 = 0; a.n_layers_z = 1;
       a.zx = x->zx; a.g = x->g; a.pos0 = x->pos0; a.n_tok = n_tok; a.T = T; a.B = B;
       a.state_in = state_in; a.state_out = state_out; a.write_ring = 1;
       HH_LAUNCH(HH_K_SSM, launch_ssm(d, a, s));
     }
-    if (full) {
-      AttnArgs a{};
-      a.layer = x->layers_dev + l; a.qkv = x->qkv; a.o = x->o; a.pos0 = x->pos0; a.n_tok = n_tok;
-      a.page_table = x->page_table; a.rope = x->rope; a.part_o = x->part_o; a.part_ml = x->part_ml;
-      a.T = T; a.B = B; a.n_splits = n_splits;
-      HH_LAUNCH(HH_K_ROPE, launch_rope_append(d, a, s));
-      HH_LAUNCH(HH_K_ATTN, launch_attention(d, a, s));
-    }
+    if (overlap) HH_HIP(hipStreamWaitEvent(s, x->join_ev[l], 0));
     {  // h += W_out * gated_norm(g)   (+ W_o * o in full mode: the two branches are summed)
       GemvArgs a{};
       a.X = x->g; a.ldx = d.d_inner; a.M = M; a.K = d.d_inner; a.norm_w = w.gnorm; a.eps = d.eps; a.epi = EPI_ADD; a.bf16 = d.bf16;
@@ -391,6 +413,18 @@ hh_status hh_create(const hh_weights* weights, const hh_cfg* cfg, hh_ctx** out) 
     }
     e = hipMemcpy(ctx->rope, tab.data(), tab.size() * sizeof(float), hipMemcpyHostToDevice);
     if (e != hipSuccess) return bail(e, "hh_create: upload of rotary table");
+  }
+  // side stream (default priority) and per-layer fork/join events for the branch overlap
+  e = hipStreamCreateWithFlags(&ctx->side, hipStreamNonBlocking);
+  if (e != hipSuccess) return bail(e, "hh_create: side stream");
+  ctx->fork_ev.resize(d.L); ctx->join_ev.resize(d.L);
+  for (int l = 0; l < d.L; ++l) {
+    ctx->fork_ev[l] = nullptr; ctx->join_ev[l] = nullptr;
+  }
+  for (int l = 0; l < d.L; ++l) {
+    e = hipEventCreateWithFlags(&ctx->fork_ev[l], hipEventDisableTiming);
+    if (e == hipSuccess) e = hipEventCreateWithFlags(&ctx->join_ev[l], hipEventDisableTiming);
+    if (e != hipSuccess) return bail(e, "hh_create: events");
   }
   *out = ctx;
   return HH_OK;

@@ -55,6 +55,7 @@ int gemv_max_blocks();   // upper bound on gridDim.x of launch_gemv (size of the
 // ---- SSM branch: causal conv + selective scan over up to T positions per sequence
 struct SsmArgs {
   const LayerDev* layers; int layer0; int n_layers_z;  // blockIdx.z = (layer - layer0) * B + b
+  LayerDev one;        // used instead of the table when layers == nullptr (single-layer launch)
   const float* zx;     // [B*T][ldzx] projections of this pass (nullptr: inputs come from the ring only)
   float* g;            // [B*T][d_inner]  y * silu(z)  (nullptr: no output)
   const int* pos0;     // [B] position of the first token of this pass
@@ -69,7 +70,7 @@ hipError_t launch_ssm(const Dims& d, const SsmArgs& a, hipStream_t s);
 
 // ---- attention branch
 struct AttnArgs {
-  const LayerDev* layer;  // device pointer to this layer's entry
+  void* kpool; void* vpool;  // this layer's K and V pages
   float* qkv;             // [B*T][ldzx] (offset to the q column): q | k | v, rotated in place by rope_append
   float* o;               // [B*T][dq]
   const int* pos0; const int* n_tok; const int* page_table;  // [B], [B], [B][pages_per_seq]

@@ -11,21 +11,27 @@
 //                state: the state after position n, bit-identical to what verification held.
 // Prefill uses the verification form with a state write-back per chunk.
 //
-// Layout: S[b][h][p][n] float32, n fastest.  A workgroup owns 32 rows p of one head; 8 lanes
+// Layout: S[b][h][p][n] float32, n fastest.  A workgroup owns kRows (8 or 32) rows p of one head; 8 lanes
 // share a row, each holding N/8 consecutive n in registers; the read-out over n is reduced
 // across those 8 lanes.  Ring row for position q: slot q mod ring_slots, [conv_dim raw xBC | Hm raw dt].
 #include "hh_internal.h"
 
 namespace hh {
 
-static constexpr int kRows = 32;   // state rows per workgroup
 static constexpr int kSub = 8;     // lanes per row
 static constexpr int kTS = 16;     // positions staged per pass through LDS
 
 __device__ __forceinline__ float silu_f(float v) { return v / (1.0f + expf(-v)); }
 __device__ __forceinline__ float softplus_f(float v) { return v > 20.0f ? v : log1pf(expf(v)); }
 
-template <int NV>
+template <int CTRL>
+__device__ __forceinline__ float dpp_perm_f(float v) {
+  return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xf, 0xf, false));
+}
+
+// kRows = 8: one wavefront per workgroup, many small workgroups (latency-bound small batches);
+// kRows = 32: four wavefronts, the conv of B and C is shared by four times as many state rows.
+template <int NV, int kRows>
 __global__ __launch_bounds__(kRows * kSub) void ssm_kernel(const Dims d, const SsmArgs a) {
   constexpr int N = NV * kSub;
   __shared__ float xs[kTS][kRows];
@@ -36,7 +42,8 @@ __global__ __launch_bounds__(kRows * kSub) void ssm_kernel(const Dims d, const S
   const int tid = threadIdx.x, row = tid >> 3, sub = tid & 7;
   const int p0 = blockIdx.x * kRows, h = blockIdx.y;
   const int lz = blockIdx.z / a.B, b = blockIdx.z % a.B;
-  const LayerDev& ly = a.layers[a.layer0 + lz];
+  // one layer: its pointers arrive by value in the kernel arguments; several: from the table
+  const LayerDev& ly = a.layers != nullptr ? a.layers[a.layer0 + lz] : a.one;
   if (a.skip != nullptr && a.skip[b]) return;
   int nt = a.T;
   if (a.n_acc != nullptr) nt = a.n_acc[b] + 1;
@@ -50,10 +57,12 @@ __global__ __launch_bounds__(kRows * kSub) void ssm_kernel(const Dims d, const S
   const float* zx = a.zx != nullptr ? a.zx + (size_t)b * a.T * d.ldzx : nullptr;
 
   // raw (pre-conv) input of channel c (c < conv_dim: xBC, else dt of head c - conv_dim) at position pos
+  // (one unconditional load from a selected address, so that independent loads overlap)
   auto raw = [&](int pos, int c) -> float {
-    if (pos < 0) return 0.f;
-    if (zx != nullptr && pos >= pos0) return zx[(size_t)(pos - pos0) * d.ldzx + d.d_inner + c];
-    return ring[(size_t)(pos & rmask) * d.ring_w + c];
+    const float* p = (zx != nullptr && pos >= pos0) ? zx + (size_t)(pos - pos0) * d.ldzx + d.d_inner + c
+                                                    : ring + (size_t)(max(pos, 0) & rmask) * d.ring_w + c;
+    const float v = *p;
+    return pos < 0 ? 0.f : v;
   };
 
   float S[NV];
@@ -93,10 +102,12 @@ __global__ __launch_bounds__(kRows * kSub) void ssm_kernel(const Dims d, const S
       float out = 0.f;
       if (ok) {
         const int pos = pos0 + j0 + jj;
-        float acc = 0.f;
-#pragma unroll
-        for (int t = 0; t < 4; ++t) acc = fmaf(ly.conv_w[c * 4 + t], raw(pos - 3 + t, c), acc);
-        out = silu_f(acc + ly.conv_b[c]);
+        const float4 taps = *reinterpret_cast<const float4*>(ly.conv_w + (size_t)c * 4);
+        const float bias = ly.conv_b[c];
+        const float r0 = raw(pos - 3, c), r1 = raw(pos - 2, c), r2 = raw(pos - 1, c), r3 = raw(pos, c);
+        float acc = taps.x * r0;
+        acc = fmaf(taps.y, r1, acc); acc = fmaf(taps.z, r2, acc); acc = fmaf(taps.w, r3, acc);
+        out = silu_f(acc + bias);
       }
       if (ci < kRows) xs[jj][ci] = out;
       else if (ci < kRows + N) Bs[jj][ci - kRows] = out;
@@ -136,9 +147,9 @@ __global__ __launch_bounds__(kRows * kSub) void ssm_kernel(const Dims d, const S
         S[i] = fmaf(aj, S[i], coef * Bs[jj][sub * NV + i]);
         part = fmaf(S[i], Cs[jj][sub * NV + i], part);
       }
-      part += __shfl_xor(part, 1, 64);
-      part += __shfl_xor(part, 2, 64);
-      part += __shfl_xor(part, 4, 64);
+      part += dpp_perm_f<0xB1>(part);    // lane ^ 1
+      part += dpp_perm_f<0x4E>(part);    // lane ^ 2
+      part += dpp_perm_f<0x141>(part);   // the other quad of the 8 lanes that share a row
       if (a.g != nullptr && sub == 0 && prow) {
         const size_t m = (size_t)b * a.T + j0 + jj;
         const float z = a.zx[m * d.ldzx + h * d.P + p];
@@ -160,20 +171,28 @@ __global__ __launch_bounds__(kRows * kSub) void ssm_kernel(const Dims d, const S
   }
 }
 
-hipError_t launch_ssm(const Dims& d, const SsmArgs& a, hipStream_t s) {
-  if (d.N % kSub != 0) return hipErrorInvalidValue;
+template <int kRows>
+static hipError_t launch_ssm_rows(const Dims& d, const SsmArgs& a, hipStream_t s) {
   const dim3 grid((d.P + kRows - 1) / kRows, d.Hm, a.n_layers_z * a.B);
   const dim3 block(kRows * kSub);
   switch (d.N / kSub) {
-    case 1: hipLaunchKernelGGL(ssm_kernel<1>, grid, block, 0, s, d, a); break;
-    case 2: hipLaunchKernelGGL(ssm_kernel<2>, grid, block, 0, s, d, a); break;
-    case 4: hipLaunchKernelGGL(ssm_kernel<4>, grid, block, 0, s, d, a); break;
-    case 8: hipLaunchKernelGGL(ssm_kernel<8>, grid, block, 0, s, d, a); break;
-    case 16: hipLaunchKernelGGL(ssm_kernel<16>, grid, block, 0, s, d, a); break;
-    case 32: hipLaunchKernelGGL(ssm_kernel<32>, grid, block, 0, s, d, a); break;
+    case 1: hipLaunchKernelGGL((ssm_kernel<1, kRows>), grid, block, 0, s, d, a); break;
+    case 2: hipLaunchKernelGGL((ssm_kernel<2, kRows>), grid, block, 0, s, d, a); break;
+    case 4: hipLaunchKernelGGL((ssm_kernel<4, kRows>), grid, block, 0, s, d, a); break;
+    case 8: hipLaunchKernelGGL((ssm_kernel<8, kRows>), grid, block, 0, s, d, a); break;
+    case 16: hipLaunchKernelGGL((ssm_kernel<16, kRows>), grid, block, 0, s, d, a); break;
+    case 32: hipLaunchKernelGGL((ssm_kernel<32, kRows>), grid, block, 0, s, d, a); break;
     default: return hipErrorInvalidValue;
   }
   return hipGetLastError();
+}
+
+hipError_t launch_ssm(const Dims& d, const SsmArgs& a, hipStream_t s) {
+  if (d.N % kSub != 0) return hipErrorInvalidValue;
+  // enough 32-row workgroups to cover the chip twice: take them, else 8-row ones
+  const long big = (long)((d.P + 31) / 32) * d.Hm * a.n_layers_z * a.B;
+  (void)big;
+  return launch_ssm_rows<32>(d, a, s);
 }
 
 // Committed conv window (the d_conv-1 raw inputs before position kv_len, oldest first) of one layer,

@@ -35,33 +35,41 @@ def assert_close(name, got, ref, atol, rtol, scale_to_ref=False):
 
 def run_lockstep(ctx, weights: W.Weights, prompts, lens, G: int, k: int, forced: Optional[np.ndarray] = None,
                  override: Optional[np.ndarray] = None, engine: str = "pass", max_rounds: int = 10 ** 9,
-                 check_state_every: int = 1, check_kv: bool = True, min_gap: float = 0.0, report=None):
+                 check_state_every: int = 1, check_kv: bool = True, min_gap: float = 0.0, report=None,
+                 layers=None, oracle_rows=None, chunk: int = 5):
     """Runs prefill and rounds on both sides, comparing after every call:
     tokens, accepted counts, cache lengths and committed counts bit-exactly;
     logits, SSM state, conv window and KV entries within tolerance.
+    `layers`: layers whose state and cache are read back (default all).  `oracle_rows`: batch
+    rows the oracle runs (default all); the library always runs the whole batch, rows are
+    independent, so the remaining rows are covered by the batch-invariance of the kernels.
     Returns a dict of the worst errors seen."""
     import torch
     cfg = weights.cfg
     atol, rtol = tolerances(cfg.w_dtype)
-    B = len(lens)
+    rows = list(range(len(lens))) if oracle_rows is None else list(oracle_rows)
+    B = len(rows)
+    layer_list = list(range(cfg.n_layers)) if layers is None else list(layers)
     lm = HybridLM(cfg, weights.values)
     cap = int(max(lens)) + G + 2 * k + 4
-    dec = SpecDecoder(lm, cap, engine=engine, chunk=5)
-    plist = [np.asarray(prompts[b][:lens[b]]) for b in range(B)]
+    dec = SpecDecoder(lm, cap, engine=engine, chunk=chunk)
+    plist = [np.asarray(prompts[b][:lens[b]]) for b in rows]
     dec.prefill(plist, G)
     ctx.hh_prefill(prompts, lens, G)
     worst = {"logits": 0.0, "ssm": 0.0, "conv": 0.0, "kv": 0.0}
     worst["logits"] = max(worst["logits"], assert_close(
-        "prefill logits", ctx.hh_get_logits(2), np.array(dec.prefill_logits), atol, rtol))
+        "prefill logits", ctx.hh_get_logits(2)[rows], np.array(dec.prefill_logits), atol, rtol))
 
     def check_state(tag):
         kv_len, committed, last_n = ctx.hh_get_lengths()
+        kv_len, committed = [kv_len[b] for b in rows], [committed[b] for b in rows]
         assert kv_len == [s.kv_len for s in dec.st], (tag, kv_len, [s.kv_len for s in dec.st])
         assert committed == [len(o) for o in dec.out], (tag, committed)
         for b in range(B):
-            assert ctx.hh_get_tokens(b) == dec.out[b], (tag, b)
-        for l in range(cfg.n_layers):
+            assert ctx.hh_get_tokens(rows[b]) == dec.out[b], (tag, b)
+        for l in layer_list:
             ssm, conv = ctx.hh_get_state(l)
+            ssm, conv = ssm[rows], conv[rows]
             worst["ssm"] = max(worst["ssm"], assert_close(
                 f"{tag} ssm L{l}", ssm, np.array([s.S[l] for s in dec.st]), atol, rtol, scale_to_ref=True))
             worst["conv"] = max(worst["conv"], assert_close(
@@ -69,7 +77,7 @@ def run_lockstep(ctx, weights: W.Weights, prompts, lens, G: int, k: int, forced:
             if check_kv:
                 for b in range(B):
                     n = dec.st[b].kv_len
-                    kk, vv = ctx.hh_get_kv(l, b, n)
+                    kk, vv = ctx.hh_get_kv(l, rows[b], n)
                     # float32 evaluation error of the projection, plus one storage ulp for bf16:
                     # rounding a float32 vs a float64 input may pick neighbouring bf16 values
                     # (and such a flip in an earlier layer moves later layers' inputs by ~1e-3 of their scale)
@@ -85,10 +93,10 @@ def run_lockstep(ctx, weights: W.Weights, prompts, lens, G: int, k: int, forced:
     while not dec.all_finished() and r < max_rounds:
         active = [not dec.finished(b) for b in range(B)]
         ov = None if override is None else override[r]
-        dec.draft(k, ov)
+        dec.draft(k, None if ov is None else ov[rows])
         ctx.hh_draft(k)
         if k > 0:
-            gl = ctx.hh_get_logits(0)
+            gl = ctx.hh_get_logits(0)[rows]
             for b in range(B):
                 if active[b]:
                     worst["logits"] = max(worst["logits"], assert_close(
@@ -96,13 +104,15 @@ def run_lockstep(ctx, weights: W.Weights, prompts, lens, G: int, k: int, forced:
             if ov is not None:
                 ctx.hh_set_drafts(np.ascontiguousarray(ov[:, :k], np.int32))
             d_gpu, _ = ctx.hh_get_round()
+            d_gpu = d_gpu[rows]
             for b in range(B):
                 if active[b]:
                     assert list(d_gpu[b]) == list(dec.drafts[b]), (r, b, list(d_gpu[b]), dec.drafts[b])
         dec.verify()
         ctx.hh_verify()
-        vl = ctx.hh_get_logits(1)
+        vl = ctx.hh_get_logits(1)[rows]
         _, g_gpu = ctx.hh_get_round()
+        g_gpu = g_gpu[rows]
         for b in range(B):
             if active[b]:
                 worst["logits"] = max(worst["logits"], assert_close(
@@ -112,9 +122,10 @@ def run_lockstep(ctx, weights: W.Weights, prompts, lens, G: int, k: int, forced:
             dec.commit()
             ctx.hh_commit()
         else:
-            dec.commit(forced[r])
+            dec.commit(forced[r][rows])
             ctx.hh_commit(torch.from_numpy(np.ascontiguousarray(forced[r], np.int32)).to(ctx.device))
         _, _, last_n = ctx.hh_get_lengths()
+        last_n = [last_n[b] for b in rows]
         for b in range(B):
             if active[b]:
                 assert last_n[b] == dec.last_n[b], (r, b, last_n[b], dec.last_n[b])

@@ -1,0 +1,58 @@
+"""Parity at the full sizes of the paper-shaped workloads, in the launch configuration the
+benchmark times (HIP graphs on, default page and chunk sizes).  The oracle runs the sequences it
+can afford (float64 numpy); rows of a batch are independent, so for the batched workload it
+follows the first and the last sequence while the library runs all of them."""
+import time
+
+import numpy as np
+import pytest
+
+from paper_2605_01106_amd import workloads as W
+
+pytestmark = pytest.mark.gpu
+
+from parity_util import run_lockstep  # noqa: E402
+
+
+def _run(name, seed, G, rounds, batch=None, lens=None, rows=None, layers=None, forced_p=None, min_gap=0.0):
+    import torch
+    from paper_2605_01106_amd import binding as B
+    wl = W.WORKLOADS[name]
+    Bn = wl.batch if batch is None else batch
+    lens = [wl.prompt_len] * Bn if lens is None else lens
+    t0 = time.time()
+    wts = W.make_weights(wl.cfg, seed)
+    prompts = W.make_prompts(wl.cfg.vocab, Bn, lens, seed)
+    forced = None if forced_p is None else W.make_forced_pattern(rounds + 2, Bn, wl.k, forced_p, seed)
+    print(f"[{name}] inputs {time.time() - t0:.1f}s", flush=True)
+    stream = torch.cuda.Stream()
+    with torch.cuda.stream(stream):
+        ctx = B.Context(wts, Bn, max(lens) + G + 2 * wl.k + 4, wl.k, G, use_graphs=1)
+        w = run_lockstep(ctx, wts, prompts, lens, G, wl.k, forced=forced, engine="pass", chunk=64,
+                         max_rounds=rounds, check_state_every=max(rounds // 2, 1), oracle_rows=rows, layers=layers,
+                         min_gap=min_gap)
+    stream.synchronize()
+    print(f"[{name}] {time.time() - t0:.1f}s rounds={w['rounds']} mean_n={w['mean_n']:.2f} min_gap={w['min_gap']:.2e} "
+          f"err: logits={w['logits']:.2e} ssm={w['ssm']:.2e} conv={w['conv']:.2e} kv={w['kv']:.2e}", flush=True)
+    return w
+
+
+def test_c1_falcon_h1_0p5b_shape():
+    """36 layers, d_model 1024, vocab 32768, bf16, batch 1, prompt 512, k = 2."""
+    w = _run("c1", seed=0, G=40, rounds=12, layers=[0, 17, 35])
+    assert w["rounds"] == 12
+
+
+def test_c2_batch16_ragged_forced():
+    """Same shape, batch 16, k = 4, ragged prompts around 600 tokens (the oracle cannot afford
+    sixteen 2048-token prefills), forced acceptance pattern p = 0.37; oracle on rows 0 and 15."""
+    lens = [600 - 13 * i for i in range(16)]
+    w = _run("c2f", seed=0, G=24, rounds=6, lens=lens, rows=[0, 15], layers=[0, 35], forced_p=0.37)
+    assert w["rounds"] == 6
+
+
+def test_c3_falcon_h1_3b_shape():
+    """32 layers, d_model 2560, vocab 65536, head_dim 128, d_state 256, bf16, batch 1, k = 4.
+    Prompt 1024 here (the oracle's float64 prefill of 4096 tokens takes minutes)."""
+    w = _run("c3", seed=0, G=16, rounds=4, lens=[1024], layers=[0, 31])
+    assert w["rounds"] == 4

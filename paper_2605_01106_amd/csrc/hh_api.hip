@@ -49,6 +49,7 @@ struct hh_ctx {
   int *kv_len, *committed, *last_n, *pending, *n_acc, *skip, *adv, *drafts, *targets, *tok, *pos0, *out_tok,
       *page_table, *plan_ntok, *plan_last, *first_tok;
   unsigned long long* best;
+  uint16_t* planes;   // split activations of the matrix-core products
   float *rope, *h, *zx, *qkv, *g, *o, *act, *logits_d, *logits_v, *logits_p, *lasth, *part_o, *part_ml, *export_buf;
   int max_passes;
   // host state
@@ -141,6 +142,12 @@ size_t carve(hh_ctx* x, char* base) {
   x->plan_ntok = c.take<int>((size_t)x->max_passes * B);
   x->plan_last = c.take<int>((size_t)x->max_passes * B);
   x->best = c.take<unsigned long long>(Mv * gemv_max_blocks());
+  {
+    int kmax = d.D > d.d_inner ? d.D : d.d_inner;
+    if (d.dq > kmax) kmax = d.dq;
+    if (d.F > kmax) kmax = d.F;
+    x->planes = c.take<uint16_t>(gemm_planes_elems((int)Mmax, kmax));
+  }
   x->rope = c.take<float>((size_t)d.max_seq * d.Dh);
   x->h = c.take<float>(Mmax * d.D);
   x->zx = c.take<float>(Mmax * d.ldzx);
@@ -201,6 +208,14 @@ hh_status fail(hh_ctx* x, hh_status st, const std::string& msg) {
     if (p_) HH_HIP(hipEventRecord(x->prof_ev.back(), s));                                      \
   } while (0)
 
+// One dense projection: the weight-streaming FMA kernel for a few activation rows, the matrix
+// cores beyond that (bf16 weights).
+constexpr int kMfmaMinRows = 9;
+hipError_t product(hh_ctx* x, const GemvArgs& a, hipStream_t s) {
+  if (a.bf16 && a.M >= kMfmaMinRows) return launch_gemm_mfma(a, x->planes, s);
+  return launch_gemv(a, nullptr, s);
+}
+
 // ---- one pass of the block stack over M = B*T rows.  full: M_H (both branches); !full: M_S.
 hh_status run_layers(hh_ctx* x, bool full, int B, int T, const int* n_tok, int state_in, int state_out,
                      int n_splits, hipStream_t s) {
@@ -213,7 +228,7 @@ hh_status run_layers(hh_ctx* x, bool full, int B, int T, const int* n_tok, int s
       a.X = x->h; a.ldx = d.D; a.M = M; a.K = d.D; a.norm_w = w.norm1; a.eps = d.eps; a.epi = EPI_STORE; a.bf16 = d.bf16;
       a.seg[0] = {w.w_inqkv, nullptr, x->zx, full ? d.ldzx : d.d_in_proj, d.ldzx};
       a.n_seg = 1;
-      HH_LAUNCH(HH_K_IN_PROJ, launch_gemv(a, nullptr, s));
+      HH_LAUNCH(HH_K_IN_PROJ, product(x, a, s));
     }
     // The two branches of the block (Eq. 2) only share their input: the attention branch is
     // enqueued on a side stream so that it overlaps the SSM branch, and joins before the sum.
@@ -250,23 +265,23 @@ hh_status run_layers(hh_ctx* x, bool full, int B, int T, const int* n_tok, int s
       GemvArgs a{};
       a.X = x->g; a.ldx = d.d_inner; a.M = M; a.K = d.d_inner; a.norm_w = w.gnorm; a.eps = d.eps; a.epi = EPI_ADD; a.bf16 = d.bf16;
       a.seg[0] = {w.w_out, nullptr, x->h, d.D, d.D}; a.n_seg = 1;
-      HH_LAUNCH(HH_K_OUT_PROJ, launch_gemv(a, nullptr, s));
+      HH_LAUNCH(HH_K_OUT_PROJ, product(x, a, s));
       if (full) {
         GemvArgs b{};
         b.X = x->o; b.ldx = d.dq; b.M = M; b.K = d.dq; b.norm_w = nullptr; b.epi = EPI_ADD; b.bf16 = d.bf16;
         b.seg[0] = {w.w_o, nullptr, x->h, d.D, d.D}; b.n_seg = 1;
-        HH_LAUNCH(HH_K_O_PROJ, launch_gemv(b, nullptr, s));
+        HH_LAUNCH(HH_K_O_PROJ, product(x, b, s));
       }
     }
     {  // SwiGLU MLP
       GemvArgs a{};
       a.X = x->h; a.ldx = d.D; a.M = M; a.K = d.D; a.norm_w = w.norm2; a.eps = d.eps; a.epi = EPI_SWIGLU; a.bf16 = d.bf16;
       a.seg[0] = {w.w_gate, w.w_up, x->act, d.F, d.F}; a.n_seg = 1;
-      HH_LAUNCH(HH_K_MLP_UP, launch_gemv(a, nullptr, s));
+      HH_LAUNCH(HH_K_MLP_UP, product(x, a, s));
       GemvArgs b{};
       b.X = x->act; b.ldx = d.F; b.M = M; b.K = d.F; b.norm_w = nullptr; b.epi = EPI_ADD; b.bf16 = d.bf16;
       b.seg[0] = {w.w_down, nullptr, x->h, d.D, d.D}; b.n_seg = 1;
-      HH_LAUNCH(HH_K_MLP_DOWN, launch_gemv(b, nullptr, s));
+      HH_LAUNCH(HH_K_MLP_DOWN, product(x, b, s));
     }
   }
   return HH_OK;
@@ -280,6 +295,12 @@ hh_status run_head(hh_ctx* x, const float* X, int M, int T, float* logits, int l
   a.X = X; a.ldx = d.D; a.M = M; a.K = d.D; a.norm_w = static_cast<const float*>(x->final_norm); a.eps = d.eps;
   a.epi = EPI_STORE; a.bf16 = d.bf16; a.best = x->best;
   a.seg[0] = {x->lm_head, nullptr, logits, d.V, ld_logits}; a.n_seg = 1;
+  if (a.bf16 && M >= kMfmaMinRows) {
+    a.best = nullptr;
+    HH_LAUNCH(HH_K_LM_HEAD, launch_gemm_mfma(a, x->planes, s));
+    HH_HIP(launch_argmax_rows(logits, ld_logits, d.V, M, out, out_stride, out_off, T, s));
+    return HH_OK;
+  }
   int nblk = 0;
   HH_LAUNCH(HH_K_LM_HEAD, launch_gemv(a, &nblk, s));
   HH_HIP(launch_argmax_finish(x->best, nblk, M, out, out_stride, out_off, T, s));

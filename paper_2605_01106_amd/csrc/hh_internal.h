@@ -52,6 +52,12 @@ struct GemvArgs {
 hipError_t launch_gemv(const GemvArgs& a, int* n_blocks_out, hipStream_t s);
 int gemv_max_blocks();   // upper bound on gridDim.x of launch_gemv (size of the argmax partial rows)
 
+// ---- the same product on the matrix cores (bf16 weights, more than a few activation rows)
+size_t gemm_planes_elems(int M, int K);   // bf16 elements of scratch for the split activations
+hipError_t launch_gemm_mfma(const GemvArgs& a, uint16_t* planes, hipStream_t s);
+hipError_t launch_argmax_rows(const float* logits, int ld, int V, int M, int* out, int out_stride, int out_off, int T,
+                              hipStream_t s);
+
 // ---- SSM branch: causal conv + selective scan over up to T positions per sequence
 struct SsmArgs {
   const LayerDev* layers; int layer0; int n_layers_z;  // blockIdx.z = (layer - layer0) * B + b

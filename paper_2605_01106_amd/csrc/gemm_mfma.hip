@@ -7,9 +7,9 @@
 // is the sum of three bf16 MFMA products accumulated in float32.  While the pass is bound by
 // streaming the weights the two extra MFMAs per weight fragment are free.
 //
-// GEMM kernel: a wavefront owns a strip of 32 output columns (16 gate + 16 up columns for
-// SwiGLU) and up to 128 activation rows.  Per step of 32 columns of K it loads its two weight
-// fragments straight from global memory into registers (v_mfma_f32_16x16x32_bf16 B operand:
+// GEMM kernel: a workgroup owns a strip of 16 output columns (16 gate + 16 up columns for
+// SwiGLU) and up to 128 activation rows; its wavefronts split K.  Per step of 32 columns of K a
+// wavefront loads its weight fragment straight from global memory into registers (v_mfma_f32_16x16x32_bf16 B operand:
 // lane l holds W[n0 + l%16][k0 + 8*(l/16) .. +7], one 16-byte load) and reuses them for every
 // 16-row tile and every split term of the activations (A operand: lane l holds
 // A[m0 + l%16][k0 + 8*(l/16) .. +7], read from the split planes through L1/L2).  No LDS.
@@ -68,72 +68,101 @@ struct GemmArgs {
   const uint16_t* W; const uint16_t* W2;  // [N][K] bf16 (W2: the "up" matrix for SwiGLU)
   float* Y; int ldy;
   int M, N, K, m0, mt;                    // rows m0 .. m0 + 16*mt of the planes in this launch
+  int ksteps;                             // steps of 32 columns per wavefront (K split over the workgroup)
 };
 
+static constexpr int kGroupK = 2;   // weight fragments loaded ahead, in steps of 32 columns
+
+// One workgroup per strip of 16 output columns; its KS wavefronts split K between them and add
+// their partial tiles through LDS.  Small per-wavefront work, many wavefronts: the weights of a
+// wavefront's K slice are requested up to 8 steps ahead.
 template <int EPI>
-__global__ __launch_bounds__(256) void gemm_mfma_kernel(const GemmArgs a) {
-  constexpr int NCOL = EPI == EPI_SWIGLU ? 16 : 32;
+__global__ __launch_bounds__(512) void gemm_mfma_kernel(const GemmArgs a) {
+  constexpr int NF = EPI == EPI_SWIGLU ? 2 : 1;
+  extern __shared__ __align__(16) float red[];   // [KS][mt][NF][64][4]
   const int lane = threadIdx.x & 63;
-  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int ks = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int KS = blockDim.x >> 6;
   const int i = lane & 15, g = lane >> 4;
-  const int n0 = (blockIdx.x * 4 + wave) * NCOL;
-  if (n0 >= a.N) return;
-  const uint16_t* wrow[2];
-  if (EPI == EPI_SWIGLU) {
-    const size_t r = (size_t)min(n0 + i, a.N - 1) * a.K;
-    wrow[0] = a.W + r; wrow[1] = a.W2 + r;
-  } else {
-    wrow[0] = a.W + (size_t)min(n0 + i, a.N - 1) * a.K;
-    wrow[1] = a.W + (size_t)min(n0 + 16 + i, a.N - 1) * a.K;
-  }
+  const int n0 = blockIdx.x * 16;
+  const size_t wr = (size_t)min(n0 + i, a.N - 1) * a.K;
+  const uint16_t* wrow[2] = {a.W + wr, EPI == EPI_SWIGLU ? a.W2 + wr : a.W + wr};
   const size_t plane = (size_t)a.Mp * a.Kp;
   const uint16_t* arow = a.planes + (size_t)(a.m0 + i) * a.Kp + g * 8;
+  const int kbeg = ks * a.ksteps * 32, kend = min(a.Kp, kbeg + a.ksteps * 32);
 
-  f32x4 acc[kTiles][2];
+  f32x4 acc[kTiles][NF];
 #pragma unroll
-  for (int t = 0; t < kTiles; ++t) { acc[t][0] = f32x4{0.f, 0.f, 0.f, 0.f}; acc[t][1] = acc[t][0]; }
+  for (int t = 0; t < kTiles; ++t)
+#pragma unroll
+    for (int f = 0; f < NF; ++f) acc[t][f] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-#pragma unroll 2
-  for (int k0 = 0; k0 < a.Kp; k0 += 32) {
-    const int kb = min(k0 + g * 8, a.K - 8);   // columns past K meet zero activations
-    const bf16x8 b0 = *reinterpret_cast<const bf16x8*>(wrow[0] + kb);
-    const bf16x8 b1 = *reinterpret_cast<const bf16x8*>(wrow[1] + kb);
+  for (int kg = kbeg; kg < kend; kg += 32 * kGroupK) {
+    bf16x8 bw[kGroupK][NF];
 #pragma unroll
-    for (int t = 0; t < kTiles; ++t) {
-      if (t < a.mt) {
-        const uint16_t* ap = arow + (size_t)t * 16 * a.Kp + k0;
+    for (int u = 0; u < kGroupK; ++u) {
+      const int kb = min(kg + u * 32 + g * 8, a.K - 8);   // past K: clamped, meets zero activations
 #pragma unroll
-        for (int term = 0; term < 3; ++term) {
-          const bf16x8 av = *reinterpret_cast<const bf16x8*>(ap + term * plane);
-          acc[t][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, b0, acc[t][0], 0, 0, 0);
-          acc[t][1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, b1, acc[t][1], 0, 0, 0);
+      for (int f = 0; f < NF; ++f) bw[u][f] = *reinterpret_cast<const bf16x8*>(wrow[f] + kb);
+    }
+#pragma unroll
+    for (int u = 0; u < kGroupK; ++u) {
+      const int k0 = kg + u * 32;
+      if (k0 < kend) {
+#pragma unroll
+        for (int t = 0; t < kTiles; ++t) {
+          if (t < a.mt) {
+            const uint16_t* ap = arow + (size_t)t * 16 * a.Kp + k0;
+#pragma unroll
+            for (int term = 0; term < 3; ++term) {
+              const bf16x8 av = *reinterpret_cast<const bf16x8*>(ap + term * plane);
+#pragma unroll
+              for (int f = 0; f < NF; ++f)
+                acc[t][f] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, bw[u][f], acc[t][f], 0, 0, 0);
+            }
+          }
         }
       }
+      // keep the activation loads of later steps from being hoisted above this step's MFMAs
+      // (hoisting all of them exhausts the register file)
+      __builtin_amdgcn_sched_barrier(0);
     }
   }
 
+  // ---- add the partial tiles of the KS wavefronts; wavefront ks finishes tiles ks, ks+KS, ...
+  if (KS > 1) {
+#pragma unroll
+    for (int t = 0; t < kTiles; ++t)
+      if (t < a.mt)
+#pragma unroll
+        for (int f = 0; f < NF; ++f)
+          *reinterpret_cast<f32x4*>(&red[((((size_t)ks * a.mt + t) * NF + f) * 64 + lane) * 4]) = acc[t][f];
+    __syncthreads();
+  }
 #pragma unroll
   for (int t = 0; t < kTiles; ++t) {
-    if (t < a.mt) {
+    if (t < a.mt && (KS == 1 || t % KS == ks)) {
+      f32x4 sum[NF];
+#pragma unroll
+      for (int f = 0; f < NF; ++f) {
+        if (KS == 1) sum[f] = acc[t][f];
+        else {
+          sum[f] = f32x4{0.f, 0.f, 0.f, 0.f};
+          for (int j = 0; j < KS; ++j)
+            sum[f] += *reinterpret_cast<const f32x4*>(&red[((((size_t)j * a.mt + t) * NF + f) * 64 + lane) * 4]);
+        }
+      }
+      const int n = n0 + i;
 #pragma unroll
       for (int r = 0; r < 4; ++r) {
         const int m = a.m0 + t * 16 + g * 4 + r;
-        if (m < a.M) {
+        if (m < a.M && n < a.N) {
+          float* y = a.Y + (size_t)m * a.ldy + n;
           if (EPI == EPI_SWIGLU) {
-            const int n = n0 + i;
-            if (n < a.N) {
-              const float gt = acc[t][0][r], up = acc[t][1][r];
-              a.Y[(size_t)m * a.ldy + n] = gt / (1.0f + expf(-gt)) * up;
-            }
+            const float gt = sum[0][r], up = sum[NF - 1][r];
+            *y = gt / (1.0f + expf(-gt)) * up;
           } else {
-#pragma unroll
-            for (int f = 0; f < 2; ++f) {
-              const int n = n0 + f * 16 + i;
-              if (n < a.N) {
-                float* y = a.Y + (size_t)m * a.ldy + n;
-                *y = EPI == EPI_ADD ? *y + acc[t][f][r] : acc[t][f][r];
-              }
-            }
+            *y = EPI == EPI_ADD ? *y + sum[0][r] : sum[0][r];
           }
         }
       }
@@ -159,17 +188,35 @@ hipError_t launch_gemm_mfma(const GemvArgs& g, uint16_t* planes, hipStream_t s) 
   a.planes = planes; a.Mp = Mp; a.Kp = Kp;
   a.W = static_cast<const uint16_t*>(g.seg[0].W); a.W2 = static_cast<const uint16_t*>(g.seg[0].W2);
   a.Y = g.seg[0].Y; a.ldy = g.seg[0].ldy; a.M = M; a.N = N; a.K = K;
-  const int ncol = g.epi == EPI_SWIGLU ? 16 : 32;
-  const int blocks = ((N + ncol - 1) / ncol + 3) / 4;
+  const int strips = (N + 15) / 16, nf = g.epi == EPI_SWIGLU ? 2 : 1, steps = Kp / 32;
   for (int m0 = 0; m0 < Mp; m0 += 16 * kTiles) {
     a.m0 = m0;
     a.mt = (Mp - m0) / 16 < kTiles ? (Mp - m0) / 16 : kTiles;
+    // K split: enough wavefronts to cover the chip, bounded by the steps available and by the
+    // LDS the partial tiles need (1 KB per wavefront, tile and fragment)
+    int KS = 1;
+    while (KS < 8 && strips * KS < 1024 && steps / (KS * 2) >= 2 && (size_t)KS * 2 * a.mt * nf * 1024 <= 96 * 1024) KS *= 2;
+    a.ksteps = (steps + KS - 1) / KS;
+    const size_t lds = KS > 1 ? (size_t)KS * a.mt * nf * 1024 : 0;
+#define HH_GEMM_LAUNCH(E)                                                                              \
+    {                                                                                                  \
+      auto kern = gemm_mfma_kernel<E>;                                                                 \
+      static size_t lds_enabled = 48 * 1024;                                                           \
+      if (lds > lds_enabled) {                                                                         \
+        e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),                                   \
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);                 \
+        if (e != hipSuccess) return e;                                                                 \
+        lds_enabled = lds;                                                                             \
+      }                                                                                                \
+      hipLaunchKernelGGL(kern, dim3(strips), dim3(64 * KS), lds, s, a);                                \
+    }
     switch (g.epi) {
-      case EPI_STORE: hipLaunchKernelGGL(gemm_mfma_kernel<EPI_STORE>, dim3(blocks), dim3(256), 0, s, a); break;
-      case EPI_ADD: hipLaunchKernelGGL(gemm_mfma_kernel<EPI_ADD>, dim3(blocks), dim3(256), 0, s, a); break;
-      case EPI_SWIGLU: hipLaunchKernelGGL(gemm_mfma_kernel<EPI_SWIGLU>, dim3(blocks), dim3(256), 0, s, a); break;
+      case EPI_STORE: HH_GEMM_LAUNCH(EPI_STORE) break;
+      case EPI_ADD: HH_GEMM_LAUNCH(EPI_ADD) break;
+      case EPI_SWIGLU: HH_GEMM_LAUNCH(EPI_SWIGLU) break;
       default: return hipErrorInvalidValue;
     }
+#undef HH_GEMM_LAUNCH
     e = hipGetLastError();
     if (e != hipSuccess) return e;
   }

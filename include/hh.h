@@ -179,6 +179,15 @@ HH_API hh_status hh_profile(hh_ctx* ctx, int32_t enable);
  * receive the number of timed launches and their summed duration. */
 HH_API hh_status hh_profile_read(hh_ctx* ctx, int32_t n_tags, int32_t* launches, float* total_ms, void* stream);
 
+/* Launch duration of one kind of kernel in its place: enqueues `reps` draft (phase HH_PHASE_DRAFT)
+ * or verification (HH_PHASE_VERIFY, k+1 positions) passes in which ONLY kernels of `kind` are
+ * launched (so consecutive launches read different layers' weights, as in a real pass), between
+ * one HIP event pair on `stream`; synchronises.  *total_ms / *launches is the average duration
+ * including the launch gap.  Valid between rounds; activations and draft scratch are left
+ * undefined, committed state is untouched.  HOST outputs. */
+HH_API hh_status hh_time_kind(hh_ctx* ctx, int32_t phase, int32_t kind, int32_t k, int32_t reps, float* total_ms,
+                              int32_t* launches, void* stream);
+
 /* Human-readable description of the last error on this context (or of the last
  * failed hh_create when ctx is NULL).  Never NULL. */
 HH_API const char* hh_last_error(const hh_ctx* ctx);

@@ -76,6 +76,7 @@ EXPORTS = {
     "hh_get_kv": (C.c_int, [_ctx_p, C.c_int32, C.c_int32, C.c_int32, _f32p, _f32p, C.c_void_p]),
     "hh_profile": (C.c_int, [_ctx_p, C.c_int32]),
     "hh_profile_read": (C.c_int, [_ctx_p, C.c_int32, _i32p, _f32p, C.c_void_p]),
+    "hh_time_kind": (C.c_int, [_ctx_p, C.c_int32, C.c_int32, C.c_int32, C.c_int32, _f32p, _i32p, C.c_void_p]),
     "hh_last_error": (C.c_char_p, [_ctx_p]),
 }
 for _name, (_res, _args) in EXPORTS.items():
@@ -256,6 +257,12 @@ class Context:
         cnt, ms = (C.c_int32 * n)(), (C.c_float * n)()
         _check(lib.hh_profile_read(self.ctx, n, cnt, ms, _stream_ptr(stream)), self.ctx)
         return {(t // 16, t % 16): (cnt[t], ms[t]) for t in range(n) if cnt[t]}
+
+    def hh_time_kind(self, phase: int, kind: int, k: int, reps: int, stream=None):
+        """(average microseconds per launch, launches) of one kind of kernel, launched alone."""
+        ms, n = C.c_float(0), C.c_int32(0)
+        _check(lib.hh_time_kind(self.ctx, phase, kind, k, reps, C.byref(ms), C.byref(n), _stream_ptr(stream)), self.ctx)
+        return ms.value * 1e3 / max(n.value, 1), n.value
 
     def hh_get_kv(self, layer: int, seq: int, n_tokens: int, stream=None):
         c = self.model_cfg

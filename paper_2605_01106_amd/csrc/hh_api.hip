@@ -60,6 +60,7 @@ struct hh_ctx {
   std::string err;
   // optional per-launch timing (hh_profile): event pairs tagged phase*16 + kind
   bool prof_on = false;
+  int only_kind = -1;   // hh_time_kind: launch only this kind of kernel
   int prof_phase = 0;
   std::vector<hipEvent_t> prof_ev;
   std::vector<int> prof_tag;
@@ -196,6 +197,7 @@ hh_status fail(hh_ctx* x, hh_status st, const std::string& msg) {
 // Launch `call`, bracketed by an event pair when profiling is on.
 #define HH_LAUNCH(kind, call)                                                                  \
   do {                                                                                         \
+    if (x->only_kind >= 0 && x->only_kind != (kind)) break;                                    \
     const bool p_ = x->prof_on && x->prof_ev.size() < kProfCap * 2;                            \
     if (p_) {                                                                                  \
       hipEvent_t a_, b_;                                                                       \
@@ -716,6 +718,61 @@ hh_status hh_get_kv(hh_ctx* x, int32_t layer, int32_t seq, int32_t n_tokens, flo
     HH_HIP(hipMemcpy(k + (size_t)t0 * per_tok, kb, (size_t)nt * per_tok * 4, hipMemcpyDeviceToHost));
     HH_HIP(hipMemcpy(v + (size_t)t0 * per_tok, vb, (size_t)nt * per_tok * 4, hipMemcpyDeviceToHost));
   }
+  return HH_OK;
+}
+
+hh_status hh_time_kind(hh_ctx* x, int32_t phase, int32_t kind, int32_t k, int32_t reps, float* total_ms,
+                       int32_t* launches, void* stream) {
+  if (!x) return HH_EINVAL;
+  if (x->phase != PH_READY) return fail(x, HH_ESTATE, "hh_time_kind: needs a prefilled context with no round in flight");
+  const Dims& d = x->d;
+  if ((phase != HH_PHASE_DRAFT && phase != HH_PHASE_VERIFY) || kind < 0 || kind > HH_K_LM_HEAD || reps < 1 ||
+      k < 0 || k > d.Kmax || !total_ms || !launches)
+    return fail(x, HH_EINVAL, "hh_time_kind: bad argument");
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  const bool full = phase == HH_PHASE_VERIFY;
+  const int B = x->B, T = full ? k + 1 : 1;
+  hipEvent_t e0, e1;
+  HH_HIP(hipEventCreate(&e0));
+  HH_HIP(hipEventCreate(&e1));
+  // positions and tokens of an ordinary pass, so that every kernel sees valid inputs
+  HH_HIP(launch_gather_tokens(x->pending, x->drafts, d.Kmax, B, T, full ? 1 : 0, 0, x->tok, x->kv_len, x->pos0, s));
+  HH_HIP(launch_embed(d, x->embed, x->tok, B * T, x->h, s));
+  const bool prof = x->prof_on;
+  x->prof_on = true;            // serial launches on one stream (no side stream), but no event pairs:
+  const size_t cap = x->prof_ev.size();
+  x->only_kind = kind;
+  hh_status st = HH_OK;
+  int n = 0;
+  {
+    // suppress the per-launch events by pretending the record is full
+    std::vector<hipEvent_t> saved;
+    saved.swap(x->prof_ev);
+    x->prof_ev.resize(kProfCap * 2, nullptr);
+    HH_HIP(hipEventRecord(e0, s));
+    for (int r = 0; r < reps && st == HH_OK; ++r) {
+      if (kind == HH_K_LM_HEAD) {
+        st = run_head(x, x->h, B * T, T, full ? x->logits_v : x->logits_d, full ? d.V : d.Kmax * d.V,
+                      full ? x->targets : x->drafts, full ? d.Kmax + 1 : d.Kmax, 0, s);
+        n += 1;
+      } else {
+        st = run_layers(x, full, B, T, nullptr, 0, full ? 0 : 2, pick_splits(d, B, T, x->len_upper), s);
+        n += d.L;
+      }
+    }
+    hipError_t er = hipEventRecord(e1, s);
+    x->prof_ev.swap(saved);
+    (void)cap;
+    x->only_kind = -1;
+    x->prof_on = prof;
+    if (st != HH_OK) return st;
+    HH_HIP(er);
+  }
+  HH_HIP(hipEventSynchronize(e1));
+  HH_HIP(hipEventElapsedTime(total_ms, e0, e1));
+  (void)hipEventDestroy(e0);
+  (void)hipEventDestroy(e1);
+  *launches = n;
   return HH_OK;
 }
 

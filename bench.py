@@ -47,8 +47,7 @@ def algorithmic_bytes(cfg, B, k, kv_len):
         (1, 8): V * D * esz,
         (2, 0): (cfg.d_in_proj + cfg.d_q + 2 * cfg.d_kv) * D * esz,
         (2, 1): B * (state + (3 + 2 * T) * conv),
-        (2, 2): B * T * kv_tok,
-        (2, 3): B * (kv_len + T) * kv_tok,
+        (2, 3): B * (kv_len + 2 * T) * kv_tok,
         (2, 4): D * cfg.d_inner * esz,
         (2, 5): D * cfg.d_q * esz,
         (2, 6): 2 * F * D * esz,
@@ -57,7 +56,7 @@ def algorithmic_bytes(cfg, B, k, kv_len):
         (3, 1): L * B * (2 * state + (3 + T) * conv),
     }
     draft_step = sum(per_kind[(1, i)] for i in (0, 1, 4, 6, 7)) * L + per_kind[(1, 8)]
-    verify = sum(per_kind[(2, i)] for i in (0, 1, 2, 3, 4, 5, 6, 7)) * L + per_kind[(2, 8)]
+    verify = sum(per_kind[(2, i)] for i in (0, 1, 3, 4, 5, 6, 7)) * L + per_kind[(2, 8)]
     commit = per_kind[(3, 1)]
     return per_kind, draft_step, verify, commit
 
@@ -190,7 +189,7 @@ def main():
     per_round = {1: k, 2: 1}
     for ph in (1, 2):
         for kind in sorted(KIND_NAMES):
-            if ph == 1 and kind in (2, 3, 5):
+            if kind == 2 or (ph == 1 and kind in (3, 5)):   # RoPE/append is fused into attention
                 continue
             avg_us, n = ctx.hh_time_kind(ph, kind, k, 4)
             by = per_kind.get((ph, kind))

@@ -172,7 +172,7 @@ HH_API hh_status hh_get_kv(hh_ctx* ctx, int32_t layer, int32_t seq, int32_t n_to
  * While enabled, every kernel launch of prefill/draft/verify/commit is bracketed by a HIP event
  * pair on the call's stream, tagged  phase * 16 + kind.  Enabling clears earlier records. */
 enum { HH_PHASE_PREFILL = 0, HH_PHASE_DRAFT = 1, HH_PHASE_VERIFY = 2, HH_PHASE_COMMIT = 3 };
-enum { HH_K_IN_PROJ = 0, HH_K_SSM = 1, HH_K_ROPE = 2, HH_K_ATTN = 3, HH_K_OUT_PROJ = 4, HH_K_O_PROJ = 5,
+enum { HH_K_IN_PROJ = 0, HH_K_SSM = 1, HH_K_RESERVED = 2, HH_K_ATTN = 3, HH_K_OUT_PROJ = 4, HH_K_O_PROJ = 5,
        HH_K_MLP_UP = 6, HH_K_MLP_DOWN = 7, HH_K_LM_HEAD = 8 };
 HH_API hh_status hh_profile(hh_ctx* ctx, int32_t enable);
 /* Synchronises `stream`; launches[tag] and total_ms[tag] (HOST, n_tags entries, tag as above)

@@ -49,6 +49,7 @@ struct hh_ctx {
   int *kv_len, *committed, *last_n, *pending, *n_acc, *skip, *adv, *drafts, *targets, *tok, *pos0, *out_tok,
       *page_table, *plan_ntok, *plan_last, *first_tok;
   unsigned long long* best;
+  int* attn_counters;   // tickets of the attention key slices (zero between launches)
   uint16_t* planes;   // split activations of the matrix-core products
   float *rope, *h, *zx, *qkv, *g, *o, *act, *logits_d, *logits_v, *logits_p, *lasth, *part_o, *part_ml, *export_buf;
   int max_passes;
@@ -143,6 +144,7 @@ size_t carve(hh_ctx* x, char* base) {
   x->plan_ntok = c.take<int>((size_t)x->max_passes * B);
   x->plan_last = c.take<int>((size_t)x->max_passes * B);
   x->best = c.take<unsigned long long>(Mv * gemv_max_blocks());
+  x->attn_counters = c.take<int>(B * d.Hkv * attention_row_chunks(d, d.Tmax));
   {
     int kmax = d.D > d.d_inner ? d.D : d.d_inner;
     if (d.dq > kmax) kmax = d.dq;
@@ -245,13 +247,12 @@ hh_status run_layers(hh_ctx* x, bool full, int B, int T, const int* n_tok, int s
       AttnArgs a{};
       a.kpool = w.kpool; a.vpool = w.vpool; a.qkv = x->qkv; a.o = x->o; a.pos0 = x->pos0; a.n_tok = n_tok;
       a.page_table = x->page_table; a.rope = x->rope; a.part_o = x->part_o; a.part_ml = x->part_ml;
+      a.counters = x->attn_counters;
       a.T = T; a.B = B; a.n_splits = n_splits;
       if (overlap) {
-        HH_HIP(launch_rope_append(d, a, sa));
         HH_HIP(launch_attention(d, a, sa));
         HH_HIP(hipEventRecord(x->join_ev[l], sa));
       } else {
-        HH_LAUNCH(HH_K_ROPE, launch_rope_append(d, a, s));
         HH_LAUNCH(HH_K_ATTN, launch_attention(d, a, s));
       }
     }
@@ -422,6 +423,8 @@ hh_status hh_create(const hh_weights* weights, const hh_cfg* cfg, hh_ctx** out) 
   };
   hipError_t e = hipMemcpy(ctx->layers_dev, ctx->layers_host.data(), sizeof(LayerDev) * d.L, hipMemcpyHostToDevice);
   if (e != hipSuccess) return bail(e, "hh_create: upload of layer table");
+  e = hipMemset(ctx->attn_counters, 0, sizeof(int) * (size_t)d.Bmax * d.Hkv * attention_row_chunks(d, d.Tmax));
+  if (e != hipSuccess) return bail(e, "hh_create: clearing the attention tickets");
   // rotary table: angle pos * base^(-2i/Dh) evaluated in double, stored as float (cos, sin)
   {
     const int half = d.Dh / 2;

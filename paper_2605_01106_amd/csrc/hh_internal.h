@@ -77,14 +77,15 @@ hipError_t launch_ssm(const Dims& d, const SsmArgs& a, hipStream_t s);
 // ---- attention branch
 struct AttnArgs {
   void* kpool; void* vpool;  // this layer's K and V pages
-  float* qkv;             // [B*T][ldzx] (offset to the q column): q | k | v, rotated in place by rope_append
+  const float* qkv;       // [B*T][ldzx] (offset to the q column): raw q | k | v of this pass
   float* o;               // [B*T][dq]
   const int* pos0; const int* n_tok; const int* page_table;  // [B], [B], [B][pages_per_seq]
   const float* rope;      // [max_seq][Dh/2][2] (cos, sin)
   float* part_o; float* part_ml;  // split scratch: [B*T*Hq][S][Dh], [B*T*Hq][S][2]
+  int* counters;          // [B][Hkv][row chunks], zero between launches: tickets of the key slices
   int T, B, n_splits;
 };
-hipError_t launch_rope_append(const Dims& d, const AttnArgs& a, hipStream_t s);
+int attention_row_chunks(const Dims& d, int T);
 hipError_t launch_attention(const Dims& d, const AttnArgs& a, hipStream_t s);
 
 // ---- small kernels

@@ -1,11 +1,12 @@
-// Attention branch of the hybrid block for multi-position passes (verification, prefill), one
-// kernel per layer: rotary embedding of q and k, append of k and v to the paged KV cache
+// Attention branch of the hybrid block for multi-position passes (verification, prefill):
+// the float32-FMA kernel (float32 KV cache; any head dimension that is a multiple of 8), the
+// append of new keys and values to the paged cache, and the dispatch between this kernel and
+// the matrix-core kernel used for a bf16 cache.
+//
+// One kernel per layer: rotary embedding of q and k, append of k and v to the paged KV cache
 // (rounded to the storage type), causal grouped-query attention of the T new positions over
 // all keys up to each position, split along the keys, and the log-sum-exp merge of the key
 // slices in slice order.
-//
-// Cache layout per layer: pages [page][kv_head][token_in_page][Dh]; page_table[b][i] is the
-// page holding tokens i*page_tokens .. of sequence b.
 //
 // A workgroup owns 16 query rows (row = position j x query head of one KV group) and one
 // slice of the keys.  K and V tiles of 64 keys are staged through LDS in float32: cached keys
@@ -14,32 +15,16 @@
 // Lane t scores key t for the wavefront's 4 rows, the softmax is kept online per row, lane d
 // accumulates output dimension d.  With several key slices every workgroup stores its partial
 // result; the last one to finish (a counter per row chunk) merges them, so no second launch.
-#include "hh_internal.h"
+#include <stdlib.h>
+
+#include "attn_common.h"
 
 namespace hh {
-
-#ifdef HH_ATTN_TRACE
-__device__ long long g_attn_trace[4096 * 16];
-#define TR(i) do { if (threadIdx.x == 0) g_attn_trace[((blockIdx.z * gridDim.y + blockIdx.y) * gridDim.x + blockIdx.x) * 16 + (i)] = wall_clock64(); } while (0)
-#else
-#define TR(i)
-#endif
 
 static constexpr int kKeys = 64;      // keys per LDS tile
 static constexpr int kRowsPerWave = 4;
 static constexpr int kRowsPerBlock = 16;
 static constexpr int kMaxDh = 256;
-
-__device__ __forceinline__ uint16_t f32_to_bf16_rne(float f) {
-  uint32_t u = __float_as_uint(f);
-  u += 0x7FFFu + ((u >> 16) & 1u);
-  return (uint16_t)(u >> 16);
-}
-
-__device__ __forceinline__ size_t kv_index(const Dims& d, const int* pt_row, int kvh, int pos) {
-  const int page = pt_row[pos / d.page_tokens], off = pos % d.page_tokens;
-  return (((size_t)page * d.Hkv + kvh) * d.page_tokens + off) * d.Dh;
-}
 
 // Reductions over the 64 lanes without LDS traffic: DPP butterflies inside each row of 16
 // lanes, then the four row results are read out and combined.  All lanes must be active.
@@ -126,8 +111,10 @@ __global__ __launch_bounds__(256) void attention_kernel(const Dims d, const Attn
   const int cpk = Dh / EPI;                 // items per key
   const int n_items = kKeys * cpk;
 
-  // ---- cached keys of a tile: pages -> registers -> LDS as float32
+  // ---- cached keys of a tile: pages -> registers -> LDS as float32.  A K item is 16 bytes of
+  // one key row; a V item is 16 bytes of one dimension (consecutive tokens of a page).
   uint4 kreg[NI], vreg[NI];
+  constexpr int TPI = EPI;                   // tokens per V item
   auto load_tile = [&](int t) {
     const int key0 = t * kKeys;
     const int n_old = min(max(pos0 - key0, 0), kKeys);          // keys of this tile already in the cache
@@ -135,11 +122,9 @@ __global__ __launch_bounds__(256) void attention_kernel(const Dims d, const Attn
     for (int i = 0; i < NI; ++i) {
       const int it = tid + 256 * i;
       const int kk = it / cpk, c = (it - kk * cpk) * EPI;
-      if (kk < n_old) {
-        const size_t at = (kv_index(d, pt_row, kvh, key0 + kk) + c) * esz;
-        kreg[i] = *reinterpret_cast<const uint4*>(kbytes + at);
-        vreg[i] = *reinterpret_cast<const uint4*>(vbytes + at);
-      }
+      if (kk < n_old) kreg[i] = *reinterpret_cast<const uint4*>(kbytes + (k_index(d, pt_row, kvh, key0 + kk) + c) * esz);
+      const int grp = it / Dh, dd = it - grp * Dh;
+      if (grp * TPI < n_old) vreg[i] = *reinterpret_cast<const uint4*>(vbytes + v_index(d, pt_row, kvh, key0 + grp * TPI, dd) * esz);
     }
   };
   auto store_tile = [&](int t) {
@@ -148,25 +133,29 @@ __global__ __launch_bounds__(256) void attention_kernel(const Dims d, const Attn
 #pragma unroll
     for (int i = 0; i < NI; ++i) {
       const int it = tid + 256 * i;
-      const int kk = it / cpk, c = (it - kk * cpk) * EPI;
       if (it >= n_items) continue;
+      const int kk = it / cpk, c = (it - kk * cpk) * EPI;
       float* kd = Ks + kk * ldk + c;
-      float* vd = Vs + kk * Dh + c;
       if (kk < n_old) {
         const uint32_t kw[4] = {kreg[i].x, kreg[i].y, kreg[i].z, kreg[i].w};
-        const uint32_t vw[4] = {vreg[i].x, vreg[i].y, vreg[i].z, vreg[i].w};
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
-          if (BF16) {
-            kd[2 * e] = __uint_as_float(kw[e] << 16); kd[2 * e + 1] = __uint_as_float(kw[e] & 0xffff0000u);
-            vd[2 * e] = __uint_as_float(vw[e] << 16); vd[2 * e + 1] = __uint_as_float(vw[e] & 0xffff0000u);
-          } else {
-            kd[e] = __uint_as_float(kw[e]); vd[e] = __uint_as_float(vw[e]);
-          }
+          if (BF16) { kd[2 * e] = __uint_as_float(kw[e] << 16); kd[2 * e + 1] = __uint_as_float(kw[e] & 0xffff0000u); }
+          else kd[e] = __uint_as_float(kw[e]);
         }
-      } else if (key0 + kk >= nk) {           // past the last key: zeros (the new keys are staged below)
+      } else if (key0 + kk >= nk) {           // past the last key: zeros (the new keys are staged separately)
 #pragma unroll
-        for (int e = 0; e < EPI; ++e) { kd[e] = 0.f; vd[e] = 0.f; }
+        for (int e = 0; e < EPI; ++e) kd[e] = 0.f;
+      }
+      const int grp = it / Dh, dd = it - grp * Dh;
+      const uint32_t vw[4] = {vreg[i].x, vreg[i].y, vreg[i].z, vreg[i].w};
+#pragma unroll
+      for (int e = 0; e < TPI; ++e) {
+        const int vk = grp * TPI + e;
+        float val = 0.f;
+        if (vk < n_old) val = BF16 ? ((e & 1) ? __uint_as_float(vw[e >> 1] & 0xffff0000u) : __uint_as_float(vw[e >> 1] << 16))
+                                   : __uint_as_float(vw[e & 3]);
+        if (vk < n_old || key0 + vk >= nk) Vs[vk * Dh + dd] = val;
       }
     }
   };
@@ -196,16 +185,17 @@ __global__ __launch_bounds__(256) void attention_kernel(const Dims d, const Attn
     Ks[kk * ldk + i] = klo; Ks[kk * ldk + i + half] = khi;
     Vs[kk * Dh + i] = vlo; Vs[kk * Dh + i + half] = vhi;
     if (chunk == (j * G) / kRowsPerBlock) {   // the one row chunk that owns position j writes it
-      const size_t at = kv_index(d, pt_row, kvh, pos0 + j);
+      const size_t at = k_index(d, pt_row, kvh, pos0 + j);
+      const size_t v0 = v_index(d, pt_row, kvh, pos0 + j, i), v1 = v_index(d, pt_row, kvh, pos0 + j, i + half);
       if (BF16) {
         uint16_t* kp = static_cast<uint16_t*>(a.kpool) + at;
-        uint16_t* vp = static_cast<uint16_t*>(a.vpool) + at;
+        uint16_t* vp = static_cast<uint16_t*>(a.vpool);
         kp[i] = (uint16_t)(__float_as_uint(klo) >> 16); kp[i + half] = (uint16_t)(__float_as_uint(khi) >> 16);
-        vp[i] = (uint16_t)(__float_as_uint(vlo) >> 16); vp[i + half] = (uint16_t)(__float_as_uint(vhi) >> 16);
+        vp[v0] = (uint16_t)(__float_as_uint(vlo) >> 16); vp[v1] = (uint16_t)(__float_as_uint(vhi) >> 16);
       } else {
         float* kp = static_cast<float*>(a.kpool) + at;
-        float* vp = static_cast<float*>(a.vpool) + at;
-        kp[i] = klo; kp[i + half] = khi; vp[i] = vlo; vp[i + half] = vhi;
+        float* vp = static_cast<float*>(a.vpool);
+        kp[i] = klo; kp[i + half] = khi; vp[v0] = vlo; vp[v1] = vhi;
       }
     }
   };
@@ -439,8 +429,54 @@ static hipError_t launch_attention_t(const Dims& d, const AttnArgs& a, int row_c
   return hipGetLastError();
 }
 
+// Keys and values of the new positions: rotate k, round to the storage type, write to the pages.
+// grid: one workgroup per (sequence, new position).
+__global__ __launch_bounds__(256) void kv_append_kernel(const Dims d, const AttnArgs a) {
+  const int m = blockIdx.x, b = m / a.T, j = m - b * a.T;
+  const int nt = a.n_tok != nullptr ? a.n_tok[b] : a.T;
+  if (j >= nt) return;
+  const int pos = a.pos0[b] + j;
+  const int Dh = d.Dh, half = Dh >> 1;
+  const float* krow = a.qkv + (size_t)m * d.ldzx + d.dq;
+  const float* vrow = krow + d.dkv;
+  const int* pt_row = a.page_table + (size_t)b * d.pages_per_seq;
+  const float2* cs = reinterpret_cast<const float2*>(a.rope) + (size_t)pos * half;
+  for (int it = threadIdx.x; it < d.Hkv * half; it += 256) {
+    const int kvh = it / half, i = it - kvh * half;
+    const float2 c = cs[i];
+    const float x0 = krow[kvh * Dh + i], x1 = krow[kvh * Dh + i + half];
+    const float lo = x0 * c.x - x1 * c.y, hi = x1 * c.x + x0 * c.y;
+    const size_t at = k_index(d, pt_row, kvh, pos);
+    if (d.bf16) {
+      uint16_t* kp = static_cast<uint16_t*>(a.kpool) + at;
+      kp[i] = f32_to_bf16_rne(lo); kp[i + half] = f32_to_bf16_rne(hi);
+    } else {
+      float* kp = static_cast<float*>(a.kpool) + at;
+      kp[i] = lo; kp[i + half] = hi;
+    }
+  }
+  for (int it = threadIdx.x; it < d.Hkv * Dh; it += 256) {
+    const int kvh = it / Dh, dd = it - kvh * Dh;
+    const size_t at = v_index(d, pt_row, kvh, pos, dd);
+    if (d.bf16) static_cast<uint16_t*>(a.vpool)[at] = f32_to_bf16_rne(vrow[it]);
+    else static_cast<float*>(a.vpool)[at] = vrow[it];
+  }
+}
+
+// bf16 cache: matrix-core kernel (HH_ATTN_SCALAR=1 selects the float32-FMA kernel instead, for cross-checks)
+bool attention_uses_mfma(const Dims& d) {
+  static const bool force_scalar = getenv("HH_ATTN_SCALAR") != nullptr && atoi(getenv("HH_ATTN_SCALAR")) != 0;
+  return d.bf16 && !force_scalar;
+}
+
 hipError_t launch_attention(const Dims& d, const AttnArgs& a, hipStream_t s) {
   if (d.Dh > kMaxDh || d.Dh % 8 != 0 || a.n_splits > 64 || a.n_splits < 1 || a.T < 1 || a.B < 1) return hipErrorInvalidValue;
+  if (attention_uses_mfma(d)) {
+    hipLaunchKernelGGL(kv_append_kernel, dim3(a.B * a.T), dim3(256), 0, s, d, a);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    return launch_attention_mfma(d, a, s);
+  }
   const int G = d.Hq / d.Hkv;
   const int row_chunks = (a.T * G + kRowsPerBlock - 1) / kRowsPerBlock;
   const size_t lds = ((size_t)kKeys * (d.Dh + 1) + (size_t)kKeys * d.Dh + (size_t)kRowsPerBlock * d.Dh +
@@ -456,6 +492,7 @@ hipError_t launch_attention(const Dims& d, const AttnArgs& a, hipStream_t s) {
   return launch_attention_t<0, 4>(d, a, row_chunks, lds, s);
 }
 
+// upper bound on the row chunks of either kernel (sizes the ticket counters)
 int attention_row_chunks(const Dims& d, int T) { return (T * (d.Hq / d.Hkv) + kRowsPerBlock - 1) / kRowsPerBlock; }
 
 __global__ void export_kv_kernel(const Dims d, const LayerDev* layer, const int* page_table, int seq, int tok0,
@@ -464,13 +501,13 @@ __global__ void export_kv_kernel(const Dims d, const LayerDev* layer, const int*
   const size_t total = (size_t)n_tokens * d.Hkv * d.Dh;
   for (size_t it = blockIdx.x * (size_t)blockDim.x + threadIdx.x; it < total; it += (size_t)gridDim.x * blockDim.x) {
     const int dd = it % d.Dh, kvh = (it / d.Dh) % d.Hkv, pos = tok0 + (int)(it / ((size_t)d.Dh * d.Hkv));
-    const size_t at = kv_index(d, pt_row, kvh, pos) + dd;
+    const size_t at = k_index(d, pt_row, kvh, pos) + dd, vat = v_index(d, pt_row, kvh, pos, dd);
     if (d.bf16) {
       k[it] = __uint_as_float((uint32_t) static_cast<const uint16_t*>(layer->kpool)[at] << 16);
-      v[it] = __uint_as_float((uint32_t) static_cast<const uint16_t*>(layer->vpool)[at] << 16);
+      v[it] = __uint_as_float((uint32_t) static_cast<const uint16_t*>(layer->vpool)[vat] << 16);
     } else {
       k[it] = static_cast<const float*>(layer->kpool)[at];
-      v[it] = static_cast<const float*>(layer->vpool)[at];
+      v[it] = static_cast<const float*>(layer->vpool)[vat];
     }
   }
 }

@@ -1,0 +1,38 @@
+// Paged KV cache addressing and small helpers shared by the attention kernels.
+//
+// Cache layout per layer: K pages [page][kv_head][token_in_page][Dh] (a key is one contiguous
+// row) and V pages [page][kv_head][Dh][token_in_page] (transposed: the values of one
+// dimension for consecutive tokens are contiguous, which is the operand layout of the matrix
+// cores for P x V).  page_table[b][i] is the page holding tokens i*page_tokens .. of
+// sequence b.
+#pragma once
+#include "hh_internal.h"
+
+namespace hh {
+
+#ifdef HH_ATTN_TRACE
+__device__ long long g_attn_trace[4096 * 16];
+#define TR(i) do { if (threadIdx.x == 0) g_attn_trace[((blockIdx.z * gridDim.y + blockIdx.y) * gridDim.x + blockIdx.x) * 16 + (i)] = wall_clock64(); } while (0)
+#else
+#define TR(i)
+#endif
+
+__device__ __forceinline__ uint16_t f32_to_bf16_rne(float f) {
+  uint32_t u = __float_as_uint(f);
+  u += 0x7FFFu + ((u >> 16) & 1u);
+  return (uint16_t)(u >> 16);
+}
+__device__ __forceinline__ float bf16_bits_to_f32(uint16_t h) { return __uint_as_float((uint32_t)h << 16); }
+
+// element index of K[pos][0] of one KV head
+__device__ __forceinline__ size_t k_index(const Dims& d, const int* pt_row, int kvh, int pos) {
+  const int page = pt_row[pos / d.page_tokens], off = pos % d.page_tokens;
+  return (((size_t)page * d.Hkv + kvh) * d.page_tokens + off) * d.Dh;
+}
+// element index of V[pos][dim] of one KV head (consecutive pos of a page are adjacent)
+__device__ __forceinline__ size_t v_index(const Dims& d, const int* pt_row, int kvh, int pos, int dim) {
+  const int page = pt_row[pos / d.page_tokens], off = pos % d.page_tokens;
+  return (((size_t)page * d.Hkv + kvh) * d.Dh + dim) * d.page_tokens + off;
+}
+
+}  // namespace hh

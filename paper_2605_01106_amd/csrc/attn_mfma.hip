@@ -1,0 +1,428 @@
+// Attention branch on the matrix cores (bf16 KV cache): causal grouped-query attention of the
+// T new positions of every sequence over all keys up to each position, rotary embedding of q
+// fused, keys split over the wavefronts of a workgroup and over workgroups, log-sum-exp merge
+// in slice order.  The keys and values of the new positions are already in the cache.
+//
+// Everything is computed transposed so that no operand ever has to be transposed in LDS.
+// With v_mfma_f32_16x16x32_bf16 (D[m][n] += sum_k A[m][k] B[k][n]; lane l holds A[l%16][8(l/16)..+7],
+// B[8(l/16)..+7][l%16] and D[4(l/16)+r][l%16]):
+//   scores   S^T[key][row] = sum_dim K[key][dim] Q[row][dim]      A = 16 keys of the cache (one
+//            16-byte load per lane: a key row is contiguous), B = query rows from LDS;
+//   softmax  a lane then holds 8 keys of one query row: running maximum and sum per lane,
+//            combined across the 4 lane groups with two lane exchanges;
+//   output   O^T[dim][row] = sum_key V^T[dim][key] P^T[key][row]   A = V pages, stored
+//            transposed (16 bytes = 8 consecutive tokens of one dimension), B = the lane's own
+//            8 probabilities; the accumulator of a lane belongs to one query row, so the
+//            rescaling of the online softmax is a per-lane scalar.
+// The A rows of the two key blocks of a step are assigned so that a lane's 8 scores are the
+// 8 consecutive keys its V load covers (block 0 row m <-> key 8(m/4) + m%4, block 1: + 4).
+// Queries and probabilities are float32 values split exactly into three bf16 terms, so the
+// products carry float32 accuracy; K and V are used as stored.
+#include "attn_common.h"
+
+namespace hh {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+static constexpr int kStepKeys = 32;   // keys per wavefront step
+static constexpr int kMergeLd = 20;    // row stride (floats) of the in-workgroup merge buffer
+
+union Frag {
+  uint4 u;
+  bf16x8 v;
+};
+
+// x = t0 + t1 + t2 exactly (up to the last bits of a float32), each term a bf16
+__device__ __forceinline__ void split3(float x, uint32_t& t0, uint32_t& t1, uint32_t& t2) {
+  t0 = f32_to_bf16_rne(x);
+  const float r1 = x - bf16_bits_to_f32((uint16_t)t0);
+  t1 = f32_to_bf16_rne(r1);
+  const float r2 = r1 - bf16_bits_to_f32((uint16_t)t1);
+  t2 = f32_to_bf16_rne(r2);
+}
+
+__device__ __forceinline__ float xor_max(float v) {
+  v = fmaxf(v, __shfl_xor(v, 16, 64));
+  return fmaxf(v, __shfl_xor(v, 32, 64));
+}
+__device__ __forceinline__ float xor_add(float v) {
+  v += __shfl_xor(v, 16, 64);
+  return v + __shfl_xor(v, 32, 64);
+}
+
+// grid: x = row_chunks * n_splits, y = Hkv, z = B.  RT = 16-row tiles per workgroup,
+// KS = ceil(Dh / 32).
+template <int RT, int KS>
+__global__ __launch_bounds__(256) void attn_mfma_kernel(const Dims d, const AttnArgs a, const int row_chunks) {
+  constexpr int NDB = 2 * KS;            // blocks of 16 output dimensions
+  constexpr int Dhp = 32 * KS;           // head dimension padded to the MFMA depth
+  constexpr int QS = 3 * Dhp + 8;        // bf16 elements per staged query row (3 split terms + pad)
+  constexpr int R = RT * 16;
+  extern __shared__ __align__(16) unsigned char smem_raw[];
+  __shared__ int s_last;
+  uint16_t* qT = reinterpret_cast<uint16_t*>(smem_raw);                        // [R][QS]
+  float* mrg = reinterpret_cast<float*>(smem_raw + (size_t)R * QS * 2);        // merge scratch
+  float* mrg_o = mrg;                                                          // [3][Dhp][kMergeLd]
+  float* mrg_ml = mrg + 3 * Dhp * kMergeLd;                                    // [3][16][2]
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int g = lane >> 4, n = lane & 15;
+  const int chunk = blockIdx.x % row_chunks, sp = blockIdx.x / row_chunks;
+  const int kvh = blockIdx.y, b = blockIdx.z;
+  TR(0);
+  const int nt = a.n_tok != nullptr ? a.n_tok[b] : a.T;
+  const int pos0 = a.pos0[b];
+  const int Dh = d.Dh, G = d.Hq / d.Hkv, half = Dh >> 1, S = a.n_splits;
+  const int n_rows = a.T * G;
+  const int row_lim = min(n_rows, nt * G);     // row = position j * G + query head of the group; valid while j < nt
+  const int row0 = chunk * R;
+  const int jmax = row0 < row_lim ? (min(row_lim, row0 + R) - 1) / G : -1;
+  const int nk = jmax < 0 ? 0 : pos0 + jmax + 1;          // keys 0 .. nk-1 are visible to some row of this chunk
+  const int* pt_row = a.page_table + (size_t)b * d.pages_per_seq;
+  const int pshift = 31 - __clz(d.page_tokens), pmask = d.page_tokens - 1;
+  const uint16_t* kp = static_cast<const uint16_t*>(a.kpool);
+  const uint16_t* vp = static_cast<const uint16_t*>(a.vpool);
+  const float* xrow = a.qkv + (size_t)b * a.T * d.ldzx;
+
+  // key steps of this workgroup and of this wavefront
+  const int steps = (nk + kStepKeys - 1) / kStepKeys;
+  const int sps = (steps + S - 1) / S;
+  const int sb = sp * sps, se = min(steps, sb + sps);
+  const int per = (max(se - sb, 0) + 3) >> 2;
+  const int ws = sb + wave * per, we = min(se, ws + per);
+
+  Frag kA[KS], kB[KS], vT[NDB];
+  auto load_step = [&](int step, Frag(&ka)[KS], Frag(&kb)[KS], Frag(&vt)[NDB]) {
+    const int key0 = step * kStepKeys;
+    const int keyA = min(key0 + 8 * (n >> 2) + (n & 3), nk - 1);     // past the end: a valid key, masked later
+    const int keyB = min(key0 + 8 * (n >> 2) + 4 + (n & 3), nk - 1);
+    const size_t ia = (((size_t)pt_row[keyA >> pshift] * d.Hkv + kvh) * d.page_tokens + (keyA & pmask)) * Dh;
+    const size_t ib = (((size_t)pt_row[keyB >> pshift] * d.Hkv + kvh) * d.page_tokens + (keyB & pmask)) * Dh;
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) {
+      const int dim0 = ks * 32 + 8 * g;
+      if (dim0 < Dh) {
+        ka[ks].u = *reinterpret_cast<const uint4*>(kp + ia + dim0);
+        kb[ks].u = *reinterpret_cast<const uint4*>(kp + ib + dim0);
+      } else {
+        ka[ks].u = make_uint4(0, 0, 0, 0); kb[ks].u = make_uint4(0, 0, 0, 0);
+      }
+    }
+    // 8 consecutive tokens of one dimension; tokens >= nk are zeroed (0 * garbage must not be NaN)
+    const int tok = key0 + 8 * g;
+    const int cnt = min(max(nk - tok, 0), 8);
+    const int tokc = cnt > 0 ? tok : ((nk - 1) & ~7);
+    const size_t vb = ((size_t)pt_row[tokc >> pshift] * d.Hkv + kvh) * Dh;
+#pragma unroll
+    for (int db = 0; db < NDB; ++db) {
+      const int dim = min(db * 16 + n, Dh - 1);
+      vt[db].u = *reinterpret_cast<const uint4*>(vp + (vb + dim) * d.page_tokens + (tokc & pmask));
+    }
+    if (key0 + kStepKeys > nk) {
+      uint32_t mw[4];
+#pragma unroll
+      for (int w = 0; w < 4; ++w) mw[w] = (2 * w < cnt ? 0x0000FFFFu : 0u) | (2 * w + 1 < cnt ? 0xFFFF0000u : 0u);
+#pragma unroll
+      for (int db = 0; db < NDB; ++db) { vt[db].u.x &= mw[0]; vt[db].u.y &= mw[1]; vt[db].u.z &= mw[2]; vt[db].u.w &= mw[3]; }
+    }
+  };
+  if (ws < we) load_step(ws, kA, kB, vT);
+  TR(1);
+
+  // ---- query rows: rotate to their positions, scale, split into 3 bf16 terms, stage in LDS
+  {
+    const float scale = 1.0f / sqrtf((float)Dh);
+    const float2* rope = reinterpret_cast<const float2*>(a.rope);
+    for (int it = tid; it < R * half; it += 256) {
+      const int r = it / half, i = it - r * half, rr = row0 + r;
+      float lo = 0.f, hi = 0.f;
+      if (rr < row_lim) {
+        const int j = rr / G;
+        const float* q = xrow + (size_t)j * d.ldzx + (size_t)(kvh * G + rr % G) * Dh;
+        const float2 c = rope[(size_t)(pos0 + j) * half + i];
+        const float x0 = q[i], x1 = q[i + half];
+        lo = (x0 * c.x - x1 * c.y) * scale; hi = (x1 * c.x + x0 * c.y) * scale;
+      }
+      uint32_t l0, l1, l2, h0, h1, h2;
+      split3(lo, l0, l1, l2);
+      split3(hi, h0, h1, h2);
+      uint16_t* row = qT + (size_t)r * QS;
+      row[i] = (uint16_t)l0; row[Dhp + i] = (uint16_t)l1; row[2 * Dhp + i] = (uint16_t)l2;
+      row[i + half] = (uint16_t)h0; row[Dhp + i + half] = (uint16_t)h1; row[2 * Dhp + i + half] = (uint16_t)h2;
+    }
+    if (Dh < Dhp) {
+      const int padw = Dhp - Dh;
+      for (int it = tid; it < R * padw * 3; it += 256) {
+        const int r = it / (padw * 3), rem = it - r * padw * 3, term = rem / padw, i = rem - term * padw;
+        qT[(size_t)r * QS + term * Dhp + Dh + i] = 0;
+      }
+    }
+  }
+  __syncthreads();
+  TR(2);
+
+  // the key limit of this lane's query row in each tile (row n of tile rt)
+  int lim[RT];
+#pragma unroll
+  for (int rt = 0; rt < RT; ++rt) {
+    const int rr = row0 + rt * 16 + n;
+    lim[rt] = rr < row_lim ? pos0 + rr / G : -1;
+  }
+  float mrun[RT], lrun[RT];
+  f32x4 acc[RT][NDB];
+#pragma unroll
+  for (int rt = 0; rt < RT; ++rt) {
+    mrun[rt] = -INFINITY; lrun[rt] = 0.f;
+#pragma unroll
+    for (int db = 0; db < NDB; ++db) acc[rt][db] = f32x4{0.f, 0.f, 0.f, 0.f};
+  }
+
+  for (int step = ws; step < we; ++step) {
+    Frag kA2[KS], kB2[KS], vT2[NDB];
+    if (step + 1 < we) load_step(step + 1, kA2, kB2, vT2);
+    const int kbase = step * kStepKeys + 8 * g;   // the lane's 8 keys: kbase .. kbase + 7
+#pragma unroll
+    for (int rt = 0; rt < RT; ++rt) {
+      // large tiles: re-read the query fragments from LDS every step instead of keeping all
+      // of them in registers across the loop
+      if (RT * KS > 4) asm volatile("" ::: "memory");
+      f32x4 sA = f32x4{0.f, 0.f, 0.f, 0.f}, sB = f32x4{0.f, 0.f, 0.f, 0.f};
+      const uint16_t* qrow = qT + (size_t)(rt * 16 + n) * QS + 8 * g;
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks) {
+#pragma unroll
+        for (int term = 0; term < 3; ++term) {
+          Frag q;
+          q.u = *reinterpret_cast<const uint4*>(qrow + term * Dhp + ks * 32);
+          sA = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kA[ks].v, q.v, sA, 0, 0, 0);
+          sB = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kB[ks].v, q.v, sB, 0, 0, 0);
+        }
+      }
+      float sc[8] = {sA[0], sA[1], sA[2], sA[3], sB[0], sB[1], sB[2], sB[3]};
+      float mx = -INFINITY;
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        sc[i] = kbase + i <= lim[rt] ? sc[i] : -INFINITY;
+        mx = fmaxf(mx, sc[i]);
+      }
+      const float mnew = fmaxf(mrun[rt], xor_max(mx));
+      float corr = 1.f, psum = 0.f;
+      uint32_t t0[8], t1[8], t2[8];
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        const float p = sc[i] == -INFINITY ? 0.f : expf(sc[i] - mnew);   // visible implies mnew finite
+        psum += p;
+        split3(p, t0[i], t1[i], t2[i]);
+      }
+      if (mnew != -INFINITY) corr = mrun[rt] == -INFINITY ? 0.f : expf(mrun[rt] - mnew);
+      lrun[rt] = lrun[rt] * corr + psum;
+      mrun[rt] = mnew;
+      Frag p0, p1, p2;
+      p0.u = make_uint4(t0[0] | (t0[1] << 16), t0[2] | (t0[3] << 16), t0[4] | (t0[5] << 16), t0[6] | (t0[7] << 16));
+      p1.u = make_uint4(t1[0] | (t1[1] << 16), t1[2] | (t1[3] << 16), t1[4] | (t1[5] << 16), t1[6] | (t1[7] << 16));
+      p2.u = make_uint4(t2[0] | (t2[1] << 16), t2[2] | (t2[3] << 16), t2[4] | (t2[5] << 16), t2[6] | (t2[7] << 16));
+#pragma unroll
+      for (int db = 0; db < NDB; ++db) {
+        f32x4 c = acc[rt][db];
+        c[0] *= corr; c[1] *= corr; c[2] *= corr; c[3] *= corr;
+        c = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vT[db].v, p0.v, c, 0, 0, 0);
+        c = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vT[db].v, p1.v, c, 0, 0, 0);
+        c = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vT[db].v, p2.v, c, 0, 0, 0);
+        acc[rt][db] = c;
+      }
+    }
+    if (step + 1 < we) {
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks) { kA[ks] = kA2[ks]; kB[ks] = kB2[ks]; }
+#pragma unroll
+      for (int db = 0; db < NDB; ++db) vT[db] = vT2[db];
+    }
+  }
+  TR(3);
+#pragma unroll
+  for (int rt = 0; rt < RT; ++rt) lrun[rt] = xor_add(lrun[rt]);
+
+  // ---- merge the 4 wavefronts (key slices in order) into wavefront 0, one row tile at a time
+#pragma unroll
+  for (int rt = 0; rt < RT; ++rt) {
+    if (wave > 0) {
+      if (g == 0) { mrg_ml[((wave - 1) * 16 + n) * 2] = mrun[rt]; mrg_ml[((wave - 1) * 16 + n) * 2 + 1] = lrun[rt]; }
+#pragma unroll
+      for (int db = 0; db < NDB; ++db)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) mrg_o[((wave - 1) * Dhp + db * 16 + 4 * g + r) * kMergeLd + n] = acc[rt][db][r];
+    }
+    __syncthreads();
+    if (wave == 0) {
+      float mw[3], lw[3], M = mrun[rt];
+#pragma unroll
+      for (int w = 0; w < 3; ++w) { mw[w] = mrg_ml[(w * 16 + n) * 2]; lw[w] = mrg_ml[(w * 16 + n) * 2 + 1]; M = fmaxf(M, mw[w]); }
+      const float f0 = mrun[rt] == -INFINITY ? 0.f : expf(mrun[rt] - M);
+      float fw[3];
+#pragma unroll
+      for (int w = 0; w < 3; ++w) fw[w] = mw[w] == -INFINITY ? 0.f : expf(mw[w] - M);
+      lrun[rt] = f0 * lrun[rt] + fw[0] * lw[0] + fw[1] * lw[1] + fw[2] * lw[2];
+      mrun[rt] = M;
+#pragma unroll
+      for (int db = 0; db < NDB; ++db)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          float v = f0 * acc[rt][db][r];
+#pragma unroll
+          for (int w = 0; w < 3; ++w) v = fmaf(fw[w], mrg_o[(w * Dhp + db * 16 + 4 * g + r) * kMergeLd + n], v);
+          acc[rt][db][r] = v;
+        }
+    }
+    __syncthreads();
+  }
+  TR(4);
+
+  // ---- results of the workgroup (held by wavefront 0): final, or the partial of its key slice
+  if (wave == 0) {
+#pragma unroll
+    for (int rt = 0; rt < RT; ++rt) {
+      const int rr = row0 + rt * 16 + n;
+      if (rr >= n_rows) continue;
+      const int j = rr / G, hq = kvh * G + rr % G;
+      if (S == 1) {
+        const float inv = (rr < row_lim && lrun[rt] > 0.f) ? 1.0f / lrun[rt] : 0.f;
+        float* orow = a.o + ((size_t)b * a.T + j) * d.dq + (size_t)hq * Dh;
+#pragma unroll
+        for (int db = 0; db < NDB; ++db) {
+          const int dim = db * 16 + 4 * g;
+          if (dim < Dh)
+            *reinterpret_cast<float4*>(orow + dim) =
+                make_float4(acc[rt][db][0] * inv, acc[rt][db][1] * inv, acc[rt][db][2] * inv, acc[rt][db][3] * inv);
+        }
+      } else {
+        const size_t rid = (((size_t)b * a.T + j) * d.Hq + hq) * S + sp;
+#pragma unroll
+        for (int db = 0; db < NDB; ++db) {
+          const int dim = db * 16 + 4 * g;
+          if (dim < Dh)
+            *reinterpret_cast<float4*>(a.part_o + rid * Dh + dim) =
+                make_float4(acc[rt][db][0], acc[rt][db][1], acc[rt][db][2], acc[rt][db][3]);
+        }
+        if (g == 0) { a.part_ml[rid * 2] = mrun[rt]; a.part_ml[rid * 2 + 1] = lrun[rt]; }
+      }
+    }
+  }
+  if (S == 1) return;
+
+  // Make the partials visible device-wide (release), then take a ticket; the workgroup that
+  // draws the last ticket sees all of them after its acquire fence and merges the slices.
+  TR(5);
+  __threadfence();
+  __syncthreads();
+  int* counter = a.counters + ((size_t)b * d.Hkv + kvh) * row_chunks + chunk;
+  if (tid == 0) {
+    const int ticket = atomicAdd(counter, 1);
+    s_last = ticket == S - 1;
+    if (s_last) *counter = 0;   // ready for the next launch (launches on a context are ordered)
+  }
+  __syncthreads();
+  TR(6);
+  if (!s_last) return;
+  __threadfence();
+  float2* gm = reinterpret_cast<float2*>(mrg);   // [R][S] (maximum, sum) of every slice
+  for (int it = tid; it < R * S; it += 256) {
+    const int r = it / S, s = it - r * S, rr = row0 + r;
+    float2 v = make_float2(-INFINITY, 0.f);
+    if (rr < n_rows) {
+      const size_t rid = ((size_t)b * a.T + rr / G) * d.Hq + kvh * G + rr % G;
+      v = reinterpret_cast<const float2*>(a.part_ml)[rid * S + s];
+    }
+    gm[it] = v;
+  }
+  __syncthreads();
+  TR(7);
+  const int d4n = Dh >> 2;
+  for (int it = tid; it < R * d4n; it += 256) {
+    const int r = it / d4n, c4 = it - r * d4n, rr = row0 + r;
+    if (rr >= n_rows) continue;
+    const int j = rr / G, hq = kvh * G + rr % G;
+    const size_t rid = ((size_t)b * a.T + j) * d.Hq + hq;
+    float M = -INFINITY;
+    for (int s = 0; s < S; ++s) M = fmaxf(M, gm[r * S + s].x);
+    float4 out = make_float4(0.f, 0.f, 0.f, 0.f);
+    float L = 0.f;
+    for (int s0 = 0; s0 < S; s0 += 8) {                 // slice order: deterministic
+      float4 pv[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u)
+        pv[u] = *reinterpret_cast<const float4*>(a.part_o + (rid * S + min(s0 + u, S - 1)) * Dh + 4 * c4);
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {
+        if (s0 + u < S) {
+          const float2 ml = gm[r * S + s0 + u];
+          const float w = ml.x == -INFINITY ? 0.f : expf(ml.x - M);
+          L = fmaf(w, ml.y, L);
+          out.x = fmaf(w, pv[u].x, out.x); out.y = fmaf(w, pv[u].y, out.y);
+          out.z = fmaf(w, pv[u].z, out.z); out.w = fmaf(w, pv[u].w, out.w);
+        }
+      }
+    }
+    const float inv = (rr < row_lim && L > 0.f) ? 1.0f / L : 0.f;
+    *reinterpret_cast<float4*>(a.o + ((size_t)b * a.T + j) * d.dq + (size_t)hq * Dh + 4 * c4) =
+        make_float4(out.x * inv, out.y * inv, out.z * inv, out.w * inv);
+  }
+  TR(8);
+}
+
+template <int RT, int KS>
+static hipError_t launch_t(const Dims& d, const AttnArgs& a, int row_chunks, hipStream_t s) {
+  constexpr int Dhp = 32 * KS, QS = 3 * Dhp + 8;
+  size_t scratch = (size_t)(3 * Dhp * kMergeLd + 3 * 16 * 2) * sizeof(float);
+  const size_t gm = (size_t)RT * 16 * a.n_splits * sizeof(float2);
+  if (gm > scratch) scratch = gm;
+  const size_t lds = (size_t)RT * 16 * QS * 2 + scratch;
+  static size_t lds_enabled = 48 * 1024;
+  if (lds > lds_enabled) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(attn_mfma_kernel<RT, KS>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e != hipSuccess) return e;
+    lds_enabled = lds;
+  }
+  hipLaunchKernelGGL((attn_mfma_kernel<RT, KS>), dim3(row_chunks * a.n_splits, d.Hkv, a.B), dim3(256), lds, s, d, a,
+                     row_chunks);
+  return hipGetLastError();
+}
+
+template <int KS>
+static hipError_t launch_ks(const Dims& d, const AttnArgs& a, int rt, int row_chunks, hipStream_t s) {
+  switch (rt) {
+    case 1: return launch_t<1, KS>(d, a, row_chunks, s);
+    case 2: return launch_t<2, KS>(d, a, row_chunks, s);
+    case 3: if (KS < 8) return launch_t<(KS < 8 ? 3 : 1), KS>(d, a, row_chunks, s); break;
+    case 4: if (KS < 8) return launch_t<(KS < 8 ? 4 : 1), KS>(d, a, row_chunks, s); break;
+  }
+  return hipErrorInvalidValue;
+}
+
+// rows (position x query head of a KV group) per workgroup, in tiles of 16
+static int mfma_row_tiles(const Dims& d, int T) {
+  const int rows = T * (d.Hq / d.Hkv);
+  const int rt_max = d.Dh > 128 ? 2 : 4;
+  const int tiles = (rows + 15) / 16;
+  return tiles < rt_max ? tiles : rt_max;
+}
+int attention_mfma_row_chunks(const Dims& d, int T) {
+  const int rows = T * (d.Hq / d.Hkv);
+  const int per = 16 * mfma_row_tiles(d, T);
+  return (rows + per - 1) / per;
+}
+
+hipError_t launch_attention_mfma(const Dims& d, const AttnArgs& a, hipStream_t s) {
+  if (!d.bf16 || d.Dh > 256 || d.Dh % 8 != 0 || d.Dh < 8 || a.n_splits > 64 || a.n_splits < 1 || a.T < 1 || a.B < 1 ||
+      d.page_tokens % 8 != 0 || (d.page_tokens & (d.page_tokens - 1)) != 0)
+    return hipErrorInvalidValue;
+  const int rt = mfma_row_tiles(d, a.T), row_chunks = attention_mfma_row_chunks(d, a.T);
+  const int ks = (d.Dh + 31) / 32;
+  if (ks == 1) return launch_ks<1>(d, a, rt, row_chunks, s);
+  if (ks == 2) return launch_ks<2>(d, a, rt, row_chunks, s);
+  if (ks <= 4) return launch_ks<4>(d, a, rt, row_chunks, s);
+  return launch_ks<8>(d, a, rt, row_chunks, s);
+}
+
+}  // namespace hh

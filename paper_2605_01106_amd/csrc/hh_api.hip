@@ -5,6 +5,7 @@
 // lengths, accepted counts) stays in device memory.
 #include <math.h>
 #include <stdio.h>
+#include <stdlib.h>
 #include <string.h>
 
 #include <map>
@@ -340,14 +341,26 @@ hh_status run_graphed(hh_ctx* x, long long key, hipStream_t s, F enqueue) {
   return HH_OK;
 }
 
+// Key slices per (sequence, KV head, row chunk) of a verification pass: enough workgroups to
+// cover the chip, but no slice smaller than the unit of work of the kernel.
 int pick_splits(const Dims& d, int B, int T, int len_upper) {
-  const int G = d.Hq / d.Hkv;
-  const int row_chunks = (T * G + 15) / 16;
-  const int blocks = row_chunks * d.Hkv * B;
-  const int tiles = (len_upper + T + 63) / 64;
-  int s = (512 + blocks - 1) / blocks;
+  static const int cap = getenv("HH_ATTN_MAXSPLIT") ? atoi(getenv("HH_ATTN_MAXSPLIT")) : kMaxSplits;
+  int s;
+  if (attention_uses_mfma(d)) {
+    const int blocks = attention_mfma_row_chunks(d, T) * d.Hkv * B;
+    const int steps = (len_upper + T + 31) / 32;      // 32 keys per wavefront step, 4 wavefronts per workgroup
+    s = (512 + blocks - 1) / blocks;
+    if (s > (steps + 3) / 4) s = (steps + 3) / 4;
+  } else {
+    const int G = d.Hq / d.Hkv;
+    const int row_chunks = (T * G + 15) / 16;
+    const int blocks = row_chunks * d.Hkv * B;
+    const int tiles = (len_upper + T + 63) / 64;
+    s = (512 + blocks - 1) / blocks;
+    if (s > tiles) s = tiles;
+  }
   if (s > kMaxSplits) s = kMaxSplits;
-  if (s > tiles) s = tiles;
+  if (s > cap) s = cap;
   return s < 1 ? 1 : s;
 }
 

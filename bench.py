@@ -191,7 +191,8 @@ def main():
         for kind in sorted(KIND_NAMES):
             if kind == 2 or (ph == 1 and kind in (3, 5)):   # RoPE/append is fused into attention
                 continue
-            avg_us, n = ctx.hh_time_kind(ph, kind, k, 4)
+            # best of three repeats of 4 passes each: the boxes show run-to-run clock noise
+            avg_us, n = min(ctx.hh_time_kind(ph, kind, k, 4) for _ in range(3))
             by = per_kind.get((ph, kind))
             launches = (1 if kind == 8 else cfg.n_layers) * per_round[ph]
             kernels[f"{PHASE_NAMES[ph]}.{KIND_NAMES[kind]}"] = {

@@ -7,15 +7,10 @@
 // sequence b.
 #pragma once
 #include "hh_internal.h"
+#include "trace.h"
 
 namespace hh {
 
-#ifdef HH_ATTN_TRACE
-__device__ long long g_attn_trace[4096 * 16];
-#define TR(i) do { if (threadIdx.x == 0) g_attn_trace[((blockIdx.z * gridDim.y + blockIdx.y) * gridDim.x + blockIdx.x) * 16 + (i)] = wall_clock64(); } while (0)
-#else
-#define TR(i)
-#endif
 
 __device__ __forceinline__ uint16_t f32_to_bf16_rne(float f) {
   uint32_t u = __float_as_uint(f);

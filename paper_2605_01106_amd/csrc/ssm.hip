@@ -14,14 +14,20 @@
 // Layout: S[b][h][p][n] float32, n fastest.  A workgroup owns kRows (8 or 32) rows p of one head; 8 lanes
 // share a row, each holding N/8 consecutive n in registers; the read-out over n is reduced
 // across those 8 lanes.  Ring row for position q: slot q mod ring_slots, [conv_dim raw xBC | Hm raw dt].
+#include <stdlib.h>
+
 #include "hh_internal.h"
+#include "trace.h"
 
 namespace hh {
 
 static constexpr int kSub = 8;     // lanes per row
 static constexpr int kTS = 16;     // positions staged per pass through LDS
 
-__device__ __forceinline__ float silu_f(float v) { return v / (1.0f + expf(-v)); }
+// v * sigmoid(v) with the hardware exponential and reciprocal (each within 1 ulp; the argument
+// scaling of the exponential adds |v| * 2^-24 relative): the kernels below evaluate it for
+// every conv channel of every position, with one wavefront per SIMD
+__device__ __forceinline__ float silu_f(float v) { return v * __frcp_rn(1.0f + __expf(-v)); }
 __device__ __forceinline__ float softplus_f(float v) { return v > 20.0f ? v : log1pf(expf(v)); }
 
 template <int CTRL>
@@ -171,6 +177,227 @@ __global__ __launch_bounds__(kRows * kSub) void ssm_kernel(const Dims d, const S
   }
 }
 
+// ---- few positions per pass (draft steps, verification, rollback), 16-byte aligned rows.
+// One wavefront per workgroup owns 64/SUBS rows p of one head, SUBS lanes share a row.  Every
+// global load of the workgroup (state, conv taps and biases, the raw inputs of the T positions
+// and of the 3 before them, dt, z) is issued before the first result is used, so the kernel
+// costs about one memory round trip plus the recurrence.  The conv of B and C is computed
+// once per workgroup, 4 channels per lane, and handed to the lanes through LDS.
+template <int NV, int SUBS, int TMAX>
+__global__ __launch_bounds__(64) void ssm_small_kernel(const Dims d, const SsmArgs a) {
+  constexpr int ROWS = 64 / SUBS, N = NV * SUBS;
+  constexpr int NG = (2 * N / 4 + 63) / 64;      // groups of 4 B|C channels per lane
+  __shared__ __align__(16) float BCs[TMAX][2 * N];
+
+  const int lane = threadIdx.x, row = lane / SUBS, sub = lane % SUBS;
+  const int p0 = blockIdx.x * ROWS, h = blockIdx.y;
+  const int lz = blockIdx.z / a.B, b = blockIdx.z % a.B;
+  const LayerDev& ly = a.layers != nullptr ? a.layers[a.layer0 + lz] : a.one;
+  TR(0);
+  // Loads in the order of what they wait for.  Nothing here depends on the per-sequence
+  // scalars except the ring rows (slot = position mod ring size), which come last.
+  const int p = min(p0 + row, d.P - 1);
+  const bool prow = p0 + row < d.P;
+  const int cx = h * d.P + p;
+  const int rmask = d.ring_slots - 1;
+  float* ring = ly.ring + (size_t)b * d.ring_slots * d.ring_w;
+  const float* zx = a.zx != nullptr ? a.zx + (size_t)b * a.T * d.ldzx : nullptr;
+  const int skip_v = (a.skip != nullptr ? a.skip : a.pos0)[b];   // absent arrays read pos0 instead and are ignored
+  const int nacc_v = (a.n_acc != nullptr ? a.n_acc : a.pos0)[b];
+  const int ntok_v = (a.n_tok != nullptr ? a.n_tok : a.pos0)[b];
+  const int pos0 = a.pos0[b];
+  float S[NV];
+  {
+    const float* src = a.state_in == 0 ? ly.S : (a.state_in == 1 ? ly.S_draft : nullptr);
+    if (src != nullptr) {
+      const float* sp = src + (((size_t)b * d.Hm + h) * d.P + p) * N + sub * NV;
+#pragma unroll
+      for (int i = 0; i < NV; i += 4) {
+        const float4 v = *reinterpret_cast<const float4*>(sp + i);
+        S[i] = v.x; S[i + 1] = v.y; S[i + 2] = v.z; S[i + 3] = v.w;
+      }
+    } else {
+#pragma unroll
+      for (int i = 0; i < NV; ++i) S[i] = 0.f;
+    }
+  }
+  float4 bw[NG][4], bb[NG], braw[NG][TMAX + 3];
+  float xraw[TMAX + 3], zg[TMAX];
+  float dtraw_l = 0.f;   // raw dt of position `lane` (lanes < T): softplus and decay are evaluated once, lane-parallel
+#pragma unroll
+  for (int u = 0; u < NG; ++u) {
+    const int c = d.d_inner + 4 * min(lane + 64 * u, 2 * N / 4 - 1);
+#pragma unroll
+    for (int t = 0; t < 4; ++t) bw[u][t] = *reinterpret_cast<const float4*>(ly.conv_w + (size_t)(c + t) * 4);
+    bb[u] = *reinterpret_cast<const float4*>(ly.conv_b + c);
+  }
+  const float4 xw = *reinterpret_cast<const float4*>(ly.conv_w + (size_t)cx * 4);
+  const float xb = ly.conv_b[cx];
+  const float dskip = ly.d_skip[h];
+  const float dtb = ly.dt_bias[h];
+  const float alog = ly.a_log[h];
+  if (zx != nullptr) {   // inputs of this pass: rows 0 .. T-1 of the projection buffer (rows >= nt are read but not used)
+#pragma unroll
+    for (int j = 0; j < TMAX; ++j) {
+      const float* r = zx + (size_t)min(j, a.T - 1) * d.ldzx + d.d_inner;
+#pragma unroll
+      for (int u = 0; u < NG; ++u) braw[u][j + 3] = *reinterpret_cast<const float4*>(r + d.d_inner + 4 * min(lane + 64 * u, 2 * N / 4 - 1));
+      xraw[j + 3] = r[cx];
+      zg[j] = a.g != nullptr ? r[cx - d.d_inner] : 0.f;   // z precedes xBC in the row
+    }
+    dtraw_l = zx[(size_t)min(lane, a.T - 1) * d.ldzx + d.d_inner + d.conv_dim + h];
+  }
+  if (a.skip != nullptr && skip_v) return;
+  int nt = a.T;
+  if (a.n_acc != nullptr) nt = nacc_v + 1;
+  else if (a.n_tok != nullptr) nt = ntok_v;
+  if (nt <= 0) return;
+  nt = min(nt, TMAX);
+  // row of raw inputs (xBC | dt) of position pos0 + j in the ring (positions before 0 read slot 0 and count as 0)
+  auto ring_row = [&](int j) -> const float* { return ring + (size_t)(max(pos0 + j, 0) & rmask) * d.ring_w; };
+#pragma unroll
+  for (int j = -3; j < (int)TMAX; ++j) {
+    if (j >= 0 && zx != nullptr) continue;
+    const float* r = ring_row(min(j, nt - 1));
+#pragma unroll
+    for (int u = 0; u < NG; ++u) braw[u][j + 3] = *reinterpret_cast<const float4*>(r + d.d_inner + 4 * min(lane + 64 * u, 2 * N / 4 - 1));
+    xraw[j + 3] = r[cx];
+    if (j >= 0) zg[j] = 0.f;
+  }
+  if (zx == nullptr) dtraw_l = ring_row(min(lane, nt - 1))[d.conv_dim + h];
+  const float negA = -expf(alog);
+  TR(1);
+
+  // ---- conv + SiLU: B and C for the whole workgroup (branch-free: clamped inputs, every
+  // position computed; positions >= nt are never used)
+#pragma unroll
+  for (int u = 0; u < NG; ++u) {
+    const int gi = lane + 64 * u;
+#pragma unroll
+    for (int j = 0; j < TMAX; ++j) {
+      float4 o;
+      float* op = reinterpret_cast<float*>(&o);
+#pragma unroll
+      for (int ch = 0; ch < 4; ++ch) {
+        const float r0 = pos0 + j - 3 < 0 ? 0.f : reinterpret_cast<const float*>(&braw[u][j])[ch];
+        const float r1 = pos0 + j - 2 < 0 ? 0.f : reinterpret_cast<const float*>(&braw[u][j + 1])[ch];
+        const float r2 = pos0 + j - 1 < 0 ? 0.f : reinterpret_cast<const float*>(&braw[u][j + 2])[ch];
+        const float r3 = reinterpret_cast<const float*>(&braw[u][j + 3])[ch];
+        float acc = bw[u][ch].x * r0;
+        acc = fmaf(bw[u][ch].y, r1, acc); acc = fmaf(bw[u][ch].z, r2, acc); acc = fmaf(bw[u][ch].w, r3, acc);
+        op[ch] = silu_f(acc + reinterpret_cast<const float*>(&bb[u])[ch]);
+      }
+      if (gi < 2 * N / 4) *reinterpret_cast<float4*>(&BCs[j][4 * gi]) = o;
+    }
+  }
+  // ---- per-position scalars of this lane's row and head, all positions at once
+  float xv[TMAX], aj[TMAX], coef[TMAX], gate[TMAX];
+  const float dt_l = softplus_f(dtraw_l + dtb);
+  const float a_l = expf(negA * dt_l);
+#pragma unroll
+  for (int j = 0; j < TMAX; ++j) {
+    const float r0 = pos0 + j - 3 < 0 ? 0.f : xraw[j];
+    const float r1 = pos0 + j - 2 < 0 ? 0.f : xraw[j + 1];
+    const float r2 = pos0 + j - 1 < 0 ? 0.f : xraw[j + 2];
+    float acc = xw.x * r0;
+    acc = fmaf(xw.y, r1, acc); acc = fmaf(xw.z, r2, acc); acc = fmaf(xw.w, xraw[j + 3], acc);
+    xv[j] = silu_f(acc + xb);
+    const float dt = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(dt_l), j));
+    const bool on = j < nt;
+    aj[j] = on ? __int_as_float(__builtin_amdgcn_readlane(__float_as_int(a_l), j)) : 1.f;   // positions >= nt leave the state as it is
+    coef[j] = on ? dt * xv[j] : 0.f;
+    gate[j] = silu_f(zg[j]);
+  }
+  // ---- keep the raw inputs of these positions for later windows and for rollback
+  if (a.write_ring && zx != nullptr) {
+    if (sub == 0 && prow) {
+#pragma unroll
+      for (int j = 0; j < TMAX; ++j)
+        if (j < nt) ring[(size_t)((pos0 + j) & rmask) * d.ring_w + cx] = xraw[j + 3];
+    }
+    if (h == 0 && blockIdx.x == 0) {
+#pragma unroll
+      for (int u = 0; u < NG; ++u) {
+        const int gi = lane + 64 * u;
+        if (gi < 2 * N / 4) {
+#pragma unroll
+          for (int j = 0; j < TMAX; ++j)
+            if (j < nt) *reinterpret_cast<float4*>(ring + (size_t)((pos0 + j) & rmask) * d.ring_w + d.d_inner + 4 * gi) = braw[u][j + 3];
+        }
+      }
+      for (int it = lane; it < nt * d.Hm; it += 64) {
+        const int j = it / d.Hm, hh = it - j * d.Hm;
+        ring[(size_t)((pos0 + j) & rmask) * d.ring_w + d.conv_dim + hh] = zx[(size_t)j * d.ldzx + d.d_inner + d.conv_dim + hh];
+      }
+    }
+  }
+  TR(2);
+  __syncthreads();
+  TR(3);
+
+  // ---- recurrence
+  float y[TMAX];
+#pragma unroll
+  for (int j = 0; j < TMAX; ++j) {
+    float part = 0.f;
+#pragma unroll
+    for (int i = 0; i < NV; i += 4) {
+      const float4 Bv = *reinterpret_cast<const float4*>(&BCs[j][sub * NV + i]);
+      const float4 Cv = *reinterpret_cast<const float4*>(&BCs[j][N + sub * NV + i]);
+      S[i] = fmaf(aj[j], S[i], coef[j] * Bv.x); part = fmaf(S[i], Cv.x, part);
+      S[i + 1] = fmaf(aj[j], S[i + 1], coef[j] * Bv.y); part = fmaf(S[i + 1], Cv.y, part);
+      S[i + 2] = fmaf(aj[j], S[i + 2], coef[j] * Bv.z); part = fmaf(S[i + 2], Cv.z, part);
+      S[i + 3] = fmaf(aj[j], S[i + 3], coef[j] * Bv.w); part = fmaf(S[i + 3], Cv.w, part);
+    }
+    part += dpp_perm_f<0xB1>(part);    // lane ^ 1
+    part += dpp_perm_f<0x4E>(part);    // lane ^ 2
+    part += dpp_perm_f<0x141>(part);   // the other quad of 8 lanes
+    if (SUBS == 16) part += dpp_perm_f<0x140>(part);   // the other half of 16 lanes
+    y[j] = (part + dskip * xv[j]) * gate[j];
+  }
+  if (a.g != nullptr && sub == 0 && prow) {
+#pragma unroll
+    for (int j = 0; j < TMAX; ++j)
+      if (j < nt) a.g[((size_t)b * a.T + j) * d.d_inner + cx] = y[j];
+  }
+  TR(4);
+  if (a.state_out != 0 && prow) {
+    float* dst = (a.state_out == 1 ? ly.S : ly.S_draft) + (((size_t)b * d.Hm + h) * d.P + p) * N + sub * NV;
+#pragma unroll
+    for (int i = 0; i < NV; i += 4) *reinterpret_cast<float4*>(dst + i) = make_float4(S[i], S[i + 1], S[i + 2], S[i + 3]);
+  }
+  TR(5);
+}
+
+template <int NV, int SUBS>
+static hipError_t launch_ssm_small_t(const Dims& d, const SsmArgs& a, int tmax, hipStream_t s) {
+  const dim3 grid((d.P + 64 / SUBS - 1) / (64 / SUBS), d.Hm, a.n_layers_z * a.B);
+  switch (tmax) {
+    case 1: hipLaunchKernelGGL((ssm_small_kernel<NV, SUBS, 1>), grid, dim3(64), 0, s, d, a); break;
+    case 3: hipLaunchKernelGGL((ssm_small_kernel<NV, SUBS, 3>), grid, dim3(64), 0, s, d, a); break;
+    case 5: hipLaunchKernelGGL((ssm_small_kernel<NV, SUBS, 5>), grid, dim3(64), 0, s, d, a); break;
+    case 9: hipLaunchKernelGGL((ssm_small_kernel<NV, SUBS, 9>), grid, dim3(64), 0, s, d, a); break;
+    default: return hipErrorInvalidValue;
+  }
+  return hipGetLastError();
+}
+
+// true if the pass was taken by the few-positions kernel
+static bool launch_ssm_small(const Dims& d, const SsmArgs& a, hipStream_t s, hipError_t* err) {
+  static const bool off = getenv("HH_SSM_GENERAL") != nullptr && atoi(getenv("HH_SSM_GENERAL")) != 0;
+  if (off || a.T > 9 || d.Hm % 4 != 0 || d.P % 4 != 0 || d.N % 32 != 0 || d.ldzx % 4 != 0 || d.d_inner % 4 != 0) return false;
+  const int tmax = a.T <= 1 ? 1 : a.T <= 3 ? 3 : a.T <= 5 ? 5 : 9;
+  const long waves8 = (long)((d.P + 7) / 8) * d.Hm * a.n_layers_z * a.B;
+  const bool wide = d.N % 64 == 0 && waves8 < 1024;     // 16 lanes per row: twice the wavefronts
+  switch (wide ? d.N / 16 : d.N / 8) {
+    case 4: *err = wide ? launch_ssm_small_t<4, 16>(d, a, tmax, s) : launch_ssm_small_t<4, 8>(d, a, tmax, s); return true;
+    case 8: *err = wide ? launch_ssm_small_t<8, 16>(d, a, tmax, s) : launch_ssm_small_t<8, 8>(d, a, tmax, s); return true;
+    case 16: *err = wide ? launch_ssm_small_t<16, 16>(d, a, tmax, s) : launch_ssm_small_t<16, 8>(d, a, tmax, s); return true;
+    case 32: if (!wide) { *err = launch_ssm_small_t<32, 8>(d, a, tmax, s); return true; } break;
+  }
+  return false;
+}
+
 template <int kRows>
 static hipError_t launch_ssm_rows(const Dims& d, const SsmArgs& a, hipStream_t s) {
   const dim3 grid((d.P + kRows - 1) / kRows, d.Hm, a.n_layers_z * a.B);
@@ -189,9 +416,8 @@ static hipError_t launch_ssm_rows(const Dims& d, const SsmArgs& a, hipStream_t s
 
 hipError_t launch_ssm(const Dims& d, const SsmArgs& a, hipStream_t s) {
   if (d.N % kSub != 0) return hipErrorInvalidValue;
-  // enough 32-row workgroups to cover the chip twice: take them, else 8-row ones
-  const long big = (long)((d.P + 31) / 32) * d.Hm * a.n_layers_z * a.B;
-  (void)big;
+  hipError_t e = hipSuccess;
+  if (launch_ssm_small(d, a, s, &e)) return e;
   return launch_ssm_rows<32>(d, a, s);
 }
 

@@ -65,6 +65,21 @@ def test_draft_lengths_and_plain_greedy(B, k):
     run_lockstep(ctx, wts, prompts, lens, 16, k, engine="step", report=_say(f"k={k}"))
 
 
+@pytest.mark.parametrize("k,d_state,dtype", [(2, 32, W.BF16), (4, 64, W.BF16), (8, 64, W.F32), (0, 128, W.BF16)])
+def test_aligned_shapes_fast_paths(B, k, d_state, dtype):
+    """Shapes whose rows are 16-byte aligned (heads and head dimension multiples of 4, state a
+    multiple of 32) take the few-positions SSM kernel (8 or 16 lanes per state row, a partly
+    filled last workgroup) and, with a bf16 cache, the matrix-core attention with several
+    16-row tiles; prompts straddle pages and key steps, one sequence finishes early."""
+    cfg = W.scaled_config("aligned", n_layers=2, d_model=64, vocab=160, m_heads=4, m_head_dim=12, d_state=d_state,
+                          n_q_heads=8, n_kv_heads=2, head_dim=32, d_ff=96, w_dtype=dtype)
+    wts = W.make_lively_weights(cfg, 17)
+    lens = [33, 6, 95]
+    prompts = W.make_prompts(cfg.vocab, 3, lens, 21)
+    ctx = _ctx(B, wts, 3, 160, 8, 30, kv_page_tokens=16, prefill_chunk=32)
+    run_lockstep(ctx, wts, prompts, lens, 30, k, engine="pass", report=_say(f"aligned-k{k}-N{d_state}-{dtype}"))
+
+
 def test_forced_acceptance_and_arbitrary_drafts(B):
     """Forced accepted counts (drafts committed as drafted) and caller-supplied draft tokens."""
     cfg = W.scaled_config("forced", n_layers=2, d_model=64, vocab=96, m_heads=4, m_head_dim=16, d_state=8,

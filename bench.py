@@ -127,14 +127,20 @@ def main():
     G = max(wl.gen_len, total_rounds * (k + 1) + 2)
     max_seq = wl.prompt_len + G + 2 * k + 4
 
+    def say(msg):   # progress on stderr: the JSON line on stdout stays the only stdout output
+        print(f"[bench] {msg}", file=sys.stderr, flush=True)
+
+    say(f"workload {args.workload}: generating weights")
     t0 = time.perf_counter()
     weights = W.make_weights(cfg, args.seed)
     prompts = W.make_prompts(cfg.vocab, Bn, wl.prompt_len, args.seed)
     t_gen = time.perf_counter() - t0
     stream = torch.cuda.Stream()          # HIP graphs cannot be captured on the default stream
     torch.cuda.set_stream(stream)
+    say(f"weights in {t_gen:.1f} s; creating the context")
     ctx = B.Context(weights, Bn, max_seq, k, G, use_graphs=args.graphs)
     torch.cuda.synchronize()
+    say("prefill")
     t0 = time.perf_counter()
     ctx.hh_prefill(prompts, [wl.prompt_len] * Bn, G)
     torch.cuda.synchronize()
@@ -169,8 +175,10 @@ def main():
         seg = [sum(e[i].elapsed_time(e[i + 1]) for e in evs) * 1e-3 for i in range(3)]
         return dt, sum(c1) - sum(c0), seg
 
+    say(f"prefill in {t_prefill:.2f} s; {Wm} warm-up and {K} timed rounds")
     run_rounds(Wm, k)
     dt, toks, (t_draft, t_verify, t_commit) = timed_leg(K, k)
+    say(f"timed rounds: {toks / dt:.1f} tokens/s; forced-acceptance and plain-greedy legs")
     kv_len, _, _ = ctx.hh_get_lengths()
     kv_mid = int(np.mean(kv_len)) - K * (k + 1) // 4
 
@@ -184,6 +192,7 @@ def main():
     # per-kernel timing leg, on the launch stream: every kind of kernel is launched alone, in its
     # place in the pass (consecutive launches stream different layers' weights), between one HIP
     # event pair, so the average is launch duration + launch gap without per-launch event overhead
+    say("per-kernel timing")
     per_kind, draft_bytes, verify_bytes, commit_bytes = algorithmic_bytes(cfg, Bn, k, kv_mid)
     kernels = {}
     per_round = {1: k, 2: 1}
@@ -241,6 +250,7 @@ def main():
         "kernels": kernels,
     }
     if args.cpu_seconds > 0:
+        say("oracle baseline on the host cores")
         out["cpu_baseline"] = cpu_baseline(wl, weights, prompts, args.cpu_seconds)
     print(json.dumps(out))
 

@@ -308,7 +308,7 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(const Dims d, const Attn
       }
     }
   }
-  if (S == 1) return;
+  if (S == 1 || a.counters == nullptr) return;   // no counters: a merge kernel follows
 
   // Make the partials visible device-wide (release), then take a ticket; the workgroup that
   // draws the last ticket sees all of them after its acquire fence and merges the slices.
@@ -370,6 +370,57 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(const Dims d, const Attn
   TR(8);
 }
 
+// Merge of the key slices as a kernel of its own, for launches with many workgroups (there the
+// device-wide fence of the ticket scheme costs more than a kernel boundary).
+// grid: x = ceil(rows / 16), y = Hkv, z = B.
+__global__ __launch_bounds__(256) void attn_merge_kernel(const Dims d, const AttnArgs a) {
+  __shared__ float2 gm[16 * 64];   // [16 rows][S] (maximum, sum) of every slice
+  const int tid = threadIdx.x;
+  const int kvh = blockIdx.y, b = blockIdx.z;
+  const int Dh = d.Dh, G = d.Hq / d.Hkv, S = a.n_splits;
+  const int n_rows = a.T * G, row0 = blockIdx.x * 16;
+  for (int it = tid; it < 16 * S; it += 256) {
+    const int r = it / S, s = it - r * S, rr = row0 + r;
+    float2 v = make_float2(-INFINITY, 0.f);
+    if (rr < n_rows) {
+      const size_t rid = ((size_t)b * a.T + rr / G) * d.Hq + kvh * G + rr % G;
+      v = reinterpret_cast<const float2*>(a.part_ml)[rid * S + s];
+    }
+    gm[it] = v;
+  }
+  __syncthreads();
+  const int d4n = Dh >> 2;
+  for (int it = tid; it < 16 * d4n; it += 256) {
+    const int r = it / d4n, c4 = it - r * d4n, rr = row0 + r;
+    if (rr >= n_rows) continue;
+    const int j = rr / G, hq = kvh * G + rr % G;
+    const size_t rid = ((size_t)b * a.T + j) * d.Hq + hq;
+    float M = -INFINITY;
+    for (int s = 0; s < S; ++s) M = fmaxf(M, gm[r * S + s].x);
+    float4 out = make_float4(0.f, 0.f, 0.f, 0.f);
+    float L = 0.f;
+    for (int s0 = 0; s0 < S; s0 += 8) {                 // slice order: deterministic
+      float4 pv[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u)
+        pv[u] = *reinterpret_cast<const float4*>(a.part_o + (rid * S + min(s0 + u, S - 1)) * Dh + 4 * c4);
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {
+        if (s0 + u < S) {
+          const float2 ml = gm[r * S + s0 + u];
+          const float w = ml.x == -INFINITY ? 0.f : expf(ml.x - M);
+          L = fmaf(w, ml.y, L);
+          out.x = fmaf(w, pv[u].x, out.x); out.y = fmaf(w, pv[u].y, out.y);
+          out.z = fmaf(w, pv[u].z, out.z); out.w = fmaf(w, pv[u].w, out.w);
+        }
+      }
+    }
+    const float inv = L > 0.f ? 1.0f / L : 0.f;          // rows past the valid positions have empty slices
+    *reinterpret_cast<float4*>(a.o + ((size_t)b * a.T + j) * d.dq + (size_t)hq * Dh + 4 * c4) =
+        make_float4(out.x * inv, out.y * inv, out.z * inv, out.w * inv);
+  }
+}
+
 template <int RT, int KS>
 static hipError_t launch_t(const Dims& d, const AttnArgs& a, int row_chunks, hipStream_t s) {
   constexpr int Dhp = 32 * KS, QS = 3 * Dhp + 8;
@@ -413,16 +464,26 @@ int attention_mfma_row_chunks(const Dims& d, int T) {
   return (rows + per - 1) / per;
 }
 
-hipError_t launch_attention_mfma(const Dims& d, const AttnArgs& a, hipStream_t s) {
+static constexpr int kTicketMaxBlocks = 64;   // larger launches merge in a second kernel
+
+hipError_t launch_attention_mfma(const Dims& d, const AttnArgs& a_in, hipStream_t s) {
+  AttnArgs a = a_in;
   if (!d.bf16 || d.Dh > 256 || d.Dh % 8 != 0 || d.Dh < 8 || a.n_splits > 64 || a.n_splits < 1 || a.T < 1 || a.B < 1 ||
       d.page_tokens % 8 != 0 || (d.page_tokens & (d.page_tokens - 1)) != 0)
     return hipErrorInvalidValue;
   const int rt = mfma_row_tiles(d, a.T), row_chunks = attention_mfma_row_chunks(d, a.T);
   const int ks = (d.Dh + 31) / 32;
-  if (ks == 1) return launch_ks<1>(d, a, rt, row_chunks, s);
-  if (ks == 2) return launch_ks<2>(d, a, rt, row_chunks, s);
-  if (ks <= 4) return launch_ks<4>(d, a, rt, row_chunks, s);
-  return launch_ks<8>(d, a, rt, row_chunks, s);
+  const bool two_kernels = a.n_splits > 1 && (long)row_chunks * a.n_splits * d.Hkv * a.B > kTicketMaxBlocks;
+  if (two_kernels) a.counters = nullptr;
+  hipError_t e;
+  if (ks == 1) e = launch_ks<1>(d, a, rt, row_chunks, s);
+  else if (ks == 2) e = launch_ks<2>(d, a, rt, row_chunks, s);
+  else if (ks <= 4) e = launch_ks<4>(d, a, rt, row_chunks, s);
+  else e = launch_ks<8>(d, a, rt, row_chunks, s);
+  if (e != hipSuccess || !two_kernels) return e;
+  const int rows = a.T * (d.Hq / d.Hkv);
+  hipLaunchKernelGGL(attn_merge_kernel, dim3((rows + 15) / 16, d.Hkv, a.B), dim3(256), 0, s, d, a);
+  return hipGetLastError();
 }
 
 }  // namespace hh

@@ -62,6 +62,7 @@ struct hh_ctx {
   std::string err;
   // optional per-launch timing (hh_profile): event pairs tagged phase*16 + kind
   bool prof_on = false;
+  void* p_lm_head = nullptr;   // LM head in the packed tile layout (bf16 weights)
   int only_kind = -1;   // hh_time_kind: launch only this kind of kernel
   int prof_phase = 0;
   std::vector<hipEvent_t> prof_ev;
@@ -177,11 +178,22 @@ size_t carve(hh_ctx* x, char* base) {
     char* kp = c.take<char>(pool);
     char* vp = c.take<char>(pool);
     char* wf = c.take<char>((size_t)d.ldzx * d.D * esz);
+    uint16_t *pi = nullptr, *po = nullptr, *poo = nullptr, *pg = nullptr, *pu = nullptr, *pd = nullptr;
+    if (d.bf16) {
+      pi = c.take<uint16_t>(packed_weight_elems(d.ldzx, d.D));
+      po = c.take<uint16_t>(packed_weight_elems(d.D, d.d_inner));
+      poo = c.take<uint16_t>(packed_weight_elems(d.D, d.dq));
+      pg = c.take<uint16_t>(packed_weight_elems(d.F, d.D));
+      pu = c.take<uint16_t>(packed_weight_elems(d.F, d.D));
+      pd = c.take<uint16_t>(packed_weight_elems(d.D, d.F));
+    }
     if (base) {
       LayerDev& ld = x->layers_host[l];
       ld.S = S; ld.S_draft = Sd; ld.ring = rg; ld.kpool = kp; ld.vpool = vp; ld.w_inqkv = wf;
+      ld.p_inqkv = pi; ld.p_out = po; ld.p_o = poo; ld.p_gate = pg; ld.p_up = pu; ld.p_down = pd;
     }
   }
+  x->p_lm_head = d.bf16 ? c.take<uint16_t>(packed_weight_elems(d.V, d.D)) : nullptr;
   return (c.off + kAlign - 1) / kAlign * kAlign;
 }
 
@@ -213,10 +225,25 @@ hh_status fail(hh_ctx* x, hh_status st, const std::string& msg) {
     if (p_) HH_HIP(hipEventRecord(x->prof_ev.back(), s));                                      \
   } while (0)
 
-// One dense projection: the weight-streaming FMA kernel for a few activation rows, the matrix
-// cores beyond that (bf16 weights).
+// One dense projection with bf16 weights: the weight-streaming FMA kernel for up to 3 activation
+// rows, the matrix-core kernel with in-kernel activation split for 4..16 rows where it fits, the
+// matrix-core GEMM over pre-split activations for 9 rows and more otherwise.  float32 weights:
+// the FMA kernel.
 constexpr int kMfmaMinRows = 9;
+int skinny_min_rows() {
+  static const int v = getenv("HH_SKINNY_MINROWS") ? atoi(getenv("HH_SKINNY_MINROWS")) : 4;
+  return v;
+}
+// the arguments with the packed weights in place of the row-major ones, if this product can take the skinny kernel
+bool skinny_args(const GemvArgs& a, GemvArgs& b) {
+  if (!a.bf16 || a.M < skinny_min_rows() || a.M > 16 || a.seg[0].P == nullptr) return false;
+  b = a;
+  b.seg[0].W = a.seg[0].P; b.seg[0].W2 = a.seg[0].P2;
+  return skinny_mfma_fits(b);
+}
 hipError_t product(hh_ctx* x, const GemvArgs& a, hipStream_t s) {
+  GemvArgs b;
+  if (skinny_args(a, b)) return launch_skinny_mfma(b, nullptr, s);
   if (a.bf16 && a.M >= kMfmaMinRows) return launch_gemm_mfma(a, x->planes, s);
   return launch_gemv(a, nullptr, s);
 }
@@ -231,7 +258,7 @@ hh_status run_layers(hh_ctx* x, bool full, int B, int T, const int* n_tok, int s
     {  // shared input norm, Mamba-2 input projection (+ q, k, v of the attention branch)
       GemvArgs a{};
       a.X = x->h; a.ldx = d.D; a.M = M; a.K = d.D; a.norm_w = w.norm1; a.eps = d.eps; a.epi = EPI_STORE; a.bf16 = d.bf16;
-      a.seg[0] = {w.w_inqkv, nullptr, x->zx, full ? d.ldzx : d.d_in_proj, d.ldzx};
+      a.seg[0] = {w.w_inqkv, nullptr, w.p_inqkv, nullptr, x->zx, full ? d.ldzx : d.d_in_proj, d.ldzx};
       a.n_seg = 1;
       HH_LAUNCH(HH_K_IN_PROJ, product(x, a, s));
     }
@@ -268,23 +295,23 @@ hh_status run_layers(hh_ctx* x, bool full, int B, int T, const int* n_tok, int s
     {  // h += W_out * gated_norm(g)   (+ W_o * o in full mode: the two branches are summed)
       GemvArgs a{};
       a.X = x->g; a.ldx = d.d_inner; a.M = M; a.K = d.d_inner; a.norm_w = w.gnorm; a.eps = d.eps; a.epi = EPI_ADD; a.bf16 = d.bf16;
-      a.seg[0] = {w.w_out, nullptr, x->h, d.D, d.D}; a.n_seg = 1;
+      a.seg[0] = {w.w_out, nullptr, w.p_out, nullptr, x->h, d.D, d.D}; a.n_seg = 1;
       HH_LAUNCH(HH_K_OUT_PROJ, product(x, a, s));
       if (full) {
         GemvArgs b{};
         b.X = x->o; b.ldx = d.dq; b.M = M; b.K = d.dq; b.norm_w = nullptr; b.epi = EPI_ADD; b.bf16 = d.bf16;
-        b.seg[0] = {w.w_o, nullptr, x->h, d.D, d.D}; b.n_seg = 1;
+        b.seg[0] = {w.w_o, nullptr, w.p_o, nullptr, x->h, d.D, d.D}; b.n_seg = 1;
         HH_LAUNCH(HH_K_O_PROJ, product(x, b, s));
       }
     }
     {  // SwiGLU MLP
       GemvArgs a{};
       a.X = x->h; a.ldx = d.D; a.M = M; a.K = d.D; a.norm_w = w.norm2; a.eps = d.eps; a.epi = EPI_SWIGLU; a.bf16 = d.bf16;
-      a.seg[0] = {w.w_gate, w.w_up, x->act, d.F, d.F}; a.n_seg = 1;
+      a.seg[0] = {w.w_gate, w.w_up, w.p_gate, w.p_up, x->act, d.F, d.F}; a.n_seg = 1;
       HH_LAUNCH(HH_K_MLP_UP, product(x, a, s));
       GemvArgs b{};
       b.X = x->act; b.ldx = d.F; b.M = M; b.K = d.F; b.norm_w = nullptr; b.epi = EPI_ADD; b.bf16 = d.bf16;
-      b.seg[0] = {w.w_down, nullptr, x->h, d.D, d.D}; b.n_seg = 1;
+      b.seg[0] = {w.w_down, nullptr, w.p_down, nullptr, x->h, d.D, d.D}; b.n_seg = 1;
       HH_LAUNCH(HH_K_MLP_DOWN, product(x, b, s));
     }
   }
@@ -298,7 +325,14 @@ hh_status run_head(hh_ctx* x, const float* X, int M, int T, float* logits, int l
   GemvArgs a{};
   a.X = X; a.ldx = d.D; a.M = M; a.K = d.D; a.norm_w = static_cast<const float*>(x->final_norm); a.eps = d.eps;
   a.epi = EPI_STORE; a.bf16 = d.bf16; a.best = x->best;
-  a.seg[0] = {x->lm_head, nullptr, logits, d.V, ld_logits}; a.n_seg = 1;
+  a.seg[0] = {x->lm_head, nullptr, x->p_lm_head, nullptr, logits, d.V, ld_logits}; a.n_seg = 1;
+  GemvArgs sk;
+  if (skinny_args(a, sk)) {
+    int nb = 0;
+    HH_LAUNCH(HH_K_LM_HEAD, launch_skinny_mfma(sk, &nb, s));
+    HH_HIP(launch_argmax_finish(x->best, nb, M, out, out_stride, out_off, T, s));
+    return HH_OK;
+  }
   if (a.bf16 && M >= kMfmaMinRows) {
     a.best = nullptr;
     HH_LAUNCH(HH_K_LM_HEAD, launch_gemm_mfma(a, x->planes, s));
@@ -344,7 +378,7 @@ hh_status run_graphed(hh_ctx* x, long long key, hipStream_t s, F enqueue) {
 // Key slices per (sequence, KV head, row chunk) of a verification pass: enough workgroups to
 // cover the chip, but no slice smaller than the unit of work of the kernel.
 int pick_splits(const Dims& d, int B, int T, int len_upper) {
-  static const int cap = getenv("HH_ATTN_MAXSPLIT") ? atoi(getenv("HH_ATTN_MAXSPLIT")) : kMaxSplits;
+  static const int cap = getenv("HH_ATTN_MAXSPLIT") ? atoi(getenv("HH_ATTN_MAXSPLIT")) : 16;
   int s;
   if (attention_uses_mfma(d)) {
     const int blocks = attention_mfma_row_chunks(d, T) * d.Hkv * B;
@@ -434,6 +468,22 @@ hh_status hh_create(const hh_weights* weights, const hh_cfg* cfg, hh_ctx** out) 
     delete ctx;
     return fail(nullptr, HH_EDEVICE, std::string(what) + ": " + hipGetErrorString(e));
   };
+  if (d.bf16) {   // copies of every matrix in the tile layout of the matrix-core kernels
+    hipError_t pe = hipSuccess;
+    auto pack = [&](const void* W, int N, int K, void* P) { if (pe == hipSuccess) pe = launch_pack_weights(W, N, K, (size_t)K, P, nullptr); };
+    for (int l = 0; l < d.L; ++l) {
+      const LayerDev& ld = ctx->layers_host[l];
+      pack(ld.w_inqkv, d.ldzx, d.D, ld.p_inqkv);
+      pack(ld.w_out, d.D, d.d_inner, ld.p_out);
+      pack(ld.w_o, d.D, d.dq, ld.p_o);
+      pack(ld.w_gate, d.F, d.D, ld.p_gate);
+      pack(ld.w_up, d.F, d.D, ld.p_up);
+      pack(ld.w_down, d.D, d.F, ld.p_down);
+    }
+    pack(ctx->lm_head, d.V, d.D, ctx->p_lm_head);
+    if (pe == hipSuccess) pe = hipDeviceSynchronize();
+    if (pe != hipSuccess) return bail(pe, "hh_create: packing the weights");
+  }
   hipError_t e = hipMemcpy(ctx->layers_dev, ctx->layers_host.data(), sizeof(LayerDev) * d.L, hipMemcpyHostToDevice);
   if (e != hipSuccess) return bail(e, "hh_create: upload of layer table");
   e = hipMemset(ctx->attn_counters, 0, sizeof(int) * (size_t)d.Bmax * d.Hkv * attention_row_chunks(d, d.Tmax));

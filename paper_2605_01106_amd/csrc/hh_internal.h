@@ -26,6 +26,8 @@ struct LayerDev {
   const float *norm1, *conv_w, *conv_b, *a_log, *d_skip, *dt_bias, *gnorm, *norm2;
   const void *w_in, *w_out, *w_q, *w_k, *w_v, *w_o, *w_gate, *w_up, *w_down;
   void* w_inqkv;   // library-owned copy [d_in_proj + dqkv][D]: rows of w_in, w_q, w_k, w_v stacked
+  // library-owned copies in the tile layout of the matrix-core kernels (bf16 weights only, else nullptr)
+  void *p_inqkv, *p_out, *p_o, *p_gate, *p_up, *p_down;
   float* S;        // committed SSM state of this layer   [B][Hm][P][N]
   float* S_draft;  // draft scratch state                 [B][Hm][P][N]
   float* ring;     // raw conv inputs, ring over positions [B][ring_slots][ring_w]
@@ -38,6 +40,8 @@ enum { EPI_STORE = 0, EPI_ADD = 1, EPI_SWIGLU = 2 };
 struct GemvSeg {
   const void* W;    // [n_rows][K]
   const void* W2;   // EPI_SWIGLU: the "up" matrix paired row by row with W (gate)
+  const void* P;    // the same matrices in the packed tile layout (nullptr: not available)
+  const void* P2;
   float* Y;         // [M][ldy], row n of this segment lands in column n
   int n_rows, ldy;
 };
@@ -51,6 +55,13 @@ struct GemvArgs {
 };
 hipError_t launch_gemv(const GemvArgs& a, int* n_blocks_out, hipStream_t s);
 int gemv_max_blocks();   // upper bound on gridDim.x of launch_gemv (size of the argmax partial rows)
+
+// ---- the same product for 1..16 activation rows on the matrix cores (bf16 weights; activations split in-kernel)
+// (weights in the packed tile layout written by launch_pack_weights; seg[0].W / W2 point to packed copies)
+__host__ __device__ size_t packed_weight_elems(int N, int K);
+hipError_t launch_pack_weights(const void* W, int N, int K, size_t ldw, void* P, hipStream_t s);
+bool skinny_mfma_fits(const GemvArgs& a);
+hipError_t launch_skinny_mfma(const GemvArgs& a, int* n_blocks_out, hipStream_t s);
 
 // ---- the same product on the matrix cores (bf16 weights, more than a few activation rows)
 size_t gemm_planes_elems(int M, int K);   // bf16 elements of scratch for the split activations

@@ -31,13 +31,15 @@ def test_workspace_sizes(B):
     c1 = W.WORKLOADS["c1"]
     cfg = B.make_cfg(c1.cfg, 1, 1024, 2, 256)
     n = B.hh_workspace_bytes(cfg)
-    # at least the KV pool, both SSM states and the logits scratch
+    # at least the KV pool, both SSM states and the library's copies of the bf16 matrices (tile
+    # layout of the matrix-core kernels, plus the stacked input projections)
     kv = 36 * 1024 * 2 * 2 * 64 * 2
     ssm = 2 * 36 * 24 * 64 * 128 * 4
-    assert n > kv + ssm and n < 4 * (kv + ssm) + (1 << 28)
+    mats = 2 * c1.cfg.step_params(False)
+    assert n > kv + ssm + mats and n < 4 * (kv + ssm) + (1 << 28) + 1.4 * mats
     c4 = W.WORKLOADS["c4"]
     big = B.hh_workspace_bytes(B.make_cfg(c4.cfg, 64, 32768 + 128 + 18, 8, 128, prefill_chunk=16))
-    assert 69e9 < big < 120e9
+    assert 69e9 < big < 130e9
 
 
 @pytest.mark.parametrize("field,value", [("n_groups", 2), ("d_conv", 3), ("n_kv_heads", 3), ("head_dim", 12),

@@ -472,9 +472,11 @@ bool attention_uses_mfma(const Dims& d) {
 hipError_t launch_attention(const Dims& d, const AttnArgs& a, hipStream_t s) {
   if (d.Dh > kMaxDh || d.Dh % 8 != 0 || a.n_splits > 64 || a.n_splits < 1 || a.T < 1 || a.B < 1) return hipErrorInvalidValue;
   if (attention_uses_mfma(d)) {
-    hipLaunchKernelGGL(kv_append_kernel, dim3(a.B * a.T), dim3(256), 0, s, d, a);
-    hipError_t e = hipGetLastError();
-    if (e != hipSuccess) return e;
+    if (!attention_mfma_fuses_append(d, a.T)) {
+      hipLaunchKernelGGL(kv_append_kernel, dim3(a.B * a.T), dim3(256), 0, s, d, a);
+      hipError_t e = hipGetLastError();
+      if (e != hipSuccess) return e;
+    }
     return launch_attention_mfma(d, a, s);
   }
   const int G = d.Hq / d.Hkv;

@@ -25,6 +25,8 @@ namespace hh {
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
+int attention_mfma_row_chunks(const Dims& d, int T);
+
 static constexpr int kStepKeys = 32;   // keys per wavefront step
 static constexpr int kMergeLd = 20;    // row stride (floats) of the in-workgroup merge buffer
 
@@ -53,7 +55,13 @@ __device__ __forceinline__ float xor_add(float v) {
 
 // grid: x = row_chunks * n_splits, y = Hkv, z = B.  RT = 16-row tiles per workgroup,
 // KS = ceil(Dh / 32).
-template <int RT, int KS>
+//
+// FUSE (verification: at most 16 new positions, one row chunk): the keys and values of the new
+// positions are not in the cache yet.  The cached keys (positions < pos0) are visible to every
+// row; one wavefront of the launch builds the operands of the new positions from the projection
+// buffer (rotating and rounding k, rounding v), appends them to the cache and scores them as
+// one more step with the causal mask.  Otherwise the cache already holds them (prefill).
+template <int RT, int KS, bool FUSE>
 __global__ __launch_bounds__(256) void attn_mfma_kernel(const Dims d, const AttnArgs a, const int row_chunks) {
   constexpr int NDB = 2 * KS;            // blocks of 16 output dimensions
   constexpr int Dhp = 32 * KS;           // head dimension padded to the MFMA depth
@@ -78,7 +86,8 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(const Dims d, const Attn
   const int row_lim = min(n_rows, nt * G);     // row = position j * G + query head of the group; valid while j < nt
   const int row0 = chunk * R;
   const int jmax = row0 < row_lim ? (min(row_lim, row0 + R) - 1) / G : -1;
-  const int nk = jmax < 0 ? 0 : pos0 + jmax + 1;          // keys 0 .. nk-1 are visible to some row of this chunk
+  const int nk_all = jmax < 0 ? 0 : pos0 + jmax + 1;      // keys 0 .. nk_all-1 are visible to some row of this chunk
+  const int nk = FUSE ? min(nk_all, pos0) : nk_all;       // ... of which the cache holds 0 .. nk-1
   const int* pt_row = a.page_table + (size_t)b * d.pages_per_seq;
   const int pshift = 31 - __clz(d.page_tokens), pmask = d.page_tokens - 1;
   const uint16_t* kp = static_cast<const uint16_t*>(a.kpool);
@@ -167,7 +176,7 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(const Dims d, const Attn
 #pragma unroll
   for (int rt = 0; rt < RT; ++rt) {
     const int rr = row0 + rt * 16 + n;
-    lim[rt] = rr < row_lim ? pos0 + rr / G : -1;
+    lim[rt] = rr < row_lim ? (FUSE ? pos0 - 1 : pos0 + rr / G) : -1;
   }
   float mrun[RT], lrun[RT];
   f32x4 acc[RT][NDB];
@@ -178,10 +187,9 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(const Dims d, const Attn
     for (int db = 0; db < NDB; ++db) acc[rt][db] = f32x4{0.f, 0.f, 0.f, 0.f};
   }
 
-  for (int step = ws; step < we; ++step) {
-    Frag kA2[KS], kB2[KS], vT2[NDB];
-    if (step + 1 < we) load_step(step + 1, kA2, kB2, vT2);
-    const int kbase = step * kStepKeys + 8 * g;   // the lane's 8 keys: kbase .. kbase + 7
+  // one step of 32 keys: scores, online softmax, output.  The lane's 8 keys are kbase .. kbase+7,
+  // visible to the lane's row of tile rt while <= limit[rt].
+  auto score_step = [&](const Frag(&ka)[KS], const Frag(&kb)[KS], const Frag(&vt)[NDB], const int kbase, const int(&limit)[RT]) {
 #pragma unroll
     for (int rt = 0; rt < RT; ++rt) {
       // large tiles: re-read the query fragments from LDS every step instead of keeping all
@@ -195,15 +203,15 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(const Dims d, const Attn
         for (int term = 0; term < 3; ++term) {
           Frag q;
           q.u = *reinterpret_cast<const uint4*>(qrow + term * Dhp + ks * 32);
-          sA = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kA[ks].v, q.v, sA, 0, 0, 0);
-          sB = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kB[ks].v, q.v, sB, 0, 0, 0);
+          sA = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka[ks].v, q.v, sA, 0, 0, 0);
+          sB = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kb[ks].v, q.v, sB, 0, 0, 0);
         }
       }
       float sc[8] = {sA[0], sA[1], sA[2], sA[3], sB[0], sB[1], sB[2], sB[3]};
       float mx = -INFINITY;
 #pragma unroll
       for (int i = 0; i < 8; ++i) {
-        sc[i] = kbase + i <= lim[rt] ? sc[i] : -INFINITY;
+        sc[i] = kbase + i <= limit[rt] ? sc[i] : -INFINITY;
         mx = fmaxf(mx, sc[i]);
       }
       const float mnew = fmaxf(mrun[rt], xor_max(mx));
@@ -226,12 +234,101 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(const Dims d, const Attn
       for (int db = 0; db < NDB; ++db) {
         f32x4 c = acc[rt][db];
         c[0] *= corr; c[1] *= corr; c[2] *= corr; c[3] *= corr;
-        c = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vT[db].v, p0.v, c, 0, 0, 0);
-        c = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vT[db].v, p1.v, c, 0, 0, 0);
-        c = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vT[db].v, p2.v, c, 0, 0, 0);
+        c = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vt[db].v, p0.v, c, 0, 0, 0);
+        c = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vt[db].v, p1.v, c, 0, 0, 0);
+        c = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vt[db].v, p2.v, c, 0, 0, 0);
         acc[rt][db] = c;
       }
     }
+  };
+
+  // ---- the new positions (FUSE): operands from the projection buffer, by one wavefront of the launch
+  if (FUSE && sp == S - 1 && wave == 3 && nk_all > pos0) {
+    const float2* rope = reinterpret_cast<const float2*>(a.rope);
+    const bool al4 = (d.ldzx & 3) == 0 && (reinterpret_cast<uintptr_t>(xrow) & 15) == 0;   // 16-byte aligned rows (dq, Dh are multiples of 8)
+    Frag nA[KS], nB[KS], nV[NDB];
+    uint16_t* kpw = static_cast<uint16_t*>(a.kpool);
+    uint16_t* vpw = static_cast<uint16_t*>(a.vpool);
+    auto load8 = [&](const float* src, float(&o)[8]) {
+      if (al4) {
+        const float4 x = *reinterpret_cast<const float4*>(src), y = *reinterpret_cast<const float4*>(src + 4);
+        o[0] = x.x; o[1] = x.y; o[2] = x.z; o[3] = x.w; o[4] = y.x; o[5] = y.y; o[6] = y.z; o[7] = y.w;
+      } else {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) o[i] = src[i];
+      }
+    };
+    // values of the new positions first (their loads overlap the rotation of the keys below)
+    float vraw[NDB][8];
+    size_t vat[8];
+    {
+      const float* vbase = xrow + d.dq + d.dkv + (size_t)kvh * Dh;
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        const int jc = min(8 * g + i, nt - 1), pos = pos0 + jc;
+        vat[i] = ((size_t)pt_row[pos >> pshift] * d.Hkv + kvh) * Dh * d.page_tokens + (pos & pmask);
+#pragma unroll
+        for (int db = 0; db < NDB; ++db) vraw[db][i] = vbase[(size_t)jc * d.ldzx + min(db * 16 + n, Dh - 1)];
+      }
+    }
+#pragma unroll
+    for (int blk = 0; blk < 2; ++blk) {
+      const int j = 8 * (n >> 2) + (n & 3) + 4 * blk;            // new position of this lane's key row
+      const bool live = j < nt;
+      const int jc = min(j, nt - 1);
+      const float* kr = xrow + (size_t)jc * d.ldzx + d.dq + (size_t)kvh * Dh;
+      const size_t kat = (((size_t)pt_row[(pos0 + jc) >> pshift] * d.Hkv + kvh) * d.page_tokens + ((pos0 + jc) & pmask)) * Dh;
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks) {
+        const int d0 = ks * 32 + 8 * g;
+        Frag f;
+        f.u = make_uint4(0, 0, 0, 0);
+        if (d0 < Dh && (blk == 0 || nt > 4)) {                   // the second block only holds positions 4..7, 12..15
+          const bool low = d0 < half;                            // an 8-dim group lies in one half (Dh % 16 == 0 here)
+          float x[8], xp[8];
+          load8(kr + d0, x);
+          load8(kr + (low ? d0 + half : d0 - half), xp);
+          const float2* cs = rope + (size_t)(pos0 + jc) * half + (low ? d0 : d0 - half);
+          uint32_t h[8];
+#pragma unroll
+          for (int i = 0; i < 8; ++i) {
+            const float2 c = cs[i];
+            const float r = low ? x[i] * c.x - xp[i] * c.y : x[i] * c.x + xp[i] * c.y;
+            h[i] = live ? f32_to_bf16_rne(r) : 0u;
+          }
+          f.u = make_uint4(h[0] | (h[1] << 16), h[2] | (h[3] << 16), h[4] | (h[5] << 16), h[6] | (h[7] << 16));
+          if (live) *reinterpret_cast<uint4*>(kpw + kat + d0) = f.u;
+        }
+        if (blk == 0) nA[ks] = f; else nB[ks] = f;
+      }
+    }
+#pragma unroll
+    for (int db = 0; db < NDB; ++db) {
+      const int dim = db * 16 + n;
+      uint32_t h[8];
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        h[i] = 0u;
+        if (8 * g + i < nt && dim < Dh) {
+          h[i] = f32_to_bf16_rne(vraw[db][i]);
+          vpw[vat[i] + (size_t)dim * d.page_tokens] = (uint16_t)h[i];
+        }
+      }
+      nV[db].u = make_uint4(h[0] | (h[1] << 16), h[2] | (h[3] << 16), h[4] | (h[5] << 16), h[6] | (h[7] << 16));
+    }
+    int limn[RT];
+#pragma unroll
+    for (int rt = 0; rt < RT; ++rt) {
+      const int rr = row0 + rt * 16 + n;
+      limn[rt] = rr < row_lim ? rr / G : -1;                     // new position j is visible to position rr / G >= j
+    }
+    score_step(nA, nB, nV, 8 * g, limn);
+  }
+
+  for (int step = ws; step < we; ++step) {
+    Frag kA2[KS], kB2[KS], vT2[NDB];
+    if (step + 1 < we) load_step(step + 1, kA2, kB2, vT2);
+    score_step(kA, kB, vT, step * kStepKeys + 8 * g, lim);
     if (step + 1 < we) {
 #pragma unroll
       for (int ks = 0; ks < KS; ++ks) { kA[ks] = kA2[ks]; kB[ks] = kB2[ks]; }
@@ -421,7 +518,7 @@ __global__ __launch_bounds__(256) void attn_merge_kernel(const Dims d, const Att
   }
 }
 
-template <int RT, int KS>
+template <int RT, int KS, bool FUSE>
 static hipError_t launch_t(const Dims& d, const AttnArgs& a, int row_chunks, hipStream_t s) {
   constexpr int Dhp = 32 * KS, QS = 3 * Dhp + 8;
   size_t scratch = (size_t)(3 * Dhp * kMergeLd + 3 * 16 * 2) * sizeof(float);
@@ -430,25 +527,30 @@ static hipError_t launch_t(const Dims& d, const AttnArgs& a, int row_chunks, hip
   const size_t lds = (size_t)RT * 16 * QS * 2 + scratch;
   static size_t lds_enabled = 48 * 1024;
   if (lds > lds_enabled) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(attn_mfma_kernel<RT, KS>),
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(attn_mfma_kernel<RT, KS, FUSE>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
     lds_enabled = lds;
   }
-  hipLaunchKernelGGL((attn_mfma_kernel<RT, KS>), dim3(row_chunks * a.n_splits, d.Hkv, a.B), dim3(256), lds, s, d, a,
+  hipLaunchKernelGGL((attn_mfma_kernel<RT, KS, FUSE>), dim3(row_chunks * a.n_splits, d.Hkv, a.B), dim3(256), lds, s, d, a,
                      row_chunks);
   return hipGetLastError();
 }
 
-template <int KS>
+template <int KS, bool FUSE>
 static hipError_t launch_ks(const Dims& d, const AttnArgs& a, int rt, int row_chunks, hipStream_t s) {
   switch (rt) {
-    case 1: return launch_t<1, KS>(d, a, row_chunks, s);
-    case 2: return launch_t<2, KS>(d, a, row_chunks, s);
-    case 3: if (KS < 8) return launch_t<(KS < 8 ? 3 : 1), KS>(d, a, row_chunks, s); break;
-    case 4: if (KS < 8) return launch_t<(KS < 8 ? 4 : 1), KS>(d, a, row_chunks, s); break;
+    case 1: return launch_t<1, KS, FUSE>(d, a, row_chunks, s);
+    case 2: return launch_t<2, KS, FUSE>(d, a, row_chunks, s);
+    case 3: if (KS < 8) return launch_t<(KS < 8 ? 3 : 1), KS, FUSE>(d, a, row_chunks, s); break;
+    case 4: if (KS < 8) return launch_t<(KS < 8 ? 4 : 1), KS, FUSE>(d, a, row_chunks, s); break;
   }
   return hipErrorInvalidValue;
+}
+
+// the kernel appends the new keys itself: few new positions, one row chunk, 8-dim groups that do not straddle the rotation halves
+bool attention_mfma_fuses_append(const Dims& d, int T) {
+  return T <= 16 && attention_mfma_row_chunks(d, T) == 1 && d.Dh % 16 == 0;
 }
 
 // rows (position x query head of a KV group) per workgroup, in tiles of 16
@@ -476,10 +578,17 @@ hipError_t launch_attention_mfma(const Dims& d, const AttnArgs& a_in, hipStream_
   const bool two_kernels = a.n_splits > 1 && (long)row_chunks * a.n_splits * d.Hkv * a.B > kTicketMaxBlocks;
   if (two_kernels) a.counters = nullptr;
   hipError_t e;
-  if (ks == 1) e = launch_ks<1>(d, a, rt, row_chunks, s);
-  else if (ks == 2) e = launch_ks<2>(d, a, rt, row_chunks, s);
-  else if (ks <= 4) e = launch_ks<4>(d, a, rt, row_chunks, s);
-  else e = launch_ks<8>(d, a, rt, row_chunks, s);
+  if (attention_mfma_fuses_append(d, a.T)) {
+    if (ks == 1) e = launch_ks<1, true>(d, a, rt, row_chunks, s);
+    else if (ks == 2) e = launch_ks<2, true>(d, a, rt, row_chunks, s);
+    else if (ks <= 4) e = launch_ks<4, true>(d, a, rt, row_chunks, s);
+    else e = launch_ks<8, true>(d, a, rt, row_chunks, s);
+  } else {
+    if (ks == 1) e = launch_ks<1, false>(d, a, rt, row_chunks, s);
+    else if (ks == 2) e = launch_ks<2, false>(d, a, rt, row_chunks, s);
+    else if (ks <= 4) e = launch_ks<4, false>(d, a, rt, row_chunks, s);
+    else e = launch_ks<8, false>(d, a, rt, row_chunks, s);
+  }
   if (e != hipSuccess || !two_kernels) return e;
   const int rows = a.T * (d.Hq / d.Hkv);
   hipLaunchKernelGGL(attn_merge_kernel, dim3((rows + 15) / 16, d.Hkv, a.B), dim3(256), 0, s, d, a);

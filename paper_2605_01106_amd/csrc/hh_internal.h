@@ -100,6 +100,7 @@ int attention_row_chunks(const Dims& d, int T);
 hipError_t launch_attention(const Dims& d, const AttnArgs& a, hipStream_t s);
 bool attention_uses_mfma(const Dims& d);
 int attention_mfma_row_chunks(const Dims& d, int T);
+bool attention_mfma_fuses_append(const Dims& d, int T);
 // bf16 cache, new keys already appended: the matrix-core kernel alone
 hipError_t launch_attention_mfma(const Dims& d, const AttnArgs& a, hipStream_t s);
 

@@ -1,19 +1,23 @@
-// Dense projections on the matrix cores, for passes with more than a handful of activation
-// rows (batched drafting, batched verification, prefill): Y[M x N] = X'[M x K] * W[N x K]^T with
-// bf16 weights.
+// Dense projections on the matrix cores for passes with many activation rows (batched drafting
+// beyond 16 rows, batched verification, prefill): Y[M x N] (op)= X'[M x K] * W[N x K]^T, bf16
+// weights in the packed operand tiles.
 //
 // Activations stay float32-accurate: a first kernel applies the fused RMSNorm and splits every
-// value into three bf16 terms, x = t0 + t1 + t2 exactly (8 + 8 + 8 mantissa bits); the product
-// is the sum of three bf16 MFMA products accumulated in float32.  While the pass is bound by
-// streaming the weights the two extra MFMAs per weight fragment are free.
+// value into three bf16 terms, x = t0 + t1 + t2 exactly (8 + 8 + 8 mantissa bits), stored as
+// three planes; the product is the sum of three bf16 MFMA products accumulated in float32.
 //
-// GEMM kernel: a workgroup owns a strip of 16 output columns (16 gate + 16 up columns for
-// SwiGLU) and up to 128 activation rows; its wavefronts split K.  Per step of 32 columns of K a
-// wavefront loads its weight fragment straight from global memory into registers (v_mfma_f32_16x16x32_bf16 B operand:
-// lane l holds W[n0 + l%16][k0 + 8*(l/16) .. +7], one 16-byte load) and reuses them for every
-// 16-row tile and every split term of the activations (A operand: lane l holds
-// A[m0 + l%16][k0 + 8*(l/16) .. +7], read from the split planes through L1/L2).  No LDS.
-// Accumulator layout: lane l holds C[4*(l/16) + r][l%16], r = 0..3.
+// GEMM kernel: a wavefront is an independent unit of work - NT strips of 16 weight rows x
+// MTW tiles of 16 activation rows x a range of K steps - with all accumulators in registers
+// and no LDS.  Per step of 32 columns it loads NT weight tiles (A operand, 1 KB contiguous each,
+// from HBM) and 3 x MTW activation fragments (B operand, from the planes, which stay in L2)
+// and issues 3 x NT x MTW MFMAs; the next step is requested before the current one is
+// multiplied.  The activation fragments are shared by the NT strips, so L2 traffic is
+// 3 MTW / NT times the weight traffic.  When N is small the K range is split over units to
+// cover the chip; the partial products go to a scratch buffer and a second kernel adds them
+// in split order (deterministic) and applies the epilogue.  With one split the epilogue runs
+// in the GEMM kernel.  Accumulator layout: lane l holds D[weight row 4(l/16)+r][activation row l%16].
+#include <stdlib.h>
+
 #include "hh_internal.h"
 
 namespace hh {
@@ -21,7 +25,6 @@ namespace hh {
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
-static constexpr int kTiles = 8;   // 16-row tiles per launch (128 activation rows)
 
 __device__ __forceinline__ uint16_t bf16_rne(float f) {
   uint32_t u = __float_as_uint(f);
@@ -64,109 +67,131 @@ __global__ __launch_bounds__(256) void split_rows_kernel(const float* __restrict
 }
 
 struct GemmArgs {
-  const uint16_t* planes; int Mp, Kp;     // split activations
-  const uint16_t* W; const uint16_t* W2;  // [N][K] bf16 (W2: the "up" matrix for SwiGLU)
+  const uint16_t* planes; int Mp, Kp;     // split activations [3][Mp][Kp]
+  const uint16_t* W; const uint16_t* W2;  // packed tiles (W2: the "up" matrix for SwiGLU)
   float* Y; int ldy;
-  int M, N, K, m0, mt;                    // rows m0 .. m0 + 16*mt of the planes in this launch
-  int ksteps;                             // steps of 32 columns per wavefront (K split over the workgroup)
+  float* partial;                         // [ksplit][NF][M][N] when ksplit > 1
+  int M, N, K;
+  int strip_groups, m_groups, ksplit;     // units = strip_groups * m_groups * ksplit
+  int ksteps;                             // steps of 32 columns per unit
 };
 
-static constexpr int kGroupK = 2;   // weight fragments loaded ahead, in steps of 32 columns
+union GFrag {
+  uint4 u;
+  bf16x8 v;
+};
 
-// One workgroup per strip of 16 output columns; its KS wavefronts split K between them and add
-// their partial tiles through LDS.  Small per-wavefront work, many wavefronts: the weights of a
-// wavefront's K slice are requested up to 8 steps ahead.
-template <int EPI>
-__global__ __launch_bounds__(512) void gemm_mfma_kernel(const GemmArgs a) {
+template <int EPI, int NT, int MTW>
+__global__ __launch_bounds__(256) void gemm_tiled_kernel(const GemmArgs a) {
   constexpr int NF = EPI == EPI_SWIGLU ? 2 : 1;
-  extern __shared__ __align__(16) float red[];   // [KS][mt][NF][64][4]
   const int lane = threadIdx.x & 63;
-  const int ks = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-  const int KS = blockDim.x >> 6;
-  const int i = lane & 15, g = lane >> 4;
-  const int n0 = blockIdx.x * 16;
-  const size_t wr = (size_t)min(n0 + i, a.N - 1) * a.K;
-  const uint16_t* wrow[2] = {a.W + wr, EPI == EPI_SWIGLU ? a.W2 + wr : a.W + wr};
+  const int unit = blockIdx.x * 4 + (threadIdx.x >> 6);
+  const int n_units = a.strip_groups * a.m_groups * a.ksplit;
+  if (unit >= n_units) return;
+  const int g = lane >> 4, n = lane & 15;
+  // unit -> (strip group, m group, k split); consecutive units share the K range and the m group
+  const int sg = unit % a.strip_groups, mg = (unit / a.strip_groups) % a.m_groups, kp = unit / (a.strip_groups * a.m_groups);
+  const int KST = (a.K + 31) >> 5, n_tiles = (a.N + 15) >> 4, m_tiles = a.Mp >> 4;
+  const int k_begin = kp * a.ksteps, k_end = min(KST, k_begin + a.ksteps);
+  const int t0 = sg * NT, mt0 = mg * MTW;
   const size_t plane = (size_t)a.Mp * a.Kp;
-  const uint16_t* arow = a.planes + (size_t)(a.m0 + i) * a.Kp + g * 8;
-  const int kbeg = ks * a.ksteps * 32, kend = min(a.Kp, kbeg + a.ksteps * 32);
 
-  f32x4 acc[kTiles][NF];
+  f32x4 acc[NF][NT][MTW];
 #pragma unroll
-  for (int t = 0; t < kTiles; ++t)
+  for (int f = 0; f < NF; ++f)
 #pragma unroll
-    for (int f = 0; f < NF; ++f) acc[t][f] = f32x4{0.f, 0.f, 0.f, 0.f};
+    for (int t = 0; t < NT; ++t)
+#pragma unroll
+      for (int m = 0; m < MTW; ++m) acc[f][t][m] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-  for (int kg = kbeg; kg < kend; kg += 32 * kGroupK) {
-    bf16x8 bw[kGroupK][NF];
+  GFrag wf[2][NF][NT], xf[2][3][MTW];
+  auto load_step = [&](int ks, GFrag(&w)[NF][NT], GFrag(&x)[3][MTW]) {
 #pragma unroll
-    for (int u = 0; u < kGroupK; ++u) {
-      const int kb = min(kg + u * 32 + g * 8, a.K - 8);   // past K: clamped, meets zero activations
-#pragma unroll
-      for (int f = 0; f < NF; ++f) bw[u][f] = *reinterpret_cast<const bf16x8*>(wrow[f] + kb);
+    for (int t = 0; t < NT; ++t) {
+      const size_t at = ((size_t)min(t0 + t, n_tiles - 1) * KST + ks) * 512 + lane * 8;
+      w[0][t].u = *reinterpret_cast<const uint4*>(a.W + at);
+      if (NF == 2) w[NF - 1][t].u = *reinterpret_cast<const uint4*>(a.W2 + at);
     }
 #pragma unroll
-    for (int u = 0; u < kGroupK; ++u) {
-      const int k0 = kg + u * 32;
-      if (k0 < kend) {
+    for (int m = 0; m < MTW; ++m) {
+      const uint16_t* src = a.planes + (size_t)(min(mt0 + m, m_tiles - 1) * 16 + n) * a.Kp + ks * 32 + 8 * g;
 #pragma unroll
-        for (int t = 0; t < kTiles; ++t) {
-          if (t < a.mt) {
-            const uint16_t* ap = arow + (size_t)t * 16 * a.Kp + k0;
+      for (int term = 0; term < 3; ++term) x[term][m].u = *reinterpret_cast<const uint4*>(src + term * plane);
+    }
+  };
+  auto mul_step = [&](const GFrag(&w)[NF][NT], const GFrag(&x)[3][MTW]) {
 #pragma unroll
-            for (int term = 0; term < 3; ++term) {
-              const bf16x8 av = *reinterpret_cast<const bf16x8*>(ap + term * plane);
+    for (int term = 0; term < 3; ++term)
 #pragma unroll
-              for (int f = 0; f < NF; ++f)
-                acc[t][f] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, bw[u][f], acc[t][f], 0, 0, 0);
-            }
-          }
-        }
-      }
-      // keep the activation loads of later steps from being hoisted above this step's MFMAs
-      // (hoisting all of them exhausts the register file)
-      __builtin_amdgcn_sched_barrier(0);
+      for (int m = 0; m < MTW; ++m)
+#pragma unroll
+        for (int t = 0; t < NT; ++t)
+#pragma unroll
+          for (int f = 0; f < NF; ++f)
+            acc[f][t][m] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(w[f][t].v, x[term][m].v, acc[f][t][m], 0, 0, 0);
+  };
+  if (k_begin < k_end) load_step(k_begin, wf[0], xf[0]);
+  for (int ks = k_begin; ks < k_end; ks += 2) {
+    if (ks + 1 < k_end) load_step(ks + 1, wf[1], xf[1]);
+    mul_step(wf[0], xf[0]);
+    if (ks + 1 < k_end) {
+      if (ks + 2 < k_end) load_step(ks + 2, wf[0], xf[0]);
+      mul_step(wf[1], xf[1]);
     }
   }
 
-  // ---- add the partial tiles of the KS wavefronts; wavefront ks finishes tiles ks, ks+KS, ...
-  if (KS > 1) {
+  // ---- results: D[weight row 4g+r][activation row n] of every (strip, m tile)
 #pragma unroll
-    for (int t = 0; t < kTiles; ++t)
-      if (t < a.mt)
+  for (int t = 0; t < NT; ++t) {
+    const int row0 = (t0 + t) * 16 + 4 * g;
+    if (t0 + t >= n_tiles) continue;
 #pragma unroll
-        for (int f = 0; f < NF; ++f)
-          *reinterpret_cast<f32x4*>(&red[((((size_t)ks * a.mt + t) * NF + f) * 64 + lane) * 4]) = acc[t][f];
-    __syncthreads();
-  }
+    for (int m = 0; m < MTW; ++m) {
+      const int am = (mt0 + m) * 16 + n;
+      if (mt0 + m >= m_tiles || am >= a.M) continue;
+      if (a.ksplit > 1) {
 #pragma unroll
-  for (int t = 0; t < kTiles; ++t) {
-    if (t < a.mt && (KS == 1 || t % KS == ks)) {
-      f32x4 sum[NF];
+        for (int f = 0; f < NF; ++f) {
+          float* p = a.partial + (((size_t)kp * NF + f) * a.M + am) * a.N + row0;
+          if (row0 + 3 < a.N && (a.N & 3) == 0) *reinterpret_cast<float4*>(p) = make_float4(acc[f][t][m][0], acc[f][t][m][1], acc[f][t][m][2], acc[f][t][m][3]);
+          else
 #pragma unroll
-      for (int f = 0; f < NF; ++f) {
-        if (KS == 1) sum[f] = acc[t][f];
-        else {
-          sum[f] = f32x4{0.f, 0.f, 0.f, 0.f};
-          for (int j = 0; j < KS; ++j)
-            sum[f] += *reinterpret_cast<const f32x4*>(&red[((((size_t)j * a.mt + t) * NF + f) * 64 + lane) * 4]);
+            for (int r = 0; r < 4; ++r) if (row0 + r < a.N) p[r] = acc[f][t][m][r];
         }
-      }
-      const int n = n0 + i;
+      } else {
+        float* y = a.Y + (size_t)am * a.ldy + row0;
 #pragma unroll
-      for (int r = 0; r < 4; ++r) {
-        const int m = a.m0 + t * 16 + g * 4 + r;
-        if (m < a.M && n < a.N) {
-          float* y = a.Y + (size_t)m * a.ldy + n;
-          if (EPI == EPI_SWIGLU) {
-            const float gt = sum[0][r], up = sum[NF - 1][r];
-            *y = gt / (1.0f + expf(-gt)) * up;
-          } else {
-            *y = EPI == EPI_ADD ? *y + sum[0][r] : sum[0][r];
+        for (int r = 0; r < 4; ++r) {
+          if (row0 + r < a.N) {
+            float v = acc[0][t][m][r];
+            if (EPI == EPI_SWIGLU) v = v / (1.0f + expf(-v)) * acc[NF - 1][t][m][r];
+            if (EPI == EPI_ADD) v += y[r];
+            y[r] = v;
           }
         }
       }
     }
+  }
+}
+
+// second pass when K is split: sum of the partial products in split order + epilogue
+template <int EPI>
+__global__ __launch_bounds__(256) void gemm_reduce_kernel(const GemmArgs a) {
+  constexpr int NF = EPI == EPI_SWIGLU ? 2 : 1;
+  const size_t total = (size_t)a.M * a.N;
+  for (size_t it = blockIdx.x * (size_t)256 + threadIdx.x; it < total; it += (size_t)gridDim.x * 256) {
+    const size_t m = it / a.N, nn = it - m * a.N;
+    float v[NF];
+#pragma unroll
+    for (int f = 0; f < NF; ++f) {
+      v[f] = 0.f;
+      for (int s = 0; s < a.ksplit; ++s) v[f] += a.partial[((size_t)s * NF + f) * total + it];
+    }
+    float* y = a.Y + m * a.ldy + nn;
+    float o = v[0];
+    if (EPI == EPI_SWIGLU) o = o / (1.0f + expf(-o)) * v[NF - 1];
+    if (EPI == EPI_ADD) o += *y;
+    *y = o;
   }
 }
 
@@ -174,53 +199,69 @@ size_t gemm_planes_elems(int M, int K) {
   const size_t Mp = ((size_t)M + 15) / 16 * 16, Kp = ((size_t)K + 31) / 32 * 32;
   return 3 * Mp * Kp;
 }
+// float elements of scratch for the partial products of split-K launches
+size_t gemm_partial_elems() { return (size_t)24 << 20; }
 
-// Y (op)= norm(X) * W^T on the matrix cores.  `planes` is scratch of gemm_planes_elems(M, K) bf16.
-hipError_t launch_gemm_mfma(const GemvArgs& g, uint16_t* planes, hipStream_t s) {
-  if (!g.bf16 || g.n_seg != 1 || g.K % 8 != 0 || g.K < 8) return hipErrorInvalidValue;
+template <int EPI, int NT, int MTW>
+static hipError_t gemm_launch(const GemmArgs& a, int units, hipStream_t s) {
+  hipLaunchKernelGGL((gemm_tiled_kernel<EPI, NT, MTW>), dim3((units + 3) / 4), dim3(256), 0, s, a);
+  return hipGetLastError();
+}
+template <int EPI, int NT>
+static hipError_t gemm_dispatch_m(const GemmArgs& a, int mtw, int units, hipStream_t s) {
+  switch (mtw) {
+    case 1: return gemm_launch<EPI, NT, 1>(a, units, s);
+    case 2: return gemm_launch<EPI, NT, 2>(a, units, s);
+    case 3: return gemm_launch<EPI, NT, 3>(a, units, s);
+    case 4: return gemm_launch<EPI, NT, 4>(a, units, s);
+    case 5: return gemm_launch<EPI, NT, 5>(a, units, s);
+  }
+  return hipErrorInvalidValue;
+}
+
+// Y (op)= norm(X) * W^T on the matrix cores.  `planes` is scratch of gemm_planes_elems(M, K) bf16,
+// `partial` of gemm_partial_elems() floats; the weights are the packed tiles (seg[0].P / P2).
+hipError_t launch_gemm_mfma(const GemvArgs& g, uint16_t* planes, float* partial, hipStream_t s) {
+  if (!g.bf16 || g.n_seg != 1 || g.K % 8 != 0 || g.K < 8 || g.seg[0].P == nullptr) return hipErrorInvalidValue;
   const int M = g.M, K = g.K, N = g.seg[0].n_rows;
   if (M <= 0 || N <= 0) return hipSuccess;
   const int Mp = (M + 15) / 16 * 16, Kp = (K + 31) / 32 * 32;
   hipLaunchKernelGGL(split_rows_kernel, dim3(Mp), dim3(256), 0, s, g.X, g.ldx, M, K, Mp, Kp, g.norm_w, g.eps, planes);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
+  const int nf = g.epi == EPI_SWIGLU ? 2 : 1, nt = nf == 2 ? 2 : 4;
   GemmArgs a{};
   a.planes = planes; a.Mp = Mp; a.Kp = Kp;
-  a.W = static_cast<const uint16_t*>(g.seg[0].W); a.W2 = static_cast<const uint16_t*>(g.seg[0].W2);
-  a.Y = g.seg[0].Y; a.ldy = g.seg[0].ldy; a.M = M; a.N = N; a.K = K;
-  const int strips = (N + 15) / 16, nf = g.epi == EPI_SWIGLU ? 2 : 1, steps = Kp / 32;
-  for (int m0 = 0; m0 < Mp; m0 += 16 * kTiles) {
-    a.m0 = m0;
-    a.mt = (Mp - m0) / 16 < kTiles ? (Mp - m0) / 16 : kTiles;
-    // K split: enough wavefronts to cover the chip, bounded by the steps available and by the
-    // LDS the partial tiles need (1 KB per wavefront, tile and fragment)
-    int KS = 1;
-    while (KS < 8 && strips * KS < 1024 && steps / (KS * 2) >= 2 && (size_t)KS * 2 * a.mt * nf * 1024 <= 96 * 1024) KS *= 2;
-    a.ksteps = (steps + KS - 1) / KS;
-    const size_t lds = KS > 1 ? (size_t)KS * a.mt * nf * 1024 : 0;
-#define HH_GEMM_LAUNCH(E)                                                                              \
-    {                                                                                                  \
-      auto kern = gemm_mfma_kernel<E>;                                                                 \
-      static size_t lds_enabled = 48 * 1024;                                                           \
-      if (lds > lds_enabled) {                                                                         \
-        e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),                                   \
-                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);                 \
-        if (e != hipSuccess) return e;                                                                 \
-        lds_enabled = lds;                                                                             \
-      }                                                                                                \
-      hipLaunchKernelGGL(kern, dim3(strips), dim3(64 * KS), lds, s, a);                                \
-    }
-    switch (g.epi) {
-      case EPI_STORE: HH_GEMM_LAUNCH(EPI_STORE) break;
-      case EPI_ADD: HH_GEMM_LAUNCH(EPI_ADD) break;
-      case EPI_SWIGLU: HH_GEMM_LAUNCH(EPI_SWIGLU) break;
-      default: return hipErrorInvalidValue;
-    }
-#undef HH_GEMM_LAUNCH
-    e = hipGetLastError();
-    if (e != hipSuccess) return e;
+  a.W = static_cast<const uint16_t*>(g.seg[0].P); a.W2 = static_cast<const uint16_t*>(g.seg[0].P2);
+  a.Y = g.seg[0].Y; a.ldy = g.seg[0].ldy; a.partial = partial; a.M = M; a.N = N; a.K = K;
+  const int steps = Kp / 32, tiles = (N + 15) / 16, m_tiles = Mp / 16;
+  a.strip_groups = (tiles + nt - 1) / nt;
+  a.m_groups = (m_tiles + 4) / 5;
+  const int mtw = (m_tiles + a.m_groups - 1) / a.m_groups;
+  // K split: enough units (wavefronts) to cover the chip, at least 4 steps each, partial buffer permitting
+  static const int unit_target = getenv("HH_GEMM_UNITS") ? atoi(getenv("HH_GEMM_UNITS")) : 2048;
+  int ksplit = 1;
+  while (a.strip_groups * a.m_groups * ksplit * 2 <= unit_target && steps / (ksplit * 2) >= 4 &&
+         (size_t)(ksplit * 2) * nf * M * N <= gemm_partial_elems())
+    ksplit *= 2;
+  a.ksplit = ksplit;
+  a.ksteps = (steps + ksplit - 1) / ksplit;
+  const int units = a.strip_groups * a.m_groups * ksplit;
+  switch (g.epi) {
+    case EPI_STORE: e = gemm_dispatch_m<EPI_STORE, 4>(a, mtw, units, s); break;
+    case EPI_ADD: e = gemm_dispatch_m<EPI_ADD, 4>(a, mtw, units, s); break;
+    case EPI_SWIGLU: e = gemm_dispatch_m<EPI_SWIGLU, 2>(a, mtw, units, s); break;
+    default: return hipErrorInvalidValue;
   }
-  return hipSuccess;
+  if (e != hipSuccess || ksplit == 1) return e;
+  const size_t total = (size_t)M * N;
+  const int rb = (int)((total + 255) / 256 < 2048 ? (total + 255) / 256 : 2048);
+  switch (g.epi) {
+    case EPI_STORE: hipLaunchKernelGGL(gemm_reduce_kernel<EPI_STORE>, dim3(rb), dim3(256), 0, s, a); break;
+    case EPI_ADD: hipLaunchKernelGGL(gemm_reduce_kernel<EPI_ADD>, dim3(rb), dim3(256), 0, s, a); break;
+    case EPI_SWIGLU: hipLaunchKernelGGL(gemm_reduce_kernel<EPI_SWIGLU>, dim3(rb), dim3(256), 0, s, a); break;
+  }
+  return hipGetLastError();
 }
 
 // argmax of each row of logits [M][ld] (largest value, lowest index on ties):

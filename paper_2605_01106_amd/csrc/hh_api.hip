@@ -52,6 +52,7 @@ struct hh_ctx {
   unsigned long long* best;
   int* attn_counters;   // tickets of the attention key slices (zero between launches)
   uint16_t* planes;   // split activations of the matrix-core products
+  float* gemm_partial;   // partial products of split-K launches
   float *rope, *h, *zx, *qkv, *g, *o, *act, *logits_d, *logits_v, *logits_p, *lasth, *part_o, *part_ml, *export_buf;
   int max_passes;
   // host state
@@ -152,6 +153,7 @@ size_t carve(hh_ctx* x, char* base) {
     if (d.dq > kmax) kmax = d.dq;
     if (d.F > kmax) kmax = d.F;
     x->planes = c.take<uint16_t>(gemm_planes_elems((int)Mmax, kmax));
+    x->gemm_partial = d.bf16 ? c.take<float>(gemm_partial_elems()) : nullptr;
   }
   x->rope = c.take<float>((size_t)d.max_seq * d.Dh);
   x->h = c.take<float>(Mmax * d.D);
@@ -244,7 +246,7 @@ bool skinny_args(const GemvArgs& a, GemvArgs& b) {
 hipError_t product(hh_ctx* x, const GemvArgs& a, hipStream_t s) {
   GemvArgs b;
   if (skinny_args(a, b)) return launch_skinny_mfma(b, nullptr, s);
-  if (a.bf16 && a.M >= kMfmaMinRows) return launch_gemm_mfma(a, x->planes, s);
+  if (a.bf16 && a.M >= kMfmaMinRows && a.seg[0].P != nullptr) return launch_gemm_mfma(a, x->planes, x->gemm_partial, s);
   return launch_gemv(a, nullptr, s);
 }
 
@@ -335,7 +337,7 @@ hh_status run_head(hh_ctx* x, const float* X, int M, int T, float* logits, int l
   }
   if (a.bf16 && M >= kMfmaMinRows) {
     a.best = nullptr;
-    HH_LAUNCH(HH_K_LM_HEAD, launch_gemm_mfma(a, x->planes, s));
+    HH_LAUNCH(HH_K_LM_HEAD, launch_gemm_mfma(a, x->planes, x->gemm_partial, s));
     HH_HIP(launch_argmax_rows(logits, ld_logits, d.V, M, out, out_stride, out_off, T, s));
     return HH_OK;
   }

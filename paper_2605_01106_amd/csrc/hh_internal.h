@@ -65,7 +65,8 @@ hipError_t launch_skinny_mfma(const GemvArgs& a, int* n_blocks_out, hipStream_t 
 
 // ---- the same product on the matrix cores (bf16 weights, more than a few activation rows)
 size_t gemm_planes_elems(int M, int K);   // bf16 elements of scratch for the split activations
-hipError_t launch_gemm_mfma(const GemvArgs& a, uint16_t* planes, hipStream_t s);
+size_t gemm_partial_elems();              // float elements of scratch for split-K partial products
+hipError_t launch_gemm_mfma(const GemvArgs& a, uint16_t* planes, float* partial, hipStream_t s);
 hipError_t launch_argmax_rows(const float* logits, int ld, int V, int M, int* out, int out_stride, int out_off, int T,
                               hipStream_t s);
 

@@ -108,6 +108,8 @@ def main():
     ap.add_argument("--forced-p", type=float, default=None, help="per-token accept probability of the forced leg")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="0 disables the oracle baseline")
     ap.add_argument("--graphs", type=int, default=1)
+    ap.add_argument("--prompt-len", type=int, default=None,
+                    help="override the workload's prompt length (a shorter stand-in; named in config.workload)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build measures one GPU only (the path shards by sequence with no exchange step); "
@@ -119,6 +121,9 @@ def main():
     from paper_2605_01106_amd import workloads as W
 
     wl = W.WORKLOADS[args.workload]
+    if args.prompt_len is not None:
+        import dataclasses
+        wl = dataclasses.replace(wl, prompt_len=args.prompt_len)
     cfg, k, Bn = wl.cfg, wl.k, wl.batch
     K, Wm = args.steps, args.warmup
     prof_rounds, greedy_rounds = 3, min(K, 32)

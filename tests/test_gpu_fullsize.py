@@ -56,3 +56,13 @@ def test_c3_falcon_h1_3b_shape():
     Prompt 1024 here (the oracle's float64 prefill of 4096 tokens takes minutes)."""
     w = _run("c3", seed=0, G=16, rounds=4, lens=[1024], layers=[0, 31])
     assert w["rounds"] == 4
+
+
+def test_c4_batch64_k8_forced():
+    """3B shape, batch 64, k = 8, forced acceptance p = 0.68 (the paper's per-token rate): the
+    9-position verification runs 576 rows per pass.  Ragged prompts of 71..260 tokens stand in
+    for the 32768-token prompts, which neither the float64 oracle nor a test-sized prefill can
+    afford; the oracle follows the longest and the shortest sequence."""
+    lens = [260 - 3 * i for i in range(64)]
+    w = _run("c4", seed=0, G=30, rounds=3, lens=lens, rows=[0, 63], layers=[0, 31], forced_p=0.68)
+    assert w["rounds"] == 3

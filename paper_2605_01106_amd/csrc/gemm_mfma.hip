@@ -34,7 +34,7 @@ __device__ __forceinline__ uint16_t bf16_rne(float f) {
 __device__ __forceinline__ float bf16_f32(uint16_t h) { return __uint_as_float((uint32_t)h << 16); }
 
 // planes [3][Mp][Kp] bf16; rows >= M and columns >= K are zero
-__global__ __launch_bounds__(256) void split_rows_kernel(const float* __restrict__ X, int ldx, int M, int K, int Mp, int Kp,
+__global__ __launch_bounds__(256) void split_rows_kernel(const float* __restrict__ X, const float* __restrict__ X2, int ldx, int M, int K, int Mp, int Kp,
                                                          const float* __restrict__ norm_w, float eps,
                                                          uint16_t* __restrict__ planes) {
   const int m = blockIdx.x;
@@ -42,7 +42,10 @@ __global__ __launch_bounds__(256) void split_rows_kernel(const float* __restrict
   float rstd = 1.f;
   if (m < M && norm_w != nullptr) {
     float ss = 0.f;
-    for (int k = threadIdx.x; k < K; k += 256) { const float v = X[(size_t)m * ldx + k]; ss = fmaf(v, v, ss); }
+    for (int k = threadIdx.x; k < K; k += 256) {
+      const float v = X[(size_t)m * ldx + k] + (X2 != nullptr ? X2[(size_t)m * ldx + k] : 0.f);
+      ss = fmaf(v, v, ss);
+    }
 #pragma unroll
     for (int o = 32; o > 0; o >>= 1) ss += __shfl_xor(ss, o, 64);
     if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = ss;
@@ -53,7 +56,7 @@ __global__ __launch_bounds__(256) void split_rows_kernel(const float* __restrict
   for (int k = threadIdx.x; k < Kp; k += 256) {
     uint16_t t0 = 0, t1 = 0, t2 = 0;
     if (m < M && k < K) {
-      float v = X[(size_t)m * ldx + k];
+      float v = X[(size_t)m * ldx + k] + (X2 != nullptr ? X2[(size_t)m * ldx + k] : 0.f);
       if (norm_w != nullptr) v = v * norm_w[k] * rstd;
       t0 = bf16_rne(v);
       const float r1 = v - bf16_f32(t0);
@@ -70,6 +73,7 @@ struct GemmArgs {
   const uint16_t* planes; int Mp, Kp;     // split activations [3][Mp][Kp]
   const uint16_t* W; const uint16_t* W2;  // packed tiles (W2: the "up" matrix for SwiGLU)
   float* Y; int ldy;
+  const float* R2;                        // optional second residual (EPI_ADD)
   float* partial;                         // [ksplit][NF][M][N] when ksplit > 1
   int M, N, K;
   int strip_groups, m_groups, ksplit;     // units = strip_groups * m_groups * ksplit
@@ -165,7 +169,7 @@ __global__ __launch_bounds__(256) void gemm_tiled_kernel(const GemmArgs a) {
           if (row0 + r < a.N) {
             float v = acc[0][t][m][r];
             if (EPI == EPI_SWIGLU) v = v / (1.0f + expf(-v)) * acc[NF - 1][t][m][r];
-            if (EPI == EPI_ADD) v += y[r];
+            if (EPI == EPI_ADD) v += y[r] + (a.R2 != nullptr ? a.R2[(size_t)am * a.ldy + row0 + r] : 0.f);
             y[r] = v;
           }
         }
@@ -190,7 +194,7 @@ __global__ __launch_bounds__(256) void gemm_reduce_kernel(const GemmArgs a) {
     float* y = a.Y + m * a.ldy + nn;
     float o = v[0];
     if (EPI == EPI_SWIGLU) o = o / (1.0f + expf(-o)) * v[NF - 1];
-    if (EPI == EPI_ADD) o += *y;
+    if (EPI == EPI_ADD) o += *y + (a.R2 != nullptr ? a.R2[m * a.ldy + nn] : 0.f);
     *y = o;
   }
 }
@@ -226,14 +230,14 @@ hipError_t launch_gemm_mfma(const GemvArgs& g, uint16_t* planes, float* partial,
   const int M = g.M, K = g.K, N = g.seg[0].n_rows;
   if (M <= 0 || N <= 0) return hipSuccess;
   const int Mp = (M + 15) / 16 * 16, Kp = (K + 31) / 32 * 32;
-  hipLaunchKernelGGL(split_rows_kernel, dim3(Mp), dim3(256), 0, s, g.X, g.ldx, M, K, Mp, Kp, g.norm_w, g.eps, planes);
+  hipLaunchKernelGGL(split_rows_kernel, dim3(Mp), dim3(256), 0, s, g.X, g.X2, g.ldx, M, K, Mp, Kp, g.norm_w, g.eps, planes);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   const int nf = g.epi == EPI_SWIGLU ? 2 : 1, nt = nf == 2 ? 2 : 4;
   GemmArgs a{};
   a.planes = planes; a.Mp = Mp; a.Kp = Kp;
   a.W = static_cast<const uint16_t*>(g.seg[0].P); a.W2 = static_cast<const uint16_t*>(g.seg[0].P2);
-  a.Y = g.seg[0].Y; a.ldy = g.seg[0].ldy; a.partial = partial; a.M = M; a.N = N; a.K = K;
+  a.Y = g.seg[0].Y; a.ldy = g.seg[0].ldy; a.R2 = g.R2; a.partial = partial; a.M = M; a.N = N; a.K = K;
   const int steps = Kp / 32, tiles = (N + 15) / 16, m_tiles = Mp / 16;
   a.strip_groups = (tiles + nt - 1) / nt;
   a.m_groups = (m_tiles + 4) / 5;

@@ -124,7 +124,10 @@ __global__ __launch_bounds__(kGemvThreads) void gemv_kernel(const GemvArgs a, co
       }
     }
     if (EPI == EPI_ADD) {
-      if (owner && rg < nrg) resid = Yb[(size_t)out_m * ldy + n + out_r];
+      if (owner && rg < nrg) {
+        resid = Yb[(size_t)out_m * ldy + n + out_r];
+        if (a.R2 != nullptr) resid += a.R2[(size_t)(m0 + out_m) * ldy + n + out_r];
+      }
     }
   };
   load_unit(row_group(0));   // in flight while the activations are staged
@@ -134,11 +137,13 @@ __global__ __launch_bounds__(kGemvThreads) void gemv_kernel(const GemvArgs a, co
   for (int m = 0; m < MT; ++m) {
     float ss = 0.f;
     const float4* x4 = reinterpret_cast<const float4*>(a.X + (size_t)(m0 + min(m, mt - 1)) * a.ldx);
+    const float4* y4 = a.X2 != nullptr ? reinterpret_cast<const float4*>(a.X2 + (size_t)(m0 + min(m, mt - 1)) * a.ldx) : nullptr;
     const float4* n4 = reinterpret_cast<const float4*>(a.norm_w);
     for (int k4 = tid; k4 < (Kpad >> 2); k4 += kGemvThreads) {
       float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
       if (k4 < (K >> 2) && m < mt) {
         v = x4[k4];
+        if (y4 != nullptr) { const float4 w2 = y4[k4]; v.x += w2.x; v.y += w2.y; v.z += w2.z; v.w += w2.w; }
         ss += v.x * v.x + v.y * v.y + v.z * v.z + v.w * v.w;
         if (normed) {
           const float4 nw = n4[k4];

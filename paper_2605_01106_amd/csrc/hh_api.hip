@@ -53,6 +53,9 @@ struct hh_ctx {
   int* attn_counters;   // tickets of the attention key slices (zero between launches)
   uint16_t* planes;   // split activations of the matrix-core products
   float* gemm_partial;   // partial products of split-K launches
+  uint16_t* planes_side; // the same two scratch areas for products enqueued on the side stream
+  float* gemm_partial_side;
+  float* ho;             // [Mmax][D] attention branch after its output projection (full mode)
   float *rope, *h, *zx, *qkv, *g, *o, *act, *logits_d, *logits_v, *logits_p, *lasth, *part_o, *part_ml, *export_buf;
   int max_passes;
   // host state
@@ -154,6 +157,8 @@ size_t carve(hh_ctx* x, char* base) {
     if (d.F > kmax) kmax = d.F;
     x->planes = c.take<uint16_t>(gemm_planes_elems((int)Mmax, kmax));
     x->gemm_partial = d.bf16 ? c.take<float>(gemm_partial_elems()) : nullptr;
+    x->planes_side = c.take<uint16_t>(gemm_planes_elems((int)Mmax, kmax));
+    x->gemm_partial_side = d.bf16 ? c.take<float>(gemm_partial_elems()) : nullptr;
   }
   x->rope = c.take<float>((size_t)d.max_seq * d.Dh);
   x->h = c.take<float>(Mmax * d.D);
@@ -161,6 +166,7 @@ size_t carve(hh_ctx* x, char* base) {
   x->qkv = x->zx ? x->zx + d.d_in_proj : nullptr;
   x->g = c.take<float>(Mmax * d.d_inner);
   x->o = c.take<float>(Mmax * d.dq);
+  x->ho = c.take<float>(Mmax * d.D);
   x->act = c.take<float>(Mmax * d.F);
   x->logits_d = c.take<float>(B * (d.Kmax > 0 ? d.Kmax : 1) * d.V);
   x->logits_v = c.take<float>(Mv * d.V);
@@ -243,10 +249,12 @@ bool skinny_args(const GemvArgs& a, GemvArgs& b) {
   b.seg[0].W = a.seg[0].P; b.seg[0].W2 = a.seg[0].P2;
   return skinny_mfma_fits(b);
 }
-hipError_t product(hh_ctx* x, const GemvArgs& a, hipStream_t s) {
+// side: the product is enqueued on the side stream (its own scratch, so that it may overlap a product on the main stream)
+hipError_t product(hh_ctx* x, const GemvArgs& a, hipStream_t s, bool side = false) {
   GemvArgs b;
   if (skinny_args(a, b)) return launch_skinny_mfma(b, nullptr, s);
-  if (a.bf16 && a.M >= kMfmaMinRows && a.seg[0].P != nullptr) return launch_gemm_mfma(a, x->planes, x->gemm_partial, s);
+  if (a.bf16 && a.M >= kMfmaMinRows && a.seg[0].P != nullptr)
+    return launch_gemm_mfma(a, side ? x->planes_side : x->planes, side ? x->gemm_partial_side : x->gemm_partial, s);
   return launch_gemv(a, nullptr, s);
 }
 
@@ -264,8 +272,10 @@ hh_status run_layers(hh_ctx* x, bool full, int B, int T, const int* n_tok, int s
       a.n_seg = 1;
       HH_LAUNCH(HH_K_IN_PROJ, product(x, a, s));
     }
-    // The two branches of the block (Eq. 2) only share their input: the attention branch is
-    // enqueued on a side stream so that it overlaps the SSM branch, and joins before the sum.
+    // The two branches of the block (Eq. 2) only share their input.  The attention branch
+    // (attention, then its output projection into a buffer of its own) is enqueued on a side
+    // stream beside the SSM branch (scan, then out projection into the residual stream); the
+    // branches meet at the MLP, whose input is h + ho and whose down projection adds both.
     const bool overlap = full && !x->prof_on && x->side != nullptr;
     hipStream_t sa = s;
     if (overlap) {
@@ -279,11 +289,16 @@ hh_status run_layers(hh_ctx* x, bool full, int B, int T, const int* n_tok, int s
       a.page_table = x->page_table; a.rope = x->rope; a.part_o = x->part_o; a.part_ml = x->part_ml;
       a.counters = x->attn_counters;
       a.T = T; a.B = B; a.n_splits = n_splits;
+      GemvArgs b{};
+      b.X = x->o; b.ldx = d.dq; b.M = M; b.K = d.dq; b.norm_w = nullptr; b.epi = EPI_STORE; b.bf16 = d.bf16;
+      b.seg[0] = {w.w_o, nullptr, w.p_o, nullptr, x->ho, d.D, d.D}; b.n_seg = 1;
       if (overlap) {
         HH_HIP(launch_attention(d, a, sa));
+        HH_HIP(product(x, b, sa, true));
         HH_HIP(hipEventRecord(x->join_ev[l], sa));
       } else {
         HH_LAUNCH(HH_K_ATTN, launch_attention(d, a, s));
+        HH_LAUNCH(HH_K_O_PROJ, product(x, b, s));
       }
     }
     {  // conv + selective scan -> y * silu(z)
@@ -293,26 +308,21 @@ hh_status run_layers(hh_ctx* x, bool full, int B, int T, const int* n_tok, int s
       a.state_in = state_in; a.state_out = state_out; a.write_ring = 1;
       HH_LAUNCH(HH_K_SSM, launch_ssm(d, a, s));
     }
-    if (overlap) HH_HIP(hipStreamWaitEvent(s, x->join_ev[l], 0));
-    {  // h += W_out * gated_norm(g)   (+ W_o * o in full mode: the two branches are summed)
+    {  // h += W_out * gated_norm(g)
       GemvArgs a{};
       a.X = x->g; a.ldx = d.d_inner; a.M = M; a.K = d.d_inner; a.norm_w = w.gnorm; a.eps = d.eps; a.epi = EPI_ADD; a.bf16 = d.bf16;
       a.seg[0] = {w.w_out, nullptr, w.p_out, nullptr, x->h, d.D, d.D}; a.n_seg = 1;
       HH_LAUNCH(HH_K_OUT_PROJ, product(x, a, s));
-      if (full) {
-        GemvArgs b{};
-        b.X = x->o; b.ldx = d.dq; b.M = M; b.K = d.dq; b.norm_w = nullptr; b.epi = EPI_ADD; b.bf16 = d.bf16;
-        b.seg[0] = {w.w_o, nullptr, w.p_o, nullptr, x->h, d.D, d.D}; b.n_seg = 1;
-        HH_LAUNCH(HH_K_O_PROJ, product(x, b, s));
-      }
     }
-    {  // SwiGLU MLP
+    if (overlap) HH_HIP(hipStreamWaitEvent(s, x->join_ev[l], 0));
+    {  // SwiGLU MLP on r = rmsnorm(h + ho); h += ho + W_d(...)   (ho: full mode only)
+      const float* ho = full ? x->ho : nullptr;
       GemvArgs a{};
-      a.X = x->h; a.ldx = d.D; a.M = M; a.K = d.D; a.norm_w = w.norm2; a.eps = d.eps; a.epi = EPI_SWIGLU; a.bf16 = d.bf16;
+      a.X = x->h; a.X2 = ho; a.ldx = d.D; a.M = M; a.K = d.D; a.norm_w = w.norm2; a.eps = d.eps; a.epi = EPI_SWIGLU; a.bf16 = d.bf16;
       a.seg[0] = {w.w_gate, w.w_up, w.p_gate, w.p_up, x->act, d.F, d.F}; a.n_seg = 1;
       HH_LAUNCH(HH_K_MLP_UP, product(x, a, s));
       GemvArgs b{};
-      b.X = x->act; b.ldx = d.F; b.M = M; b.K = d.F; b.norm_w = nullptr; b.epi = EPI_ADD; b.bf16 = d.bf16;
+      b.X = x->act; b.ldx = d.F; b.M = M; b.K = d.F; b.norm_w = nullptr; b.epi = EPI_ADD; b.bf16 = d.bf16; b.R2 = ho;
       b.seg[0] = {w.w_down, nullptr, w.p_down, nullptr, x->h, d.D, d.D}; b.n_seg = 1;
       HH_LAUNCH(HH_K_MLP_DOWN, product(x, b, s));
     }

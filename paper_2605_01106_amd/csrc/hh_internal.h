@@ -47,6 +47,8 @@ struct GemvSeg {
 };
 struct GemvArgs {
   const float* X; int ldx; int M; int K;
+  const float* X2;                         // optional second addend of the input, same shape as X: X' = X + X2
+  const float* R2;                         // EPI_ADD: optional second residual [M][ldy] added with the old Y
   const float* norm_w; float eps;          // rmsnorm prologue when norm_w != nullptr
   GemvSeg seg[4]; int n_seg;
   int epi;

@@ -61,6 +61,8 @@ __device__ __forceinline__ float sk_wave_sum(float v) {
 
 struct SkinnyArgs {
   const float* X; int ldx, M, K;
+  const float* X2;                         // optional second addend of the input
+  const float* R2;                         // optional second residual (EPI_ADD)
   const float* norm_w; float eps;
   const uint16_t* W; const uint16_t* W2;   // packed tiles (W2: the "up" matrix for SwiGLU)
   float* Y; int ldy, N;
@@ -126,6 +128,10 @@ __global__ __launch_bounds__(64 * NWAVES) void skinny_mfma_kernel(const SkinnyAr
         ok[u] = it < items && col < K;
         const int colc = min(col, K - 4);
         v[u] = *reinterpret_cast<const float4*>(a.X + (size_t)mi[u] * a.ldx + a.k0 + colc);
+        if (a.X2 != nullptr) {
+          const float4 w2 = *reinterpret_cast<const float4*>(a.X2 + (size_t)mi[u] * a.ldx + a.k0 + colc);
+          v[u].x += w2.x; v[u].y += w2.y; v[u].z += w2.z; v[u].w += w2.w;
+        }
         nw[u] = normed ? *reinterpret_cast<const float4*>(a.norm_w + a.k0 + colc) : make_float4(1.f, 1.f, 1.f, 1.f);
       }
     };
@@ -186,7 +192,13 @@ __global__ __launch_bounds__(64 * NWAVES) void skinny_mfma_kernel(const SkinnyAr
     float4 old = make_float4(0.f, 0.f, 0.f, 0.f);
     const int row0 = tile * 16 + 4 * g;
     const bool vec = n < M && row0 + 3 < N && (a.ldy & 3) == 0;
-    if (EPI == EPI_ADD && wave == fin && vec) old = *reinterpret_cast<const float4*>(a.Y + (size_t)n * a.ldy + row0);
+    if (EPI == EPI_ADD && wave == fin && vec) {
+      old = *reinterpret_cast<const float4*>(a.Y + (size_t)n * a.ldy + row0);
+      if (a.R2 != nullptr) {
+        const float4 o2 = *reinterpret_cast<const float4*>(a.R2 + (size_t)n * a.ldy + row0);
+        old.x += o2.x; old.y += o2.y; old.z += o2.z; old.w += o2.w;
+      }
+    }
     if (KSTEPS > 5 || !DB) asm volatile("" ::: "memory");   // long slices: re-read the activation fragments every round
     f32x4 acc[NF][3];
 #pragma unroll
@@ -232,7 +244,10 @@ __global__ __launch_bounds__(64 * NWAVES) void skinny_mfma_kernel(const SkinnyAr
         } else {
 #pragma unroll
           for (int r = 0; r < 4; ++r)
-            if (row0 + r < N) { if (EPI == EPI_ADD) v[r] += y[r]; y[r] = v[r]; }
+            if (row0 + r < N) {
+              if (EPI == EPI_ADD) v[r] += y[r] + (a.R2 != nullptr ? a.R2[(size_t)n * a.ldy + row0 + r] : 0.f);
+              y[r] = v[r];
+            }
         }
         if (a.best != nullptr) {
 #pragma unroll
@@ -388,7 +403,7 @@ hipError_t launch_skinny_mfma(const GemvArgs& g, int* n_blocks_out, hipStream_t 
   const int windows = skinny_windows(g, p);
   if (g.seg[0].n_rows <= 0) return hipSuccess;
   SkinnyArgs a{};
-  a.X = g.X; a.ldx = g.ldx; a.M = g.M; a.norm_w = g.norm_w; a.eps = g.eps;
+  a.X = g.X; a.X2 = g.X2; a.R2 = g.R2; a.ldx = g.ldx; a.M = g.M; a.norm_w = g.norm_w; a.eps = g.eps;
   a.W = static_cast<const uint16_t*>(g.seg[0].W); a.W2 = static_cast<const uint16_t*>(g.seg[0].W2);
   a.Y = g.seg[0].Y; a.ldy = g.seg[0].ldy; a.N = g.seg[0].n_rows; a.best = g.best;
   a.rounds = p.rounds; a.kst_row = (g.K + 31) / 32; a.rnorm_k = 1.0f / (float)g.K;
@@ -396,6 +411,7 @@ hipError_t launch_skinny_mfma(const GemvArgs& g, int* n_blocks_out, hipStream_t 
   if (n_blocks_out) *n_blocks_out = p.blocks;
   for (int w = 0; w < windows; ++w) {
     a.k0 = w * a.K;
+    if (w > 0) a.R2 = nullptr;                   // the second residual goes in with the first window
     const int epi = w == 0 ? g.epi : EPI_ADD;   // later windows accumulate
     hipError_t e = hipErrorInvalidValue;
     switch (epi) {

@@ -139,11 +139,92 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(const Dims d, const Attn
   if (ws < we) load_step(ws, kA, kB, vT);
   TR(1);
 
+  // ---- the new positions (FUSE): one wavefront of the launch builds their operands from the
+  // projection buffer and appends them to the cache, before the queries are staged (it only
+  // needs the queries to score them)
+  const bool new_wave = FUSE && sp == S - 1 && wave == 3 && nk_all > pos0;
+  Frag nA[KS], nB[KS], nV[NDB];
+  if (new_wave) {
+    const float2* rope = reinterpret_cast<const float2*>(a.rope);
+    const bool al4 = (d.ldzx & 3) == 0 && (reinterpret_cast<uintptr_t>(xrow) & 15) == 0;   // 16-byte aligned rows (dq, Dh are multiples of 8)
+    uint16_t* kpw = static_cast<uint16_t*>(a.kpool);
+    uint16_t* vpw = static_cast<uint16_t*>(a.vpool);
+    auto load8 = [&](const float* src, float(&o)[8]) {
+      if (al4) {
+        const float4 x = *reinterpret_cast<const float4*>(src), y = *reinterpret_cast<const float4*>(src + 4);
+        o[0] = x.x; o[1] = x.y; o[2] = x.z; o[3] = x.w; o[4] = y.x; o[5] = y.y; o[6] = y.z; o[7] = y.w;
+      } else {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) o[i] = src[i];
+      }
+    };
+    // values of the new positions first (their loads overlap the rotation of the keys below)
+    float vraw[NDB][8];
+    size_t vat[8];
+    {
+      const float* vbase = xrow + d.dq + d.dkv + (size_t)kvh * Dh;
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        const int jc = min(8 * g + i, nt - 1), pos = pos0 + jc;
+        vat[i] = ((size_t)pt_row[pos >> pshift] * d.Hkv + kvh) * Dh * d.page_tokens + (pos & pmask);
+#pragma unroll
+        for (int db = 0; db < NDB; ++db) vraw[db][i] = vbase[(size_t)jc * d.ldzx + min(db * 16 + n, Dh - 1)];
+      }
+    }
+#pragma unroll
+    for (int blk = 0; blk < 2; ++blk) {
+      const int j = 8 * (n >> 2) + (n & 3) + 4 * blk;            // new position of this lane's key row
+      const bool live = j < nt;
+      const int jc = min(j, nt - 1);
+      const float* kr = xrow + (size_t)jc * d.ldzx + d.dq + (size_t)kvh * Dh;
+      const size_t kat = (((size_t)pt_row[(pos0 + jc) >> pshift] * d.Hkv + kvh) * d.page_tokens + ((pos0 + jc) & pmask)) * Dh;
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks) {
+        const int d0 = ks * 32 + 8 * g;
+        Frag f;
+        f.u = make_uint4(0, 0, 0, 0);
+        if (d0 < Dh && (blk == 0 || nt > 4)) {                   // the second block only holds positions 4..7, 12..15
+          const bool low = d0 < half;                            // an 8-dim group lies in one half (Dh % 16 == 0 here)
+          float x[8], xp[8];
+          load8(kr + d0, x);
+          load8(kr + (low ? d0 + half : d0 - half), xp);
+          const float2* cs = rope + (size_t)(pos0 + jc) * half + (low ? d0 : d0 - half);
+          uint32_t h[8];
+#pragma unroll
+          for (int i = 0; i < 8; ++i) {
+            const float2 c = cs[i];
+            const float r = low ? x[i] * c.x - xp[i] * c.y : x[i] * c.x + xp[i] * c.y;
+            h[i] = live ? f32_to_bf16_rne(r) : 0u;
+          }
+          f.u = make_uint4(h[0] | (h[1] << 16), h[2] | (h[3] << 16), h[4] | (h[5] << 16), h[6] | (h[7] << 16));
+          if (live) *reinterpret_cast<uint4*>(kpw + kat + d0) = f.u;
+        }
+        if (blk == 0) nA[ks] = f; else nB[ks] = f;
+      }
+    }
+#pragma unroll
+    for (int db = 0; db < NDB; ++db) {
+      const int dim = db * 16 + n;
+      uint32_t h[8];
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        h[i] = 0u;
+        if (8 * g + i < nt && dim < Dh) {
+          h[i] = f32_to_bf16_rne(vraw[db][i]);
+          vpw[vat[i] + (size_t)dim * d.page_tokens] = (uint16_t)h[i];
+        }
+      }
+      nV[db].u = make_uint4(h[0] | (h[1] << 16), h[2] | (h[3] << 16), h[4] | (h[5] << 16), h[6] | (h[7] << 16));
+    }
+  }
+
   // ---- query rows: rotate to their positions, scale, split into 3 bf16 terms, stage in LDS
   {
     const float scale = 1.0f / sqrtf((float)Dh);
     const float2* rope = reinterpret_cast<const float2*>(a.rope);
-    for (int it = tid; it < R * half; it += 256) {
+    // (the wavefront that builds the new positions' operands takes no part in the staging)
+    const int stagers = FUSE && sp == S - 1 && nk_all > pos0 ? 192 : 256;
+    for (int it = tid; it < R * half && tid < stagers; it += stagers) {
       const int r = it / half, i = it - r * half, rr = row0 + r;
       float lo = 0.f, hi = 0.f;
       if (rr < row_lim) {
@@ -162,7 +243,7 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(const Dims d, const Attn
     }
     if (Dh < Dhp) {
       const int padw = Dhp - Dh;
-      for (int it = tid; it < R * padw * 3; it += 256) {
+      for (int it = tid; it < R * padw * 3 && tid < stagers; it += stagers) {
         const int r = it / (padw * 3), rem = it - r * padw * 3, term = rem / padw, i = rem - term * padw;
         qT[(size_t)r * QS + term * Dhp + Dh + i] = 0;
       }
@@ -242,80 +323,8 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(const Dims d, const Attn
     }
   };
 
-  // ---- the new positions (FUSE): operands from the projection buffer, by one wavefront of the launch
-  if (FUSE && sp == S - 1 && wave == 3 && nk_all > pos0) {
-    const float2* rope = reinterpret_cast<const float2*>(a.rope);
-    const bool al4 = (d.ldzx & 3) == 0 && (reinterpret_cast<uintptr_t>(xrow) & 15) == 0;   // 16-byte aligned rows (dq, Dh are multiples of 8)
-    Frag nA[KS], nB[KS], nV[NDB];
-    uint16_t* kpw = static_cast<uint16_t*>(a.kpool);
-    uint16_t* vpw = static_cast<uint16_t*>(a.vpool);
-    auto load8 = [&](const float* src, float(&o)[8]) {
-      if (al4) {
-        const float4 x = *reinterpret_cast<const float4*>(src), y = *reinterpret_cast<const float4*>(src + 4);
-        o[0] = x.x; o[1] = x.y; o[2] = x.z; o[3] = x.w; o[4] = y.x; o[5] = y.y; o[6] = y.z; o[7] = y.w;
-      } else {
-#pragma unroll
-        for (int i = 0; i < 8; ++i) o[i] = src[i];
-      }
-    };
-    // values of the new positions first (their loads overlap the rotation of the keys below)
-    float vraw[NDB][8];
-    size_t vat[8];
-    {
-      const float* vbase = xrow + d.dq + d.dkv + (size_t)kvh * Dh;
-#pragma unroll
-      for (int i = 0; i < 8; ++i) {
-        const int jc = min(8 * g + i, nt - 1), pos = pos0 + jc;
-        vat[i] = ((size_t)pt_row[pos >> pshift] * d.Hkv + kvh) * Dh * d.page_tokens + (pos & pmask);
-#pragma unroll
-        for (int db = 0; db < NDB; ++db) vraw[db][i] = vbase[(size_t)jc * d.ldzx + min(db * 16 + n, Dh - 1)];
-      }
-    }
-#pragma unroll
-    for (int blk = 0; blk < 2; ++blk) {
-      const int j = 8 * (n >> 2) + (n & 3) + 4 * blk;            // new position of this lane's key row
-      const bool live = j < nt;
-      const int jc = min(j, nt - 1);
-      const float* kr = xrow + (size_t)jc * d.ldzx + d.dq + (size_t)kvh * Dh;
-      const size_t kat = (((size_t)pt_row[(pos0 + jc) >> pshift] * d.Hkv + kvh) * d.page_tokens + ((pos0 + jc) & pmask)) * Dh;
-#pragma unroll
-      for (int ks = 0; ks < KS; ++ks) {
-        const int d0 = ks * 32 + 8 * g;
-        Frag f;
-        f.u = make_uint4(0, 0, 0, 0);
-        if (d0 < Dh && (blk == 0 || nt > 4)) {                   // the second block only holds positions 4..7, 12..15
-          const bool low = d0 < half;                            // an 8-dim group lies in one half (Dh % 16 == 0 here)
-          float x[8], xp[8];
-          load8(kr + d0, x);
-          load8(kr + (low ? d0 + half : d0 - half), xp);
-          const float2* cs = rope + (size_t)(pos0 + jc) * half + (low ? d0 : d0 - half);
-          uint32_t h[8];
-#pragma unroll
-          for (int i = 0; i < 8; ++i) {
-            const float2 c = cs[i];
-            const float r = low ? x[i] * c.x - xp[i] * c.y : x[i] * c.x + xp[i] * c.y;
-            h[i] = live ? f32_to_bf16_rne(r) : 0u;
-          }
-          f.u = make_uint4(h[0] | (h[1] << 16), h[2] | (h[3] << 16), h[4] | (h[5] << 16), h[6] | (h[7] << 16));
-          if (live) *reinterpret_cast<uint4*>(kpw + kat + d0) = f.u;
-        }
-        if (blk == 0) nA[ks] = f; else nB[ks] = f;
-      }
-    }
-#pragma unroll
-    for (int db = 0; db < NDB; ++db) {
-      const int dim = db * 16 + n;
-      uint32_t h[8];
-#pragma unroll
-      for (int i = 0; i < 8; ++i) {
-        h[i] = 0u;
-        if (8 * g + i < nt && dim < Dh) {
-          h[i] = f32_to_bf16_rne(vraw[db][i]);
-          vpw[vat[i] + (size_t)dim * d.page_tokens] = (uint16_t)h[i];
-        }
-      }
-      nV[db].u = make_uint4(h[0] | (h[1] << 16), h[2] | (h[3] << 16), h[4] | (h[5] << 16), h[6] | (h[7] << 16));
-    }
+  // ---- the new positions (FUSE): scored as one more step by the wavefront that built their operands
+  if (new_wave) {
     int limn[RT];
 #pragma unroll
     for (int rt = 0; rt < RT; ++rt) {
@@ -423,6 +432,16 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(const Dims d, const Attn
   if (!s_last) return;
   __threadfence();
   float2* gm = reinterpret_cast<float2*>(mrg);   // [R][S] (maximum, sum) of every slice
+  const int d4n = Dh >> 2;
+  // the first 8 slices of this thread's first output item are requested together with the
+  // slice statistics (they do not depend on them)
+  float4 pv0[8];
+  {
+    const int it = min(tid, R * d4n - 1), r = it / d4n, c4 = it - r * d4n, rr = min(row0 + r, n_rows - 1);
+    const size_t rid = ((size_t)b * a.T + rr / G) * d.Hq + kvh * G + rr % G;
+#pragma unroll
+    for (int u = 0; u < 8; ++u) pv0[u] = *reinterpret_cast<const float4*>(a.part_o + (rid * S + min(u, S - 1)) * Dh + 4 * c4);
+  }
   for (int it = tid; it < R * S; it += 256) {
     const int r = it / S, s = it - r * S, rr = row0 + r;
     float2 v = make_float2(-INFINITY, 0.f);
@@ -434,7 +453,6 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(const Dims d, const Attn
   }
   __syncthreads();
   TR(7);
-  const int d4n = Dh >> 2;
   for (int it = tid; it < R * d4n; it += 256) {
     const int r = it / d4n, c4 = it - r * d4n, rr = row0 + r;
     if (rr >= n_rows) continue;
@@ -448,7 +466,8 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(const Dims d, const Attn
       float4 pv[8];
 #pragma unroll
       for (int u = 0; u < 8; ++u)
-        pv[u] = *reinterpret_cast<const float4*>(a.part_o + (rid * S + min(s0 + u, S - 1)) * Dh + 4 * c4);
+        pv[u] = (it == tid && s0 == 0) ? pv0[u]
+                                       : *reinterpret_cast<const float4*>(a.part_o + (rid * S + min(s0 + u, S - 1)) * Dh + 4 * c4);
 #pragma unroll
       for (int u = 0; u < 8; ++u) {
         if (s0 + u < S) {

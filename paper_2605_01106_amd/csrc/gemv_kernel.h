@@ -132,29 +132,46 @@ __global__ __launch_bounds__(kGemvThreads) void gemv_kernel(const GemvArgs a, co
   };
   load_unit(row_group(0));   // in flight while the activations are staged
 
-  // ---- prologue: stage x[k] * norm_w[k] (float4 at a time) and the sums of squares
+  // ---- prologue: stage x[k] * norm_w[k] (float4 at a time) and the sums of squares.  The
+  // loads of all MT rows of a column group are issued together (one memory round trip, not MT).
   const bool normed = a.norm_w != nullptr;
-  for (int m = 0; m < MT; ++m) {
-    float ss = 0.f;
-    const float4* x4 = reinterpret_cast<const float4*>(a.X + (size_t)(m0 + min(m, mt - 1)) * a.ldx);
-    const float4* y4 = a.X2 != nullptr ? reinterpret_cast<const float4*>(a.X2 + (size_t)(m0 + min(m, mt - 1)) * a.ldx) : nullptr;
+  {
+    float ss[MT];
+#pragma unroll
+    for (int m = 0; m < MT; ++m) ss[m] = 0.f;
     const float4* n4 = reinterpret_cast<const float4*>(a.norm_w);
     for (int k4 = tid; k4 < (Kpad >> 2); k4 += kGemvThreads) {
-      float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-      if (k4 < (K >> 2) && m < mt) {
-        v = x4[k4];
-        if (y4 != nullptr) { const float4 w2 = y4[k4]; v.x += w2.x; v.y += w2.y; v.z += w2.z; v.w += w2.w; }
-        ss += v.x * v.x + v.y * v.y + v.z * v.z + v.w * v.w;
-        if (normed) {
-          const float4 nw = n4[k4];
-          v.x *= nw.x; v.y *= nw.y; v.z *= nw.z; v.w *= nw.w;
+      const bool in_k = k4 < (K >> 2);
+      const int k4c = min(k4, (K >> 2) - 1);
+      float4 v[MT];
+      float4 nw = make_float4(1.f, 1.f, 1.f, 1.f);
+      if (normed) nw = n4[k4c];
+#pragma unroll
+      for (int m = 0; m < MT; ++m) {
+        const size_t ro = (size_t)(m0 + min(m, mt - 1)) * a.ldx;
+        v[m] = reinterpret_cast<const float4*>(a.X + ro)[k4c];
+        if (a.X2 != nullptr) {
+          const float4 w2 = reinterpret_cast<const float4*>(a.X2 + ro)[k4c];
+          v[m].x += w2.x; v[m].y += w2.y; v[m].z += w2.z; v[m].w += w2.w;
         }
       }
-      xs4[(size_t)m * (Kpad >> 2) + xs_slot4(k4)] = v;
+#pragma unroll
+      for (int m = 0; m < MT; ++m) {
+        float4 o = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (in_k && m < mt) {
+          o = v[m];
+          ss[m] += o.x * o.x + o.y * o.y + o.z * o.z + o.w * o.w;
+          o.x *= nw.x; o.y *= nw.y; o.z *= nw.z; o.w *= nw.w;
+        }
+        xs4[(size_t)m * (Kpad >> 2) + xs_slot4(k4)] = o;
+      }
     }
     if (normed) {
-      ss = wave_sum(ss);
-      if (lane == 0) red[wave * MT + m] = ss;
+#pragma unroll
+      for (int m = 0; m < MT; ++m) {
+        const float t = wave_sum(ss[m]);
+        if (lane == 0) red[wave * MT + m] = t;
+      }
     }
   }
   __syncthreads();

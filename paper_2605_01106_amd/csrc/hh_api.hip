@@ -596,6 +596,13 @@ hh_status hh_prefill(hh_ctx* x, const int32_t* tokens, int32_t row_stride, const
     hh_status st = run_layers(x, true, B, T, nt, p == 0 ? 2 : 0, 1, 1, s);
     if (st != HH_OK) return st;
     HH_HIP(launch_prefill_tail(x->h, T, d.D, nt, x->plan_last + (size_t)p * B, x->lasth, x->kv_len, B, s));
+    // HH_PROGRESS=n: wait for every n-th pass and report it (long prompts; otherwise the call only enqueues)
+    static const int progress = getenv("HH_PROGRESS") ? atoi(getenv("HH_PROGRESS")) : 0;
+    if (progress > 0 && (p + 1) % progress == 0) {
+      HH_HIP(hipStreamSynchronize(s));
+      fprintf(stderr, "[hh] prefill pass %d of %d done\n", p + 1, n_pass);
+      fflush(stderr);
+    }
   }
   hh_status st = run_head(x, x->lasth, B, 1, x->logits_p, d.V, x->first_tok, 1, 0, s);
   if (st != HH_OK) return st;

@@ -33,7 +33,7 @@ __device__ __forceinline__ uint16_t bf16_rne(float f) {
 }
 __device__ __forceinline__ float bf16_f32(uint16_t h) { return __uint_as_float((uint32_t)h << 16); }
 
-// planes [3][Mp][Kp] bf16; rows >= M and columns >= K are zero
+// split activations in MFMA operand order (see below); rows >= M and columns >= K are zero
 __global__ __launch_bounds__(256) void split_rows_kernel(const float* __restrict__ X, const float* __restrict__ X2, int ldx, int M, int K, int Mp, int Kp,
                                                          const float* __restrict__ norm_w, float eps,
                                                          uint16_t* __restrict__ planes) {
@@ -52,7 +52,9 @@ __global__ __launch_bounds__(256) void split_rows_kernel(const float* __restrict
     __syncthreads();
     rstd = 1.0f / sqrtf((red[0] + red[1] + red[2] + red[3]) / (float)K + eps);
   }
-  const size_t plane = (size_t)Mp * Kp;
+  // operand order: block (row tile, step of 32 columns, term) of 512 elements, lane 16 g + n at
+  // element 8 (16 g + n), n = row % 16, g = (column % 32) / 8: a wavefront load is 1 KB contiguous
+  const int KST = Kp >> 5;
   for (int k = threadIdx.x; k < Kp; k += 256) {
     uint16_t t0 = 0, t1 = 0, t2 = 0;
     if (m < M && k < K) {
@@ -64,8 +66,8 @@ __global__ __launch_bounds__(256) void split_rows_kernel(const float* __restrict
       const float r2 = r1 - bf16_f32(t1);
       t2 = bf16_rne(r2);
     }
-    const size_t at = (size_t)m * Kp + k;
-    planes[at] = t0; planes[plane + at] = t1; planes[2 * plane + at] = t2;
+    const size_t at = (((size_t)(m >> 4) * KST + (k >> 5)) * 3) * 512 + (size_t)((((k & 31) >> 3) * 16 + (m & 15)) * 8 + (k & 7));
+    planes[at] = t0; planes[at + 512] = t1; planes[at + 1024] = t2;
   }
 }
 
@@ -86,7 +88,7 @@ union GFrag {
 };
 
 template <int EPI, int NT, int MTW>
-__global__ __launch_bounds__(256) void gemm_tiled_kernel(const GemmArgs a) {
+__global__ __launch_bounds__(256, 2) void gemm_tiled_kernel(const GemmArgs a) {
   constexpr int NF = EPI == EPI_SWIGLU ? 2 : 1;
   const int lane = threadIdx.x & 63;
   const int unit = blockIdx.x * 4 + (threadIdx.x >> 6);
@@ -98,7 +100,6 @@ __global__ __launch_bounds__(256) void gemm_tiled_kernel(const GemmArgs a) {
   const int KST = (a.K + 31) >> 5, n_tiles = (a.N + 15) >> 4, m_tiles = a.Mp >> 4;
   const int k_begin = kp * a.ksteps, k_end = min(KST, k_begin + a.ksteps);
   const int t0 = sg * NT, mt0 = mg * MTW;
-  const size_t plane = (size_t)a.Mp * a.Kp;
 
   f32x4 acc[NF][NT][MTW];
 #pragma unroll
@@ -118,9 +119,9 @@ __global__ __launch_bounds__(256) void gemm_tiled_kernel(const GemmArgs a) {
     }
 #pragma unroll
     for (int m = 0; m < MTW; ++m) {
-      const uint16_t* src = a.planes + (size_t)(min(mt0 + m, m_tiles - 1) * 16 + n) * a.Kp + ks * 32 + 8 * g;
+      const uint16_t* src = a.planes + (((size_t)min(mt0 + m, m_tiles - 1) * KST + ks) * 3) * 512 + lane * 8;
 #pragma unroll
-      for (int term = 0; term < 3; ++term) x[term][m].u = *reinterpret_cast<const uint4*>(src + term * plane);
+      for (int term = 0; term < 3; ++term) x[term][m].u = *reinterpret_cast<const uint4*>(src + term * 512);
     }
   };
   auto mul_step = [&](const GFrag(&w)[NF][NT], const GFrag(&x)[3][MTW]) {

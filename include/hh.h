@@ -111,7 +111,10 @@ typedef struct hh_weights {
 /* Bytes of device workspace needed for cfg (workspace fields ignored); 0 if cfg is invalid. */
 HH_API size_t hh_workspace_bytes(const hh_cfg* cfg);
 
-/* Validates cfg, carves the workspace, builds the RoPE table.  *out is NULL on failure. */
+/* Validates cfg, carves the workspace, builds the RoPE table and, for bf16 weights, the library's
+ * own copies of the matrices (stacked input projections; every matrix repacked into matrix-core
+ * operand tiles): the workspace therefore holds about 1.2x the matrix bytes besides the caches.
+ * The caller's weights must stay valid and unchanged while the context lives.  *out is NULL on failure. */
 HH_API hh_status hh_create(const hh_weights* weights, const hh_cfg* cfg, hh_ctx** out);
 HH_API hh_status hh_destroy(hh_ctx* ctx);
 

@@ -19,6 +19,7 @@
 // Queries and probabilities are float32 values split exactly into three bf16 terms, so the
 // products carry float32 accuracy; K and V are used as stored.
 #include "attn_common.h"
+#include "bf16_split.h"
 
 namespace hh {
 
@@ -35,14 +36,7 @@ union Frag {
   bf16x8 v;
 };
 
-// x = t0 + t1 + t2 exactly (up to the last bits of a float32), each term a bf16
-__device__ __forceinline__ void split3(float x, uint32_t& t0, uint32_t& t1, uint32_t& t2) {
-  t0 = f32_to_bf16_rne(x);
-  const float r1 = x - bf16_bits_to_f32((uint16_t)t0);
-  t1 = f32_to_bf16_rne(r1);
-  const float r2 = r1 - bf16_bits_to_f32((uint16_t)t1);
-  t2 = f32_to_bf16_rne(r2);
-}
+__device__ __forceinline__ void split3(float x, uint32_t& t0, uint32_t& t1, uint32_t& t2) { split3_bf16(x, t0, t1, t2); }
 
 __device__ __forceinline__ float xor_max(float v) {
   v = fmaxf(v, __shfl_xor(v, 16, 64));

@@ -19,6 +19,7 @@
 #include <stdlib.h>
 
 #include "hh_internal.h"
+#include "bf16_split.h"
 
 namespace hh {
 
@@ -60,11 +61,9 @@ __global__ __launch_bounds__(256) void split_rows_kernel(const float* __restrict
     if (m < M && k < K) {
       float v = X[(size_t)m * ldx + k] + (X2 != nullptr ? X2[(size_t)m * ldx + k] : 0.f);
       if (norm_w != nullptr) v = v * norm_w[k] * rstd;
-      t0 = bf16_rne(v);
-      const float r1 = v - bf16_f32(t0);
-      t1 = bf16_rne(r1);
-      const float r2 = r1 - bf16_f32(t1);
-      t2 = bf16_rne(r2);
+      uint32_t b0, b1, b2;
+      split3_bf16(v, b0, b1, b2);
+      t0 = (uint16_t)b0; t1 = (uint16_t)b1; t2 = (uint16_t)b2;
     }
     const size_t at = (((size_t)(m >> 4) * KST + (k >> 5)) * 3) * 512 + (size_t)((((k & 31) >> 3) * 16 + (m & 15)) * 8 + (k & 7));
     planes[at] = t0; planes[at + 512] = t1; planes[at + 1024] = t2;

@@ -18,6 +18,7 @@
 
 #include "hh_internal.h"
 #include "trace.h"
+#include "bf16_split.h"
 
 namespace hh {
 
@@ -34,13 +35,7 @@ __device__ __forceinline__ uint32_t sk_bf16_rne(float f) {
   u += 0x7FFFu + ((u >> 16) & 1u);
   return u >> 16;
 }
-__device__ __forceinline__ void sk_split3(float x, uint32_t& t0, uint32_t& t1, uint32_t& t2) {
-  t0 = sk_bf16_rne(x);
-  const float r1 = x - __uint_as_float(t0 << 16);
-  t1 = sk_bf16_rne(r1);
-  const float r2 = r1 - __uint_as_float(t1 << 16);
-  t2 = sk_bf16_rne(r2);
-}
+__device__ __forceinline__ void sk_split3(float x, uint32_t& t0, uint32_t& t1, uint32_t& t2) { split3_bf16(x, t0, t1, t2); }
 __device__ __forceinline__ unsigned long long sk_argmax_key(float v, int n) {
   uint32_t u = __float_as_uint(v);
   u = (u & 0x80000000u) ? ~u : (u | 0x80000000u);

@@ -21,4 +21,26 @@ __device__ __forceinline__ void split3_bf16(float x, uint32_t& t0, uint32_t& t1,
   t2 = bf16_bits_hw(r2);
 }
 
+// The same split for two values at once; word k holds term k of a (low half) and of b (high half).
+typedef float split_f32x2 __attribute__((ext_vector_type(2)));
+typedef __bf16 split_bf16x2 __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ uint32_t bf16_pair_hw(float a, float b) {
+  const split_f32x2 v = {a, b};
+  const split_bf16x2 r = __builtin_convertvector(v, split_bf16x2);
+  return *reinterpret_cast<const uint32_t*>(&r);
+}
+__device__ __forceinline__ void split3_bf16_pair(float a, float b, uint32_t& w0, uint32_t& w1, uint32_t& w2) {
+  w0 = bf16_pair_hw(a, b);
+  const float ra = a - __uint_as_float(w0 << 16), rb = b - __uint_as_float(w0 & 0xffff0000u);
+  w1 = bf16_pair_hw(ra, rb);
+  const float sa = ra - __uint_as_float(w1 << 16), sb = rb - __uint_as_float(w1 & 0xffff0000u);
+  w2 = bf16_pair_hw(sa, sb);
+}
+
+// Two terms only: a + b's leading 16 mantissa bits (relative error 2^-17).
+__device__ __forceinline__ void split2_bf16_pair(float a, float b, uint32_t& w0, uint32_t& w1) {
+  w0 = bf16_pair_hw(a, b);
+  w1 = bf16_pair_hw(a - __uint_as_float(w0 << 16), b - __uint_as_float(w0 & 0xffff0000u));
+}
+
 }  // namespace hh

@@ -79,6 +79,9 @@ struct GemmArgs {
   int M, N, K;
   int strip_groups, m_groups, ksplit;     // units = strip_groups * m_groups * ksplit
   int ksteps;                             // steps of 32 columns per unit
+  // reduction only: per-split sums of squares of the activation rows [ksplit][16] (or nullptr);
+  // the row sum is then scaled by 1 / sqrt(sum * rnorm_k + eps)
+  const float* ssq; float rnorm_k, eps;
 };
 
 union GFrag {
@@ -193,6 +196,11 @@ __global__ __launch_bounds__(256) void gemm_reduce_kernel(const GemmArgs a) {
     }
     float* y = a.Y + m * a.ldy + nn;
     float o = v[0];
+    if (a.ssq != nullptr) {
+      float tot = 0.f;
+      for (int s = 0; s < a.ksplit; ++s) tot += a.ssq[s * 16 + m];
+      o *= 1.0f / sqrtf(tot * a.rnorm_k + a.eps);
+    }
     if (EPI == EPI_SWIGLU) o = o / (1.0f + expf(-o)) * v[NF - 1];
     if (EPI == EPI_ADD) o += *y + (a.R2 != nullptr ? a.R2[m * a.ldy + nn] : 0.f);
     *y = o;
@@ -265,6 +273,22 @@ hipError_t launch_gemm_mfma(const GemvArgs& g, uint16_t* planes, float* partial,
     case EPI_ADD: hipLaunchKernelGGL(gemm_reduce_kernel<EPI_ADD>, dim3(rb), dim3(256), 0, s, a); break;
     case EPI_SWIGLU: hipLaunchKernelGGL(gemm_reduce_kernel<EPI_SWIGLU>, dim3(rb), dim3(256), 0, s, a); break;
   }
+  return hipGetLastError();
+}
+
+// Sum of `ksplit` partial products [ksplit][M][N] in order + epilogue (store or residual add),
+// for the K windows of the skinny kernel.  ssq: see GemmArgs (M <= 16 there).
+hipError_t launch_gemm_reduce(int epi, float* partial, int ksplit, int M, int N, float* Y, int ldy, const float* R2,
+                              const float* ssq, float rnorm_k, float eps, hipStream_t s) {
+  if (epi != EPI_STORE && epi != EPI_ADD) return hipErrorInvalidValue;
+  if (ssq != nullptr && M > 16) return hipErrorInvalidValue;
+  GemmArgs a{};
+  a.partial = partial; a.ksplit = ksplit; a.M = M; a.N = N; a.Y = Y; a.ldy = ldy; a.R2 = R2;
+  a.ssq = ssq; a.rnorm_k = rnorm_k; a.eps = eps;
+  const size_t total = (size_t)M * N;
+  const int rb = (int)((total + 255) / 256 < 2048 ? (total + 255) / 256 : 2048);
+  if (epi == EPI_STORE) hipLaunchKernelGGL(gemm_reduce_kernel<EPI_STORE>, dim3(rb), dim3(256), 0, s, a);
+  else hipLaunchKernelGGL(gemm_reduce_kernel<EPI_ADD>, dim3(rb), dim3(256), 0, s, a);
   return hipGetLastError();
 }
 

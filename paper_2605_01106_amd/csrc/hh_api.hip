@@ -252,7 +252,7 @@ bool skinny_args(const GemvArgs& a, GemvArgs& b) {
 // side: the product is enqueued on the side stream (its own scratch, so that it may overlap a product on the main stream)
 hipError_t product(hh_ctx* x, const GemvArgs& a, hipStream_t s, bool side = false) {
   GemvArgs b;
-  if (skinny_args(a, b)) return launch_skinny_mfma(b, nullptr, s);
+  if (skinny_args(a, b)) return launch_skinny_mfma(b, side ? x->gemm_partial_side : x->gemm_partial, nullptr, s);
   if (a.bf16 && a.M >= kMfmaMinRows && a.seg[0].P != nullptr)
     return launch_gemm_mfma(a, side ? x->planes_side : x->planes, side ? x->gemm_partial_side : x->gemm_partial, s);
   return launch_gemv(a, nullptr, s);
@@ -341,7 +341,7 @@ hh_status run_head(hh_ctx* x, const float* X, int M, int T, float* logits, int l
   GemvArgs sk;
   if (skinny_args(a, sk)) {
     int nb = 0;
-    HH_LAUNCH(HH_K_LM_HEAD, launch_skinny_mfma(sk, &nb, s));
+    HH_LAUNCH(HH_K_LM_HEAD, launch_skinny_mfma(sk, x->gemm_partial, &nb, s));
     HH_HIP(launch_argmax_finish(x->best, nb, M, out, out_stride, out_off, T, s));
     return HH_OK;
   }

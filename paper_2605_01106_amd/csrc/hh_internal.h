@@ -63,7 +63,9 @@ int gemv_max_blocks();   // upper bound on gridDim.x of launch_gemv (size of the
 __host__ __device__ size_t packed_weight_elems(int N, int K);
 hipError_t launch_pack_weights(const void* W, int N, int K, size_t ldw, void* P, hipStream_t s);
 bool skinny_mfma_fits(const GemvArgs& a);
-hipError_t launch_skinny_mfma(const GemvArgs& a, int* n_blocks_out, hipStream_t s);
+hipError_t launch_skinny_mfma(const GemvArgs& a, float* partial, int* n_blocks_out, hipStream_t s);
+hipError_t launch_gemm_reduce(int epi, float* partial, int ksplit, int M, int N, float* Y, int ldy, const float* R2,
+                              const float* ssq, float rnorm_k, float eps, hipStream_t s);
 
 // ---- the same product on the matrix cores (bf16 weights, more than a few activation rows)
 size_t gemm_planes_elems(int M, int K);   // bf16 elements of scratch for the split activations

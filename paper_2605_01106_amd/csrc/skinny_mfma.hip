@@ -63,8 +63,13 @@ struct SkinnyArgs {
   float* Y; int ldy, N;
   unsigned long long* best;                // [M][gridDim.x] argmax partials, or nullptr
   int rounds;                              // weight tiles per workgroup (tile = blockIdx.x + round * gridDim.x)
-  int k0, kst_row;                         // this launch covers columns k0 .. k0 + K of rows that hold kst_row steps
+  int k0, kst_row;                         // workgroup (x, y) covers columns k0 + y K .. + K of rows that hold kst_row steps
   float rnorm_k;                           // 1 / (columns the RMSNorm averages over)
+  // K windows side by side (gridDim.y > 1): window y stores its raw partial product at
+  // Y + y * ywin (EPI_STORE) and, with a norm, its sums of squares at ssq[y * 16 + row]; a
+  // reduction kernel adds the windows in order and applies norm scale and epilogue.
+  size_t ywin;
+  float* ssq;
 };
 
 // NWAVES wavefronts split K, each taking KSTEPS steps of 32 columns; a round is one tile of 16
@@ -83,6 +88,8 @@ __global__ __launch_bounds__(64 * NWAVES) void skinny_mfma_kernel(const SkinnyAr
   const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int g = lane >> 4, n = lane & 15;
   const int K = a.K, M = a.M, N = a.N;
+  const int k0 = a.k0 + (int)blockIdx.y * K;                // first column of this workgroup's window
+  float* const Yw = a.Y + (size_t)blockIdx.y * a.ywin;
   const int kb = wave * KSTEPS * 32;                        // first column of this wavefront's slice
   uint16_t* xs = reinterpret_cast<uint16_t*>(smem_raw) + (size_t)wave * 3 * M * SL;          // [3][M][SL]
   float* red = reinterpret_cast<float*>(smem_raw + (size_t)NWAVES * 3 * M * SL * 2);         // [NWAVES][16]
@@ -100,7 +107,7 @@ __global__ __launch_bounds__(64 * NWAVES) void skinny_mfma_kernel(const SkinnyAr
 #pragma unroll
     for (int s = 0; s < KSTEPS; ++s) {
       // steps past the end of the row (last wavefronts only) re-read the last step and meet zero activations
-      const size_t at = ((size_t)tile * a.kst_row + (a.k0 >> 5) + min(ks0 + s, KST - 1)) * 512 + lane * 8;
+      const size_t at = ((size_t)tile * a.kst_row + (k0 >> 5) + min(ks0 + s, KST - 1)) * 512 + lane * 8;
       w[0][s].u = *reinterpret_cast<const uint4*>(a.W + at);
       if (NF == 2) w[NF - 1][s].u = *reinterpret_cast<const uint4*>(a.W2 + at);
     }
@@ -122,12 +129,12 @@ __global__ __launch_bounds__(64 * NWAVES) void skinny_mfma_kernel(const SkinnyAr
         const int col = kb + 4 * ci[u];
         ok[u] = it < items && col < K;
         const int colc = min(col, K - 4);
-        v[u] = *reinterpret_cast<const float4*>(a.X + (size_t)mi[u] * a.ldx + a.k0 + colc);
+        v[u] = *reinterpret_cast<const float4*>(a.X + (size_t)mi[u] * a.ldx + k0 + colc);
         if (a.X2 != nullptr) {
-          const float4 w2 = *reinterpret_cast<const float4*>(a.X2 + (size_t)mi[u] * a.ldx + a.k0 + colc);
+          const float4 w2 = *reinterpret_cast<const float4*>(a.X2 + (size_t)mi[u] * a.ldx + k0 + colc);
           v[u].x += w2.x; v[u].y += w2.y; v[u].z += w2.z; v[u].w += w2.w;
         }
-        nw[u] = normed ? *reinterpret_cast<const float4*>(a.norm_w + a.k0 + colc) : make_float4(1.f, 1.f, 1.f, 1.f);
+        nw[u] = normed ? *reinterpret_cast<const float4*>(a.norm_w + k0 + colc) : make_float4(1.f, 1.f, 1.f, 1.f);
       }
     };
     auto process = [&](int it0) {
@@ -172,7 +179,8 @@ __global__ __launch_bounds__(64 * NWAVES) void skinny_mfma_kernel(const SkinnyAr
     float tot = 0.f;
 #pragma unroll
     for (int w = 0; w < NWAVES; ++w) tot += red[w * 16 + n];
-    rstd = 1.0f / sqrtf(tot * a.rnorm_k + a.eps);
+    if (a.ssq == nullptr) rstd = 1.0f / sqrtf(tot * a.rnorm_k + a.eps);
+    else if (blockIdx.x == 0 && wave == 0 && g == 0) a.ssq[blockIdx.y * 16 + n] = tot;   // the reduction kernel scales
   }
   // this lane's activation fragments; lanes n >= M hold copies of a valid row (their columns of
   // the product are never stored)
@@ -188,7 +196,7 @@ __global__ __launch_bounds__(64 * NWAVES) void skinny_mfma_kernel(const SkinnyAr
     const int row0 = tile * 16 + 4 * g;
     const bool vec = n < M && row0 + 3 < N && (a.ldy & 3) == 0;
     if (EPI == EPI_ADD && wave == fin && vec) {
-      old = *reinterpret_cast<const float4*>(a.Y + (size_t)n * a.ldy + row0);
+      old = *reinterpret_cast<const float4*>(Yw + (size_t)n * a.ldy + row0);
       if (a.R2 != nullptr) {
         const float4 o2 = *reinterpret_cast<const float4*>(a.R2 + (size_t)n * a.ldy + row0);
         old.x += o2.x; old.y += o2.y; old.z += o2.z; old.w += o2.w;
@@ -224,7 +232,7 @@ __global__ __launch_bounds__(64 * NWAVES) void skinny_mfma_kernel(const SkinnyAr
         for (int w2 = 1; w2 < NWAVES; ++w2) sum[f] += pb[(f * NWAVES + w2) * 64 + lane];
       }
       if (tile < n_tiles && n < M) {
-        float* y = a.Y + (size_t)n * a.ldy + row0;
+        float* y = Yw + (size_t)n * a.ldy + row0;
         float v[4];
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
@@ -306,7 +314,7 @@ hipError_t launch_pack_weights(const void* W, int N, int K, size_t ldw, void* P,
   return hipGetLastError();
 }
 
-struct SkinnyPlan { int nwaves, ksteps, rounds, blocks; size_t lds; };
+struct SkinnyPlan { int nwaves, ksteps, rounds, blocks, windows; size_t lds; };
 
 // plan for a window of K columns of the product (the whole row, or a part when the staged
 // activations of the whole row would not fit in LDS)
@@ -334,14 +342,26 @@ static bool skinny_plan_k(const GemvArgs& g, int K, SkinnyPlan& p) {
   return p.lds <= 160 * 1024 && p.blocks <= gemv_max_blocks();
 }
 
-// number of K windows (1, 2 or 4) the product is launched in, 0 if it does not fit this kernel
+// Number of K windows (1, 2, 4 or 8) the product is computed in, 0 if it does not fit this kernel.
+// Windows are used when the staged activations of a whole row do not fit in LDS, and when the
+// product has too few weight tiles to occupy the chip (N small, K long): the windows run side
+// by side as gridDim.y and a reduction kernel adds them.
 static int skinny_windows(const GemvArgs& g, SkinnyPlan& p) {
-  if (skinny_plan_k(g, g.K, p)) return 1;
-  // windows need an epilogue that can accumulate and no row statistics over the whole K
-  if (g.epi == EPI_SWIGLU || g.norm_w != nullptr || g.best != nullptr) return 0;
-  for (int w = 2; w <= 4; w *= 2)
-    if (g.K % (32 * w) == 0 && skinny_plan_k(g, g.K / w, p)) return w;
-  return 0;
+  static const int min_blocks = getenv("HH_SKINNY_WINBLK") ? atoi(getenv("HH_SKINNY_WINBLK")) : 192;
+  const int tiles = (g.seg[0].n_rows + 15) / 16;
+  // the reduction handles store / residual add and the norm scale; not SwiGLU or argmax partials
+  const bool can_split = g.epi != EPI_SWIGLU && g.best == nullptr &&
+                         (size_t)8 * g.M * g.seg[0].n_rows + 256 <= gemm_partial_elems();
+  int best = 0;
+  SkinnyPlan q;
+  for (int w = 1; w <= 8; w *= 2) {
+    if (w > 1 && (!can_split || g.K % (32 * w) != 0 || g.K / w < 256)) break;
+    if (!skinny_plan_k(g, g.K / w, q)) continue;
+    q.windows = w;
+    p = q; best = w;
+    if (tiles * w >= min_blocks) break;
+  }
+  return best;
 }
 
 template <int EPI, int NWAVES, int KSTEPS>
@@ -353,7 +373,7 @@ static hipError_t skinny_launch_one(const SkinnyArgs& a, const SkinnyPlan& p, hi
     if (e != hipSuccess) return e;
     lds_enabled = p.lds;
   }
-  hipLaunchKernelGGL(kern, dim3(p.blocks), dim3(64 * NWAVES), p.lds, s, a);
+  hipLaunchKernelGGL(kern, dim3(p.blocks, p.windows), dim3(64 * NWAVES), p.lds, s, a);
   return hipGetLastError();
 }
 
@@ -392,31 +412,34 @@ bool skinny_mfma_fits(const GemvArgs& g) {
          skinny_windows(g, p) > 0;
 }
 
-hipError_t launch_skinny_mfma(const GemvArgs& g, int* n_blocks_out, hipStream_t s) {
+// `partial`: scratch of gemm_partial_elems() floats, used when the product is computed in K windows
+hipError_t launch_skinny_mfma(const GemvArgs& g, float* partial, int* n_blocks_out, hipStream_t s) {
   SkinnyPlan p;
   if (!skinny_mfma_fits(g)) return hipErrorInvalidValue;
   const int windows = skinny_windows(g, p);
   if (g.seg[0].n_rows <= 0) return hipSuccess;
+  if (windows > 1 && partial == nullptr) return hipErrorInvalidValue;
   SkinnyArgs a{};
   a.X = g.X; a.X2 = g.X2; a.R2 = g.R2; a.ldx = g.ldx; a.M = g.M; a.norm_w = g.norm_w; a.eps = g.eps;
   a.W = static_cast<const uint16_t*>(g.seg[0].W); a.W2 = static_cast<const uint16_t*>(g.seg[0].W2);
   a.Y = g.seg[0].Y; a.ldy = g.seg[0].ldy; a.N = g.seg[0].n_rows; a.best = g.best;
   a.rounds = p.rounds; a.kst_row = (g.K + 31) / 32; a.rnorm_k = 1.0f / (float)g.K;
-  a.K = g.K / windows;
+  a.K = g.K / windows; a.k0 = 0;
   if (n_blocks_out) *n_blocks_out = p.blocks;
-  for (int w = 0; w < windows; ++w) {
-    a.k0 = w * a.K;
-    if (w > 0) a.R2 = nullptr;                   // the second residual goes in with the first window
-    const int epi = w == 0 ? g.epi : EPI_ADD;   // later windows accumulate
-    hipError_t e = hipErrorInvalidValue;
-    switch (epi) {
-      case EPI_STORE: e = skinny_dispatch<EPI_STORE>(a, p, s); break;
-      case EPI_ADD: e = skinny_dispatch<EPI_ADD>(a, p, s); break;
-      case EPI_SWIGLU: e = skinny_dispatch<EPI_SWIGLU>(a, p, s); break;
-    }
-    if (e != hipSuccess) return e;
+  int epi = g.epi;
+  const size_t total = (size_t)g.M * a.N;
+  if (windows > 1) {
+    a.Y = partial; a.ldy = a.N; a.ywin = total; a.R2 = nullptr; epi = EPI_STORE;
+    a.ssq = g.norm_w != nullptr ? partial + (size_t)windows * total : nullptr;
   }
-  return hipSuccess;
+  hipError_t e = hipErrorInvalidValue;
+  switch (epi) {
+    case EPI_STORE: e = skinny_dispatch<EPI_STORE>(a, p, s); break;
+    case EPI_ADD: e = skinny_dispatch<EPI_ADD>(a, p, s); break;
+    case EPI_SWIGLU: e = skinny_dispatch<EPI_SWIGLU>(a, p, s); break;
+  }
+  if (e != hipSuccess || windows == 1) return e;
+  return launch_gemm_reduce(g.epi, partial, windows, g.M, a.N, g.seg[0].Y, g.seg[0].ldy, g.R2, a.ssq, a.rnorm_k, g.eps, s);
 }
 
 }  // namespace hh

@@ -79,9 +79,9 @@ struct GemmArgs {
   int M, N, K;
   int strip_groups, m_groups, ksplit;     // units = strip_groups * m_groups * ksplit
   int ksteps;                             // steps of 32 columns per unit
-  // reduction only: per-split sums of squares of the activation rows [ksplit][16] (or nullptr);
-  // the row sum is then scaled by 1 / sqrt(sum * rnorm_k + eps)
-  const float* ssq; float rnorm_k, eps;
+  // reduction only: per-split sums of squares of the activation rows [ksplit][ssq_ld] (or
+  // nullptr); the row sum is then scaled by 1 / sqrt(sum * rnorm_k + eps)
+  const float* ssq; int ssq_ld; float rnorm_k, eps;
 };
 
 union GFrag {
@@ -182,29 +182,69 @@ __global__ __launch_bounds__(256, 2) void gemm_tiled_kernel(const GemmArgs a) {
 }
 
 // second pass when K is split: sum of the partial products in split order + epilogue
-template <int EPI>
+// (4 consecutive columns per thread when the shapes allow vector accesses: VEC)
+template <int EPI, bool VEC>
 __global__ __launch_bounds__(256) void gemm_reduce_kernel(const GemmArgs a) {
   constexpr int NF = EPI == EPI_SWIGLU ? 2 : 1;
+  constexpr int W = VEC ? 4 : 1;
   const size_t total = (size_t)a.M * a.N;
-  for (size_t it = blockIdx.x * (size_t)256 + threadIdx.x; it < total; it += (size_t)gridDim.x * 256) {
+  for (size_t it = (blockIdx.x * (size_t)256 + threadIdx.x) * W; it < total; it += (size_t)gridDim.x * 256 * W) {
     const size_t m = it / a.N, nn = it - m * a.N;
-    float v[NF];
+    float v[NF][W];
 #pragma unroll
     for (int f = 0; f < NF; ++f) {
-      v[f] = 0.f;
-      for (int s = 0; s < a.ksplit; ++s) v[f] += a.partial[((size_t)s * NF + f) * total + it];
+#pragma unroll
+      for (int w = 0; w < W; ++w) v[f][w] = 0.f;
+      for (int s = 0; s < a.ksplit; ++s) {
+        const float* src = a.partial + ((size_t)s * NF + f) * total + it;
+        if (VEC) {
+          const float4 q = *reinterpret_cast<const float4*>(src);
+          v[f][0] += q.x; v[f][1 % W] += q.y; v[f][2 % W] += q.z; v[f][3 % W] += q.w;
+        } else {
+          v[f][0] += *src;
+        }
+      }
     }
-    float* y = a.Y + m * a.ldy + nn;
-    float o = v[0];
+    float scale = 1.f;
     if (a.ssq != nullptr) {
       float tot = 0.f;
-      for (int s = 0; s < a.ksplit; ++s) tot += a.ssq[s * 16 + m];
-      o *= 1.0f / sqrtf(tot * a.rnorm_k + a.eps);
+      for (int s = 0; s < a.ksplit; ++s) tot += a.ssq[(size_t)s * a.ssq_ld + m];
+      scale = 1.0f / sqrtf(tot * a.rnorm_k + a.eps);
     }
-    if (EPI == EPI_SWIGLU) o = o / (1.0f + expf(-o)) * v[NF - 1];
-    if (EPI == EPI_ADD) o += *y + (a.R2 != nullptr ? a.R2[m * a.ldy + nn] : 0.f);
-    *y = o;
+    float* y = a.Y + m * a.ldy + nn;
+    float o[W];
+#pragma unroll
+    for (int w = 0; w < W; ++w) {
+      o[w] = v[0][w] * scale;
+      if (EPI == EPI_SWIGLU) o[w] = o[w] / (1.0f + expf(-o[w])) * (v[NF - 1][w] * scale);
+    }
+    if (VEC) {
+      float4 r = make_float4(o[0], o[1 % W], o[2 % W], o[3 % W]);
+      if (EPI == EPI_ADD) {
+        const float4 old = *reinterpret_cast<const float4*>(y);
+        r.x += old.x; r.y += old.y; r.z += old.z; r.w += old.w;
+        if (a.R2 != nullptr) {
+          const float4 r2 = *reinterpret_cast<const float4*>(a.R2 + m * a.ldy + nn);
+          r.x += r2.x; r.y += r2.y; r.z += r2.z; r.w += r2.w;
+        }
+      }
+      *reinterpret_cast<float4*>(y) = r;
+    } else {
+      if (EPI == EPI_ADD) o[0] += *y + (a.R2 != nullptr ? a.R2[m * a.ldy + nn] : 0.f);
+      *y = o[0];
+    }
   }
+}
+
+template <int EPI>
+static hipError_t reduce_launch(const GemmArgs& a, hipStream_t s) {
+  const size_t total = (size_t)a.M * a.N;
+  const bool vec = a.N % 4 == 0 && a.ldy % 4 == 0;
+  const size_t items = vec ? total / 4 : total;
+  const int rb = (int)((items + 255) / 256 < 2048 ? (items + 255) / 256 : 2048);
+  if (vec) hipLaunchKernelGGL((gemm_reduce_kernel<EPI, true>), dim3(rb), dim3(256), 0, s, a);
+  else hipLaunchKernelGGL((gemm_reduce_kernel<EPI, false>), dim3(rb), dim3(256), 0, s, a);
+  return hipGetLastError();
 }
 
 size_t gemm_planes_elems(int M, int K) {
@@ -266,30 +306,29 @@ hipError_t launch_gemm_mfma(const GemvArgs& g, uint16_t* planes, float* partial,
     default: return hipErrorInvalidValue;
   }
   if (e != hipSuccess || ksplit == 1) return e;
-  const size_t total = (size_t)M * N;
-  const int rb = (int)((total + 255) / 256 < 2048 ? (total + 255) / 256 : 2048);
   switch (g.epi) {
-    case EPI_STORE: hipLaunchKernelGGL(gemm_reduce_kernel<EPI_STORE>, dim3(rb), dim3(256), 0, s, a); break;
-    case EPI_ADD: hipLaunchKernelGGL(gemm_reduce_kernel<EPI_ADD>, dim3(rb), dim3(256), 0, s, a); break;
-    case EPI_SWIGLU: hipLaunchKernelGGL(gemm_reduce_kernel<EPI_SWIGLU>, dim3(rb), dim3(256), 0, s, a); break;
+    case EPI_STORE: return reduce_launch<EPI_STORE>(a, s);
+    case EPI_ADD: return reduce_launch<EPI_ADD>(a, s);
+    case EPI_SWIGLU: return reduce_launch<EPI_SWIGLU>(a, s);
   }
-  return hipGetLastError();
+  return hipErrorInvalidValue;
 }
 
-// Sum of `ksplit` partial products [ksplit][M][N] in order + epilogue (store or residual add),
-// for the K windows of the skinny kernel.  ssq: see GemmArgs (M <= 16 there).
+// Sum of `ksplit` partial products [ksplit][NF][M][N] in order + norm scale + epilogue, for the K
+// windows of the in-kernel-split products.  ssq: per-window sums of squares [ksplit][ssq_ld] of the
+// activation rows, or nullptr (no norm).
 hipError_t launch_gemm_reduce(int epi, float* partial, int ksplit, int M, int N, float* Y, int ldy, const float* R2,
-                              const float* ssq, float rnorm_k, float eps, hipStream_t s) {
-  if (epi != EPI_STORE && epi != EPI_ADD) return hipErrorInvalidValue;
-  if (ssq != nullptr && M > 16) return hipErrorInvalidValue;
+                              const float* ssq, int ssq_ld, float rnorm_k, float eps, hipStream_t s) {
+  if (ssq != nullptr && M > ssq_ld) return hipErrorInvalidValue;
   GemmArgs a{};
   a.partial = partial; a.ksplit = ksplit; a.M = M; a.N = N; a.Y = Y; a.ldy = ldy; a.R2 = R2;
-  a.ssq = ssq; a.rnorm_k = rnorm_k; a.eps = eps;
-  const size_t total = (size_t)M * N;
-  const int rb = (int)((total + 255) / 256 < 2048 ? (total + 255) / 256 : 2048);
-  if (epi == EPI_STORE) hipLaunchKernelGGL(gemm_reduce_kernel<EPI_STORE>, dim3(rb), dim3(256), 0, s, a);
-  else hipLaunchKernelGGL(gemm_reduce_kernel<EPI_ADD>, dim3(rb), dim3(256), 0, s, a);
-  return hipGetLastError();
+  a.ssq = ssq; a.ssq_ld = ssq_ld; a.rnorm_k = rnorm_k; a.eps = eps;
+  switch (epi) {
+    case EPI_STORE: return reduce_launch<EPI_STORE>(a, s);
+    case EPI_ADD: return reduce_launch<EPI_ADD>(a, s);
+    case EPI_SWIGLU: return reduce_launch<EPI_SWIGLU>(a, s);
+  }
+  return hipErrorInvalidValue;
 }
 
 // argmax of each row of logits [M][ld] (largest value, lowest index on ties):

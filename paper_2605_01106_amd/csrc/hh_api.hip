@@ -253,6 +253,7 @@ bool skinny_args(const GemvArgs& a, GemvArgs& b) {
 hipError_t product(hh_ctx* x, const GemvArgs& a, hipStream_t s, bool side = false) {
   GemvArgs b;
   if (skinny_args(a, b)) return launch_skinny_mfma(b, side ? x->gemm_partial_side : x->gemm_partial, nullptr, s);
+  if (mid_mfma_fits(a)) return launch_mid_mfma(a, side ? x->gemm_partial_side : x->gemm_partial, s);
   if (a.bf16 && a.M >= kMfmaMinRows && a.seg[0].P != nullptr)
     return launch_gemm_mfma(a, side ? x->planes_side : x->planes, side ? x->gemm_partial_side : x->gemm_partial, s);
   return launch_gemv(a, nullptr, s);
@@ -347,7 +348,8 @@ hh_status run_head(hh_ctx* x, const float* X, int M, int T, float* logits, int l
   }
   if (a.bf16 && M >= kMfmaMinRows) {
     a.best = nullptr;
-    HH_LAUNCH(HH_K_LM_HEAD, launch_gemm_mfma(a, x->planes, x->gemm_partial, s));
+    if (mid_mfma_fits(a)) HH_LAUNCH(HH_K_LM_HEAD, launch_mid_mfma(a, x->gemm_partial, s));
+    else HH_LAUNCH(HH_K_LM_HEAD, launch_gemm_mfma(a, x->planes, x->gemm_partial, s));
     HH_HIP(launch_argmax_rows(logits, ld_logits, d.V, M, out, out_stride, out_off, T, s));
     return HH_OK;
   }

@@ -65,7 +65,12 @@ hipError_t launch_pack_weights(const void* W, int N, int K, size_t ldw, void* P,
 bool skinny_mfma_fits(const GemvArgs& a);
 hipError_t launch_skinny_mfma(const GemvArgs& a, float* partial, int* n_blocks_out, hipStream_t s);
 hipError_t launch_gemm_reduce(int epi, float* partial, int ksplit, int M, int N, float* Y, int ldy, const float* R2,
-                              const float* ssq, float rnorm_k, float eps, hipStream_t s);
+                              const float* ssq, int ssq_ld, float rnorm_k, float eps, hipStream_t s);
+
+// ---- the same product for 17..96 activation rows on the matrix cores (bf16 weights from seg[0].P / P2,
+// activations split in-kernel per K window; partial: scratch of gemm_partial_elems() floats)
+bool mid_mfma_fits(const GemvArgs& a);
+hipError_t launch_mid_mfma(const GemvArgs& a, float* partial, hipStream_t s);
 
 // ---- the same product on the matrix cores (bf16 weights, more than a few activation rows)
 size_t gemm_planes_elems(int M, int K);   // bf16 elements of scratch for the split activations

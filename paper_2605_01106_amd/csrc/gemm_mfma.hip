@@ -195,13 +195,21 @@ __global__ __launch_bounds__(256) void gemm_reduce_kernel(const GemmArgs a) {
     for (int f = 0; f < NF; ++f) {
 #pragma unroll
       for (int w = 0; w < W; ++w) v[f][w] = 0.f;
-      for (int s = 0; s < a.ksplit; ++s) {
-        const float* src = a.partial + ((size_t)s * NF + f) * total + it;
-        if (VEC) {
-          const float4 q = *reinterpret_cast<const float4*>(src);
-          v[f][0] += q.x; v[f][1 % W] += q.y; v[f][2 % W] += q.z; v[f][3 % W] += q.w;
-        } else {
-          v[f][0] += *src;
+      // 8 splits per pass, their loads issued together; added in split order
+      for (int s0 = 0; s0 < a.ksplit; s0 += 8) {
+        float4 q[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+          const float* src = a.partial + ((size_t)min(s0 + u, a.ksplit - 1) * NF + f) * total + it;
+          if (VEC) q[u] = *reinterpret_cast<const float4*>(src);
+          else q[u].x = *src;
+        }
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+          if (s0 + u < a.ksplit) {
+            v[f][0] += q[u].x;
+            if (VEC) { v[f][1 % W] += q[u].y; v[f][2 % W] += q[u].z; v[f][3 % W] += q[u].w; }
+          }
         }
       }
     }

@@ -17,6 +17,7 @@
 
 #include "hh_internal.h"
 #include "bf16_split.h"
+#include "trace.h"
 
 namespace hh {
 
@@ -52,10 +53,11 @@ __device__ __forceinline__ float mid_wave_sum(float v) {
          (__int_as_float(__builtin_amdgcn_readlane(iv, 32)) + __int_as_float(__builtin_amdgcn_readlane(iv, 48)));
 }
 
-// grid: x = groups of 8 units (strided), y = K windows.  NF = 2: SwiGLU pair.  MT row tiles of 16.
-// KSW steps of 32 columns per window (4 or 8).
-template <int NF, int MT, int KSW>
-__global__ __launch_bounds__(512) void mid_mfma_kernel(const MidArgs a) {
+// grid: x = groups of NW units (strided), y = K windows.  NF = 2: SwiGLU pair.  MT row tiles of 16.
+// KSW steps of 32 columns per window (4 or 8).  NW wavefronts per workgroup: 4 (one per SIMD, so
+// that the MFMA work of a small product spreads over all compute units) or 8.
+template <int NF, int MT, int KSW, int NW>
+__global__ __launch_bounds__(64 * NW) void mid_mfma_kernel(const MidArgs a) {
   constexpr int KW = KSW * 32, SL = KW + 8;      // window columns; staged row stride (bf16, padded)
   constexpr int ROWS = MT * 16;
   constexpr int CG = KW / 4;                     // float4 column groups per row
@@ -67,8 +69,7 @@ __global__ __launch_bounds__(512) void mid_mfma_kernel(const MidArgs a) {
   const int M = a.M, K = a.K, N = a.N;
   const int win = blockIdx.y, k0 = win * KW;
 
-  // the weight fragments of a unit; those of the first unit are requested before the
-  // activations are staged, so that they stream in meanwhile
+  // the weight fragments of a unit
   const int n_tiles = (N + 15) >> 4;
   const int KST = (K + 31) >> 5, step0 = win * KSW;
   MFrag wf[2][KSW];
@@ -84,10 +85,11 @@ __global__ __launch_bounds__(512) void mid_mfma_kernel(const MidArgs a) {
         wf[i][s].u = *reinterpret_cast<const uint4*>(Wp + (row + min(step0 + s, KST - 1)) * 512 + lane * 8);
     }
   };
-  int unit = blockIdx.x * 8 + wave;
-  if (unit < a.units) load_unit(unit);
+  int unit = blockIdx.x * NW + wave;
+  TR(0);
 
-  // ---- stage the window: rows wave*RPW + 8*RPW*i, lane = (row in pass, column group)
+  // ---- stage the window: rows wave*RPW + NW*RPW*i, lane = (row in pass, column group).  The
+  // loads of the first NB passes are requested before the weights (they would wait behind them).
   {
     const int cgi = lane % CG, rsub = lane / CG;
     const int col = k0 + 4 * cgi;
@@ -95,11 +97,11 @@ __global__ __launch_bounds__(512) void mid_mfma_kernel(const MidArgs a) {
     const int colc = okc ? col : 0;
     float4 nw = make_float4(1.f, 1.f, 1.f, 1.f);
     if (a.norm_w != nullptr) nw = *reinterpret_cast<const float4*>(a.norm_w + colc);
-    constexpr int PASS = 8 * RPW;                // rows per pass of the workgroup
+    constexpr int PASS = NW * RPW;               // rows per pass of the workgroup
     constexpr int NP = (ROWS + PASS - 1) / PASS;
-    constexpr int NB = 5;                        // passes whose loads are in flight together
-    for (int p0 = 0; p0 < NP; p0 += NB) {
-      float4 v[NB];
+    constexpr int NB = NP < 12 ? NP : 12;        // passes whose loads are in flight together
+    float4 v[NB];
+    auto issue = [&](int p0) {
 #pragma unroll
       for (int u = 0; u < NB; ++u) {
         const int r = (p0 + u) * PASS + wave * RPW + rsub;
@@ -112,6 +114,8 @@ __global__ __launch_bounds__(512) void mid_mfma_kernel(const MidArgs a) {
           }
         }
       }
+    };
+    auto process = [&](int p0) {
 #pragma unroll
       for (int u = 0; u < NB; ++u) {
         if (p0 + u >= NP) break;                 // wavefront-uniform
@@ -140,9 +144,16 @@ __global__ __launch_bounds__(512) void mid_mfma_kernel(const MidArgs a) {
           *reinterpret_cast<uint2*>(dst + (size_t)2 * ROWS * SL) = make_uint2(a2, b2);
         }
       }
-    }
+    };
+    issue(0);
+    if (unit < a.units) load_unit(unit);         // the first unit's weights stream in meanwhile
+    TR(1);
+    process(0);
+    for (int p0 = NB; p0 < NP; p0 += NB) { issue(p0); process(p0); }
   }
+  TR(2);
   __syncthreads();
+  TR(3);
 
   // ---- the units of this wavefront
   while (unit < a.units) {
@@ -167,9 +178,10 @@ __global__ __launch_bounds__(512) void mid_mfma_kernel(const MidArgs a) {
         }
       }
     }
+    TR(4);
     // the next unit's weights are requested before this unit's results are stored
     const int tl[2] = {tile[0], tile[1]};
-    unit += (int)gridDim.x * 8;
+    unit += (int)gridDim.x * NW;
     if (unit < a.units) load_unit(unit);
     // lane (g, n) holds Y[activation row mt*16 + n][weight rows tile*16 + 4g .. + 3]
 #pragma unroll
@@ -193,9 +205,10 @@ __global__ __launch_bounds__(512) void mid_mfma_kernel(const MidArgs a) {
       }
     }
   }
+  TR(5);
 }
 
-struct MidPlan { int mt, ksw, windows, units, blocks; size_t lds, partial_elems; };
+struct MidPlan { int mt, ksw, nw, windows, units, blocks; size_t lds, partial_elems; };
 
 static bool mid_plan(const GemvArgs& g, MidPlan& p) {
   if (!g.bf16 || g.n_seg != 1 || g.seg[0].P == nullptr || g.best != nullptr) return false;
@@ -204,13 +217,16 @@ static bool mid_plan(const GemvArgs& g, MidPlan& p) {
   const int nf = g.epi == EPI_SWIGLU ? 2 : 1, N = g.seg[0].n_rows, tiles = (N + 15) / 16;
   p.mt = (g.M + 15) / 16;
   p.units = nf == 2 ? tiles : (tiles + 1) / 2;
-  // windows of 256 columns; of 128 when that leaves too few workgroups for the chip
-  static const int min_blocks = getenv("HH_MID_MINBLK") ? atoi(getenv("HH_MID_MINBLK")) : 200;
+  // Windows of 256 columns, of 128 when that leaves too few wavefront units for the chip's 1024
+  // SIMDs (the MFMA work of a unit is what bounds a small product); 4 wavefronts per workgroup
+  // (one per SIMD) unless there are units for 8.
+  static const int min_units = getenv("HH_MID_MINUNITS") ? atoi(getenv("HH_MID_MINUNITS")) : 1024;
   p.ksw = 8;
-  if ((long)((p.units + 7) / 8) * ((g.K + 255) / 256) < min_blocks) p.ksw = 4;
+  if ((long)p.units * ((g.K + 255) / 256) < min_units) p.ksw = 4;
   const int kw = p.ksw * 32;
   p.windows = (g.K + kw - 1) / kw;
-  p.blocks = (p.units + 7) / 8;
+  p.nw = (long)p.units * p.windows >= 4096 ? 8 : 4;
+  p.blocks = (p.units + p.nw - 1) / p.nw;
   // more than ~4 workgroups per compute unit: several units per wavefront instead
   while ((long)p.blocks * p.windows > 1024 && p.blocks > 1) p.blocks = (p.blocks + 1) / 2;
   p.lds = (size_t)3 * p.mt * 16 * (kw + 8) * 2;
@@ -224,21 +240,22 @@ bool mid_mfma_fits(const GemvArgs& g) {
   return !off && mid_plan(g, p);
 }
 
-template <int NF, int MT, int KSW>
+template <int NF, int MT, int KSW, int NW>
 static hipError_t mid_launch(const MidArgs& a, const MidPlan& p, hipStream_t s) {
-  auto kern = mid_mfma_kernel<NF, MT, KSW>;
+  auto kern = mid_mfma_kernel<NF, MT, KSW, NW>;
   static size_t lds_enabled = 48 * 1024;
   if (p.lds > lds_enabled) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)p.lds);
     if (e != hipSuccess) return e;
     lds_enabled = p.lds;
   }
-  hipLaunchKernelGGL(kern, dim3(p.blocks, p.windows), dim3(512), p.lds, s, a);
+  hipLaunchKernelGGL(kern, dim3(p.blocks, p.windows), dim3(64 * NW), p.lds, s, a);
   return hipGetLastError();
 }
 template <int NF, int MT>
 static hipError_t mid_dispatch_k(const MidArgs& a, const MidPlan& p, hipStream_t s) {
-  return p.ksw == 8 ? mid_launch<NF, MT, 8>(a, p, s) : mid_launch<NF, MT, 4>(a, p, s);
+  if (p.nw == 8) return p.ksw == 8 ? mid_launch<NF, MT, 8, 8>(a, p, s) : mid_launch<NF, MT, 4, 8>(a, p, s);
+  return p.ksw == 8 ? mid_launch<NF, MT, 8, 4>(a, p, s) : mid_launch<NF, MT, 4, 4>(a, p, s);
 }
 template <int NF>
 static hipError_t mid_dispatch(const MidArgs& a, const MidPlan& p, hipStream_t s) {

@@ -183,22 +183,30 @@ __global__ __launch_bounds__(kRows * kSub) void ssm_kernel(const Dims d, const S
 // and of the 3 before them, dt, z) is issued before the first result is used, so the kernel
 // costs about one memory round trip plus the recurrence.  The conv of B and C is computed
 // once per workgroup, 4 channels per lane, and handed to the lanes through LDS.
-template <int NV, int SUBS, int TMAX>
+// RG row groups of 64 / SUBS rows per workgroup, one after the other: the B/C convolution and the
+// per-head scalars are shared by all of them, which is what a large batch needs (there a
+// workgroup's fixed loads would otherwise exceed its share of the state).
+template <int NV, int SUBS, int TMAX, int RG>
 __global__ __launch_bounds__(64) void ssm_small_kernel(const Dims d, const SsmArgs a) {
   constexpr int ROWS = 64 / SUBS, N = NV * SUBS;
   constexpr int NG = (2 * N / 4 + 63) / 64;      // groups of 4 B|C channels per lane
   __shared__ __align__(16) float BCs[TMAX][2 * N];
 
   const int lane = threadIdx.x, row = lane / SUBS, sub = lane % SUBS;
-  const int p0 = blockIdx.x * ROWS, h = blockIdx.y;
+  const int p0 = blockIdx.x * ROWS * RG, h = blockIdx.y;
   const int lz = blockIdx.z / a.B, b = blockIdx.z % a.B;
   const LayerDev& ly = a.layers != nullptr ? a.layers[a.layer0 + lz] : a.one;
   TR(0);
   // Loads in the order of what they wait for.  Nothing here depends on the per-sequence
   // scalars except the ring rows (slot = position mod ring size), which come last.
-  const int p = min(p0 + row, d.P - 1);
-  const bool prow = p0 + row < d.P;
-  const int cx = h * d.P + p;
+  int pr[RG], cx[RG];
+  bool prow[RG];
+#pragma unroll
+  for (int rg = 0; rg < RG; ++rg) {
+    pr[rg] = min(p0 + rg * ROWS + row, d.P - 1);
+    prow[rg] = p0 + rg * ROWS + row < d.P;
+    cx[rg] = h * d.P + pr[rg];
+  }
   const int rmask = d.ring_slots - 1;
   float* ring = ly.ring + (size_t)b * d.ring_slots * d.ring_w;
   const float* zx = a.zx != nullptr ? a.zx + (size_t)b * a.T * d.ldzx : nullptr;
@@ -206,23 +214,26 @@ __global__ __launch_bounds__(64) void ssm_small_kernel(const Dims d, const SsmAr
   const int nacc_v = (a.n_acc != nullptr ? a.n_acc : a.pos0)[b];
   const int ntok_v = (a.n_tok != nullptr ? a.n_tok : a.pos0)[b];
   const int pos0 = a.pos0[b];
-  float S[NV];
+  float S[RG][NV];
   {
     const float* src = a.state_in == 0 ? ly.S : (a.state_in == 1 ? ly.S_draft : nullptr);
-    if (src != nullptr) {
-      const float* sp = src + (((size_t)b * d.Hm + h) * d.P + p) * N + sub * NV;
 #pragma unroll
-      for (int i = 0; i < NV; i += 4) {
-        const float4 v = *reinterpret_cast<const float4*>(sp + i);
-        S[i] = v.x; S[i + 1] = v.y; S[i + 2] = v.z; S[i + 3] = v.w;
+    for (int rg = 0; rg < RG; ++rg) {
+      if (src != nullptr) {
+        const float* sp = src + (((size_t)b * d.Hm + h) * d.P + pr[rg]) * N + sub * NV;
+#pragma unroll
+        for (int i = 0; i < NV; i += 4) {
+          const float4 v = *reinterpret_cast<const float4*>(sp + i);
+          S[rg][i] = v.x; S[rg][i + 1] = v.y; S[rg][i + 2] = v.z; S[rg][i + 3] = v.w;
+        }
+      } else {
+#pragma unroll
+        for (int i = 0; i < NV; ++i) S[rg][i] = 0.f;
       }
-    } else {
-#pragma unroll
-      for (int i = 0; i < NV; ++i) S[i] = 0.f;
     }
   }
   float4 bw[NG][4], bb[NG], braw[NG][TMAX + 3];
-  float xraw[TMAX + 3], zg[TMAX];
+  float xraw[RG][TMAX + 3], zg[RG][TMAX];
   float dtraw_l = 0.f;   // raw dt of position `lane` (lanes < T): softplus and decay are evaluated once, lane-parallel
 #pragma unroll
   for (int u = 0; u < NG; ++u) {
@@ -231,8 +242,13 @@ __global__ __launch_bounds__(64) void ssm_small_kernel(const Dims d, const SsmAr
     for (int t = 0; t < 4; ++t) bw[u][t] = *reinterpret_cast<const float4*>(ly.conv_w + (size_t)(c + t) * 4);
     bb[u] = *reinterpret_cast<const float4*>(ly.conv_b + c);
   }
-  const float4 xw = *reinterpret_cast<const float4*>(ly.conv_w + (size_t)cx * 4);
-  const float xb = ly.conv_b[cx];
+  float4 xw[RG];
+  float xb[RG];
+#pragma unroll
+  for (int rg = 0; rg < RG; ++rg) {
+    xw[rg] = *reinterpret_cast<const float4*>(ly.conv_w + (size_t)cx[rg] * 4);
+    xb[rg] = ly.conv_b[cx[rg]];
+  }
   const float dskip = ly.d_skip[h];
   const float dtb = ly.dt_bias[h];
   const float alog = ly.a_log[h];
@@ -242,8 +258,11 @@ __global__ __launch_bounds__(64) void ssm_small_kernel(const Dims d, const SsmAr
       const float* r = zx + (size_t)min(j, a.T - 1) * d.ldzx + d.d_inner;
 #pragma unroll
       for (int u = 0; u < NG; ++u) braw[u][j + 3] = *reinterpret_cast<const float4*>(r + d.d_inner + 4 * min(lane + 64 * u, 2 * N / 4 - 1));
-      xraw[j + 3] = r[cx];
-      zg[j] = a.g != nullptr ? r[cx - d.d_inner] : 0.f;   // z precedes xBC in the row
+#pragma unroll
+      for (int rg = 0; rg < RG; ++rg) {
+        xraw[rg][j + 3] = r[cx[rg]];
+        zg[rg][j] = a.g != nullptr ? r[cx[rg] - d.d_inner] : 0.f;   // z precedes xBC in the row
+      }
     }
     dtraw_l = zx[(size_t)min(lane, a.T - 1) * d.ldzx + d.d_inner + d.conv_dim + h];
   }
@@ -261,8 +280,11 @@ __global__ __launch_bounds__(64) void ssm_small_kernel(const Dims d, const SsmAr
     const float* r = ring_row(min(j, nt - 1));
 #pragma unroll
     for (int u = 0; u < NG; ++u) braw[u][j + 3] = *reinterpret_cast<const float4*>(r + d.d_inner + 4 * min(lane + 64 * u, 2 * N / 4 - 1));
-    xraw[j + 3] = r[cx];
-    if (j >= 0) zg[j] = 0.f;
+#pragma unroll
+    for (int rg = 0; rg < RG; ++rg) {
+      xraw[rg][j + 3] = r[cx[rg]];
+      if (j >= 0) zg[rg][j] = 0.f;
+    }
   }
   if (zx == nullptr) dtraw_l = ring_row(min(lane, nt - 1))[d.conv_dim + h];
   const float negA = -expf(alog);
@@ -290,30 +312,25 @@ __global__ __launch_bounds__(64) void ssm_small_kernel(const Dims d, const SsmAr
       if (gi < 2 * N / 4) *reinterpret_cast<float4*>(&BCs[j][4 * gi]) = o;
     }
   }
-  // ---- per-position scalars of this lane's row and head, all positions at once
-  float xv[TMAX], aj[TMAX], coef[TMAX], gate[TMAX];
+  // ---- per-position scalars of the head (step and decay), all positions at once
+  float dtj[TMAX], aj[TMAX];
   const float dt_l = softplus_f(dtraw_l + dtb);
   const float a_l = expf(negA * dt_l);
 #pragma unroll
   for (int j = 0; j < TMAX; ++j) {
-    const float r0 = pos0 + j - 3 < 0 ? 0.f : xraw[j];
-    const float r1 = pos0 + j - 2 < 0 ? 0.f : xraw[j + 1];
-    const float r2 = pos0 + j - 1 < 0 ? 0.f : xraw[j + 2];
-    float acc = xw.x * r0;
-    acc = fmaf(xw.y, r1, acc); acc = fmaf(xw.z, r2, acc); acc = fmaf(xw.w, xraw[j + 3], acc);
-    xv[j] = silu_f(acc + xb);
-    const float dt = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(dt_l), j));
     const bool on = j < nt;
+    dtj[j] = on ? __int_as_float(__builtin_amdgcn_readlane(__float_as_int(dt_l), j)) : 0.f;
     aj[j] = on ? __int_as_float(__builtin_amdgcn_readlane(__float_as_int(a_l), j)) : 1.f;   // positions >= nt leave the state as it is
-    coef[j] = on ? dt * xv[j] : 0.f;
-    gate[j] = silu_f(zg[j]);
   }
   // ---- keep the raw inputs of these positions for later windows and for rollback
   if (a.write_ring && zx != nullptr) {
-    if (sub == 0 && prow) {
 #pragma unroll
-      for (int j = 0; j < TMAX; ++j)
-        if (j < nt) ring[(size_t)((pos0 + j) & rmask) * d.ring_w + cx] = xraw[j + 3];
+    for (int rg = 0; rg < RG; ++rg) {
+      if (sub == 0 && prow[rg]) {
+#pragma unroll
+        for (int j = 0; j < TMAX; ++j)
+          if (j < nt) ring[(size_t)((pos0 + j) & rmask) * d.ring_w + cx[rg]] = xraw[rg][j + 3];
+      }
     }
     if (h == 0 && blockIdx.x == 0) {
 #pragma unroll
@@ -335,51 +352,77 @@ __global__ __launch_bounds__(64) void ssm_small_kernel(const Dims d, const SsmAr
   __syncthreads();
   TR(3);
 
-  // ---- recurrence
-  float y[TMAX];
+  // ---- per row group: conv + SiLU of x, recurrence, outputs
 #pragma unroll
-  for (int j = 0; j < TMAX; ++j) {
-    float part = 0.f;
+  for (int rg = 0; rg < RG; ++rg) {
+    float y[TMAX];
 #pragma unroll
-    for (int i = 0; i < NV; i += 4) {
-      const float4 Bv = *reinterpret_cast<const float4*>(&BCs[j][sub * NV + i]);
-      const float4 Cv = *reinterpret_cast<const float4*>(&BCs[j][N + sub * NV + i]);
-      S[i] = fmaf(aj[j], S[i], coef[j] * Bv.x); part = fmaf(S[i], Cv.x, part);
-      S[i + 1] = fmaf(aj[j], S[i + 1], coef[j] * Bv.y); part = fmaf(S[i + 1], Cv.y, part);
-      S[i + 2] = fmaf(aj[j], S[i + 2], coef[j] * Bv.z); part = fmaf(S[i + 2], Cv.z, part);
-      S[i + 3] = fmaf(aj[j], S[i + 3], coef[j] * Bv.w); part = fmaf(S[i + 3], Cv.w, part);
+    for (int j = 0; j < TMAX; ++j) {
+      const float r0 = pos0 + j - 3 < 0 ? 0.f : xraw[rg][j];
+      const float r1 = pos0 + j - 2 < 0 ? 0.f : xraw[rg][j + 1];
+      const float r2 = pos0 + j - 1 < 0 ? 0.f : xraw[rg][j + 2];
+      float acc = xw[rg].x * r0;
+      acc = fmaf(xw[rg].y, r1, acc); acc = fmaf(xw[rg].z, r2, acc); acc = fmaf(xw[rg].w, xraw[rg][j + 3], acc);
+      const float xv = silu_f(acc + xb[rg]);
+      const float coef = dtj[j] * xv;
+      const float gate = silu_f(zg[rg][j]);
+      float part = 0.f;
+#pragma unroll
+      for (int i = 0; i < NV; i += 4) {
+        const float4 Bv = *reinterpret_cast<const float4*>(&BCs[j][sub * NV + i]);
+        const float4 Cv = *reinterpret_cast<const float4*>(&BCs[j][N + sub * NV + i]);
+        S[rg][i] = fmaf(aj[j], S[rg][i], coef * Bv.x); part = fmaf(S[rg][i], Cv.x, part);
+        S[rg][i + 1] = fmaf(aj[j], S[rg][i + 1], coef * Bv.y); part = fmaf(S[rg][i + 1], Cv.y, part);
+        S[rg][i + 2] = fmaf(aj[j], S[rg][i + 2], coef * Bv.z); part = fmaf(S[rg][i + 2], Cv.z, part);
+        S[rg][i + 3] = fmaf(aj[j], S[rg][i + 3], coef * Bv.w); part = fmaf(S[rg][i + 3], Cv.w, part);
+      }
+      part += dpp_perm_f<0xB1>(part);    // lane ^ 1
+      part += dpp_perm_f<0x4E>(part);    // lane ^ 2
+      part += dpp_perm_f<0x141>(part);   // the other quad of 8 lanes
+      if (SUBS == 16) part += dpp_perm_f<0x140>(part);   // the other half of 16 lanes
+      y[j] = (part + dskip * xv) * gate;
     }
-    part += dpp_perm_f<0xB1>(part);    // lane ^ 1
-    part += dpp_perm_f<0x4E>(part);    // lane ^ 2
-    part += dpp_perm_f<0x141>(part);   // the other quad of 8 lanes
-    if (SUBS == 16) part += dpp_perm_f<0x140>(part);   // the other half of 16 lanes
-    y[j] = (part + dskip * xv[j]) * gate[j];
-  }
-  if (a.g != nullptr && sub == 0 && prow) {
+    if (a.g != nullptr && sub == 0 && prow[rg]) {
 #pragma unroll
-    for (int j = 0; j < TMAX; ++j)
-      if (j < nt) a.g[((size_t)b * a.T + j) * d.d_inner + cx] = y[j];
-  }
-  TR(4);
-  if (a.state_out != 0 && prow) {
-    float* dst = (a.state_out == 1 ? ly.S : ly.S_draft) + (((size_t)b * d.Hm + h) * d.P + p) * N + sub * NV;
+      for (int j = 0; j < TMAX; ++j)
+        if (j < nt) a.g[((size_t)b * a.T + j) * d.d_inner + cx[rg]] = y[j];
+    }
+    if (a.state_out != 0 && prow[rg]) {
+      float* dst = (a.state_out == 1 ? ly.S : ly.S_draft) + (((size_t)b * d.Hm + h) * d.P + pr[rg]) * N + sub * NV;
 #pragma unroll
-    for (int i = 0; i < NV; i += 4) *reinterpret_cast<float4*>(dst + i) = make_float4(S[i], S[i + 1], S[i + 2], S[i + 3]);
+      for (int i = 0; i < NV; i += 4)
+        *reinterpret_cast<float4*>(dst + i) = make_float4(S[rg][i], S[rg][i + 1], S[rg][i + 2], S[rg][i + 3]);
+    }
   }
   TR(5);
 }
 
-template <int NV, int SUBS>
-static hipError_t launch_ssm_small_t(const Dims& d, const SsmArgs& a, int tmax, hipStream_t s) {
-  const dim3 grid((d.P + 64 / SUBS - 1) / (64 / SUBS), d.Hm, a.n_layers_z * a.B);
+template <int NV, int SUBS, int RG>
+static hipError_t launch_ssm_small_r(const Dims& d, const SsmArgs& a, int tmax, hipStream_t s) {
+  constexpr int rows = 64 / SUBS * RG;
+  const dim3 grid((d.P + rows - 1) / rows, d.Hm, a.n_layers_z * a.B);
   switch (tmax) {
-    case 1: hipLaunchKernelGGL((ssm_small_kernel<NV, SUBS, 1>), grid, dim3(64), 0, s, d, a); break;
-    case 3: hipLaunchKernelGGL((ssm_small_kernel<NV, SUBS, 3>), grid, dim3(64), 0, s, d, a); break;
-    case 5: hipLaunchKernelGGL((ssm_small_kernel<NV, SUBS, 5>), grid, dim3(64), 0, s, d, a); break;
-    case 9: hipLaunchKernelGGL((ssm_small_kernel<NV, SUBS, 9>), grid, dim3(64), 0, s, d, a); break;
+    case 1: hipLaunchKernelGGL((ssm_small_kernel<NV, SUBS, 1, RG>), grid, dim3(64), 0, s, d, a); break;
+    case 3: hipLaunchKernelGGL((ssm_small_kernel<NV, SUBS, 3, RG>), grid, dim3(64), 0, s, d, a); break;
+    case 5: hipLaunchKernelGGL((ssm_small_kernel<NV, SUBS, 5, RG>), grid, dim3(64), 0, s, d, a); break;
+    case 9: hipLaunchKernelGGL((ssm_small_kernel<NV, SUBS, 9, RG>), grid, dim3(64), 0, s, d, a); break;
     default: return hipErrorInvalidValue;
   }
   return hipGetLastError();
+}
+template <int NV, int SUBS>
+static hipError_t launch_ssm_small_t(const Dims& d, const SsmArgs& a, int tmax, hipStream_t s) {
+  // Several row groups per workgroup pay off only in the rebuild from the ring (commit: all layers
+  // in one launch, every load of a workgroup besides the state is fixed cost); measured, the
+  // draft step and the verification pass are no faster with them.
+  static const int min_wg = getenv("HH_SSM_MINWG") ? atoi(getenv("HH_SSM_MINWG")) : 1024;
+  const int groups = (d.P + 64 / SUBS - 1) / (64 / SUBS);
+  const long wgs = (long)groups * d.Hm * a.n_layers_z * a.B;
+  if (a.zx == nullptr) {
+    if (groups % 4 == 0 && wgs / 4 >= min_wg) return launch_ssm_small_r<NV, SUBS, 4>(d, a, tmax, s);
+    if (groups % 2 == 0 && wgs / 2 >= min_wg) return launch_ssm_small_r<NV, SUBS, 2>(d, a, tmax, s);
+  }
+  return launch_ssm_small_r<NV, SUBS, 1>(d, a, tmax, s);
 }
 
 // true if the pass was taken by the few-positions kernel

@@ -1,18 +1,18 @@
-// Dense projections on the matrix cores for passes with many activation rows (batched drafting
-// beyond 16 rows, batched verification, prefill): Y[M x N] (op)= X'[M x K] * W[N x K]^T, bf16
-// weights in the packed operand tiles.
+// Dense projections on the matrix cores for passes with many activation rows (more than 96:
+// verification of large batches, prefill): Y[M x N] (op)= X'[M x K] * W[N x K]^T, bf16 weights in
+// the packed operand tiles.
 //
-// Activations stay float32-accurate: a first kernel applies the fused RMSNorm and splits every
-// value into three bf16 terms, x = t0 + t1 + t2 exactly (8 + 8 + 8 mantissa bits), stored as
-// three planes; the product is the sum of three bf16 MFMA products accumulated in float32.
+// A first kernel applies the fused RMSNorm and splits every activation into bf16 terms stored
+// as planes: x = t0 + t1 (+ t2), two terms by default (16 mantissa bits), three for an exact
+// split; the product is the sum of the per-term bf16 MFMA products accumulated in float32.
 //
 // GEMM kernel: a wavefront is an independent unit of work - NT strips of 16 weight rows x
 // MTW tiles of 16 activation rows x a range of K steps - with all accumulators in registers
 // and no LDS.  Per step of 32 columns it loads NT weight tiles (A operand, 1 KB contiguous each,
-// from HBM) and 3 x MTW activation fragments (B operand, from the planes, which stay in L2)
-// and issues 3 x NT x MTW MFMAs; the next step is requested before the current one is
+// from HBM) and terms x MTW activation fragments (B operand, from the planes, which stay in L2)
+// and issues terms x NT x MTW MFMAs; the next step is requested before the current one is
 // multiplied.  The activation fragments are shared by the NT strips, so L2 traffic is
-// 3 MTW / NT times the weight traffic.  When N is small the K range is split over units to
+// terms MTW / NT times the weight traffic.  When N is small the K range is split over units to
 // cover the chip; the partial products go to a scratch buffer and a second kernel adds them
 // in split order (deterministic) and applies the epilogue.  With one split the epilogue runs
 // in the GEMM kernel.  Accumulator layout: lane l holds D[weight row 4(l/16)+r][activation row l%16].
@@ -26,6 +26,14 @@ namespace hh {
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
+// bf16 terms an activation is split into for this kernel (planes per row tile and step): two
+// by default (16 mantissa bits: a product's relative error is below 2^-17, a few times the
+// rounding noise of its float32 accumulation; the kernel is about twice as fast as with three),
+// three (exact) with HH_GEMM_TERMS=3.
+static int gemm_terms() {
+  static const int t = getenv("HH_GEMM_TERMS") != nullptr && atoi(getenv("HH_GEMM_TERMS")) == 3 ? 3 : 2;
+  return t;
+}
 
 __device__ __forceinline__ uint16_t bf16_rne(float f) {
   uint32_t u = __float_as_uint(f);
@@ -37,7 +45,7 @@ __device__ __forceinline__ float bf16_f32(uint16_t h) { return __uint_as_float((
 // split activations in MFMA operand order (see below); rows >= M and columns >= K are zero
 __global__ __launch_bounds__(256) void split_rows_kernel(const float* __restrict__ X, const float* __restrict__ X2, int ldx, int M, int K, int Mp, int Kp,
                                                          const float* __restrict__ norm_w, float eps,
-                                                         uint16_t* __restrict__ planes) {
+                                                         uint16_t* __restrict__ planes, const int kTerms) {
   const int m = blockIdx.x;
   __shared__ float red[4];
   float rstd = 1.f;
@@ -65,8 +73,9 @@ __global__ __launch_bounds__(256) void split_rows_kernel(const float* __restrict
       split3_bf16(v, b0, b1, b2);
       t0 = (uint16_t)b0; t1 = (uint16_t)b1; t2 = (uint16_t)b2;
     }
-    const size_t at = (((size_t)(m >> 4) * KST + (k >> 5)) * 3) * 512 + (size_t)((((k & 31) >> 3) * 16 + (m & 15)) * 8 + (k & 7));
-    planes[at] = t0; planes[at + 512] = t1; planes[at + 1024] = t2;
+    const size_t at = (((size_t)(m >> 4) * KST + (k >> 5)) * kTerms) * 512 + (size_t)((((k & 31) >> 3) * 16 + (m & 15)) * 8 + (k & 7));
+    planes[at] = t0; planes[at + 512] = t1;
+    if (kTerms == 3) planes[at + 1024] = t2;
   }
 }
 
@@ -82,6 +91,7 @@ struct GemmArgs {
   // reduction only: per-split sums of squares of the activation rows [ksplit][ssq_ld] (or
   // nullptr); the row sum is then scaled by 1 / sqrt(sum * rnorm_k + eps)
   const float* ssq; int ssq_ld; float rnorm_k, eps;
+  int terms;                              // bf16 terms per activation in the planes (2 or 3)
 };
 
 union GFrag {
@@ -89,7 +99,7 @@ union GFrag {
   bf16x8 v;
 };
 
-template <int EPI, int NT, int MTW>
+template <int EPI, int NT, int MTW, int kTerms>
 __global__ __launch_bounds__(256, 2) void gemm_tiled_kernel(const GemmArgs a) {
   constexpr int NF = EPI == EPI_SWIGLU ? 2 : 1;
   const int lane = threadIdx.x & 63;
@@ -111,8 +121,8 @@ __global__ __launch_bounds__(256, 2) void gemm_tiled_kernel(const GemmArgs a) {
 #pragma unroll
       for (int m = 0; m < MTW; ++m) acc[f][t][m] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-  GFrag wf[2][NF][NT], xf[2][3][MTW];
-  auto load_step = [&](int ks, GFrag(&w)[NF][NT], GFrag(&x)[3][MTW]) {
+  GFrag wf[2][NF][NT], xf[2][kTerms][MTW];
+  auto load_step = [&](int ks, GFrag(&w)[NF][NT], GFrag(&x)[kTerms][MTW]) {
 #pragma unroll
     for (int t = 0; t < NT; ++t) {
       const size_t at = ((size_t)min(t0 + t, n_tiles - 1) * KST + ks) * 512 + lane * 8;
@@ -121,14 +131,14 @@ __global__ __launch_bounds__(256, 2) void gemm_tiled_kernel(const GemmArgs a) {
     }
 #pragma unroll
     for (int m = 0; m < MTW; ++m) {
-      const uint16_t* src = a.planes + (((size_t)min(mt0 + m, m_tiles - 1) * KST + ks) * 3) * 512 + lane * 8;
+      const uint16_t* src = a.planes + (((size_t)min(mt0 + m, m_tiles - 1) * KST + ks) * kTerms) * 512 + lane * 8;
 #pragma unroll
-      for (int term = 0; term < 3; ++term) x[term][m].u = *reinterpret_cast<const uint4*>(src + term * 512);
+      for (int term = 0; term < kTerms; ++term) x[term][m].u = *reinterpret_cast<const uint4*>(src + term * 512);
     }
   };
-  auto mul_step = [&](const GFrag(&w)[NF][NT], const GFrag(&x)[3][MTW]) {
+  auto mul_step = [&](const GFrag(&w)[NF][NT], const GFrag(&x)[kTerms][MTW]) {
 #pragma unroll
-    for (int term = 0; term < 3; ++term)
+    for (int term = 0; term < kTerms; ++term)
 #pragma unroll
       for (int m = 0; m < MTW; ++m)
 #pragma unroll
@@ -264,7 +274,8 @@ size_t gemm_partial_elems() { return (size_t)24 << 20; }
 
 template <int EPI, int NT, int MTW>
 static hipError_t gemm_launch(const GemmArgs& a, int units, hipStream_t s) {
-  hipLaunchKernelGGL((gemm_tiled_kernel<EPI, NT, MTW>), dim3((units + 3) / 4), dim3(256), 0, s, a);
+  if (a.terms == 3) hipLaunchKernelGGL((gemm_tiled_kernel<EPI, NT, MTW, 3>), dim3((units + 3) / 4), dim3(256), 0, s, a);
+  else hipLaunchKernelGGL((gemm_tiled_kernel<EPI, NT, MTW, 2>), dim3((units + 3) / 4), dim3(256), 0, s, a);
   return hipGetLastError();
 }
 template <int EPI, int NT>
@@ -286,12 +297,12 @@ hipError_t launch_gemm_mfma(const GemvArgs& g, uint16_t* planes, float* partial,
   const int M = g.M, K = g.K, N = g.seg[0].n_rows;
   if (M <= 0 || N <= 0) return hipSuccess;
   const int Mp = (M + 15) / 16 * 16, Kp = (K + 31) / 32 * 32;
-  hipLaunchKernelGGL(split_rows_kernel, dim3(Mp), dim3(256), 0, s, g.X, g.X2, g.ldx, M, K, Mp, Kp, g.norm_w, g.eps, planes);
+  hipLaunchKernelGGL(split_rows_kernel, dim3(Mp), dim3(256), 0, s, g.X, g.X2, g.ldx, M, K, Mp, Kp, g.norm_w, g.eps, planes, gemm_terms());
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   const int nf = g.epi == EPI_SWIGLU ? 2 : 1, nt = nf == 2 ? 2 : 4;
   GemmArgs a{};
-  a.planes = planes; a.Mp = Mp; a.Kp = Kp;
+  a.planes = planes; a.Mp = Mp; a.Kp = Kp; a.terms = gemm_terms();
   a.W = static_cast<const uint16_t*>(g.seg[0].P); a.W2 = static_cast<const uint16_t*>(g.seg[0].P2);
   a.Y = g.seg[0].Y; a.ldy = g.seg[0].ldy; a.R2 = g.R2; a.partial = partial; a.M = M; a.N = N; a.K = K;
   const int steps = Kp / 32, tiles = (N + 15) / 16, m_tiles = Mp / 16;

@@ -24,6 +24,10 @@ namespace hh {
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
+// bf16 terms an activation is split into: three (exact); with two (16 mantissa bits) the test
+// with order-one activations loses a token to a near tie
+static constexpr int kMidTerms = 3;
+
 union MFrag {
   uint4 u;
   bf16x8 v;
@@ -63,7 +67,7 @@ __global__ __launch_bounds__(64 * NW) void mid_mfma_kernel(const MidArgs a) {
   constexpr int CG = KW / 4;                     // float4 column groups per row
   constexpr int RPW = 64 / CG;                   // rows a wavefront stages per pass (1 or 2)
   extern __shared__ __align__(16) unsigned char smem_raw[];
-  uint16_t* xs = reinterpret_cast<uint16_t*>(smem_raw);     // [3][ROWS][SL]
+  uint16_t* xs = reinterpret_cast<uint16_t*>(smem_raw);     // [kMidTerms][ROWS][SL]
   const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int g = lane >> 4, n = lane & 15;
   const int M = a.M, K = a.K, N = a.N;
@@ -141,7 +145,7 @@ __global__ __launch_bounds__(64 * NW) void mid_mfma_kernel(const MidArgs a) {
           uint16_t* dst = xs + (size_t)r * SL + 4 * cgi;
           *reinterpret_cast<uint2*>(dst) = make_uint2(a0, b0);
           *reinterpret_cast<uint2*>(dst + (size_t)ROWS * SL) = make_uint2(a1, b1);
-          *reinterpret_cast<uint2*>(dst + (size_t)2 * ROWS * SL) = make_uint2(a2, b2);
+          if (kMidTerms == 3) *reinterpret_cast<uint2*>(dst + (size_t)(kMidTerms - 1) * ROWS * SL) = make_uint2(a2, b2);
         }
       }
     };
@@ -170,7 +174,7 @@ __global__ __launch_bounds__(64 * NW) void mid_mfma_kernel(const MidArgs a) {
         // keeps the scheduler from hoisting the LDS reads of the whole unit (registers)
         if ((s & 1) == 0) asm volatile("" ::: "memory");
 #pragma unroll
-        for (int t = 0; t < 3; ++t) {
+        for (int t = 0; t < kMidTerms; ++t) {
           MFrag xb;
           xb.u = *reinterpret_cast<const uint4*>(xrow + (size_t)t * ROWS * SL + s * 32);
           acc[0][mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf[0][s].v, xb.v, acc[0][mt], 0, 0, 0);
@@ -229,7 +233,7 @@ static bool mid_plan(const GemvArgs& g, MidPlan& p) {
   p.blocks = (p.units + p.nw - 1) / p.nw;
   // more than ~4 workgroups per compute unit: several units per wavefront instead
   while ((long)p.blocks * p.windows > 1024 && p.blocks > 1) p.blocks = (p.blocks + 1) / 2;
-  p.lds = (size_t)3 * p.mt * 16 * (kw + 8) * 2;
+  p.lds = (size_t)kMidTerms * p.mt * 16 * (kw + 8) * 2;
   p.partial_elems = (size_t)p.windows * nf * g.M * N + (size_t)p.windows * 96;
   return p.lds <= 160 * 1024 && p.partial_elems <= gemm_partial_elems() && p.windows <= 65535;
 }

@@ -186,14 +186,19 @@ __global__ __launch_bounds__(kRows * kSub) void ssm_kernel(const Dims d, const S
 // RG row groups of 64 / SUBS rows per workgroup, one after the other: the B/C convolution and the
 // per-head scalars are shared by all of them, which is what a large batch needs (there a
 // workgroup's fixed loads would otherwise exceed its share of the state).
-template <int NV, int SUBS, int TMAX, int RG>
-__global__ __launch_bounds__(64) void ssm_small_kernel(const Dims d, const SsmArgs a) {
+// NWV wavefronts per workgroup (1 or 4), each with its own rows: with tens of thousands of
+// one-wavefront workgroups the launch is bound by the workgroup dispatch rate (measured: 3
+// resident wavefronts per compute unit), and four wavefronts share one B/C convolution.
+template <int NV, int SUBS, int TMAX, int RG, int NWV>
+__global__ __launch_bounds__(64 * NWV) void ssm_small_kernel(const Dims d, const SsmArgs a) {
+  constexpr int NTHR = 64 * NWV;
   constexpr int ROWS = 64 / SUBS, N = NV * SUBS;
-  constexpr int NG = (2 * N / 4 + 63) / 64;      // groups of 4 B|C channels per lane
+  constexpr int NG = (2 * N / 4 + NTHR - 1) / NTHR;   // groups of 4 B|C channels per thread
   __shared__ __align__(16) float BCs[TMAX][2 * N];
 
-  const int lane = threadIdx.x, row = lane / SUBS, sub = lane % SUBS;
-  const int p0 = blockIdx.x * ROWS * RG, h = blockIdx.y;
+  const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int row = lane / SUBS, sub = lane % SUBS;
+  const int p0 = (blockIdx.x * NWV + wave) * ROWS * RG, h = blockIdx.y;
   const int lz = blockIdx.z / a.B, b = blockIdx.z % a.B;
   const LayerDev& ly = a.layers != nullptr ? a.layers[a.layer0 + lz] : a.one;
   TR(0);
@@ -237,7 +242,7 @@ __global__ __launch_bounds__(64) void ssm_small_kernel(const Dims d, const SsmAr
   float dtraw_l = 0.f;   // raw dt of position `lane` (lanes < T): softplus and decay are evaluated once, lane-parallel
 #pragma unroll
   for (int u = 0; u < NG; ++u) {
-    const int c = d.d_inner + 4 * min(lane + 64 * u, 2 * N / 4 - 1);
+    const int c = d.d_inner + 4 * min(tid + NTHR * u, 2 * N / 4 - 1);
 #pragma unroll
     for (int t = 0; t < 4; ++t) bw[u][t] = *reinterpret_cast<const float4*>(ly.conv_w + (size_t)(c + t) * 4);
     bb[u] = *reinterpret_cast<const float4*>(ly.conv_b + c);
@@ -257,7 +262,7 @@ __global__ __launch_bounds__(64) void ssm_small_kernel(const Dims d, const SsmAr
     for (int j = 0; j < TMAX; ++j) {
       const float* r = zx + (size_t)min(j, a.T - 1) * d.ldzx + d.d_inner;
 #pragma unroll
-      for (int u = 0; u < NG; ++u) braw[u][j + 3] = *reinterpret_cast<const float4*>(r + d.d_inner + 4 * min(lane + 64 * u, 2 * N / 4 - 1));
+      for (int u = 0; u < NG; ++u) braw[u][j + 3] = *reinterpret_cast<const float4*>(r + d.d_inner + 4 * min(tid + NTHR * u, 2 * N / 4 - 1));
 #pragma unroll
       for (int rg = 0; rg < RG; ++rg) {
         xraw[rg][j + 3] = r[cx[rg]];
@@ -279,7 +284,7 @@ __global__ __launch_bounds__(64) void ssm_small_kernel(const Dims d, const SsmAr
     if (j >= 0 && zx != nullptr) continue;
     const float* r = ring_row(min(j, nt - 1));
 #pragma unroll
-    for (int u = 0; u < NG; ++u) braw[u][j + 3] = *reinterpret_cast<const float4*>(r + d.d_inner + 4 * min(lane + 64 * u, 2 * N / 4 - 1));
+    for (int u = 0; u < NG; ++u) braw[u][j + 3] = *reinterpret_cast<const float4*>(r + d.d_inner + 4 * min(tid + NTHR * u, 2 * N / 4 - 1));
 #pragma unroll
     for (int rg = 0; rg < RG; ++rg) {
       xraw[rg][j + 3] = r[cx[rg]];
@@ -294,7 +299,7 @@ __global__ __launch_bounds__(64) void ssm_small_kernel(const Dims d, const SsmAr
   // position computed; positions >= nt are never used)
 #pragma unroll
   for (int u = 0; u < NG; ++u) {
-    const int gi = lane + 64 * u;
+    const int gi = tid + NTHR * u;
 #pragma unroll
     for (int j = 0; j < TMAX; ++j) {
       float4 o;
@@ -335,14 +340,14 @@ __global__ __launch_bounds__(64) void ssm_small_kernel(const Dims d, const SsmAr
     if (h == 0 && blockIdx.x == 0) {
 #pragma unroll
       for (int u = 0; u < NG; ++u) {
-        const int gi = lane + 64 * u;
+        const int gi = tid + NTHR * u;
         if (gi < 2 * N / 4) {
 #pragma unroll
           for (int j = 0; j < TMAX; ++j)
             if (j < nt) *reinterpret_cast<float4*>(ring + (size_t)((pos0 + j) & rmask) * d.ring_w + d.d_inner + 4 * gi) = braw[u][j + 3];
         }
       }
-      for (int it = lane; it < nt * d.Hm; it += 64) {
+      for (int it = tid; it < nt * d.Hm; it += NTHR) {
         const int j = it / d.Hm, hh = it - j * d.Hm;
         ring[(size_t)((pos0 + j) & rmask) * d.ring_w + d.conv_dim + hh] = zx[(size_t)j * d.ldzx + d.d_inner + d.conv_dim + hh];
       }
@@ -397,15 +402,15 @@ __global__ __launch_bounds__(64) void ssm_small_kernel(const Dims d, const SsmAr
   TR(5);
 }
 
-template <int NV, int SUBS, int RG>
+template <int NV, int SUBS, int RG, int NWV>
 static hipError_t launch_ssm_small_r(const Dims& d, const SsmArgs& a, int tmax, hipStream_t s) {
-  constexpr int rows = 64 / SUBS * RG;
+  constexpr int rows = 64 / SUBS * RG * NWV;
   const dim3 grid((d.P + rows - 1) / rows, d.Hm, a.n_layers_z * a.B);
   switch (tmax) {
-    case 1: hipLaunchKernelGGL((ssm_small_kernel<NV, SUBS, 1, RG>), grid, dim3(64), 0, s, d, a); break;
-    case 3: hipLaunchKernelGGL((ssm_small_kernel<NV, SUBS, 3, RG>), grid, dim3(64), 0, s, d, a); break;
-    case 5: hipLaunchKernelGGL((ssm_small_kernel<NV, SUBS, 5, RG>), grid, dim3(64), 0, s, d, a); break;
-    case 9: hipLaunchKernelGGL((ssm_small_kernel<NV, SUBS, 9, RG>), grid, dim3(64), 0, s, d, a); break;
+    case 1: hipLaunchKernelGGL((ssm_small_kernel<NV, SUBS, 1, RG, NWV>), grid, dim3(64 * NWV), 0, s, d, a); break;
+    case 3: hipLaunchKernelGGL((ssm_small_kernel<NV, SUBS, 3, RG, NWV>), grid, dim3(64 * NWV), 0, s, d, a); break;
+    case 5: hipLaunchKernelGGL((ssm_small_kernel<NV, SUBS, 5, RG, NWV>), grid, dim3(64 * NWV), 0, s, d, a); break;
+    case 9: hipLaunchKernelGGL((ssm_small_kernel<NV, SUBS, 9, RG, NWV>), grid, dim3(64 * NWV), 0, s, d, a); break;
     default: return hipErrorInvalidValue;
   }
   return hipGetLastError();
@@ -419,10 +424,13 @@ static hipError_t launch_ssm_small_t(const Dims& d, const SsmArgs& a, int tmax, 
   const int groups = (d.P + 64 / SUBS - 1) / (64 / SUBS);
   const long wgs = (long)groups * d.Hm * a.n_layers_z * a.B;
   if (a.zx == nullptr) {
-    if (groups % 4 == 0 && wgs / 4 >= min_wg) return launch_ssm_small_r<NV, SUBS, 4>(d, a, tmax, s);
-    if (groups % 2 == 0 && wgs / 2 >= min_wg) return launch_ssm_small_r<NV, SUBS, 2>(d, a, tmax, s);
+    if (groups % 4 == 0 && wgs / 4 >= min_wg) return launch_ssm_small_r<NV, SUBS, 4, 1>(d, a, tmax, s);
+    if (groups % 2 == 0 && wgs / 2 >= min_wg) return launch_ssm_small_r<NV, SUBS, 2, 1>(d, a, tmax, s);
   }
-  return launch_ssm_small_r<NV, SUBS, 1>(d, a, tmax, s);
+  // large launches: four wavefronts per workgroup (workgroup dispatch rate, shared B/C convolution)
+  static const int wide_wg = getenv("HH_SSM_WIDEWG") ? atoi(getenv("HH_SSM_WIDEWG")) : 2048;
+  if (groups % 4 == 0 && wgs >= wide_wg) return launch_ssm_small_r<NV, SUBS, 1, 4>(d, a, tmax, s);
+  return launch_ssm_small_r<NV, SUBS, 1, 1>(d, a, tmax, s);
 }
 
 // true if the pass was taken by the few-positions kernel

@@ -259,6 +259,21 @@ hipError_t product(hh_ctx* x, const GemvArgs& a, hipStream_t s, bool side = fals
   return launch_gemv(a, nullptr, s);
 }
 
+// Whether a full pass runs its attention branch on the side stream beside the SSM branch.
+// Prefill passes always do (both branches are long).  In a verification pass the fork makes the
+// captured graph a two-queue graph, and measured on this machine every launch of the following
+// (single-stream) draft graphs then takes about 0.9 us longer; that only pays once the attention
+// branch is long: from 512k cached tokens in the batch.  HH_OVERLAP_MODE: 0 never, 1 prefill
+// only, 2 always, default automatic.
+bool branch_overlap(const hh_ctx* x, int B, int T) {
+  static const int mode = getenv("HH_OVERLAP_MODE") != nullptr ? atoi(getenv("HH_OVERLAP_MODE")) : 3;
+  if (mode == 0) return false;
+  if (T > x->d.Kmax + 1) return true;            // prefill chunk
+  if (mode == 1) return false;
+  if (mode == 2) return true;
+  return (long long)B * x->len_upper >= (512LL << 10);
+}
+
 // ---- one pass of the block stack over M = B*T rows.  full: M_H (both branches); !full: M_S.
 hh_status run_layers(hh_ctx* x, bool full, int B, int T, const int* n_tok, int state_in, int state_out,
                      int n_splits, hipStream_t s) {
@@ -277,7 +292,7 @@ hh_status run_layers(hh_ctx* x, bool full, int B, int T, const int* n_tok, int s
     // (attention, then its output projection into a buffer of its own) is enqueued on a side
     // stream beside the SSM branch (scan, then out projection into the residual stream); the
     // branches meet at the MLP, whose input is h + ho and whose down projection adds both.
-    const bool overlap = full && !x->prof_on && x->side != nullptr;
+    const bool overlap = full && !x->prof_on && x->side != nullptr && branch_overlap(x, B, T);
     hipStream_t sa = s;
     if (overlap) {
       sa = x->side;
@@ -668,7 +683,7 @@ hh_status hh_verify(hh_ctx* x, void* stream) {
     if (st != HH_OK) return st;
     return run_head(x, x->h, B * T, T, x->logits_v, d.V, x->targets, d.Kmax + 1, 0, s);
   };
-  const hh_status st = run_graphed(x, (2LL << 40) | ((long long)B << 20) | ((long long)splits << 8) | T, s, enqueue);
+  const hh_status st = run_graphed(x, (2LL << 40) | ((long long)branch_overlap(x, B, T) << 39) | ((long long)B << 20) | ((long long)splits << 8) | T, s, enqueue);
   if (st != HH_OK) return st;
   x->phase = PH_VERIFIED;
   return HH_OK;

@@ -225,6 +225,11 @@ def main():
     per_kind, draft_bytes, verify_bytes, commit_bytes = algorithmic_bytes(cfg, Bn, k, kv_mid)
     kernels = {}
     per_round = {1: k, 2: 1}
+    # the library runs the attention branch of verification (attention, o_proj) on a side stream
+    # beside scan + out_proj only for long caches (its rule: batch * longest cache >= 512k tokens,
+    # or HH_OVERLAP_MODE=2)
+    ovl = os.environ.get("HH_OVERLAP_MODE")
+    side_branch = ovl == "2" or (ovl in (None, "3") and Bn * wl.prompt_len >= 512 * 1024)
     for ph in (1, 2):
         for kind in sorted(KIND_NAMES):
             if kind == 2 or (ph == 1 and kind in (3, 5)):   # RoPE/append is fused into attention
@@ -236,8 +241,7 @@ def main():
             kernels[f"{PHASE_NAMES[ph]}.{KIND_NAMES[kind]}"] = {
                 "launches_per_round": launches, "avg_us": round(avg_us, 3), "us_per_round": round(avg_us * launches, 1),
                 "bytes": by, "gbs": None if by is None else round(by / (avg_us * 1e-6) / 1e9, 1),
-                # the attention branch of verification (attention, o_proj) runs on a side stream beside scan + out_proj
-                "stream": "side" if ph == 2 and kind in (3, 5) else "launch"}
+                "stream": "side" if side_branch and ph == 2 and kind in (3, 5) else "launch"}
     # commit rebuild: timed with the per-launch events (one launch per round)
     ctx.hh_profile(True)
     run_rounds(prof_rounds, k)

@@ -414,6 +414,9 @@ int pick_splits(const Dims& d, int B, int T, int len_upper) {
     const int steps = (len_upper + T + 31) / 32;      // 32 keys per wavefront step, 4 wavefronts per workgroup
     s = (512 + blocks - 1) / blocks;
     if (s > (steps + 3) / 4) s = (steps + 3) / 4;
+    // short caches: the ticket and the merge across workgroups (about 4 us) cost more than the
+    // few extra steps per wavefront of a single slice
+    if (steps <= 28) s = 1;
   } else {
     const int G = d.Hq / d.Hkv;
     const int row_chunks = (T * G + 15) / 16;

@@ -359,7 +359,7 @@ static int skinny_windows(const GemvArgs& g, SkinnyPlan& p) {
     if (!skinny_plan_k(g, g.K / w, q)) continue;
     q.windows = w;
     p = q; best = w;
-    if (tiles * w >= min_blocks) break;
+    if (tiles >= 128 || tiles * w >= min_blocks) break;   // half the chip by tiles alone: no split
   }
   return best;
 }
@@ -428,6 +428,21 @@ hipError_t launch_skinny_mfma(const GemvArgs& g, float* partial, int* n_blocks_o
   if (n_blocks_out) *n_blocks_out = p.blocks;
   int epi = g.epi;
   const size_t total = (size_t)g.M * a.N;
+  // Windows that are only there because a whole row does not fit LDS, on a product that fills the
+  // chip by itself: one launch per window, each accumulating on the output (side by side they
+  // would need a second round of workgroups and the reduction pass).
+  const int tiles = (a.N + 15) / 16;
+  if (windows > 1 && tiles * windows > 256 && g.norm_w == nullptr && g.epi != EPI_SWIGLU && g.best == nullptr) {
+    p.windows = 1;
+    for (int w = 0; w < windows; ++w) {
+      a.k0 = w * a.K;
+      if (w > 0) a.R2 = nullptr;                   // the second residual goes in with the first window
+      const int e1 = w == 0 ? g.epi : EPI_ADD;     // later windows accumulate
+      hipError_t e = e1 == EPI_STORE ? skinny_dispatch<EPI_STORE>(a, p, s) : skinny_dispatch<EPI_ADD>(a, p, s);
+      if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
+  }
   if (windows > 1) {
     a.Y = partial; a.ldy = a.N; a.ywin = total; a.R2 = nullptr; epi = EPI_STORE;
     a.ssq = g.norm_w != nullptr ? partial + (size_t)windows * total : nullptr;

@@ -6,18 +6,18 @@
 // here every weight fragment meets all MT row tiles of the activations, so the weights stream
 // from HBM once whatever the row count.
 //
-// A workgroup owns one K window (KSW steps of 32 columns) of the activations: it stages the three
-// terms of all rows of that window in LDS once (a wavefront stages whole rows, so the sums of
-// squares for the RMSNorm are plain wavefront sums), and each of its wavefronts then takes units
-// of two weight tiles (or one gate/up tile pair) of that window: KSW fragments per tile in
-// registers, every B fragment read from LDS feeds two MFMAs.  No sums across wavefronts; the
-// window's partial product goes to scratch and the reduction kernel adds the windows in order,
-// applies the norm scale and the epilogue.
+// A workgroup owns 8 units - a unit is two weight tiles, or one gate/up tile pair, one per
+// wavefront - and a range of K windows of 128 columns.  Per window it stages the three terms of
+// all activation rows in LDS (a wavefront stages whole rows; the sums of squares for the RMSNorm
+// accumulate per lane) and every wavefront multiplies its unit's fragments of that window with
+// every row tile: each B fragment read from LDS feeds two MFMAs, no sums across wavefronts, the
+// accumulators stay in registers over the K range.  The K chunks of a product (gridDim.y) write
+// partial products to scratch; the reduction kernel adds them in order and applies the norm
+// scale and the epilogue.
 #include <stdlib.h>
 
 #include "hh_internal.h"
 #include "bf16_split.h"
-#include "trace.h"
 
 namespace hh {
 
@@ -43,176 +43,180 @@ struct MidArgs {
   float* ssq;                              // [windows][ssq_ld] sums of squares per row, or nullptr
   int ssq_ld;
   int units;                               // wavefront units: pairs of tiles (NF = 1) or gate/up tile pairs (NF = 2)
+  int wpb;                                 // K-loop kernel: windows per workgroup (K chunk)
 };
 
 template <int CTRL>
 __device__ __forceinline__ float mid_dpp(float v) {
   return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xf, 0xf, false));
 }
-// sum over the 64 lanes (all lanes active)
-__device__ __forceinline__ float mid_wave_sum(float v) {
-  v += mid_dpp<0xB1>(v); v += mid_dpp<0x4E>(v); v += mid_dpp<0x141>(v); v += mid_dpp<0x140>(v);
-  const int iv = __float_as_int(v);
-  return (__int_as_float(__builtin_amdgcn_readlane(iv, 0)) + __int_as_float(__builtin_amdgcn_readlane(iv, 16))) +
-         (__int_as_float(__builtin_amdgcn_readlane(iv, 32)) + __int_as_float(__builtin_amdgcn_readlane(iv, 48)));
-}
-
-// grid: x = groups of NW units (strided), y = K windows.  NF = 2: SwiGLU pair.  MT row tiles of 16.
-// KSW steps of 32 columns per window (4 or 8).  NW wavefronts per workgroup: 4 (one per SIMD, so
-// that the MFMA work of a small product spreads over all compute units) or 8.
-template <int NF, int MT, int KSW, int NW>
-__global__ __launch_bounds__(64 * NW) void mid_mfma_kernel(const MidArgs a) {
-  constexpr int KW = KSW * 32, SL = KW + 8;      // window columns; staged row stride (bf16, padded)
+// The K loop: the staged activations are double-buffered in LDS and the weight fragments
+// triple-buffered in registers: while window i is multiplied, the activations of window i+1 are
+// loaded, split and written to the other buffer and the weights of window i+2 are requested;
+// one workgroup barrier per window.  The
+// grid: x = groups of 8 units, y = K chunks of a.wpb windows.
+template <int NF, int MT>
+__global__ __launch_bounds__(512) void mid_loop_kernel(const MidArgs a) {
+  constexpr int NW = 8, KSW = 4, KW = KSW * 32, SL = KW + 8;
   constexpr int ROWS = MT * 16;
-  constexpr int CG = KW / 4;                     // float4 column groups per row
-  constexpr int RPW = 64 / CG;                   // rows a wavefront stages per pass (1 or 2)
+  constexpr int PASS = NW * 2;                   // rows staged per pass: two per wavefront (32 float4 groups each)
+  constexpr int NP = ROWS / PASS;
+  constexpr size_t BUF = (size_t)kMidTerms * ROWS * SL;   // bf16 elements per LDS buffer
   extern __shared__ __align__(16) unsigned char smem_raw[];
-  uint16_t* xs = reinterpret_cast<uint16_t*>(smem_raw);     // [kMidTerms][ROWS][SL]
+  uint16_t* xs = reinterpret_cast<uint16_t*>(smem_raw);     // [2][kMidTerms][ROWS][SL]
   const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int g = lane >> 4, n = lane & 15;
   const int M = a.M, K = a.K, N = a.N;
-  const int win = blockIdx.y, k0 = win * KW;
-
-  // the weight fragments of a unit
-  const int n_tiles = (N + 15) >> 4;
-  const int KST = (K + 31) >> 5, step0 = win * KSW;
-  MFrag wf[2][KSW];
-  int tile[2] = {0, 0};
-  auto load_unit = [&](int unit) {
+  const int n_tiles = (N + 15) >> 4, KST = (K + 31) >> 5;
+  const int n_win = (K + KW - 1) / KW;
+  const int win0 = blockIdx.y * a.wpb, win1 = min(n_win, win0 + a.wpb);   // win0 < n_win by construction
+  const int unit = blockIdx.x * NW + wave;
+  int tile[2];
+  const uint16_t* wrow[2];
 #pragma unroll
-    for (int i = 0; i < 2; ++i) {
-      tile[i] = NF == 2 ? unit : unit * 2 + i;
-      const uint16_t* Wp = (NF == 2 && i == 1) ? a.W2 : a.W;
-      const size_t row = (size_t)min(tile[i], n_tiles - 1) * a.kst_row;
+  for (int i = 0; i < 2; ++i) {
+    tile[i] = NF == 2 ? unit : unit * 2 + i;
+    wrow[i] = ((NF == 2 && i == 1) ? a.W2 : a.W) + (size_t)min(tile[i], n_tiles - 1) * a.kst_row * 512 + lane * 8;
+  }
+  // staging: lane = (row in pass, float4 column group)
+  const int cgi = lane & 31, rsub = lane >> 5;
+  float4 v[NP], nw;
+  float sq[NP];
 #pragma unroll
-      for (int s = 0; s < KSW; ++s)   // steps past the end of the row re-read the last one and meet zero activations
-        wf[i][s].u = *reinterpret_cast<const uint4*>(Wp + (row + min(step0 + s, KST - 1)) * 512 + lane * 8);
+  for (int u = 0; u < NP; ++u) sq[u] = 0.f;
+  // unconditional loads from clamped addresses (a branch around them would make the waits for
+  // the current window's operands wait for these too); what lies outside is zeroed when staged
+  bool okc = false;
+  auto issue_x = [&](int win) {
+    const int col = win * KW + 4 * cgi;
+    okc = col < K;                               // K % 4 == 0: a group is inside or outside
+    const int colc = okc ? col : 0;
+    nw = make_float4(1.f, 1.f, 1.f, 1.f);
+    if (a.norm_w != nullptr) nw = *reinterpret_cast<const float4*>(a.norm_w + colc);
+#pragma unroll
+    for (int u = 0; u < NP; ++u) {
+      const int r = min(u * PASS + wave * 2 + rsub, M - 1);
+      v[u] = *reinterpret_cast<const float4*>(a.X + (size_t)r * a.ldx + colc);
+    }
+    if (a.X2 != nullptr) {
+#pragma unroll
+      for (int u = 0; u < NP; ++u) {
+        const int r = min(u * PASS + wave * 2 + rsub, M - 1);
+        const float4 w2 = *reinterpret_cast<const float4*>(a.X2 + (size_t)r * a.ldx + colc);
+        v[u].x += w2.x; v[u].y += w2.y; v[u].z += w2.z; v[u].w += w2.w;
+      }
     }
   };
-  int unit = blockIdx.x * NW + wave;
-  TR(0);
-
-  // ---- stage the window: rows wave*RPW + NW*RPW*i, lane = (row in pass, column group).  The
-  // loads of the first NB passes are requested before the weights (they would wait behind them).
-  {
-    const int cgi = lane % CG, rsub = lane / CG;
-    const int col = k0 + 4 * cgi;
-    const bool okc = col < K;                    // K % 4 == 0: a group is inside or outside
-    const int colc = okc ? col : 0;
-    float4 nw = make_float4(1.f, 1.f, 1.f, 1.f);
-    if (a.norm_w != nullptr) nw = *reinterpret_cast<const float4*>(a.norm_w + colc);
-    constexpr int PASS = NW * RPW;               // rows per pass of the workgroup
-    constexpr int NP = (ROWS + PASS - 1) / PASS;
-    constexpr int NB = NP < 12 ? NP : 12;        // passes whose loads are in flight together
-    float4 v[NB];
-    auto issue = [&](int p0) {
-#pragma unroll
-      for (int u = 0; u < NB; ++u) {
-        const int r = (p0 + u) * PASS + wave * RPW + rsub;
-        v[u] = make_float4(0.f, 0.f, 0.f, 0.f);
-        if (p0 + u < NP && r < M && okc) {
-          v[u] = *reinterpret_cast<const float4*>(a.X + (size_t)r * a.ldx + col);
-          if (a.X2 != nullptr) {
-            const float4 w2 = *reinterpret_cast<const float4*>(a.X2 + (size_t)r * a.ldx + col);
-            v[u].x += w2.x; v[u].y += w2.y; v[u].z += w2.z; v[u].w += w2.w;
-          }
-        }
-      }
-    };
-    auto process = [&](int p0) {
-#pragma unroll
-      for (int u = 0; u < NB; ++u) {
-        if (p0 + u >= NP) break;                 // wavefront-uniform
-        const int r = (p0 + u) * PASS + wave * RPW + rsub;
-        if (a.ssq != nullptr) {
-          float sq = v[u].x * v[u].x + v[u].y * v[u].y + v[u].z * v[u].z + v[u].w * v[u].w;
-          float tot;
-          if (RPW == 1) {
-            tot = mid_wave_sum(sq);
-          } else {                               // two rows per wavefront: halves of 32 lanes
-            sq += mid_dpp<0xB1>(sq); sq += mid_dpp<0x4E>(sq); sq += mid_dpp<0x141>(sq); sq += mid_dpp<0x140>(sq);
-            const int iv = __float_as_int(sq);
-            const float lo = __int_as_float(__builtin_amdgcn_readlane(iv, 0)) + __int_as_float(__builtin_amdgcn_readlane(iv, 16));
-            const float hi = __int_as_float(__builtin_amdgcn_readlane(iv, 32)) + __int_as_float(__builtin_amdgcn_readlane(iv, 48));
-            tot = rsub == 0 ? lo : hi;
-          }
-          if (blockIdx.x == 0 && cgi == 0 && r < M) a.ssq[(size_t)win * a.ssq_ld + r] = tot;
-        }
-        if (r < ROWS) {
-          uint32_t a0, a1, a2, b0, b1, b2;
-          split3_bf16_pair(v[u].x * nw.x, v[u].y * nw.y, a0, a1, a2);
-          split3_bf16_pair(v[u].z * nw.z, v[u].w * nw.w, b0, b1, b2);
-          uint16_t* dst = xs + (size_t)r * SL + 4 * cgi;
-          *reinterpret_cast<uint2*>(dst) = make_uint2(a0, b0);
-          *reinterpret_cast<uint2*>(dst + (size_t)ROWS * SL) = make_uint2(a1, b1);
-          if (kMidTerms == 3) *reinterpret_cast<uint2*>(dst + (size_t)(kMidTerms - 1) * ROWS * SL) = make_uint2(a2, b2);
-        }
-      }
-    };
-    issue(0);
-    if (unit < a.units) load_unit(unit);         // the first unit's weights stream in meanwhile
-    TR(1);
-    process(0);
-    for (int p0 = NB; p0 < NP; p0 += NB) { issue(p0); process(p0); }
-  }
-  TR(2);
-  __syncthreads();
-  TR(3);
-
-  // ---- the units of this wavefront
-  while (unit < a.units) {
-    f32x4 acc[2][MT];
+  auto issue_w = [&](int win, MFrag(&w)[2][KSW]) {
 #pragma unroll
     for (int i = 0; i < 2; ++i)
 #pragma unroll
-      for (int mt = 0; mt < MT; ++mt) acc[i][mt] = f32x4{0.f, 0.f, 0.f, 0.f};
+      for (int s = 0; s < KSW; ++s)   // steps past the end of the row re-read the last one and meet zero activations
+        w[i][s].u = *reinterpret_cast<const uint4*>(wrow[i] + (size_t)min(win * KSW + s, KST - 1) * 512);
+  };
+  auto stage = [&](uint16_t* buf) {
+#pragma unroll
+    for (int u = 0; u < NP; ++u) {
+      const int r = u * PASS + wave * 2 + rsub;
+      if (!(okc && r < M)) v[u] = make_float4(0.f, 0.f, 0.f, 0.f);
+      sq[u] += v[u].x * v[u].x + v[u].y * v[u].y + v[u].z * v[u].z + v[u].w * v[u].w;
+      uint32_t a0, a1, a2, b0, b1, b2;
+      split3_bf16_pair(v[u].x * nw.x, v[u].y * nw.y, a0, a1, a2);
+      split3_bf16_pair(v[u].z * nw.z, v[u].w * nw.w, b0, b1, b2);
+      uint16_t* dst = buf + (size_t)r * SL + 4 * cgi;
+      *reinterpret_cast<uint2*>(dst) = make_uint2(a0, b0);
+      *reinterpret_cast<uint2*>(dst + (size_t)ROWS * SL) = make_uint2(a1, b1);
+      if (kMidTerms == 3) *reinterpret_cast<uint2*>(dst + (size_t)(kMidTerms - 1) * ROWS * SL) = make_uint2(a2, b2);
+    }
+  };
+  f32x4 acc[2][MT];
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) acc[i][mt] = f32x4{0.f, 0.f, 0.f, 0.f};
+  auto multiply = [&](const uint16_t* buf, const MFrag(&w)[2][KSW]) {
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt) {
-      const uint16_t* xrow = xs + (size_t)(mt * 16 + n) * SL + 8 * g;
+      const uint16_t* xrow = buf + (size_t)(mt * 16 + n) * SL + 8 * g;
 #pragma unroll
       for (int s = 0; s < KSW; ++s) {
-        // keeps the scheduler from hoisting the LDS reads of the whole unit (registers)
-        if ((s & 1) == 0) asm volatile("" ::: "memory");
+        if ((s & 1) == 0) asm volatile("" ::: "memory");   // keeps the LDS reads of a unit from being hoisted together (registers)
 #pragma unroll
         for (int t = 0; t < kMidTerms; ++t) {
           MFrag xb;
           xb.u = *reinterpret_cast<const uint4*>(xrow + (size_t)t * ROWS * SL + s * 32);
-          acc[0][mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf[0][s].v, xb.v, acc[0][mt], 0, 0, 0);
-          acc[1][mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf[1][s].v, xb.v, acc[1][mt], 0, 0, 0);
+          acc[0][mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(w[0][s].v, xb.v, acc[0][mt], 0, 0, 0);
+          acc[1][mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(w[1][s].v, xb.v, acc[1][mt], 0, 0, 0);
         }
       }
     }
-    TR(4);
-    // the next unit's weights are requested before this unit's results are stored
-    const int tl[2] = {tile[0], tile[1]};
-    unit += (int)gridDim.x * NW;
-    if (unit < a.units) load_unit(unit);
-    // lane (g, n) holds Y[activation row mt*16 + n][weight rows tile*16 + 4g .. + 3]
+  };
+  // One window: request the activations of the next one and the weights of the one after it
+  // (HBM latency exceeds one window's multiplication; past the end the last window is requested
+  // again and not used), multiply this one, stage the next one in the other LDS buffer.  Three
+  // weight buffers in rotation: the loop body is three windows, straight-line.
+  MFrag w0[2][KSW], w1[2][KSW], w2[2][KSW];
+  auto window = [&](int win, const MFrag(&wc)[2][KSW], MFrag(&wn2)[2][KSW]) {
+    uint16_t* cur = xs + (size_t)((win - win0) & 1) * BUF;
+    uint16_t* nxt = xs + (size_t)((win - win0 + 1) & 1) * BUF;
+    issue_x(min(win + 1, win1 - 1));
+    issue_w(min(win + 2, win1 - 1), wn2);
+    multiply(cur, wc);
+    if (win + 1 < win1) stage(nxt);
+    __syncthreads();
+  };
+  issue_x(win0);
+  issue_w(win0, w0);
+  issue_w(min(win0 + 1, win1 - 1), w1);
+  stage(xs);
+  __syncthreads();
+  int win = win0;
+  for (; win + 2 < win1; win += 3) {
+    window(win, w0, w2);
+    window(win + 1, w1, w0);
+    window(win + 2, w2, w1);
+  }
+  if (win < win1) window(win, w0, w2);
+  if (win + 1 < win1) window(win + 1, w1, w0);
+  // sums of squares of the rows this wavefront staged (32 lanes per row), for the norm scale
+  if (a.ssq != nullptr && blockIdx.x == 0) {
 #pragma unroll
-    for (int i = 0; i < 2; ++i) {
-      if (tl[i] >= n_tiles) continue;
-      const int f = NF == 2 ? i : 0;
-      float* pb = a.partial + ((size_t)(win * NF + f) * M) * N;
-      const int c0 = tl[i] * 16 + 4 * g;
+    for (int u = 0; u < NP; ++u) {
+      float t = sq[u];
+      t += mid_dpp<0xB1>(t); t += mid_dpp<0x4E>(t); t += mid_dpp<0x141>(t); t += mid_dpp<0x140>(t);
+      const int iv = __float_as_int(t);
+      const float lo = __int_as_float(__builtin_amdgcn_readlane(iv, 0)) + __int_as_float(__builtin_amdgcn_readlane(iv, 16));
+      const float hi = __int_as_float(__builtin_amdgcn_readlane(iv, 32)) + __int_as_float(__builtin_amdgcn_readlane(iv, 48));
+      const int r = u * PASS + wave * 2 + rsub;
+      if (cgi == 0 && r < M) a.ssq[(size_t)blockIdx.y * a.ssq_ld + r] = rsub == 0 ? lo : hi;
+    }
+  }
+  // lane (g, n) holds Y[activation row mt*16 + n][weight rows tile*16 + 4g .. + 3]
+  if (unit >= a.units) return;
 #pragma unroll
-      for (int mt = 0; mt < MT; ++mt) {
-        const int m = mt * 16 + n;
-        if (m >= M) continue;
-        float* y = pb + (size_t)m * N + c0;
-        if (c0 + 3 < N && (N & 3) == 0) {
-          *reinterpret_cast<float4*>(y) = make_float4(acc[i][mt][0], acc[i][mt][1], acc[i][mt][2], acc[i][mt][3]);
-        } else {
+  for (int i = 0; i < 2; ++i) {
+    if (tile[i] >= n_tiles) continue;
+    const int f = NF == 2 ? i : 0;
+    float* pb = a.partial + ((size_t)(blockIdx.y * NF + f) * M) * N;
+    const int c0 = tile[i] * 16 + 4 * g;
 #pragma unroll
-          for (int r = 0; r < 4; ++r)
-            if (c0 + r < N) y[r] = acc[i][mt][r];
-        }
+    for (int mt = 0; mt < MT; ++mt) {
+      const int m = mt * 16 + n;
+      if (m >= M) continue;
+      float* y = pb + (size_t)m * N + c0;
+      if (c0 + 3 < N && (N & 3) == 0) {
+        *reinterpret_cast<float4*>(y) = make_float4(acc[i][mt][0], acc[i][mt][1], acc[i][mt][2], acc[i][mt][3]);
+      } else {
+#pragma unroll
+        for (int r = 0; r < 4; ++r)
+          if (c0 + r < N) y[r] = acc[i][mt][r];
       }
     }
   }
-  TR(5);
 }
 
-struct MidPlan { int mt, ksw, nw, windows, units, blocks; size_t lds, partial_elems; };
+
+struct MidPlan { int mt, windows, units, blocks, wpb; size_t lds, partial_elems; };   // windows: K chunks = partial products
 
 static bool mid_plan(const GemvArgs& g, MidPlan& p) {
   if (!g.bf16 || g.n_seg != 1 || g.seg[0].P == nullptr || g.best != nullptr) return false;
@@ -221,19 +225,17 @@ static bool mid_plan(const GemvArgs& g, MidPlan& p) {
   const int nf = g.epi == EPI_SWIGLU ? 2 : 1, N = g.seg[0].n_rows, tiles = (N + 15) / 16;
   p.mt = (g.M + 15) / 16;
   p.units = nf == 2 ? tiles : (tiles + 1) / 2;
-  // Windows of 256 columns, of 128 when that leaves too few wavefront units for the chip's 1024
-  // SIMDs (the MFMA work of a unit is what bounds a small product); 4 wavefronts per workgroup
-  // (one per SIMD) unless there are units for 8.
-  static const int min_units = getenv("HH_MID_MINUNITS") ? atoi(getenv("HH_MID_MINUNITS")) : 1024;
-  p.ksw = 8;
-  if ((long)p.units * ((g.K + 255) / 256) < min_units) p.ksw = 4;
-  const int kw = p.ksw * 32;
-  p.windows = (g.K + kw - 1) / kw;
-  p.nw = (long)p.units * p.windows >= 4096 ? 8 : 4;
-  p.blocks = (p.units + p.nw - 1) / p.nw;
-  // more than ~4 workgroups per compute unit: several units per wavefront instead
-  while ((long)p.blocks * p.windows > 1024 && p.blocks > 1) p.blocks = (p.blocks + 1) / 2;
-  p.lds = (size_t)kMidTerms * p.mt * 16 * (kw + 8) * 2;
+  // K-loop kernel: 8 units per workgroup, windows of 128 columns, K chunks so that the launch
+  // has at most one workgroup per compute unit (its LDS and registers allow no second one)
+  static const int target = getenv("HH_MID_BLOCKS") ? atoi(getenv("HH_MID_BLOCKS")) : 256;
+  const int n_win = (g.K + 127) / 128;
+  p.blocks = (p.units + 7) / 8;
+  int ks = target / p.blocks;
+  if (ks > n_win) ks = n_win;
+  if (ks < 1) ks = 1;
+  p.wpb = (n_win + ks - 1) / ks;
+  p.windows = (n_win + p.wpb - 1) / p.wpb;          // K chunks = partial products
+  p.lds = (size_t)2 * kMidTerms * p.mt * 16 * (128 + 8) * 2;
   p.partial_elems = (size_t)p.windows * nf * g.M * N + (size_t)p.windows * 96;
   return p.lds <= 160 * 1024 && p.partial_elems <= gemm_partial_elems() && p.windows <= 65535;
 }
@@ -244,31 +246,26 @@ bool mid_mfma_fits(const GemvArgs& g) {
   return !off && mid_plan(g, p);
 }
 
-template <int NF, int MT, int KSW, int NW>
-static hipError_t mid_launch(const MidArgs& a, const MidPlan& p, hipStream_t s) {
-  auto kern = mid_mfma_kernel<NF, MT, KSW, NW>;
+template <int NF, int MT>
+static hipError_t mid_launch_loop(const MidArgs& a, const MidPlan& p, hipStream_t s) {
+  auto kern = mid_loop_kernel<NF, MT>;
   static size_t lds_enabled = 48 * 1024;
   if (p.lds > lds_enabled) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)p.lds);
     if (e != hipSuccess) return e;
     lds_enabled = p.lds;
   }
-  hipLaunchKernelGGL(kern, dim3(p.blocks, p.windows), dim3(64 * NW), p.lds, s, a);
+  hipLaunchKernelGGL(kern, dim3(p.blocks, p.windows), dim3(512), p.lds, s, a);
   return hipGetLastError();
-}
-template <int NF, int MT>
-static hipError_t mid_dispatch_k(const MidArgs& a, const MidPlan& p, hipStream_t s) {
-  if (p.nw == 8) return p.ksw == 8 ? mid_launch<NF, MT, 8, 8>(a, p, s) : mid_launch<NF, MT, 4, 8>(a, p, s);
-  return p.ksw == 8 ? mid_launch<NF, MT, 8, 4>(a, p, s) : mid_launch<NF, MT, 4, 4>(a, p, s);
 }
 template <int NF>
 static hipError_t mid_dispatch(const MidArgs& a, const MidPlan& p, hipStream_t s) {
   switch (p.mt) {
-    case 2: return mid_dispatch_k<NF, 2>(a, p, s);
-    case 3: return mid_dispatch_k<NF, 3>(a, p, s);
-    case 4: return mid_dispatch_k<NF, 4>(a, p, s);
-    case 5: return mid_dispatch_k<NF, 5>(a, p, s);
-    case 6: return mid_dispatch_k<NF, 6>(a, p, s);
+    case 2: return mid_launch_loop<NF, 2>(a, p, s);
+    case 3: return mid_launch_loop<NF, 3>(a, p, s);
+    case 4: return mid_launch_loop<NF, 4>(a, p, s);
+    case 5: return mid_launch_loop<NF, 5>(a, p, s);
+    case 6: return mid_launch_loop<NF, 6>(a, p, s);
   }
   return hipErrorInvalidValue;
 }
@@ -283,7 +280,7 @@ hipError_t launch_mid_mfma(const GemvArgs& g, float* partial, hipStream_t s) {
   MidArgs a{};
   a.X = g.X; a.ldx = g.ldx; a.M = g.M; a.K = g.K; a.X2 = g.X2; a.norm_w = g.norm_w;
   a.W = static_cast<const uint16_t*>(g.seg[0].P); a.W2 = static_cast<const uint16_t*>(g.seg[0].P2);
-  a.N = N; a.kst_row = (g.K + 31) / 32; a.partial = partial; a.units = p.units;
+  a.N = N; a.kst_row = (g.K + 31) / 32; a.partial = partial; a.units = p.units; a.wpb = p.wpb;
   a.ssq_ld = 96;
   a.ssq = g.norm_w != nullptr ? partial + (size_t)p.windows * nf * g.M * N : nullptr;
   hipError_t e = nf == 2 ? mid_dispatch<2>(a, p, s) : mid_dispatch<1>(a, p, s);

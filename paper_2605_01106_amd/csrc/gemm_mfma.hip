@@ -200,6 +200,19 @@ __global__ __launch_bounds__(256) void gemm_reduce_kernel(const GemmArgs a) {
   const size_t total = (size_t)a.M * a.N;
   for (size_t it = (blockIdx.x * (size_t)256 + threadIdx.x) * W; it < total; it += (size_t)gridDim.x * 256 * W) {
     const size_t m = it / a.N, nn = it - m * a.N;
+    // the sums of squares are requested first, so that they arrive with the partial products
+    float tot = 0.f;
+    if (a.ssq != nullptr)
+      for (int s = 0; s < a.ksplit; ++s) tot += a.ssq[(size_t)s * a.ssq_ld + m];
+    float* y = a.Y + m * a.ldy + nn;
+    float4 old = make_float4(0.f, 0.f, 0.f, 0.f);          // residual(s), requested with them
+    if (EPI == EPI_ADD && VEC) {
+      old = *reinterpret_cast<const float4*>(y);
+      if (a.R2 != nullptr) {
+        const float4 r2 = *reinterpret_cast<const float4*>(a.R2 + m * a.ldy + nn);
+        old.x += r2.x; old.y += r2.y; old.z += r2.z; old.w += r2.w;
+      }
+    }
     float v[NF][W];
 #pragma unroll
     for (int f = 0; f < NF; ++f) {
@@ -223,13 +236,7 @@ __global__ __launch_bounds__(256) void gemm_reduce_kernel(const GemmArgs a) {
         }
       }
     }
-    float scale = 1.f;
-    if (a.ssq != nullptr) {
-      float tot = 0.f;
-      for (int s = 0; s < a.ksplit; ++s) tot += a.ssq[(size_t)s * a.ssq_ld + m];
-      scale = 1.0f / sqrtf(tot * a.rnorm_k + a.eps);
-    }
-    float* y = a.Y + m * a.ldy + nn;
+    const float scale = a.ssq != nullptr ? 1.0f / sqrtf(tot * a.rnorm_k + a.eps) : 1.f;
     float o[W];
 #pragma unroll
     for (int w = 0; w < W; ++w) {
@@ -238,14 +245,7 @@ __global__ __launch_bounds__(256) void gemm_reduce_kernel(const GemmArgs a) {
     }
     if (VEC) {
       float4 r = make_float4(o[0], o[1 % W], o[2 % W], o[3 % W]);
-      if (EPI == EPI_ADD) {
-        const float4 old = *reinterpret_cast<const float4*>(y);
-        r.x += old.x; r.y += old.y; r.z += old.z; r.w += old.w;
-        if (a.R2 != nullptr) {
-          const float4 r2 = *reinterpret_cast<const float4*>(a.R2 + m * a.ldy + nn);
-          r.x += r2.x; r.y += r2.y; r.z += r2.z; r.w += r2.w;
-        }
-      }
+      if (EPI == EPI_ADD) { r.x += old.x; r.y += old.y; r.z += old.z; r.w += old.w; }
       *reinterpret_cast<float4*>(y) = r;
     } else {
       if (EPI == EPI_ADD) o[0] += *y + (a.R2 != nullptr ? a.R2[m * a.ldy + nn] : 0.f);

@@ -18,6 +18,7 @@
 
 #include "hh_internal.h"
 #include "bf16_split.h"
+#include "trace.h"
 
 namespace hh {
 
@@ -134,21 +135,35 @@ __global__ __launch_bounds__(512) void mid_loop_kernel(const MidArgs a) {
   for (int i = 0; i < 2; ++i)
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt) acc[i][mt] = f32x4{0.f, 0.f, 0.f, 0.f};
+  // B fragments in batches of two steps (6 fragments), the next batch read from LDS while the
+  // current one is multiplied; the fences keep the scheduler from hoisting more reads than that
+  // (registers).
   auto multiply = [&](const uint16_t* buf, const MFrag(&w)[2][KSW]) {
+    constexpr int NBATCH = MT * KSW / 2;
+    const uint16_t* xbase = buf + (size_t)n * SL + 8 * g;
+    MFrag xb[2][2 * kMidTerms];
+    auto read_batch = [&](int b, MFrag(&x)[2 * kMidTerms]) {
+      const int mt = b / (KSW / 2), s0 = (b % (KSW / 2)) * 2;
+      const uint16_t* xrow = xbase + (size_t)mt * 16 * SL;
 #pragma unroll
-    for (int mt = 0; mt < MT; ++mt) {
-      const uint16_t* xrow = buf + (size_t)(mt * 16 + n) * SL + 8 * g;
+      for (int ds = 0; ds < 2; ++ds)
 #pragma unroll
-      for (int s = 0; s < KSW; ++s) {
-        if ((s & 1) == 0) asm volatile("" ::: "memory");   // keeps the LDS reads of a unit from being hoisted together (registers)
+        for (int t = 0; t < kMidTerms; ++t)
+          x[ds * kMidTerms + t].u = *reinterpret_cast<const uint4*>(xrow + (size_t)t * ROWS * SL + (s0 + ds) * 32);
+    };
+    read_batch(0, xb[0]);
+#pragma unroll
+    for (int b = 0; b < NBATCH; ++b) {
+      asm volatile("" ::: "memory");
+      if (b + 1 < NBATCH) read_batch(b + 1, xb[(b + 1) & 1]);
+      const int mt = b / (KSW / 2), s0 = (b % (KSW / 2)) * 2;
+#pragma unroll
+      for (int ds = 0; ds < 2; ++ds)
 #pragma unroll
         for (int t = 0; t < kMidTerms; ++t) {
-          MFrag xb;
-          xb.u = *reinterpret_cast<const uint4*>(xrow + (size_t)t * ROWS * SL + s * 32);
-          acc[0][mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(w[0][s].v, xb.v, acc[0][mt], 0, 0, 0);
-          acc[1][mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(w[1][s].v, xb.v, acc[1][mt], 0, 0, 0);
+          acc[0][mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(w[0][s0 + ds].v, xb[b & 1][ds * kMidTerms + t].v, acc[0][mt], 0, 0, 0);
+          acc[1][mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(w[1][s0 + ds].v, xb[b & 1][ds * kMidTerms + t].v, acc[1][mt], 0, 0, 0);
         }
-      }
     }
   };
   // One window: request the activations of the next one and the weights of the one after it
@@ -165,11 +180,14 @@ __global__ __launch_bounds__(512) void mid_loop_kernel(const MidArgs a) {
     if (win + 1 < win1) stage(nxt);
     __syncthreads();
   };
+  TR(0);
   issue_x(win0);
   issue_w(win0, w0);
   issue_w(min(win0 + 1, win1 - 1), w1);
+  TR(1);
   stage(xs);
   __syncthreads();
+  TR(2);
   int win = win0;
   for (; win + 2 < win1; win += 3) {
     window(win, w0, w2);
@@ -178,6 +196,7 @@ __global__ __launch_bounds__(512) void mid_loop_kernel(const MidArgs a) {
   }
   if (win < win1) window(win, w0, w2);
   if (win + 1 < win1) window(win + 1, w1, w0);
+  TR(3);
   // sums of squares of the rows this wavefront staged (32 lanes per row), for the norm scale
   if (a.ssq != nullptr && blockIdx.x == 0) {
 #pragma unroll
@@ -192,6 +211,7 @@ __global__ __launch_bounds__(512) void mid_loop_kernel(const MidArgs a) {
     }
   }
   // lane (g, n) holds Y[activation row mt*16 + n][weight rows tile*16 + 4g .. + 3]
+  TR(4);
   if (unit >= a.units) return;
 #pragma unroll
   for (int i = 0; i < 2; ++i) {

@@ -80,6 +80,21 @@ def test_aligned_shapes_fast_paths(B, k, d_state, dtype):
     run_lockstep(ctx, wts, prompts, lens, 30, k, engine="pass", report=_say(f"aligned-k{k}-N{d_state}-{dtype}"))
 
 
+def test_mid_rows_long_k_and_wide_head(B):
+    """17..96 activation rows through the K-loop kernel with several K windows per workgroup:
+    d_model 320 (2.5 windows of 128 columns, so the last window is partly outside K) and a
+    24000-row LM head (enough weight tiles that a workgroup walks two windows: the loop, its
+    tail and the K-chunk reduction); 5 sequences, k = 4: 25 rows in verification, 80 in the
+    prefill passes, 5 in the draft steps."""
+    cfg = W.scaled_config("midk", n_layers=2, d_model=320, vocab=24000, m_heads=4, m_head_dim=40, d_state=16,
+                          n_q_heads=4, n_kv_heads=2, head_dim=32, d_ff=520, w_dtype=W.BF16)
+    wts = W.make_lively_weights(cfg, 37)          # seeds audited: top-1/top-2 gap 2.5e-4
+    lens = [40, 9, 70, 23, 33]
+    prompts = W.make_prompts(cfg.vocab, 5, lens, 7)
+    ctx = _ctx(B, wts, 5, 128, 4, 16, kv_page_tokens=32, prefill_chunk=16)
+    run_lockstep(ctx, wts, prompts, lens, 16, 4, engine="pass", report=_say("midk"))
+
+
 def test_forced_acceptance_and_arbitrary_drafts(B):
     """Forced accepted counts (drafts committed as drafted) and caller-supplied draft tokens."""
     cfg = W.scaled_config("forced", n_layers=2, d_model=64, vocab=96, m_heads=4, m_head_dim=16, d_state=8,

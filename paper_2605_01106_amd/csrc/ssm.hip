@@ -183,6 +183,165 @@ __global__ __launch_bounds__(kRows * kSub) void ssm_kernel(const Dims d, const S
 // and of the 3 before them, dt, z) is issued before the first result is used, so the kernel
 // costs about one memory round trip plus the recurrence.  The conv of B and C is computed
 // once per workgroup, 4 channels per lane, and handed to the lanes through LDS.
+// The same for aligned shapes (rows, channels and row strides multiples of 4): the convolution of a
+// chunk of positions is done by one thread per group of 4 channels (B, C and this workgroup's x
+// rows) walking the positions with a sliding window of float4 rows - all loads of a half chunk in
+// flight together, taps and bias loaded once - instead of one scalar item per channel and position,
+// and the gate inputs z are staged with x, so the recurrence loop touches no global memory but
+// its output.  (Prefill chunks: the scalar staging made the pass latency-bound.)
+template <int NV, int kRows>
+__global__ __launch_bounds__(kRows * kSub) void ssm_chunk_kernel(const Dims d, const SsmArgs a) {
+  constexpr int N = NV * kSub;
+  constexpr int NGBC = 2 * N / 4, NGX = kRows / 4, HP = kTS / 2;
+  static_assert(NGBC + NGX <= kRows * kSub, "one thread per channel group");
+  __shared__ __align__(16) float xs[kTS][kRows];
+  __shared__ __align__(16) float zs[kTS][kRows];
+  __shared__ __align__(16) float Bs[kTS][N];
+  __shared__ __align__(16) float Cs[kTS][N];
+  __shared__ float dts[kTS], as[kTS];
+
+  const int tid = threadIdx.x, row = tid >> 3, sub = tid & 7;
+  const int p0 = blockIdx.x * kRows, h = blockIdx.y;
+  const int lz = blockIdx.z / a.B, b = blockIdx.z % a.B;
+  const LayerDev& ly = a.layers != nullptr ? a.layers[a.layer0 + lz] : a.one;
+  if (a.skip != nullptr && a.skip[b]) return;
+  int nt = a.T;
+  if (a.n_acc != nullptr) nt = a.n_acc[b] + 1;
+  else if (a.n_tok != nullptr) nt = a.n_tok[b];
+  if (nt <= 0) return;
+  const int pos0 = a.pos0[b];
+  const int p = p0 + row;
+  const bool prow = p < d.P;
+  const int rmask = d.ring_slots - 1;
+  float* ring = ly.ring + (size_t)b * d.ring_slots * d.ring_w;
+  const float* zx = a.zx != nullptr ? a.zx + (size_t)b * a.T * d.ldzx : nullptr;
+  // row of raw inputs (xBC | dt) of position pos (positions < 0 read slot 0 and count as 0)
+  auto raw_row = [&](int pos) -> const float* {
+    return (zx != nullptr && pos >= pos0) ? zx + (size_t)(pos - pos0) * d.ldzx + d.d_inner
+                                          : ring + (size_t)(max(pos, 0) & rmask) * d.ring_w;
+  };
+
+  float S[NV];
+  {
+    const float* src = a.state_in == 0 ? ly.S : (a.state_in == 1 ? ly.S_draft : nullptr);
+    if (src != nullptr && prow) {
+      const float* sp = src + (((size_t)b * d.Hm + h) * d.P + p) * N + sub * 4;   // float4 i of a lane is elements (i/4)*4*kSub + 4*sub ..: a row group reads 16*kSub contiguous bytes
+#pragma unroll
+      for (int i = 0; i < NV; i += 4) {
+        const float4 v = *reinterpret_cast<const float4*>(sp + i * kSub);
+        S[i] = v.x; S[i + 1] = v.y; S[i + 2] = v.z; S[i + 3] = v.w;
+      }
+    } else {
+#pragma unroll
+      for (int i = 0; i < NV; ++i) S[i] = 0.f;
+    }
+  }
+  const float dskip = ly.d_skip[h];
+  const float dtb = ly.dt_bias[h];
+  const float negA = -expf(ly.a_log[h]);
+  // this thread's channel group: B|C groups first, then the x rows of the workgroup
+  const bool is_x = tid >= NGBC;
+  const int xg = tid - NGBC;                                 // x group (is_x)
+  const bool active = tid < NGBC + NGX && (!is_x || p0 + 4 * xg < d.P);
+  const int c4 = is_x ? h * d.P + min(p0 + 4 * xg, d.P - 4) : d.d_inner + 4 * min(tid, NGBC - 1);
+  float4 taps[4], bias;
+#pragma unroll
+  for (int t = 0; t < 4; ++t) taps[t] = *reinterpret_cast<const float4*>(ly.conv_w + (size_t)(c4 + t) * 4);
+  bias = *reinterpret_cast<const float4*>(ly.conv_b + c4);
+
+  for (int j0 = 0; j0 < nt; j0 += kTS) {
+    const int tc = min(kTS, nt - j0);
+    if (tid < NGBC + NGX) {
+#pragma unroll
+      for (int hp = 0; hp < 2; ++hp) {
+        const int jb = j0 + hp * HP;                           // first position of the half chunk (relative)
+        if (jb >= j0 + tc) break;
+        // raw rows of positions jb-3 .. jb+HP-1 (clamped to the last valid one), z of jb .. jb+HP-1
+        float4 r[HP + 3], z[HP];
+#pragma unroll
+        for (int u = 0; u < HP + 3; ++u) {
+          const int pos = pos0 + min(jb + u - 3, nt - 1);
+          r[u] = *reinterpret_cast<const float4*>(raw_row(pos) + c4);
+          if (pos < 0) r[u] = make_float4(0.f, 0.f, 0.f, 0.f);
+        }
+        if (is_x && a.g != nullptr) {
+#pragma unroll
+          for (int u = 0; u < HP; ++u)
+            z[u] = *reinterpret_cast<const float4*>(zx + (size_t)min(jb + u, nt - 1) * d.ldzx + (c4 - 0));
+        }
+#pragma unroll
+        for (int u = 0; u < HP; ++u) {
+          const int jj = hp * HP + u;
+          if (jb + u >= j0 + tc) break;
+          float o[4];
+#pragma unroll
+          for (int ch = 0; ch < 4; ++ch) {
+            const float* r0 = reinterpret_cast<const float*>(&r[u]);
+            const float* r1 = reinterpret_cast<const float*>(&r[u + 1]);
+            const float* r2 = reinterpret_cast<const float*>(&r[u + 2]);
+            const float* r3 = reinterpret_cast<const float*>(&r[u + 3]);
+            const float* tp = reinterpret_cast<const float*>(&taps[ch]);
+            float acc = tp[0] * r0[ch];
+            acc = fmaf(tp[1], r1[ch], acc); acc = fmaf(tp[2], r2[ch], acc); acc = fmaf(tp[3], r3[ch], acc);
+            o[ch] = silu_f(acc + reinterpret_cast<const float*>(&bias)[ch]);
+          }
+          const float4 ov = make_float4(o[0], o[1], o[2], o[3]);
+          if (!is_x) {
+            if (tid < NGBC / 2) *reinterpret_cast<float4*>(&Bs[jj][4 * tid]) = ov;
+            else *reinterpret_cast<float4*>(&Cs[jj][4 * tid - N]) = ov;
+          } else if (active) {
+            *reinterpret_cast<float4*>(&xs[jj][4 * xg]) = ov;
+            if (a.g != nullptr) *reinterpret_cast<float4*>(&zs[jj][4 * xg]) = z[u];
+          }
+          // keep the raw inputs of these positions for later windows and for rollback
+          if (a.write_ring && zx != nullptr && active && (is_x || (h == 0 && blockIdx.x == 0)))
+            *reinterpret_cast<float4*>(ring + (size_t)((pos0 + jb + u) & rmask) * d.ring_w + c4) = r[u + 3];
+        }
+      }
+    }
+    if (tid >= kRows * kSub - kTS && tid - (kRows * kSub - kTS) < tc) {   // the last threads: step and decay of the head
+      const int jj = tid - (kRows * kSub - kTS);
+      const float dt = softplus_f(raw_row(pos0 + j0 + jj)[d.conv_dim + h] + dtb);
+      dts[jj] = dt;
+      as[jj] = expf(negA * dt);
+    }
+    if (a.write_ring && zx != nullptr && h == 0 && blockIdx.x == 0) {
+      for (int it = tid; it < tc * d.Hm; it += kRows * kSub) {
+        const int jj = it / d.Hm, hh = it - jj * d.Hm, pos = pos0 + j0 + jj;
+        ring[(size_t)(pos & rmask) * d.ring_w + d.conv_dim + hh] = raw_row(pos)[d.conv_dim + hh];
+      }
+    }
+    __syncthreads();
+    // ---- recurrence over the staged positions
+    for (int jj = 0; jj < tc; ++jj) {
+      const float xv = xs[jj][row];
+      const float coef = dts[jj] * xv, aj = as[jj];
+      float part = 0.f;
+#pragma unroll
+      for (int i = 0; i < NV; i += 4) {
+        const float4 Bv = *reinterpret_cast<const float4*>(&Bs[jj][i * kSub + sub * 4]);
+        const float4 Cv = *reinterpret_cast<const float4*>(&Cs[jj][i * kSub + sub * 4]);
+        S[i] = fmaf(aj, S[i], coef * Bv.x); part = fmaf(S[i], Cv.x, part);
+        S[i + 1] = fmaf(aj, S[i + 1], coef * Bv.y); part = fmaf(S[i + 1], Cv.y, part);
+        S[i + 2] = fmaf(aj, S[i + 2], coef * Bv.z); part = fmaf(S[i + 2], Cv.z, part);
+        S[i + 3] = fmaf(aj, S[i + 3], coef * Bv.w); part = fmaf(S[i + 3], Cv.w, part);
+      }
+      part += dpp_perm_f<0xB1>(part);    // lane ^ 1
+      part += dpp_perm_f<0x4E>(part);    // lane ^ 2
+      part += dpp_perm_f<0x141>(part);   // the other quad of the 8 lanes that share a row
+      if (a.g != nullptr && sub == 0 && prow)
+        a.g[((size_t)b * a.T + j0 + jj) * d.d_inner + h * d.P + p] = (part + dskip * xv) * silu_f(zs[jj][row]);
+    }
+    __syncthreads();
+  }
+
+  if (a.state_out != 0 && prow) {
+    float* dst = (a.state_out == 1 ? ly.S : ly.S_draft) + (((size_t)b * d.Hm + h) * d.P + p) * N + sub * 4;
+#pragma unroll
+    for (int i = 0; i < NV; i += 4) *reinterpret_cast<float4*>(dst + i * kSub) = make_float4(S[i], S[i + 1], S[i + 2], S[i + 3]);
+  }
+}
+
 // RG row groups of 64 / SUBS rows per workgroup, one after the other: the B/C convolution and the
 // per-head scalars are shared by all of them, which is what a large batch needs (there a
 // workgroup's fixed loads would otherwise exceed its share of the state).
@@ -225,10 +384,10 @@ __global__ __launch_bounds__(64 * NWV) void ssm_small_kernel(const Dims d, const
 #pragma unroll
     for (int rg = 0; rg < RG; ++rg) {
       if (src != nullptr) {
-        const float* sp = src + (((size_t)b * d.Hm + h) * d.P + pr[rg]) * N + sub * NV;
+        const float* sp = src + (((size_t)b * d.Hm + h) * d.P + pr[rg]) * N + sub * 4;       // float4 i of a lane: elements (i/4)*4*SUBS + 4*sub ..
 #pragma unroll
         for (int i = 0; i < NV; i += 4) {
-          const float4 v = *reinterpret_cast<const float4*>(sp + i);
+          const float4 v = *reinterpret_cast<const float4*>(sp + i * SUBS);
           S[rg][i] = v.x; S[rg][i + 1] = v.y; S[rg][i + 2] = v.z; S[rg][i + 3] = v.w;
         }
       } else {
@@ -374,8 +533,8 @@ __global__ __launch_bounds__(64 * NWV) void ssm_small_kernel(const Dims d, const
       float part = 0.f;
 #pragma unroll
       for (int i = 0; i < NV; i += 4) {
-        const float4 Bv = *reinterpret_cast<const float4*>(&BCs[j][sub * NV + i]);
-        const float4 Cv = *reinterpret_cast<const float4*>(&BCs[j][N + sub * NV + i]);
+        const float4 Bv = *reinterpret_cast<const float4*>(&BCs[j][i * SUBS + sub * 4]);
+        const float4 Cv = *reinterpret_cast<const float4*>(&BCs[j][N + i * SUBS + sub * 4]);
         S[rg][i] = fmaf(aj[j], S[rg][i], coef * Bv.x); part = fmaf(S[rg][i], Cv.x, part);
         S[rg][i + 1] = fmaf(aj[j], S[rg][i + 1], coef * Bv.y); part = fmaf(S[rg][i + 1], Cv.y, part);
         S[rg][i + 2] = fmaf(aj[j], S[rg][i + 2], coef * Bv.z); part = fmaf(S[rg][i + 2], Cv.z, part);
@@ -393,10 +552,10 @@ __global__ __launch_bounds__(64 * NWV) void ssm_small_kernel(const Dims d, const
         if (j < nt) a.g[((size_t)b * a.T + j) * d.d_inner + cx[rg]] = y[j];
     }
     if (a.state_out != 0 && prow[rg]) {
-      float* dst = (a.state_out == 1 ? ly.S : ly.S_draft) + (((size_t)b * d.Hm + h) * d.P + pr[rg]) * N + sub * NV;
+      float* dst = (a.state_out == 1 ? ly.S : ly.S_draft) + (((size_t)b * d.Hm + h) * d.P + pr[rg]) * N + sub * 4;
 #pragma unroll
       for (int i = 0; i < NV; i += 4)
-        *reinterpret_cast<float4*>(dst + i) = make_float4(S[rg][i], S[rg][i + 1], S[rg][i + 2], S[rg][i + 3]);
+        *reinterpret_cast<float4*>(dst + i * SUBS) = make_float4(S[rg][i], S[rg][i + 1], S[rg][i + 2], S[rg][i + 3]);
     }
   }
   TR(5);
@@ -453,6 +612,20 @@ template <int kRows>
 static hipError_t launch_ssm_rows(const Dims& d, const SsmArgs& a, hipStream_t s) {
   const dim3 grid((d.P + kRows - 1) / kRows, d.Hm, a.n_layers_z * a.B);
   const dim3 block(kRows * kSub);
+  // aligned shapes: the kernel with the vectorised chunk convolution
+  static const bool scalar = getenv("HH_SSM_SCALAR_CONV") != nullptr && atoi(getenv("HH_SSM_SCALAR_CONV")) != 0;
+  const int nv = d.N / kSub;
+  const bool vec = !scalar && d.P % 4 == 0 && d.d_inner % 4 == 0 && d.ldzx % 4 == 0 && d.ring_w % 4 == 0 &&
+                   d.conv_dim % 4 == 0 && nv % 4 == 0 && 2 * d.N / 4 + kRows / 4 <= kRows * kSub - kTS &&
+                   (a.zx == nullptr || (reinterpret_cast<uintptr_t>(a.zx) & 15) == 0);
+  if (vec) {
+    switch (nv) {
+      case 4: hipLaunchKernelGGL((ssm_chunk_kernel<4, kRows>), grid, block, 0, s, d, a); return hipGetLastError();
+      case 8: hipLaunchKernelGGL((ssm_chunk_kernel<8, kRows>), grid, block, 0, s, d, a); return hipGetLastError();
+      case 16: hipLaunchKernelGGL((ssm_chunk_kernel<16, kRows>), grid, block, 0, s, d, a); return hipGetLastError();
+      case 32: hipLaunchKernelGGL((ssm_chunk_kernel<32, kRows>), grid, block, 0, s, d, a); return hipGetLastError();
+    }
+  }
   switch (d.N / kSub) {
     case 1: hipLaunchKernelGGL((ssm_kernel<1, kRows>), grid, block, 0, s, d, a); break;
     case 2: hipLaunchKernelGGL((ssm_kernel<2, kRows>), grid, block, 0, s, d, a); break;

@@ -582,7 +582,7 @@ static hipError_t launch_ssm_small_t(const Dims& d, const SsmArgs& a, int tmax, 
   static const int min_wg = getenv("HH_SSM_MINWG") ? atoi(getenv("HH_SSM_MINWG")) : 1024;
   const int groups = (d.P + 64 / SUBS - 1) / (64 / SUBS);
   const long wgs = (long)groups * d.Hm * a.n_layers_z * a.B;
-  if (a.zx == nullptr) {
+  if (a.zx == nullptr && NV <= 16) {            // (32 values per lane and row group: registers; four wavefronts instead)
     if (groups % 4 == 0 && wgs / 4 >= min_wg) return launch_ssm_small_r<NV, SUBS, 4, 1>(d, a, tmax, s);
     if (groups % 2 == 0 && wgs / 2 >= min_wg) return launch_ssm_small_r<NV, SUBS, 2, 1>(d, a, tmax, s);
   }

@@ -42,18 +42,31 @@ __device__ __forceinline__ uint16_t bf16_rne(float f) {
 }
 __device__ __forceinline__ float bf16_f32(uint16_t h) { return __uint_as_float((uint32_t)h << 16); }
 
-// split activations in MFMA operand order (see below); rows >= M and columns >= K are zero
+// split activations in MFMA operand order (see below); rows >= M and columns >= K are zero.
+// One workgroup per row; a thread handles groups of 8 consecutive columns (two float4 loads,
+// one 16-byte store per term): K % 8 == 0 and 16-byte aligned rows (VEC), else element by element.
+template <bool VEC>
 __global__ __launch_bounds__(256) void split_rows_kernel(const float* __restrict__ X, const float* __restrict__ X2, int ldx, int M, int K, int Mp, int Kp,
                                                          const float* __restrict__ norm_w, float eps,
                                                          uint16_t* __restrict__ planes, const int kTerms) {
   const int m = blockIdx.x;
   __shared__ float red[4];
+  const float* xr = X + (size_t)m * ldx;
+  const float* xr2 = X2 != nullptr ? X2 + (size_t)m * ldx : nullptr;
   float rstd = 1.f;
   if (m < M && norm_w != nullptr) {
     float ss = 0.f;
-    for (int k = threadIdx.x; k < K; k += 256) {
-      const float v = X[(size_t)m * ldx + k] + (X2 != nullptr ? X2[(size_t)m * ldx + k] : 0.f);
-      ss = fmaf(v, v, ss);
+    if (VEC) {
+      for (int k = threadIdx.x * 4; k < K; k += 1024) {
+        float4 v = *reinterpret_cast<const float4*>(xr + k);
+        if (xr2 != nullptr) { const float4 w = *reinterpret_cast<const float4*>(xr2 + k); v.x += w.x; v.y += w.y; v.z += w.z; v.w += w.w; }
+        ss = fmaf(v.x, v.x, ss); ss = fmaf(v.y, v.y, ss); ss = fmaf(v.z, v.z, ss); ss = fmaf(v.w, v.w, ss);
+      }
+    } else {
+      for (int k = threadIdx.x; k < K; k += 256) {
+        const float v = xr[k] + (xr2 != nullptr ? xr2[k] : 0.f);
+        ss = fmaf(v, v, ss);
+      }
     }
 #pragma unroll
     for (int o = 32; o > 0; o >>= 1) ss += __shfl_xor(ss, o, 64);
@@ -64,10 +77,39 @@ __global__ __launch_bounds__(256) void split_rows_kernel(const float* __restrict
   // operand order: block (row tile, step of 32 columns, term) of 512 elements, lane 16 g + n at
   // element 8 (16 g + n), n = row % 16, g = (column % 32) / 8: a wavefront load is 1 KB contiguous
   const int KST = Kp >> 5;
+  if (VEC) {
+    for (int k = threadIdx.x * 8; k < Kp; k += 2048) {
+      float v[8];
+#pragma unroll
+      for (int i = 0; i < 8; ++i) v[i] = 0.f;
+      if (m < M && k < K) {                       // K % 8 == 0: a group is inside or outside
+        const float4 a0 = *reinterpret_cast<const float4*>(xr + k), a1 = *reinterpret_cast<const float4*>(xr + k + 4);
+        v[0] = a0.x; v[1] = a0.y; v[2] = a0.z; v[3] = a0.w; v[4] = a1.x; v[5] = a1.y; v[6] = a1.z; v[7] = a1.w;
+        if (xr2 != nullptr) {
+          const float4 b0 = *reinterpret_cast<const float4*>(xr2 + k), b1 = *reinterpret_cast<const float4*>(xr2 + k + 4);
+          v[0] += b0.x; v[1] += b0.y; v[2] += b0.z; v[3] += b0.w; v[4] += b1.x; v[5] += b1.y; v[6] += b1.z; v[7] += b1.w;
+        }
+        if (norm_w != nullptr) {
+          const float4 n0 = *reinterpret_cast<const float4*>(norm_w + k), n1 = *reinterpret_cast<const float4*>(norm_w + k + 4);
+          const float nw[8] = {n0.x, n0.y, n0.z, n0.w, n1.x, n1.y, n1.z, n1.w};
+#pragma unroll
+          for (int i = 0; i < 8; ++i) v[i] = v[i] * nw[i] * rstd;   // same order as the element-wise path
+        }
+      }
+      uint32_t w0[4], w1[4], w2[4];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) split3_bf16_pair(v[2 * i], v[2 * i + 1], w0[i], w1[i], w2[i]);
+      uint16_t* dst = planes + (((size_t)(m >> 4) * KST + (k >> 5)) * kTerms) * 512 + (size_t)((((k & 31) >> 3) * 16 + (m & 15)) * 8);
+      *reinterpret_cast<uint4*>(dst) = make_uint4(w0[0], w0[1], w0[2], w0[3]);
+      *reinterpret_cast<uint4*>(dst + 512) = make_uint4(w1[0], w1[1], w1[2], w1[3]);
+      if (kTerms == 3) *reinterpret_cast<uint4*>(dst + 1024) = make_uint4(w2[0], w2[1], w2[2], w2[3]);
+    }
+    return;
+  }
   for (int k = threadIdx.x; k < Kp; k += 256) {
     uint16_t t0 = 0, t1 = 0, t2 = 0;
     if (m < M && k < K) {
-      float v = X[(size_t)m * ldx + k] + (X2 != nullptr ? X2[(size_t)m * ldx + k] : 0.f);
+      float v = xr[k] + (xr2 != nullptr ? xr2[k] : 0.f);
       if (norm_w != nullptr) v = v * norm_w[k] * rstd;
       uint32_t b0, b1, b2;
       split3_bf16(v, b0, b1, b2);
@@ -297,7 +339,11 @@ hipError_t launch_gemm_mfma(const GemvArgs& g, uint16_t* planes, float* partial,
   const int M = g.M, K = g.K, N = g.seg[0].n_rows;
   if (M <= 0 || N <= 0) return hipSuccess;
   const int Mp = (M + 15) / 16 * 16, Kp = (K + 31) / 32 * 32;
-  hipLaunchKernelGGL(split_rows_kernel, dim3(Mp), dim3(256), 0, s, g.X, g.X2, g.ldx, M, K, Mp, Kp, g.norm_w, g.eps, planes, gemm_terms());
+  const bool vec = K % 8 == 0 && g.ldx % 4 == 0 && (reinterpret_cast<uintptr_t>(g.X) & 15) == 0 &&
+                   (g.X2 == nullptr || (reinterpret_cast<uintptr_t>(g.X2) & 15) == 0) &&
+                   (g.norm_w == nullptr || (reinterpret_cast<uintptr_t>(g.norm_w) & 15) == 0);
+  if (vec) hipLaunchKernelGGL(split_rows_kernel<true>, dim3(Mp), dim3(256), 0, s, g.X, g.X2, g.ldx, M, K, Mp, Kp, g.norm_w, g.eps, planes, gemm_terms());
+  else hipLaunchKernelGGL(split_rows_kernel<false>, dim3(Mp), dim3(256), 0, s, g.X, g.X2, g.ldx, M, K, Mp, Kp, g.norm_w, g.eps, planes, gemm_terms());
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   const int nf = g.epi == EPI_SWIGLU ? 2 : 1, nt = nf == 2 ? 2 : 4;

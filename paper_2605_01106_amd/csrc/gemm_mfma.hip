@@ -3,8 +3,8 @@
 // the packed operand tiles.
 //
 // A first kernel applies the fused RMSNorm and splits every activation into bf16 terms stored
-// as planes: x = t0 + t1 (+ t2), two terms by default (16 mantissa bits), three for an exact
-// split; the product is the sum of the per-term bf16 MFMA products accumulated in float32.
+// as planes: x = t0 + t1 + t2 exactly (two terms, 16 mantissa bits, as an option); the product
+// is the sum of the per-term bf16 MFMA products accumulated in float32.
 //
 // GEMM kernel: a wavefront is an independent unit of work - NT strips of 16 weight rows x
 // MTW tiles of 16 activation rows x a range of K steps - with all accumulators in registers
@@ -26,21 +26,16 @@ namespace hh {
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
-// bf16 terms an activation is split into for this kernel (planes per row tile and step): two
-// by default (16 mantissa bits: a product's relative error is below 2^-17, a few times the
-// rounding noise of its float32 accumulation; the kernel is about twice as fast as with three),
-// three (exact) with HH_GEMM_TERMS=3.
-static int gemm_terms() {
-  static const int t = getenv("HH_GEMM_TERMS") != nullptr && atoi(getenv("HH_GEMM_TERMS")) == 3 ? 3 : 2;
-  return t;
+// bf16 terms an activation is split into for this kernel (planes per row tile and step): three
+// (exact).  HH_GEMM_TERMS=2 keeps 16 mantissa bits only: the kernel is then about twice as fast
+// (fewer MFMAs, fewer plane re-reads) and the benign random-weight workloads still match the
+// float64 reference, but models with order-one activations and recurrences amplify the 2^-17
+// relative error beyond the logit tolerance (seen on the test initialisation with 160 prefill
+// rows), so it is an option, not the default.
+static int gemm_terms(int M) {
+  static const int t = getenv("HH_GEMM_TERMS") != nullptr && atoi(getenv("HH_GEMM_TERMS")) == 2 ? 2 : 3;
+  return M <= 96 ? 3 : t;   // up to 96 rows (only with the mid-row kernel switched off) always exact
 }
-
-__device__ __forceinline__ uint16_t bf16_rne(float f) {
-  uint32_t u = __float_as_uint(f);
-  u += 0x7FFFu + ((u >> 16) & 1u);
-  return (uint16_t)(u >> 16);
-}
-__device__ __forceinline__ float bf16_f32(uint16_t h) { return __uint_as_float((uint32_t)h << 16); }
 
 // split activations in MFMA operand order (see below); rows >= M and columns >= K are zero.
 // One workgroup per row; a thread handles groups of 8 consecutive columns (two float4 loads,
@@ -342,13 +337,13 @@ hipError_t launch_gemm_mfma(const GemvArgs& g, uint16_t* planes, float* partial,
   const bool vec = K % 8 == 0 && g.ldx % 4 == 0 && (reinterpret_cast<uintptr_t>(g.X) & 15) == 0 &&
                    (g.X2 == nullptr || (reinterpret_cast<uintptr_t>(g.X2) & 15) == 0) &&
                    (g.norm_w == nullptr || (reinterpret_cast<uintptr_t>(g.norm_w) & 15) == 0);
-  if (vec) hipLaunchKernelGGL(split_rows_kernel<true>, dim3(Mp), dim3(256), 0, s, g.X, g.X2, g.ldx, M, K, Mp, Kp, g.norm_w, g.eps, planes, gemm_terms());
-  else hipLaunchKernelGGL(split_rows_kernel<false>, dim3(Mp), dim3(256), 0, s, g.X, g.X2, g.ldx, M, K, Mp, Kp, g.norm_w, g.eps, planes, gemm_terms());
+  if (vec) hipLaunchKernelGGL(split_rows_kernel<true>, dim3(Mp), dim3(256), 0, s, g.X, g.X2, g.ldx, M, K, Mp, Kp, g.norm_w, g.eps, planes, gemm_terms(M));
+  else hipLaunchKernelGGL(split_rows_kernel<false>, dim3(Mp), dim3(256), 0, s, g.X, g.X2, g.ldx, M, K, Mp, Kp, g.norm_w, g.eps, planes, gemm_terms(M));
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   const int nf = g.epi == EPI_SWIGLU ? 2 : 1, nt = nf == 2 ? 2 : 4;
   GemmArgs a{};
-  a.planes = planes; a.Mp = Mp; a.Kp = Kp; a.terms = gemm_terms();
+  a.planes = planes; a.Mp = Mp; a.Kp = Kp; a.terms = gemm_terms(M);
   a.W = static_cast<const uint16_t*>(g.seg[0].P); a.W2 = static_cast<const uint16_t*>(g.seg[0].P2);
   a.Y = g.seg[0].Y; a.ldy = g.seg[0].ldy; a.R2 = g.R2; a.partial = partial; a.M = M; a.N = N; a.K = K;
   const int steps = Kp / 32, tiles = (N + 15) / 16, m_tiles = Mp / 16;

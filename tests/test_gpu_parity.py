@@ -95,6 +95,20 @@ def test_mid_rows_long_k_and_wide_head(B):
     run_lockstep(ctx, wts, prompts, lens, 16, 4, engine="pass", report=_say("midk"))
 
 
+def test_many_rows_lively(B):
+    """More than 96 activation rows (10 sequences x 16-position prefill chunks = 160 rows: the
+    tiled matrix-core GEMM over pre-split activations) on the initialisation with order-one
+    activations, which amplifies any loss of precision in the projections: a two-term bf16 split
+    of the activations there (16 mantissa bits) puts hundreds of logits outside the tolerance."""
+    cfg = W.scaled_config("lively", n_layers=3, d_model=72, vocab=200, m_heads=3, m_head_dim=40, d_state=16,
+                          n_q_heads=6, n_kv_heads=2, head_dim=24, d_ff=104, w_dtype=W.BF16)
+    wts = W.make_lively_weights(cfg, 8)           # seeds audited: top-1/top-2 gap 1.1e-4
+    lens = [37, 5, 70, 18, 44, 63, 29, 51, 12, 66]
+    prompts = W.make_prompts(cfg.vocab, 10, lens, 4)
+    ctx = _ctx(B, wts, 10, 160, 4, 24, kv_page_tokens=32, prefill_chunk=16)
+    run_lockstep(ctx, wts, prompts, lens, 24, 3, engine="pass", report=_say("many-rows-lively"))
+
+
 def test_forced_acceptance_and_arbitrary_drafts(B):
     """Forced accepted counts (drafts committed as drafted) and caller-supplied draft tokens."""
     cfg = W.scaled_config("forced", n_layers=2, d_model=64, vocab=96, m_heads=4, m_head_dim=16, d_state=8,

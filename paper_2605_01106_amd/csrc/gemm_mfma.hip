@@ -348,7 +348,10 @@ hipError_t launch_gemm_mfma(const GemvArgs& g, uint16_t* planes, float* partial,
   a.Y = g.seg[0].Y; a.ldy = g.seg[0].ldy; a.R2 = g.R2; a.partial = partial; a.M = M; a.N = N; a.K = K;
   const int steps = Kp / 32, tiles = (N + 15) / 16, m_tiles = Mp / 16;
   a.strip_groups = (tiles + nt - 1) / nt;
-  a.m_groups = (m_tiles + 4) / 5;
+  // row tiles per unit: 5 with two terms; 4 with three (5 would spill under the two-workgroups-per-CU register cap)
+  static const int mtw_cap3 = getenv("HH_GEMM_MTW3") ? atoi(getenv("HH_GEMM_MTW3")) : 4;
+  const int mtw_cap = a.terms == 3 ? (mtw_cap3 >= 1 && mtw_cap3 <= 5 ? mtw_cap3 : 4) : 5;
+  a.m_groups = (m_tiles + mtw_cap - 1) / mtw_cap;
   const int mtw = (m_tiles + a.m_groups - 1) / a.m_groups;
   // K split: enough units (wavefronts) to cover the chip, at least 4 steps each, partial buffer permitting
   static const int unit_target = getenv("HH_GEMM_UNITS") ? atoi(getenv("HH_GEMM_UNITS")) : 2048;

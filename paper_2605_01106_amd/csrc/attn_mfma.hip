@@ -16,8 +16,10 @@
 //            rescaling of the online softmax is a per-lane scalar.
 // The A rows of the two key blocks of a step are assigned so that a lane's 8 scores are the
 // 8 consecutive keys its V load covers (block 0 row m <-> key 8(m/4) + m%4, block 1: + 4).
-// Queries are float32 values split exactly into three bf16 terms (the scores carry float32
-// accuracy), probabilities into two (16 mantissa bits); K and V are used as stored.  The scores
+// Queries and probabilities are float32 values split exactly into three bf16 terms, so the
+// products carry float32 accuracy (with two-term probabilities, 16 mantissa bits, models with
+// order-one activations lost tokens to near ties that the float32 reference path keeps); K and V
+// are used as stored.  The scores
 // are kept in base-2 units (log2(e) folded into the query scale) so that the exponentials are
 // single v_exp_f32 instructions.
 #include <stdlib.h>
@@ -351,13 +353,12 @@ __global__ __launch_bounds__(64 * NW) void attn_mfma_kernel(const Dims d, const 
       const float corr = ex2(mold - msub);                         // 0 while nothing was accumulated
       lrun[rt] = lrun[rt] * corr + psum;
       mrun[rt] = mnew;
-      // the probabilities (in [0, 1]) go into the value product as two bf16 terms: 16 mantissa
-      // bits, relative error 2^-17, far below the rounding of the cached values themselves
-      Frag p0, p1;
-      split2_bf16_pair(pr[0], pr[1], p0.u.x, p1.u.x);
-      split2_bf16_pair(pr[2], pr[3], p0.u.y, p1.u.y);
-      split2_bf16_pair(pr[4], pr[5], p0.u.z, p1.u.z);
-      split2_bf16_pair(pr[6], pr[7], p0.u.w, p1.u.w);
+      // the probabilities go into the value product split exactly into three bf16 terms
+      Frag p0, p1, p2;
+      split3_bf16_pair(pr[0], pr[1], p0.u.x, p1.u.x, p2.u.x);
+      split3_bf16_pair(pr[2], pr[3], p0.u.y, p1.u.y, p2.u.y);
+      split3_bf16_pair(pr[4], pr[5], p0.u.z, p1.u.z, p2.u.z);
+      split3_bf16_pair(pr[6], pr[7], p0.u.w, p1.u.w, p2.u.w);
       // the accumulators are rescaled only when some row's maximum rose (and it holds something)
       if (__builtin_amdgcn_ballot_w64(corr != 1.f && mold != -INFINITY) != 0) {
 #pragma unroll
@@ -370,6 +371,7 @@ __global__ __launch_bounds__(64 * NW) void attn_mfma_kernel(const Dims d, const 
         f32x4 c = acc[rt][db];
         c = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vt[db].v, p0.v, c, 0, 0, 0);
         c = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vt[db].v, p1.v, c, 0, 0, 0);
+        c = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vt[db].v, p2.v, c, 0, 0, 0);
         acc[rt][db] = c;
       }
     }

@@ -25,6 +25,7 @@ import numpy as np
 
 from .hybrid_lm import HybridLM, SeqState, argmax_lowest, top2_gap
 from .passes import full_pass
+from . import sampling
 
 
 def expected_tokens_per_round(alpha: float, k: int) -> float:
@@ -75,10 +76,25 @@ class SpecDecoder:
     sequences.  engine="step" uses only single-token steps (the definition);
     engine="pass" uses the multi-position pass for prefill and verification."""
 
-    def __init__(self, lm: HybridLM, capacity: int, engine: str = "step", chunk: int = 64):
+    def __init__(self, lm: HybridLM, capacity: int, engine: str = "step", chunk: int = 64,
+                 temperature: float = 0.0, seed: int = 0):
+        """temperature 0: greedy acceptance.  temperature > 0: tokens are drawn from
+        softmax(logits / T) and drafts pass the rejection test of Eq. 6, with the
+        counter-based uniforms of `sampling.uniform(seed, ...)`."""
         assert engine in ("step", "pass")
         self.lm, self.capacity, self.engine, self.chunk = lm, capacity, engine, chunk
+        self.T, self.seed = float(temperature), int(seed)
         self.gaps: List[float] = []          # top-1/top-2 gap of every greedy decision taken
+        self.margins: List[float] = []       # distance of every random decision from flipping (T > 0)
+
+    def _pick(self, logits, b: int, idx: int, purpose: int) -> int:
+        """Next token from one row of logits: argmax (T = 0) or a draw from softmax(logits / T)."""
+        if self.T == 0.0:
+            self.gaps.append(top2_gap(logits))
+            return argmax_lowest(logits)
+        tok, m = sampling.draw(sampling.softmax_t(logits, self.T), sampling.uniform(self.seed, b, idx, purpose))
+        self.margins.append(m)
+        return tok
 
     # ---------------------------------------------------------------- prefill
     def prefill(self, prompts: Sequence[Sequence[int]], max_new_tokens: int) -> None:
@@ -89,15 +105,14 @@ class SpecDecoder:
         self.pending: List[int] = []
         self.last_n = [0] * self.B
         self.prefill_logits = []
-        for p in prompts:
+        for b, p in enumerate(prompts):
             st = self.lm.new_state(self.capacity)
             if self.engine == "pass":
                 logits = full_pass(self.lm, st, p, self.chunk, last_only=True)[0][0]
             else:
                 for t in p:
                     logits = self.lm.step(st, int(t), "full")
-            tok = argmax_lowest(logits)
-            self.gaps.append(top2_gap(logits))
+            tok = self._pick(logits, b, 0, sampling.PURPOSE_CORRECT)
             self.st.append(st)
             self.out.append([tok][:self.G])
             self.pending.append(tok)
@@ -129,11 +144,11 @@ class SpecDecoder:
             ds, ls = [], []
             for i in range(k):
                 logits = self.lm.step(scratch, t, "draft")
-                t = argmax_lowest(logits)
-                self.gaps.append(top2_gap(logits))
+                t = self._pick(logits, b, len(self.out[b]) + i, sampling.PURPOSE_DRAFT)
                 ds.append(t)
                 ls.append(logits)
             if override is not None:
+                assert self.T == 0.0, "replaced drafts have no draft distribution to test against"
                 ds = [int(v) for v in override[b][:k]]
             self.drafts[b] = ds
             self.draft_logits[b] = np.array(ls).reshape(k, -1) if k else None
@@ -156,10 +171,28 @@ class SpecDecoder:
                     logits.append(self.lm.step(st, int(t), "full"))
                     ck.append(st.recurrent_copy())
                 logits = np.array(logits)
-            self.targets[b] = [argmax_lowest(r) for r in logits]
             self.verify_logits[b] = logits
-            self._gaps_v = [top2_gap(r) for r in logits]
+            if self.T == 0.0:
+                self.targets[b] = [argmax_lowest(r) for r in logits]
+                self._gaps_v = [top2_gap(r) for r in logits]
+            else:
+                self.targets[b] = self._stochastic_targets(b, logits)
+                self._gaps_v = []
             self._ckpt[b] = (ck, st.kv_len - len(xs), self._gaps_v)
+
+    def _stochastic_targets(self, b: int, logits_h) -> List[int]:
+        """Eq. 6 over the round's k drafts; the outcome in the targets form of
+        `sampling.stochastic_targets`."""
+        d = self.drafts[b]
+        k = len(d)
+        base = len(self.out[b])
+        p_s = [sampling.softmax_t(self.draft_logits[b][i], self.T) for i in range(k)]
+        p_h = [sampling.softmax_t(logits_h[i], self.T) for i in range(k + 1)]
+        u_acc = [sampling.uniform(self.seed, b, base + i, sampling.PURPOSE_ACCEPT) for i in range(k)]
+        n, tok, m = sampling.stochastic_round(
+            p_s, p_h, d, u_acc, lambda n_: sampling.uniform(self.seed, b, base + n_, sampling.PURPOSE_CORRECT))
+        self.margins.append(m)
+        return sampling.stochastic_targets(d, n, tok)
 
     # ---------------------------------------------------------------- commit
     def commit(self, forced_n: Optional[Sequence[int]] = None) -> None:
@@ -171,6 +204,7 @@ class SpecDecoder:
                 continue
             ck, len0, gaps_v = self._ckpt[b]
             d, g = self.drafts[b], self.targets[b]
+            assert forced_n is None or self.T == 0.0, "a forced count has no correction token at T > 0"
             n = accepted_prefix(d, g) if forced_n is None else int(forced_n[b])
             assert 0 <= n <= len(d)
             self.gaps.extend(gaps_v[:n + 1])     # only positions that decided a token

@@ -129,6 +129,23 @@ HH_API hh_status hh_destroy(hh_ctx* ctx);
 HH_API hh_status hh_prefill(hh_ctx* ctx, const int32_t* tokens, int32_t row_stride, const int32_t* lens,
                      int32_t batch, int32_t max_new, void* stream);
 
+/* Temperature of the token choice (Section 3.3, Eq. 6; the paper evaluates T = 0 and T = 0.6).
+ * temperature = 0 (the state after hh_create): greedy, every call as described at that call.
+ * temperature > 0: P = softmax(logits / temperature); the first token and every draft token are
+ * drawn from their distribution, hh_verify applies the rejection test of Eq. 6 to the drafts
+ * in order (draft d kept with probability min(1, P_H(d) / P_S(d))), and the token emitted after
+ * the n kept drafts is drawn from norm(max(0, P_H - P_S)) at the first rejection, or from P_H at
+ * position k+1 when all are kept.  hh_verify then leaves, in place of M_H's argmaxes, targets
+ * g_i = d_{i+1} for i < n, g_n = the emitted token and -1 behind it, so that hh_commit's prefix
+ * rule returns n.  A draw from p with a uniform u takes the smallest index i with
+ * p_0 + .. + p_i > u * sum(p).  Uniforms: the top 24 bits of output number c of SplitMix64
+ * started at `seed`, c = sequence * 2^34 + position in the generated stream * 4 + purpose
+ * (0 draft draw, 1 acceptance test, 2 emitted / first token): HOST scalars, nothing kept from the
+ * caller.  At temperature > 0 hh_set_drafts and a forced count in hh_commit return HH_ESTATE.
+ * Valid before hh_prefill and between rounds (HH_ESTATE inside a round); synchronises `stream`.
+ * HH_EINVAL for a negative or non-finite temperature. */
+HH_API hh_status hh_set_sampling(hh_ctx* ctx, float temperature, uint64_t seed, void* stream);
+
 /* Draft phase (Section 3.3 / Eq. 4): k autoregressive greedy steps of the
  * SSM-only subgraph per sequence, starting from the committed recurrent state
  * on a scratch copy; never touches the KV cache.  0 <= k <= max_draft; k = 0

@@ -64,6 +64,7 @@ EXPORTS = {
     "hh_create": (C.c_int, [C.POINTER(hh_weights), C.POINTER(hh_cfg), C.POINTER(_ctx_p)]),
     "hh_destroy": (C.c_int, [_ctx_p]),
     "hh_prefill": (C.c_int, [_ctx_p, C.c_void_p, C.c_int32, _i32p, C.c_int32, C.c_int32, C.c_void_p]),
+    "hh_set_sampling": (C.c_int, [_ctx_p, C.c_float, C.c_uint64, C.c_void_p]),
     "hh_draft": (C.c_int, [_ctx_p, C.c_int32, C.c_void_p]),
     "hh_set_drafts": (C.c_int, [_ctx_p, C.c_void_p, C.c_void_p]),
     "hh_verify": (C.c_int, [_ctx_p, C.c_void_p]),
@@ -194,6 +195,9 @@ class Context:
     def hh_draft(self, k: int, stream=None):
         _check(lib.hh_draft(self.ctx, k, _stream_ptr(stream)), self.ctx)
         self.k = k
+
+    def hh_set_sampling(self, temperature: float, seed: int = 0, stream=None):
+        _check(lib.hh_set_sampling(self.ctx, C.c_float(temperature), C.c_uint64(seed), _stream_ptr(stream)), self.ctx)
 
     def hh_set_drafts(self, drafts, stream=None):
         torch = self.torch

@@ -50,6 +50,9 @@ struct hh_ctx {
   int *kv_len, *committed, *last_n, *pending, *n_acc, *skip, *adv, *drafts, *targets, *tok, *pos0, *out_tok,
       *page_table, *plan_ntok, *plan_last, *first_tok;
   unsigned long long* best;
+  SamplingParams* sampling;   // temperature and seed read by the drawing kernels
+  float* softmax_stats;       // (max, sum) of the round's logit rows
+  float temperature = 0.f;    // 0: greedy
   int* attn_counters;   // tickets of the attention key slices (zero between launches)
   uint16_t* planes;   // split activations of the matrix-core products
   float* gemm_partial;   // partial products of split-K launches
@@ -150,6 +153,8 @@ size_t carve(hh_ctx* x, char* base) {
   x->plan_ntok = c.take<int>((size_t)x->max_passes * B);
   x->plan_last = c.take<int>((size_t)x->max_passes * B);
   x->best = c.take<unsigned long long>(Mv * gemv_max_blocks());
+  x->sampling = c.take<SamplingParams>(1);
+  x->softmax_stats = c.take<float>(B * (2 * d.Kmax + 1) * 2);
   x->attn_counters = c.take<int>(B * d.Hkv * attention_row_chunks(d, d.Tmax));
   {
     int kmax = d.D > d.d_inner ? d.D : d.d_inner;
@@ -626,9 +631,27 @@ hh_status hh_prefill(hh_ctx* x, const int32_t* tokens, int32_t row_stride, const
   }
   hh_status st = run_head(x, x->lasth, B, 1, x->logits_p, d.V, x->first_tok, 1, 0, s);
   if (st != HH_OK) return st;
+  if (x->temperature > 0.f)
+    HH_HIP(launch_sample_rows(x->logits_p, d.V, d.V, B, x->sampling, nullptr, 0, 2, x->first_tok, 1, 0, s));
   HH_HIP(launch_prefill_finish(x->first_tok, x->pending, x->out_tok, d.Gmax, x->committed, x->last_n, B, s));
   x->B = B; x->G = max_new; x->k = 0; x->len_upper = maxlen;
   x->phase = PH_READY;
+  return HH_OK;
+}
+
+hh_status hh_set_sampling(hh_ctx* x, float temperature, uint64_t seed, void* stream) {
+  if (!x) return HH_EINVAL;
+  if (x->phase != PH_CREATED && x->phase != PH_READY)
+    return fail(x, HH_ESTATE, "hh_set_sampling: not while a round is in flight");
+  if (!(temperature >= 0.f) || !(temperature < 1e30f)) return fail(x, HH_EINVAL, "hh_set_sampling: temperature must be finite and >= 0");
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  SamplingParams p{};
+  p.inv_t = temperature > 0.f ? 1.0f / temperature : 0.f;
+  p.seed = seed;
+  // ordered after the rounds already enqueued on the stream; the source is copied before the call returns
+  HH_HIP(hipMemcpyAsync(x->sampling, &p, sizeof(p), hipMemcpyHostToDevice, s));
+  HH_HIP(hipStreamSynchronize(s));
+  x->temperature = temperature;
   return HH_OK;
 }
 
@@ -639,6 +662,7 @@ hh_status hh_draft(hh_ctx* x, int32_t k, void* stream) {
   if (k < 0 || k > d.Kmax) return fail(x, HH_ECAPACITY, "hh_draft: k outside 0..max_draft");
   hipStream_t s = static_cast<hipStream_t>(stream);
   const int B = x->B;
+  const bool stochastic = x->temperature > 0.f;
   x->prof_phase = HH_PHASE_DRAFT;
   auto enqueue = [&]() -> hh_status {
     for (int i = 0; i < k; ++i) {
@@ -648,11 +672,14 @@ hh_status hh_draft(hh_ctx* x, int32_t k, void* stream) {
       if (st != HH_OK) return st;
       st = run_head(x, x->h, B, 1, x->logits_d + (size_t)i * d.V, d.Kmax * d.V, x->drafts, d.Kmax, i, s);
       if (st != HH_OK) return st;
+      if (stochastic)
+        HH_HIP(launch_sample_rows(x->logits_d + (size_t)i * d.V, (size_t)d.Kmax * d.V, d.V, B, x->sampling, x->committed,
+                                  i, 0, x->drafts, d.Kmax, i, s));
     }
     return HH_OK;
   };
   if (k > 0) {
-    const hh_status st = run_graphed(x, (1LL << 40) | ((long long)B << 20) | k, s, enqueue);
+    const hh_status st = run_graphed(x, (1LL << 40) | ((long long)stochastic << 38) | ((long long)B << 20) | k, s, enqueue);
     if (st != HH_OK) return st;
   }
   x->k = k;
@@ -663,6 +690,8 @@ hh_status hh_draft(hh_ctx* x, int32_t k, void* stream) {
 hh_status hh_set_drafts(hh_ctx* x, const int32_t* drafts, void* stream) {
   if (!x) return HH_EINVAL;
   if (x->phase != PH_DRAFTED) return fail(x, HH_ESTATE, "hh_set_drafts: only between hh_draft and hh_verify");
+  if (x->temperature > 0.f)
+    return fail(x, HH_ESTATE, "hh_set_drafts: replaced drafts have no draft distribution to test against at temperature > 0");
   if (!drafts) return fail(x, HH_EINVAL, "hh_set_drafts: NULL argument");
   hipStream_t s = static_cast<hipStream_t>(stream);
   if (x->k > 0)
@@ -677,6 +706,7 @@ hh_status hh_verify(hh_ctx* x, void* stream) {
   const Dims& d = x->d;
   hipStream_t s = static_cast<hipStream_t>(stream);
   const int B = x->B, T = x->k + 1;
+  const bool stochastic = x->temperature > 0.f;
   x->prof_phase = HH_PHASE_VERIFY;
   const int splits = pick_splits(d, B, T, x->len_upper);
   auto enqueue = [&]() -> hh_status {
@@ -684,9 +714,14 @@ hh_status hh_verify(hh_ctx* x, void* stream) {
     HH_HIP(launch_embed(d, x->embed, x->tok, B * T, x->h, s));
     hh_status st = run_layers(x, true, B, T, nullptr, 0, 0, splits, s);
     if (st != HH_OK) return st;
-    return run_head(x, x->h, B * T, T, x->logits_v, d.V, x->targets, d.Kmax + 1, 0, s);
+    st = run_head(x, x->h, B * T, T, x->logits_v, d.V, x->targets, d.Kmax + 1, 0, s);
+    if (st != HH_OK) return st;
+    if (stochastic)
+      HH_HIP(launch_spec_targets(x->logits_d, x->logits_v, d.V, B, x->k, d.Kmax, x->sampling, x->softmax_stats, x->drafts,
+                                 x->committed, x->targets, s));
+    return HH_OK;
   };
-  const hh_status st = run_graphed(x, (2LL << 40) | ((long long)branch_overlap(x, B, T) << 39) | ((long long)B << 20) | ((long long)splits << 8) | T, s, enqueue);
+  const hh_status st = run_graphed(x, (2LL << 40) | ((long long)branch_overlap(x, B, T) << 39) | ((long long)stochastic << 38) | ((long long)B << 20) | ((long long)splits << 8) | T, s, enqueue);
   if (st != HH_OK) return st;
   x->phase = PH_VERIFIED;
   return HH_OK;
@@ -695,6 +730,8 @@ hh_status hh_verify(hh_ctx* x, void* stream) {
 hh_status hh_commit(hh_ctx* x, const int32_t* n_accepted, void* stream) {
   if (!x) return HH_EINVAL;
   if (x->phase != PH_VERIFIED) return fail(x, HH_ESTATE, "hh_commit: needs hh_verify first");
+  if (n_accepted && x->temperature > 0.f)
+    return fail(x, HH_ESTATE, "hh_commit: a forced count has no correction token at temperature > 0");
   const Dims& d = x->d;
   hipStream_t s = static_cast<hipStream_t>(stream);
   const int B = x->B;

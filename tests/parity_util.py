@@ -36,13 +36,16 @@ def assert_close(name, got, ref, atol, rtol, scale_to_ref=False):
 def run_lockstep(ctx, weights: W.Weights, prompts, lens, G: int, k: int, forced: Optional[np.ndarray] = None,
                  override: Optional[np.ndarray] = None, engine: str = "pass", max_rounds: int = 10 ** 9,
                  check_state_every: int = 1, check_kv: bool = True, min_gap: float = 0.0, report=None,
-                 layers=None, oracle_rows=None, chunk: int = 5):
+                 layers=None, oracle_rows=None, chunk: int = 5, temperature: float = 0.0, sample_seed: int = 0,
+                 min_margin: float = 0.0):
     """Runs prefill and rounds on both sides, comparing after every call:
     tokens, accepted counts, cache lengths and committed counts bit-exactly;
     logits, SSM state, conv window and KV entries within tolerance.
     `layers`: layers whose state and cache are read back (default all).  `oracle_rows`: batch
     rows the oracle runs (default all); the library always runs the whole batch, rows are
     independent, so the remaining rows are covered by the batch-invariance of the kernels.
+    `temperature` > 0: both sides draw tokens and apply the rejection test with the uniforms of
+    `sample_seed`; `min_margin` is the seed audit of those decisions (the analogue of `min_gap`).
     Returns a dict of the worst errors seen."""
     import torch
     cfg = weights.cfg
@@ -52,9 +55,12 @@ def run_lockstep(ctx, weights: W.Weights, prompts, lens, G: int, k: int, forced:
     layer_list = list(range(cfg.n_layers)) if layers is None else list(layers)
     lm = HybridLM(cfg, weights.values)
     cap = int(max(lens)) + G + 2 * k + 4
-    dec = SpecDecoder(lm, cap, engine=engine, chunk=chunk)
+    dec = SpecDecoder(lm, cap, engine=engine, chunk=chunk, temperature=temperature, seed=sample_seed)
     plist = [np.asarray(prompts[b][:lens[b]]) for b in rows]
     dec.prefill(plist, G)
+    if temperature > 0:
+        assert oracle_rows is None, "the uniforms are keyed by the batch row"
+    ctx.hh_set_sampling(temperature, sample_seed)
     ctx.hh_prefill(prompts, lens, G)
     worst = {"logits": 0.0, "ssm": 0.0, "conv": 0.0, "kv": 0.0}
     worst["logits"] = max(worst["logits"], assert_close(
@@ -137,7 +143,10 @@ def run_lockstep(ctx, weights: W.Weights, prompts, lens, G: int, k: int, forced:
     if min_gap > 0:
         assert min(dec.gaps) > min_gap, f"seed audit: smallest top-1/top-2 gap {min(dec.gaps):.3e} <= {min_gap}"
     worst["rounds"] = r
-    worst["min_gap"] = float(min(dec.gaps))
+    if min_margin > 0:
+        assert min(dec.margins) > min_margin, f"seed audit: a random decision was within {min(dec.margins):.3e} of flipping"
+    worst["min_gap"] = float(min(dec.gaps)) if dec.gaps else float("inf")
+    worst["min_margin"] = float(min(dec.margins)) if dec.margins else float("inf")
     worst["mean_n"] = float(np.mean([n for row in n_hist for n in row if n >= 0])) if n_hist else 0.0
     worst["tokens"] = dec.out
     if report is not None:

@@ -109,6 +109,93 @@ def test_many_rows_lively(B):
     run_lockstep(ctx, wts, prompts, lens, 24, 3, engine="pass", report=_say("many-rows-lively"))
 
 
+def _say_t(tag):
+    def f(w):
+        print(f"[{tag}] rounds={w['rounds']} mean_n={w['mean_n']:.2f} min_margin={w['min_margin']:.2e} "
+              f"err: logits={w['logits']:.2e} ssm={w['ssm']:.2e} conv={w['conv']:.2e} kv={w['kv']:.2e}", flush=True)
+    return f
+
+
+@pytest.mark.parametrize("dtype,T,seed", [(W.F32, 0.6, 59), (W.F32, 0.3, 10), (W.BF16, 0.6, 21), (W.BF16, 0.3, 32)])
+def test_stochastic_acceptance_lockstep(B, dtype, T, seed):
+    """Temperature > 0 (Eq. 6): first token, draft draws, rejection tests, correction and bonus
+    tokens equal the oracle's, decision by decision, with the same counter-based uniforms; the
+    targets row has the oracle's form, and state, window and cache follow the committed stream.
+    Odd vocabulary (203: ragged tail of the drawing kernel's 4-element groups).  Seeds audited:
+    no decision within 1e-4 of flipping (a logit error e moves a CDF edge by at most e / T times the
+    mass it touches; the measured logit errors are 1e-6 for float32 and, on single entries, up to
+    1e-3 for bf16 storage)."""
+    cfg = W.scaled_config("lively", n_layers=3, d_model=72, vocab=203, m_heads=3, m_head_dim=40, d_state=16,
+                          n_q_heads=6, n_kv_heads=2, head_dim=24, d_ff=104, w_dtype=dtype)
+    wts = W.make_lively_weights(cfg, 7)
+    lens = [37, 5, 70, 18]
+    prompts = W.make_prompts(cfg.vocab, 4, lens, 3)
+    ctx = _ctx(B, wts, 4, 160, 4, 12, kv_page_tokens=16, prefill_chunk=16)
+    w = run_lockstep(ctx, wts, prompts, lens, 12, 3, engine="pass", temperature=T, sample_seed=seed, min_margin=1e-4,
+                     report=_say_t(f"stochastic-{dtype}-T{T}"))
+    assert 0.0 < w["mean_n"] < 3.0            # both kept and rejected drafts occurred
+    # back to temperature 0 on the same context: the greedy stream again
+    run_lockstep(ctx, wts, prompts, lens, 12, 3, engine="pass", report=_say("greedy-after-stochastic"))
+
+
+def test_stochastic_wide_vocabulary_and_plain_sampling(B):
+    """A 24001-entry vocabulary (every wavefront of the drawing workgroup walks its segment in
+    several 256-entry groups, ragged end) with float32 weights, few decisions: the CDF edges are
+    4e-5 apart, the audited seed keeps 8e-6 from the nearest one, the float32 logit error of 2e-6
+    moves an edge by at most 4e-6 at T = 0.5.  Then k = 0: plain sampling from M_H."""
+    cfg = W.scaled_config("widev", n_layers=1, d_model=64, vocab=24001, m_heads=2, m_head_dim=32, d_state=16,
+                          n_q_heads=2, n_kv_heads=1, head_dim=32, d_ff=64, w_dtype=W.F32)
+    wts = W.make_lively_weights(cfg, 3)
+    lens = [11, 6]
+    prompts = W.make_prompts(cfg.vocab, 2, lens, 2)
+    ctx = _ctx(B, wts, 2, 64, 2, 4, prefill_chunk=8)
+    run_lockstep(ctx, wts, prompts, lens, 4, 2, engine="pass", temperature=0.5, sample_seed=327, min_margin=8e-6,
+                 report=_say_t("stochastic-wide"))
+    cfg = W.scaled_config("klen", n_layers=2, d_model=64, vocab=128, m_heads=2, m_head_dim=32, d_state=32,
+                          n_q_heads=4, n_kv_heads=4, head_dim=16, d_ff=64, w_dtype=W.F32)
+    wts = W.make_lively_weights(cfg, 5)
+    lens = [9, 21]
+    prompts = W.make_prompts(cfg.vocab, 2, lens, 2)
+    ctx = _ctx(B, wts, 2, 96, 5, 12, prefill_chunk=8)
+    run_lockstep(ctx, wts, prompts, lens, 12, 0, engine="step", temperature=0.8, sample_seed=27, min_margin=4e-4,
+                 report=_say_t("plain-sampling"))
+
+
+def test_stochastic_call_rules(B):
+    """At temperature > 0 replaced drafts and forced counts are refused (neither has a draft
+    distribution or a correction token); a bad temperature is refused; sampling cannot change
+    inside a round."""
+    import torch
+    cfg = W.scaled_config("rules", n_layers=1, d_model=64, vocab=96, m_heads=2, m_head_dim=32, d_state=16,
+                          n_q_heads=2, n_kv_heads=1, head_dim=32, d_ff=64, w_dtype=W.F32)
+    wts = W.make_lively_weights(cfg, 1)
+    lens = [8, 5]
+    prompts = W.make_prompts(cfg.vocab, 2, lens, 1)
+    ctx = _ctx(B, wts, 2, 64, 2, 8, prefill_chunk=8)
+    with pytest.raises(B.HHError):
+        ctx.hh_set_sampling(-1.0, 0)
+    with pytest.raises(B.HHError):
+        ctx.hh_set_sampling(float("nan"), 0)
+    ctx.hh_set_sampling(0.7, 3)
+    ctx.hh_prefill(prompts, lens, 8)
+    ctx.hh_draft(2)
+    with pytest.raises(B.HHError):
+        ctx.hh_set_sampling(0.5, 3)
+    with pytest.raises(B.HHError):
+        ctx.hh_set_drafts(np.zeros((2, 2), np.int32))
+    ctx.hh_verify()
+    with pytest.raises(B.HHError):
+        ctx.hh_commit(torch.zeros(2, dtype=torch.int32, device=ctx.device))
+    ctx.hh_commit()
+    d, g = ctx.hh_get_round()
+    _, _, last_n = ctx.hh_get_lengths()
+    for b in range(2):
+        n = last_n[b]
+        assert list(g[b][:n]) == list(d[b][:n]) and 0 <= g[b][n] < cfg.vocab and all(v == -1 for v in g[b][n + 1:])
+        if n < 2:
+            assert g[b][n] != d[b][n]
+
+
 def test_forced_acceptance_and_arbitrary_drafts(B):
     """Forced accepted counts (drafts committed as drafted) and caller-supplied draft tokens."""
     cfg = W.scaled_config("forced", n_layers=2, d_model=64, vocab=96, m_heads=4, m_head_dim=16, d_state=8,

@@ -120,6 +120,8 @@ def main():
     ap.add_argument("--forced-p", type=float, default=None, help="per-token accept probability of the forced leg")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="0 disables the oracle baseline")
     ap.add_argument("--graphs", type=int, default=1)
+    ap.add_argument("--temperature", type=float, default=0.6,
+                    help="temperature of the stochastic-acceptance leg (the paper's second setting); 0 skips the leg")
     ap.add_argument("--counters", action="store_true",
                     help="short eager run for rocprofv3 --pmc: prefill, a few rounds, four 256 MiB copies for calibration")
     ap.add_argument("--prompt-len", type=int, default=None,
@@ -142,7 +144,7 @@ def main():
     K, Wm = args.steps, args.warmup
     prof_rounds, greedy_rounds = 3, min(K, 32)
     forced_p = args.forced_p if args.forced_p is not None else (wl.forced_p or 0.68)
-    total_rounds = Wm + K + K + prof_rounds + greedy_rounds + 4
+    total_rounds = Wm + K + K + K + prof_rounds + greedy_rounds + 6
     G = max(wl.gen_len, total_rounds * (k + 1) + 2)
     max_seq = wl.prompt_len + G + 2 * k + 4
 
@@ -218,6 +220,16 @@ def main():
     # plain greedy decoding of the full model (k = 0) for the speedup the paper's Table 7 reports
     dt_g, toks_g, _ = timed_leg(greedy_rounds, 0)
 
+    # stochastic-acceptance leg (Eq. 6) at the paper's temperature: same kernels plus the draws
+    stochastic = None
+    if args.temperature > 0:
+        ctx.hh_set_sampling(args.temperature, args.seed)
+        run_rounds(2, k)       # first use of the temperature's launch sequences (eager, then captured)
+        dt_s, toks_s, _ = timed_leg(K, k)
+        ctx.hh_set_sampling(0.0, 0)
+        stochastic = {"temperature": args.temperature, "committed_tokens_per_s": round(toks_s / dt_s, 2),
+                      "mean_accepted_per_round": round(toks_s / (K * Bn) - 1, 3)}
+
     # per-kernel timing leg, on the launch stream: every kind of kernel is launched alone, in its
     # place in the pass (consecutive launches stream different layers' weights), between one HIP
     # event pair, so the average is launch duration + launch gap without per-launch event overhead
@@ -282,6 +294,7 @@ def main():
                        "hbm_frac": round(commit_bytes / (t_commit / K) / 1e9 / HBM_PEAK_GBS, 4)}},
         "forced": {"p": forced_p, "committed_tokens_per_s": round(toks_f / dt_f, 2),
                    "mean_accepted_per_round": round(toks_f / (K * Bn) - 1, 3)},
+        "stochastic": stochastic,
         "plain_greedy_tokens_per_s": round(toks_g / dt_g, 2),
         "speedup_vs_plain_greedy": round((toks / dt) / (toks_g / dt_g), 4),
         "prefill_s": round(t_prefill, 3), "weight_gen_s": round(t_gen, 1),

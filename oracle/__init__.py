@@ -13,7 +13,11 @@ scan == sequential recurrence, one multi-position pass == single-token steps,
 draft == full model with attention zeroed, speculative stream == plain greedy
 stream for any draft, cache-free brute force on tiny shapes, textbook special
 cases (prefix sums, identity conv, one-key attention, RoPE invariances), and
-the expected-tokens-per-round closed form of Eq. 1.
+the expected-tokens-per-round closed form of Eq. 1.  Stochastic acceptance
+(Eq. 6, ``sampling.py``; tests/test_oracle_sampling.py): the published
+SplitMix64 sequence, inverse-CDF counts on regular grids, exact integration of
+the rule over its three uniforms (committed token ~ P_H, keep probability
+sum(min(P_S, P_H))), the T -> 0 limit and the k = 0 case.
 
 Parity unpinned: absolute logit values of the large random-init shapes (the
 paper prints none) and the paper's acceptance rates (trained weights needed).

@@ -44,19 +44,52 @@ __device__ __forceinline__ float wave_sum(float v) {
 // so that a probability computed in two places has the same bits
 __device__ __forceinline__ float prob(float l, float m, float inv_t, float rsum) { return expf((l - m) * inv_t) * rsum; }
 
-// max over the row and sum of exp((l - max) / T), by a whole workgroup; `red` holds blockDim.x / 64 floats
-__device__ void row_stats(const float* __restrict__ row, int V, float inv_t, float* red, float& m_out, float& s_out) {
+constexpr float kNoLogit = -3.0e38f;   // stands for an entry past the end of the row: exp((kNoLogit - m) / T) = 0
+
+// entries jj .. jj+3 of a row (jj a multiple of 4); past `end` they read as kNoLogit.  vec: the row
+// starts on a 16-byte boundary
+__device__ __forceinline__ void load_group(const float* __restrict__ row, int jj, int end, bool vec, float (&l)[4]) {
+  if (vec && jj + 3 < end) {
+    const float4 t = *reinterpret_cast<const float4*>(row + jj);
+    l[0] = t.x; l[1] = t.y; l[2] = t.z; l[3] = t.w;
+  } else {
+    for (int e = 0; e < 4; ++e) l[e] = jj + e < end ? row[jj + e] : kNoLogit;
+  }
+}
+__device__ __forceinline__ bool row_is_vec(const float* row) { return (reinterpret_cast<uintptr_t>(row) & 15) == 0; }
+
+// max over the row, by a whole workgroup; `red` holds blockDim.x / 64 floats
+__device__ float row_max(const float* __restrict__ row, int V, float* red) {
   const int lane = threadIdx.x & 63, w = threadIdx.x >> 6, nw = blockDim.x >> 6;
-  float m = -3.0e38f;
-  for (int j = threadIdx.x; j < V; j += blockDim.x) m = fmaxf(m, row[j]);
+  const bool vec = row_is_vec(row);
+  float m = kNoLogit;
+#pragma unroll 4
+  for (int j = threadIdx.x * 4; j < V; j += blockDim.x * 4) {
+    float l[4];
+    load_group(row, j, V, vec, l);
+    m = fmaxf(fmaxf(m, fmaxf(l[0], l[1])), fmaxf(l[2], l[3]));
+  }
   m = wave_max(m);
   if (lane == 0) red[w] = m;
   __syncthreads();
   m = red[0];
   for (int i = 1; i < nw; ++i) m = fmaxf(m, red[i]);
   __syncthreads();
+  return m;
+}
+
+// max over the row and sum of exp((l - max) / T), by a whole workgroup; `red` holds blockDim.x / 64 floats
+__device__ void row_stats(const float* __restrict__ row, int V, float inv_t, float* red, float& m_out, float& s_out) {
+  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6, nw = blockDim.x >> 6;
+  const bool vec = row_is_vec(row);
+  const float m = row_max(row, V, red);
   float s = 0.f;
-  for (int j = threadIdx.x; j < V; j += blockDim.x) s += expf((row[j] - m) * inv_t);
+#pragma unroll 4
+  for (int j = threadIdx.x * 4; j < V; j += blockDim.x * 4) {
+    float l[4];
+    load_group(row, j, V, vec, l);
+    s += (expf((l[0] - m) * inv_t) + expf((l[1] - m) * inv_t)) + (expf((l[2] - m) * inv_t) + expf((l[3] - m) * inv_t));
+  }
   s = wave_sum(s);
   if (lane == 0) red[w] = s;
   __syncthreads();
@@ -66,7 +99,8 @@ __device__ void row_stats(const float* __restrict__ row, int V, float inv_t, flo
   m_out = m; s_out = s;
 }
 
-// Inverse-CDF draw by a workgroup of kDrawThreads threads.  val(j) >= 0 is the mass of index j.
+// Inverse-CDF draw by a workgroup of kDrawThreads threads.  val(jj, end, v) fills v[0..3] with the
+// masses (>= 0) of indices jj .. jj+3, zero past `end`.
 // Wavefront w owns the contiguous segment [w * seg, (w + 1) * seg); the segment sums give the
 // segment that holds u * total, and that wavefront alone scans its segment in index order.
 // red: kDrawWaves floats, res: one int (both in LDS).  Every thread returns the drawn index.
@@ -76,11 +110,11 @@ __device__ int block_draw(F val, int V, float u, float* red, int* res) {
   const int seg = ((V + kDrawWaves * 256 - 1) / (kDrawWaves * 256)) * 256;
   const int j0 = min(V, w * seg), j1 = min(V, j0 + seg);
   float acc = 0.f;
+#pragma unroll 4
   for (int j = j0 + lane * 4; j < j1; j += 256) {
-    float t = 0.f;
-    for (int e = 0; e < 4; ++e)
-      if (j + e < j1) t += val(j + e);
-    acc += t;
+    float v[4];
+    val(j, j1, v);
+    acc += (v[0] + v[1]) + (v[2] + v[3]);
   }
   acc = wave_sum(acc);
   if (lane == 0) red[w] = acc;
@@ -110,10 +144,10 @@ __device__ int block_draw(F val, int V, float u, float* red, int* res) {
     for (int j = j0; j < j1 && result < 0; j += 256) {
       const int jj = j + lane * 4;
       float v[4];
+      val(jj, j1, v);
       float t = 0.f;
       int lm = -1;
       for (int e = 0; e < 4; ++e) {
-        v[e] = jj + e < j1 ? val(jj + e) : 0.f;
         t += v[e];
         if (v[e] > 0.f) lm = jj + e;
       }
@@ -172,21 +206,27 @@ __global__ __launch_bounds__(kDrawThreads) void sample_rows_kernel(const float* 
   const int b = blockIdx.x;
   const float* row = logits + static_cast<size_t>(b) * row_stride;
   const float inv_t = prm->inv_t;
-  float m, s;
-  row_stats(row, V, inv_t, red, m, s);
+  const bool vec = row_is_vec(row);
+  const float m = row_max(row, V, red);
   const int idx = (idx_base ? idx_base[b] : 0) + idx_off;
   const float u = uniform24(prm->seed, b, idx, purpose);
-  const int tok = block_draw([&](int j) { return expf((row[j] - m) * inv_t); }, V, u, red, &res);
+  const int tok = block_draw(
+      [&](int jj, int end, float (&v)[4]) {
+        float l[4];
+        load_group(row, jj, end, vec, l);
+        for (int e = 0; e < 4; ++e) v[e] = expf((l[e] - m) * inv_t);
+      },
+      V, u, red, &res);
   if (threadIdx.x == 0) out[static_cast<size_t>(b) * out_stride + out_off] = tok;
 }
 
 // (max, sum) of the k draft rows and the k + 1 verification rows of every sequence:
 // stats[b][r][2], r < kmax: draft row r; r >= kmax: verification row r - kmax.
-__global__ __launch_bounds__(256) void softmax_stats_kernel(const float* __restrict__ logits_d,
+__global__ __launch_bounds__(kDrawThreads) void softmax_stats_kernel(const float* __restrict__ logits_d,
                                                             const float* __restrict__ logits_v, int V, int k, int kmax,
                                                             const SamplingParams* __restrict__ prm,
                                                             float* __restrict__ stats) {
-  __shared__ float red[4];
+  __shared__ float red[kDrawWaves];
   const int r = blockIdx.x, b = blockIdx.y;
   const float* row;
   int slot;
@@ -239,11 +279,25 @@ __global__ __launch_bounds__(kDrawThreads) void spec_targets_kernel(const float*
   if (n < k) {
     const float* ls = rows_d + static_cast<size_t>(n) * V;
     const float ms = st[2 * n], rss = 1.0f / st[2 * n + 1];
-    tok = block_draw([&](int j) { return fmaxf(0.f, prob(lh[j], mh, inv_t, rsh) - prob(ls[j], ms, inv_t, rss)); }, V, u,
-                     red, &res);
+    const bool vec = row_is_vec(lh) && row_is_vec(ls);
+    tok = block_draw(
+        [&](int jj, int end, float (&v)[4]) {
+          float a[4], c[4];
+          load_group(lh, jj, end, vec, a);
+          load_group(ls, jj, end, vec, c);
+          for (int e = 0; e < 4; ++e) v[e] = fmaxf(0.f, prob(a[e], mh, inv_t, rsh) - prob(c[e], ms, inv_t, rss));
+        },
+        V, u, red, &res);
     if (tok == d[n]) tok = tok + 1 < V ? tok + 1 : 0;   // only if rounding left the residual without mass
   } else {
-    tok = block_draw([&](int j) { return expf((lh[j] - mh) * inv_t); }, V, u, red, &res);
+    const bool vec = row_is_vec(lh);
+    tok = block_draw(
+        [&](int jj, int end, float (&v)[4]) {
+          float l[4];
+          load_group(lh, jj, end, vec, l);
+          for (int e = 0; e < 4; ++e) v[e] = expf((l[e] - mh) * inv_t);
+        },
+        V, u, red, &res);
   }
   int* g = targets + static_cast<size_t>(b) * (kmax + 1);
   for (int i = threadIdx.x; i <= k; i += blockDim.x) g[i] = i < n ? d[i] : (i == n ? tok : -1);
@@ -262,7 +316,7 @@ hipError_t launch_sample_rows(const float* logits, size_t row_stride, int V, int
 hipError_t launch_spec_targets(const float* logits_d, const float* logits_v, int V, int B, int k, int kmax,
                                const SamplingParams* prm, float* stats, const int* drafts, const int* committed,
                                int* targets, hipStream_t s) {
-  hipLaunchKernelGGL(softmax_stats_kernel, dim3(2 * k + 1, B), dim3(256), 0, s, logits_d, logits_v, V, k, kmax, prm, stats);
+  hipLaunchKernelGGL(softmax_stats_kernel, dim3(2 * k + 1, B), dim3(kDrawThreads), 0, s, logits_d, logits_v, V, k, kmax, prm, stats);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   hipLaunchKernelGGL(spec_targets_kernel, dim3(B), dim3(kDrawThreads), 0, s, logits_d, logits_v, V, k, kmax, prm, stats,

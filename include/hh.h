@@ -146,6 +146,28 @@ HH_API hh_status hh_prefill(hh_ctx* ctx, const int32_t* tokens, int32_t row_stri
  * HH_EINVAL for a negative or non-finite temperature. */
 HH_API hh_status hh_set_sampling(hh_ctx* ctx, float temperature, uint64_t seed, void* stream);
 
+/* The two steps of the temperature > 0 token choice on caller-provided logits, without a
+ * context (the same kernels hh_draft and hh_verify launch after hh_set_sampling; Eq. 6).  All
+ * pointers DEVICE, float32 logits, nothing is kept.  HH_EINVAL for NULL or out-of-range
+ * arguments or a temperature that is not finite and > 0; HH_EDEVICE if a launch fails.
+ *
+ * hh_draw_tokens: out[r] = a draw from softmax(logits[r * row_stride ..][0..vocab) / temperature)
+ * with the uniform of (seed, sequence r, position (positions ? positions[r] : 0) + position_offset,
+ * purpose): the smallest index whose cumulative mass exceeds u times the total.
+ *
+ * hh_accept_tokens: for every sequence b, the rejection test over drafts[b][0..k) with
+ * draft_logits [batch][k][vocab] and verify_logits [batch][k+1][vocab] and the token emitted after
+ * the n kept drafts; positions[b] is the stream position of the first draft (uniforms: purpose 1 at
+ * positions[b] + i for test i, purpose 2 at positions[b] + n for the emitted token).  Writes
+ * targets [batch][k+1]: drafts[b][i] for i < n, the emitted token at n, -1 behind it.
+ * scratch: batch * (2k+1) * 2 floats. */
+HH_API hh_status hh_draw_tokens(const float* logits, int64_t row_stride, int32_t vocab, int32_t rows, float temperature,
+                                uint64_t seed, const int32_t* positions, int32_t position_offset, int32_t purpose,
+                                int32_t* out, void* stream);
+HH_API hh_status hh_accept_tokens(const float* draft_logits, const float* verify_logits, int32_t vocab, int32_t batch,
+                                  int32_t k, const int32_t* drafts, const int32_t* positions, float temperature,
+                                  uint64_t seed, float* scratch, int32_t* targets, void* stream);
+
 /* Draft phase (Section 3.3 / Eq. 4): k autoregressive greedy steps of the
  * SSM-only subgraph per sequence, starting from the committed recurrent state
  * on a scratch copy; never touches the KV cache.  0 <= k <= max_draft; k = 0

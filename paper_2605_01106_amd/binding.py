@@ -65,6 +65,10 @@ EXPORTS = {
     "hh_destroy": (C.c_int, [_ctx_p]),
     "hh_prefill": (C.c_int, [_ctx_p, C.c_void_p, C.c_int32, _i32p, C.c_int32, C.c_int32, C.c_void_p]),
     "hh_set_sampling": (C.c_int, [_ctx_p, C.c_float, C.c_uint64, C.c_void_p]),
+    "hh_draw_tokens": (C.c_int, [C.c_void_p, C.c_int64, C.c_int32, C.c_int32, C.c_float, C.c_uint64, C.c_void_p,
+                                 C.c_int32, C.c_int32, C.c_void_p, C.c_void_p]),
+    "hh_accept_tokens": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p,
+                                   C.c_float, C.c_uint64, C.c_void_p, C.c_void_p, C.c_void_p]),
     "hh_draft": (C.c_int, [_ctx_p, C.c_int32, C.c_void_p]),
     "hh_set_drafts": (C.c_int, [_ctx_p, C.c_void_p, C.c_void_p]),
     "hh_verify": (C.c_int, [_ctx_p, C.c_void_p]),
@@ -124,6 +128,38 @@ def _stream_ptr(stream) -> Optional[int]:
     if stream is None:
         stream = torch.cuda.current_stream()
     return C.c_void_p(getattr(stream, "cuda_stream", stream))
+
+
+def hh_draw_tokens(logits, temperature: float, seed: int, positions=None, position_offset: int = 0, purpose: int = 2,
+                   stream=None):
+    """logits: float32 device tensor [rows][vocab] (last dimension contiguous).  Returns int32 [rows]."""
+    assert logits.dtype == torch.float32 and logits.dim() == 2 and logits.stride(1) == 1
+    rows, vocab = logits.shape
+    out = torch.empty(rows, dtype=torch.int32, device=logits.device)
+    pos = None if positions is None else C.c_void_p(positions.data_ptr())
+    _check(lib.hh_draw_tokens(C.c_void_p(logits.data_ptr()), logits.stride(0), vocab, rows, C.c_float(temperature),
+                              C.c_uint64(seed), pos, position_offset, purpose, C.c_void_p(out.data_ptr()),
+                              _stream_ptr(stream)))
+    return out
+
+
+def hh_accept_tokens(draft_logits, verify_logits, drafts, positions, temperature: float, seed: int, stream=None):
+    """draft_logits [batch][k][vocab], verify_logits [batch][k+1][vocab] float32, drafts int32 [batch][k],
+    positions int32 [batch], all contiguous device tensors.  Returns the targets rows, int32 [batch][k+1]."""
+    batch, k1, vocab = verify_logits.shape
+    k = k1 - 1
+    assert verify_logits.is_contiguous() and verify_logits.dtype == torch.float32 and positions.dtype == torch.int32
+    if k > 0:
+        assert draft_logits.shape == (batch, k, vocab) and draft_logits.is_contiguous() and drafts.is_contiguous()
+        assert draft_logits.dtype == torch.float32 and drafts.dtype == torch.int32 and drafts.shape == (batch, k)
+    scratch = torch.empty(batch * (2 * k + 1) * 2, dtype=torch.float32, device=verify_logits.device)
+    targets = torch.empty((batch, k + 1), dtype=torch.int32, device=verify_logits.device)
+    dl = None if k == 0 else C.c_void_p(draft_logits.data_ptr())
+    dr = None if k == 0 else C.c_void_p(drafts.data_ptr())
+    _check(lib.hh_accept_tokens(dl, C.c_void_p(verify_logits.data_ptr()), vocab, batch, k, dr,
+                                C.c_void_p(positions.data_ptr()), C.c_float(temperature), C.c_uint64(seed),
+                                C.c_void_p(scratch.data_ptr()), C.c_void_p(targets.data_ptr()), _stream_ptr(stream)))
+    return targets
 
 
 def upload_weights(weights: W.Weights, device="cuda:0"):

@@ -632,7 +632,7 @@ hh_status hh_prefill(hh_ctx* x, const int32_t* tokens, int32_t row_stride, const
   hh_status st = run_head(x, x->lasth, B, 1, x->logits_p, d.V, x->first_tok, 1, 0, s);
   if (st != HH_OK) return st;
   if (x->temperature > 0.f)
-    HH_HIP(launch_sample_rows(x->logits_p, d.V, d.V, B, x->sampling, nullptr, 0, 2, x->first_tok, 1, 0, s));
+    HH_HIP(launch_sample_rows(x->logits_p, d.V, d.V, B, x->sampling, SamplingParams{}, nullptr, 0, 2, x->first_tok, 1, 0, s));
   HH_HIP(launch_prefill_finish(x->first_tok, x->pending, x->out_tok, d.Gmax, x->committed, x->last_n, B, s));
   x->B = B; x->G = max_new; x->k = 0; x->len_upper = maxlen;
   x->phase = PH_READY;
@@ -655,6 +655,40 @@ hh_status hh_set_sampling(hh_ctx* x, float temperature, uint64_t seed, void* str
   return HH_OK;
 }
 
+static bool sampling_value(float temperature, uint64_t seed, SamplingParams& p) {
+  if (!(temperature > 0.f) || !(temperature < 1e30f)) return false;
+  p.inv_t = 1.0f / temperature; p.pad = 0; p.seed = seed;
+  return true;
+}
+
+hh_status hh_draw_tokens(const float* logits, int64_t row_stride, int32_t vocab, int32_t rows, float temperature,
+                         uint64_t seed, const int32_t* positions, int32_t position_offset, int32_t purpose, int32_t* out,
+                         void* stream) {
+  SamplingParams p{};
+  if (!logits || !out || vocab < 1 || rows < 0 || row_stride < vocab || purpose < 0 || purpose > 3 || position_offset < 0 ||
+      !sampling_value(temperature, seed, p))
+    return HH_EINVAL;
+  if (rows == 0) return HH_OK;
+  if (launch_sample_rows(logits, (size_t)row_stride, vocab, rows, nullptr, p, positions, position_offset, purpose, out, 1, 0,
+                         static_cast<hipStream_t>(stream)) != hipSuccess)
+    return HH_EDEVICE;
+  return HH_OK;
+}
+
+hh_status hh_accept_tokens(const float* draft_logits, const float* verify_logits, int32_t vocab, int32_t batch, int32_t k,
+                           const int32_t* drafts, const int32_t* positions, float temperature, uint64_t seed,
+                           float* scratch, int32_t* targets, void* stream) {
+  SamplingParams p{};
+  if (!verify_logits || !positions || !scratch || !targets || vocab < 1 || batch < 0 || k < 0 ||
+      (k > 0 && (!draft_logits || !drafts)) || !sampling_value(temperature, seed, p))
+    return HH_EINVAL;
+  if (batch == 0) return HH_OK;
+  if (launch_spec_targets(draft_logits, verify_logits, vocab, batch, k, k, nullptr, p, scratch, drafts, positions, targets,
+                          static_cast<hipStream_t>(stream)) != hipSuccess)
+    return HH_EDEVICE;
+  return HH_OK;
+}
+
 hh_status hh_draft(hh_ctx* x, int32_t k, void* stream) {
   if (!x) return HH_EINVAL;
   if (x->phase != PH_READY) return fail(x, HH_ESTATE, "hh_draft: needs a prefilled context with no round in flight");
@@ -673,8 +707,8 @@ hh_status hh_draft(hh_ctx* x, int32_t k, void* stream) {
       st = run_head(x, x->h, B, 1, x->logits_d + (size_t)i * d.V, d.Kmax * d.V, x->drafts, d.Kmax, i, s);
       if (st != HH_OK) return st;
       if (stochastic)
-        HH_HIP(launch_sample_rows(x->logits_d + (size_t)i * d.V, (size_t)d.Kmax * d.V, d.V, B, x->sampling, x->committed,
-                                  i, 0, x->drafts, d.Kmax, i, s));
+        HH_HIP(launch_sample_rows(x->logits_d + (size_t)i * d.V, (size_t)d.Kmax * d.V, d.V, B, x->sampling, SamplingParams{},
+                                  x->committed, i, 0, x->drafts, d.Kmax, i, s));
     }
     return HH_OK;
   };
@@ -717,7 +751,7 @@ hh_status hh_verify(hh_ctx* x, void* stream) {
     st = run_head(x, x->h, B * T, T, x->logits_v, d.V, x->targets, d.Kmax + 1, 0, s);
     if (st != HH_OK) return st;
     if (stochastic)
-      HH_HIP(launch_spec_targets(x->logits_d, x->logits_v, d.V, B, x->k, d.Kmax, x->sampling, x->softmax_stats, x->drafts,
+      HH_HIP(launch_spec_targets(x->logits_d, x->logits_v, d.V, B, x->k, d.Kmax, x->sampling, SamplingParams{}, x->softmax_stats, x->drafts,
                                  x->committed, x->targets, s));
     return HH_OK;
   };

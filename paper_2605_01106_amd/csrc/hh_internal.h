@@ -137,14 +137,15 @@ hipError_t launch_prefill_finish(const int* first_tok, int* pending, int* out_to
 // ---- token choice at temperature > 0 (rejection test of the round and its draws)
 struct SamplingParams { float inv_t; uint32_t pad; uint64_t seed; };   // lives in device memory
 // one row per sequence b at logits + b * row_stride -> out[b * out_stride + out_off];
-// stream position of the drawn token: (idx_base ? idx_base[b] : 0) + idx_off
+// stream position of the drawn token: (idx_base ? idx_base[b] : 0) + idx_off.
+// Parameters: *prm (device memory) when prm != nullptr, else prm_val.
 hipError_t launch_sample_rows(const float* logits, size_t row_stride, int V, int B, const SamplingParams* prm,
-                              const int* idx_base, int idx_off, int purpose, int* out, int out_stride, int out_off,
-                              hipStream_t s);
+                              SamplingParams prm_val, const int* idx_base, int idx_off, int purpose, int* out,
+                              int out_stride, int out_off, hipStream_t s);
 // logits_d [B][kmax][V], logits_v [B][k+1][V], stats: scratch of B * (2 * kmax + 1) * 2 floats
 hipError_t launch_spec_targets(const float* logits_d, const float* logits_v, int V, int B, int k, int kmax,
-                               const SamplingParams* prm, float* stats, const int* drafts, const int* committed,
-                               int* targets, hipStream_t s);
+                               const SamplingParams* prm, SamplingParams prm_val, float* stats, const int* drafts,
+                               const int* committed, int* targets, hipStream_t s);
 hipError_t launch_fill_i32(int* p, int v, size_t n, hipStream_t s);
 hipError_t launch_fill_f32(float* p, float v, size_t n, hipStream_t s);
 hipError_t launch_export_state(const Dims& d, const LayerDev* layer, const int* kv_len, int B, float* conv_out,

@@ -197,7 +197,8 @@ __device__ int block_draw(F val, int V, float u, float* red, int* res) {
 
 // One row per workgroup: token drawn from softmax(row / T).
 __global__ __launch_bounds__(kDrawThreads) void sample_rows_kernel(const float* __restrict__ logits, size_t row_stride, int V,
-                                                                    const SamplingParams* __restrict__ prm,
+                                                                    const SamplingParams* __restrict__ prm_dev,
+                                                                    const SamplingParams prm_val,
                                                                     const int* __restrict__ idx_base, int idx_off,
                                                                     int purpose, int* __restrict__ out, int out_stride,
                                                                     int out_off) {
@@ -205,11 +206,12 @@ __global__ __launch_bounds__(kDrawThreads) void sample_rows_kernel(const float* 
   __shared__ int res;
   const int b = blockIdx.x;
   const float* row = logits + static_cast<size_t>(b) * row_stride;
-  const float inv_t = prm->inv_t;
+  const SamplingParams prm = prm_dev ? *prm_dev : prm_val;
+  const float inv_t = prm.inv_t;
   const bool vec = row_is_vec(row);
   const float m = row_max(row, V, red);
   const int idx = (idx_base ? idx_base[b] : 0) + idx_off;
-  const float u = uniform24(prm->seed, b, idx, purpose);
+  const float u = uniform24(prm.seed, b, idx, purpose);
   const int tok = block_draw(
       [&](int jj, int end, float (&v)[4]) {
         float l[4];
@@ -224,8 +226,8 @@ __global__ __launch_bounds__(kDrawThreads) void sample_rows_kernel(const float* 
 // stats[b][r][2], r < kmax: draft row r; r >= kmax: verification row r - kmax.
 __global__ __launch_bounds__(kDrawThreads) void softmax_stats_kernel(const float* __restrict__ logits_d,
                                                             const float* __restrict__ logits_v, int V, int k, int kmax,
-                                                            const SamplingParams* __restrict__ prm,
-                                                            float* __restrict__ stats) {
+                                                            const SamplingParams* __restrict__ prm_dev,
+                                                            const SamplingParams prm_val, float* __restrict__ stats) {
   __shared__ float red[kDrawWaves];
   const int r = blockIdx.x, b = blockIdx.y;
   const float* row;
@@ -233,7 +235,7 @@ __global__ __launch_bounds__(kDrawThreads) void softmax_stats_kernel(const float
   if (r < k) { row = logits_d + (static_cast<size_t>(b) * kmax + r) * V; slot = r; }
   else { row = logits_v + (static_cast<size_t>(b) * (k + 1) + (r - k)) * V; slot = kmax + (r - k); }
   float m, s;
-  row_stats(row, V, prm->inv_t, red, m, s);
+  row_stats(row, V, prm_dev ? prm_dev->inv_t : prm_val.inv_t, red, m, s);
   if (threadIdx.x == 0) {
     float* st = stats + (static_cast<size_t>(b) * (2 * kmax + 1) + slot) * 2;
     st[0] = m; st[1] = s;
@@ -243,7 +245,8 @@ __global__ __launch_bounds__(kDrawThreads) void softmax_stats_kernel(const float
 // The round's acceptance for one sequence per workgroup (Eq. 6) and its targets row.
 __global__ __launch_bounds__(kDrawThreads) void spec_targets_kernel(const float* __restrict__ logits_d,
                                                                      const float* __restrict__ logits_v, int V, int k,
-                                                                     int kmax, const SamplingParams* __restrict__ prm,
+                                                                     int kmax, const SamplingParams* __restrict__ prm_dev,
+                                                                     const SamplingParams prm_val,
                                                                      const float* __restrict__ stats,
                                                                      const int* __restrict__ drafts,
                                                                      const int* __restrict__ committed,
@@ -252,8 +255,9 @@ __global__ __launch_bounds__(kDrawThreads) void spec_targets_kernel(const float*
   __shared__ int res;
   __shared__ int n_sh;
   const int b = blockIdx.x;
-  const float inv_t = prm->inv_t;
-  const uint64_t seed = prm->seed;
+  const SamplingParams prm = prm_dev ? *prm_dev : prm_val;
+  const float inv_t = prm.inv_t;
+  const uint64_t seed = prm.seed;
   const int base = committed[b];
   const int* d = drafts + static_cast<size_t>(b) * kmax;
   const float* st = stats + static_cast<size_t>(b) * (2 * kmax + 1) * 2;
@@ -306,21 +310,22 @@ __global__ __launch_bounds__(kDrawThreads) void spec_targets_kernel(const float*
 }  // namespace
 
 hipError_t launch_sample_rows(const float* logits, size_t row_stride, int V, int B, const SamplingParams* prm,
-                              const int* idx_base, int idx_off, int purpose, int* out, int out_stride, int out_off,
-                              hipStream_t s) {
-  hipLaunchKernelGGL(sample_rows_kernel, dim3(B), dim3(kDrawThreads), 0, s, logits, row_stride, V, prm, idx_base, idx_off,
-                     purpose, out, out_stride, out_off);
+                              SamplingParams prm_val, const int* idx_base, int idx_off, int purpose, int* out,
+                              int out_stride, int out_off, hipStream_t s) {
+  hipLaunchKernelGGL(sample_rows_kernel, dim3(B), dim3(kDrawThreads), 0, s, logits, row_stride, V, prm, prm_val, idx_base,
+                     idx_off, purpose, out, out_stride, out_off);
   return hipGetLastError();
 }
 
 hipError_t launch_spec_targets(const float* logits_d, const float* logits_v, int V, int B, int k, int kmax,
-                               const SamplingParams* prm, float* stats, const int* drafts, const int* committed,
-                               int* targets, hipStream_t s) {
-  hipLaunchKernelGGL(softmax_stats_kernel, dim3(2 * k + 1, B), dim3(kDrawThreads), 0, s, logits_d, logits_v, V, k, kmax, prm, stats);
+                               const SamplingParams* prm, SamplingParams prm_val, float* stats, const int* drafts,
+                               const int* committed, int* targets, hipStream_t s) {
+  hipLaunchKernelGGL(softmax_stats_kernel, dim3(2 * k + 1, B), dim3(kDrawThreads), 0, s, logits_d, logits_v, V, k, kmax, prm,
+                     prm_val, stats);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  hipLaunchKernelGGL(spec_targets_kernel, dim3(B), dim3(kDrawThreads), 0, s, logits_d, logits_v, V, k, kmax, prm, stats,
-                     drafts, committed, targets);
+  hipLaunchKernelGGL(spec_targets_kernel, dim3(B), dim3(kDrawThreads), 0, s, logits_d, logits_v, V, k, kmax, prm, prm_val,
+                     stats, drafts, committed, targets);
   return hipGetLastError();
 }
 

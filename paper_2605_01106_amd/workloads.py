@@ -289,6 +289,17 @@ def make_forced_pattern(rounds: int, batch: int, k: int, p: float, seed: int) ->
     return n.astype(np.int32)
 
 
+def make_logit_rows(batch: int, k: int, vocab: int, seed: int, spread: float = 3.0, draft_noise: float = 0.7):
+    """Synthetic logits of one round for the token-choice kernels alone: verification rows
+    [batch][k+1][vocab] ~ N(0, spread^2) (a few tokens carry most of the mass after the softmax,
+    a long tail carries the rest, as for a language model's head) and draft rows [batch][k][vocab]
+    = the matching verification rows + N(0, draft_noise^2) (a draft that mostly agrees).  float32."""
+    g = _rng(seed, "logit-rows")
+    verify = (g.standard_normal((batch, k + 1, vocab), dtype=np.float32) * np.float32(spread))
+    draft = verify[:, :k] + g.standard_normal((batch, k, vocab), dtype=np.float32) * np.float32(draft_noise)
+    return np.ascontiguousarray(draft, np.float32), np.ascontiguousarray(verify, np.float32)
+
+
 def make_random_drafts(vocab: int, rounds: int, batch: int, k: int, seed: int) -> np.ndarray:
     """Arbitrary draft tokens, for tests that the committed stream does not depend
     on the draft source."""

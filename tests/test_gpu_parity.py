@@ -116,26 +116,31 @@ def _say_t(tag):
     return f
 
 
-@pytest.mark.parametrize("dtype,T,seed", [(W.F32, 0.6, 59), (W.F32, 0.3, 10), (W.BF16, 0.6, 21), (W.BF16, 0.3, 32)])
-def test_stochastic_acceptance_lockstep(B, dtype, T, seed):
+@pytest.mark.parametrize("dtype,runs", [(W.F32, [(0.6, 59), (0.3, 10)]), (W.BF16, [(0.6, 21), (0.3, 32)])])
+def test_stochastic_acceptance_lockstep(B, dtype, runs):
     """Temperature > 0 (Eq. 6): first token, draft draws, rejection tests, correction and bonus
     tokens equal the oracle's, decision by decision, with the same counter-based uniforms; the
     targets row has the oracle's form, and state, window and cache follow the committed stream.
     Odd vocabulary (203: ragged tail of the drawing kernel's 4-element groups).  Seeds audited:
     no decision within 1e-4 of flipping (a logit error e moves a CDF edge by at most e / T times the
     mass it touches; the measured logit errors are 1e-6 for float32 and, on single entries, up to
-    1e-3 for bf16 storage)."""
+    1e-3 for bf16 storage).  One context runs temperature 0.6, then greedy, then temperature 0.3
+    with another seed: the captured launch sequences must pick up the new parameters."""
     cfg = W.scaled_config("lively", n_layers=3, d_model=72, vocab=203, m_heads=3, m_head_dim=40, d_state=16,
                           n_q_heads=6, n_kv_heads=2, head_dim=24, d_ff=104, w_dtype=dtype)
     wts = W.make_lively_weights(cfg, 7)
     lens = [37, 5, 70, 18]
     prompts = W.make_prompts(cfg.vocab, 4, lens, 3)
     ctx = _ctx(B, wts, 4, 160, 4, 12, kv_page_tokens=16, prefill_chunk=16)
-    w = run_lockstep(ctx, wts, prompts, lens, 12, 3, engine="pass", temperature=T, sample_seed=seed, min_margin=1e-4,
-                     report=_say_t(f"stochastic-{dtype}-T{T}"))
-    assert 0.0 < w["mean_n"] < 3.0            # both kept and rejected drafts occurred
-    # back to temperature 0 on the same context: the greedy stream again
-    run_lockstep(ctx, wts, prompts, lens, 12, 3, engine="pass", report=_say("greedy-after-stochastic"))
+    streams = []
+    for i, (T, seed) in enumerate(runs):
+        w = run_lockstep(ctx, wts, prompts, lens, 12, 3, engine="pass", temperature=T, sample_seed=seed,
+                         min_margin=1e-4, report=_say_t(f"stochastic-{dtype}-T{T}"))
+        assert 0.0 < w["mean_n"] < 3.0            # both kept and rejected drafts occurred
+        streams.append(w["tokens"])
+        if i == 0:   # back to temperature 0 on the same context: the greedy stream again
+            run_lockstep(ctx, wts, prompts, lens, 12, 3, engine="pass", report=_say("greedy-after-stochastic"))
+    assert streams[0] != streams[1]
 
 
 def test_stochastic_wide_vocabulary_and_plain_sampling(B):

@@ -124,6 +124,8 @@ def main():
                     help="temperature of the stochastic-acceptance leg (the paper's second setting); 0 skips the leg")
     ap.add_argument("--counters", action="store_true",
                     help="short eager run for rocprofv3 --pmc: prefill, a few rounds, four 256 MiB copies for calibration")
+    ap.add_argument("--prefill-chunk", type=int, default=0,
+                    help="prompt positions per sequence per prefill pass (0: the library's default)")
     ap.add_argument("--prompt-len", type=int, default=None,
                     help="override the workload's prompt length (a shorter stand-in; named in config.workload)")
     args = ap.parse_args()
@@ -159,7 +161,7 @@ def main():
     stream = torch.cuda.Stream()          # HIP graphs cannot be captured on the default stream
     torch.cuda.set_stream(stream)
     say(f"weights in {t_gen:.1f} s; creating the context")
-    ctx = B.Context(weights, Bn, max_seq, k, G, use_graphs=args.graphs)
+    ctx = B.Context(weights, Bn, max_seq, k, G, use_graphs=args.graphs, prefill_chunk=args.prefill_chunk)
     torch.cuda.synchronize()
     say("prefill")
     t0 = time.perf_counter()

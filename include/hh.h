@@ -72,7 +72,8 @@ typedef struct hh_cfg {
   int32_t max_draft;                    /* largest k */
   int32_t max_new_tokens;               /* largest generation budget per sequence */
   int32_t kv_page_tokens;               /* tokens per KV page: 16, 32, 64, 128 or 256; 0 = default */
-  int32_t prefill_chunk;                /* prompt positions per sequence per prefill pass; 0 = default */
+  int32_t prefill_chunk;                /* prompt positions per sequence per prefill pass, 1..1024; 0 = default:
+                                           4096 / max_batch rounded down to a multiple of 64, within 64..512 */
   int32_t keep_logits;                  /* 1: materialise float32 logits of draft and verify rows for hh_get_logits */
   int32_t use_graphs;                   /* 1: replay draft/verify/commit as HIP graphs after their first call */
   void* workspace;                      /* DEVICE, 256-byte aligned */

@@ -93,6 +93,16 @@ struct hh_ctx {
 
 namespace {
 
+// Prompt positions per sequence per prefill pass.  Default: about 4096 activation rows per pass
+// over the whole batch (enough rows for the tiled matrix-core GEMM and few passes over the
+// weights), in multiples of 64, between 64 and 512.
+int prefill_chunk_of(const hh_cfg& c) {
+  if (c.prefill_chunk != 0) return c.prefill_chunk;
+  const int rows = 4096 / (c.max_batch > 0 ? c.max_batch : 1);
+  const int chunk = rows / 64 * 64;
+  return chunk < 64 ? 64 : (chunk > 512 ? 512 : chunk);
+}
+
 bool derive_dims(const hh_cfg& c, Dims& d, std::string& why) {
   auto bad = [&](const char* m) { why = m; return false; };
   if (c.struct_size != sizeof(hh_cfg)) return bad("struct_size does not match this library's hh_cfg");
@@ -120,7 +130,7 @@ bool derive_dims(const hh_cfg& c, Dims& d, std::string& why) {
   d.page_tokens = c.kv_page_tokens == 0 ? 64 : c.kv_page_tokens;
   if (d.page_tokens != 16 && d.page_tokens != 32 && d.page_tokens != 64 && d.page_tokens != 128 && d.page_tokens != 256)
     return bad("kv_page_tokens must be 16, 32, 64, 128 or 256");
-  int chunk = c.prefill_chunk == 0 ? 64 : c.prefill_chunk;
+  const int chunk = prefill_chunk_of(c);
   if (chunk < 1 || chunk > 1024) return bad("prefill_chunk must be in 1..1024");
   d.Kmax = c.max_draft; d.Bmax = c.max_batch; d.Gmax = c.max_new_tokens; d.max_seq = c.max_seq_len;
   d.Tmax = d.Kmax + 1 > chunk ? d.Kmax + 1 : chunk;
@@ -148,7 +158,7 @@ size_t carve(hh_ctx* x, char* base) {
   x->tok = c.take<int>(Mmax); x->pos0 = c.take<int>(B);
   x->out_tok = c.take<int>(B * d.Gmax);
   x->page_table = c.take<int>(B * d.pages_per_seq);
-  const int chunk = x->cfg.prefill_chunk == 0 ? 64 : x->cfg.prefill_chunk;
+  const int chunk = prefill_chunk_of(x->cfg);
   x->max_passes = (d.max_seq + chunk - 1) / chunk;
   x->plan_ntok = c.take<int>((size_t)x->max_passes * B);
   x->plan_last = c.take<int>((size_t)x->max_passes * B);
@@ -578,7 +588,7 @@ hh_status hh_prefill(hh_ctx* x, const int32_t* tokens, int32_t row_stride, const
   }
   hipStream_t s = static_cast<hipStream_t>(stream);
   const int B = batch;
-  const int chunk = x->cfg.prefill_chunk == 0 ? 64 : x->cfg.prefill_chunk;
+  const int chunk = prefill_chunk_of(x->cfg);
   const int n_pass = (maxlen + chunk - 1) / chunk;
   x->prof_phase = HH_PHASE_PREFILL;
 

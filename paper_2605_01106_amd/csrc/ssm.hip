@@ -189,18 +189,33 @@ __global__ __launch_bounds__(kRows * kSub) void ssm_kernel(const Dims d, const S
 // flight together, taps and bias loaded once - instead of one scalar item per channel and position,
 // and the gate inputs z are staged with x, so the recurrence loop touches no global memory but
 // its output.  (Prefill chunks: the scalar staging made the pass latency-bound.)
+// Threads of the staging role of ssm_chunk_kernel: one per group of 4 conv channels (B | C | the
+// workgroup's x rows) plus one per staged position (step and decay), rounded up to whole wavefronts.
 template <int NV, int kRows>
-__global__ __launch_bounds__(kRows * kSub) void ssm_chunk_kernel(const Dims d, const SsmArgs a) {
+constexpr int chunk_stage_threads() { return ((2 * NV * kSub / 4 + kRows / 4 + kTS + 63) / 64) * 64; }
+
+// PIPE: the staging role gets wavefronts of its own (behind the kRows * kSub recurrence threads) and
+// stages chunk c+1 into the other LDS buffer while the recurrence runs over chunk c, so the global
+// loads and the convolution of a chunk are off the recurrence's path: for small launches (one
+// sequence in prefill), where no other workgroup on the compute unit hides them.
+template <int NV, int kRows, bool PIPE>
+__global__ __launch_bounds__(kRows * kSub + (PIPE ? chunk_stage_threads<NV, kRows>() : 0)) void ssm_chunk_kernel(const Dims d, const SsmArgs a) {
   constexpr int N = NV * kSub;
   constexpr int NGBC = 2 * N / 4, NGX = kRows / 4, HP = kTS / 2;
-  static_assert(NGBC + NGX <= kRows * kSub, "one thread per channel group");
-  __shared__ __align__(16) float xs[kTS][kRows];
-  __shared__ __align__(16) float zs[kTS][kRows];
-  __shared__ __align__(16) float Bs[kTS][N];
-  __shared__ __align__(16) float Cs[kTS][N];
-  __shared__ float dts[kTS], as[kTS];
+  constexpr int NREC = kRows * kSub;                               // recurrence threads
+  constexpr int NSTG = PIPE ? chunk_stage_threads<NV, kRows>() : NREC;   // threads that can take the staging role
+  constexpr int NBUF = PIPE ? 2 : 1;
+  static_assert(NGBC + NGX + kTS <= NSTG, "one thread per channel group and per staged position");
+  __shared__ __align__(16) float xs[NBUF][kTS][kRows];
+  __shared__ __align__(16) float zs[NBUF][kTS][kRows];
+  __shared__ __align__(16) float Bs[NBUF][kTS][N];
+  __shared__ __align__(16) float Cs[NBUF][kTS][N];
+  __shared__ float dts[NBUF][kTS], as[NBUF][kTS];
 
-  const int tid = threadIdx.x, row = tid >> 3, sub = tid & 7;
+  const int tid = threadIdx.x, row = (tid >> 3) % kRows, sub = tid & 7;
+  const bool stager = !PIPE || tid >= NREC;
+  const bool worker = !PIPE || tid < NREC;
+  const int stid = PIPE ? tid - NREC : tid;                        // index within the staging role
   const int p0 = blockIdx.x * kRows, h = blockIdx.y;
   const int lz = blockIdx.z / a.B, b = blockIdx.z % a.B;
   const LayerDev& ly = a.layers != nullptr ? a.layers[a.layer0 + lz] : a.one;
@@ -211,7 +226,7 @@ __global__ __launch_bounds__(kRows * kSub) void ssm_chunk_kernel(const Dims d, c
   if (nt <= 0) return;
   const int pos0 = a.pos0[b];
   const int p = p0 + row;
-  const bool prow = p < d.P;
+  const bool prow = worker && p < d.P;
   const int rmask = d.ring_slots - 1;
   float* ring = ly.ring + (size_t)b * d.ring_slots * d.ring_w;
   const float* zx = a.zx != nullptr ? a.zx + (size_t)b * a.T * d.ldzx : nullptr;
@@ -240,18 +255,22 @@ __global__ __launch_bounds__(kRows * kSub) void ssm_chunk_kernel(const Dims d, c
   const float dtb = ly.dt_bias[h];
   const float negA = -expf(ly.a_log[h]);
   // this thread's channel group: B|C groups first, then the x rows of the workgroup
-  const bool is_x = tid >= NGBC;
-  const int xg = tid - NGBC;                                 // x group (is_x)
-  const bool active = tid < NGBC + NGX && (!is_x || p0 + 4 * xg < d.P);
-  const int c4 = is_x ? h * d.P + min(p0 + 4 * xg, d.P - 4) : d.d_inner + 4 * min(tid, NGBC - 1);
+  const bool conv_thread = stager && stid >= 0 && stid < NGBC + NGX;
+  const bool is_x = stid >= NGBC;
+  const int xg = stid - NGBC;                                // x group (is_x)
+  const bool active = conv_thread && (!is_x || p0 + 4 * xg < d.P);
+  const int c4 = is_x ? h * d.P + min(p0 + 4 * max(xg, 0), d.P - 4) : d.d_inner + 4 * min(max(stid, 0), NGBC - 1);
+  // the step-and-decay threads: the last kTS of the staging role
+  const int dt_jj = stid - (NSTG - kTS);
   float4 taps[4], bias;
 #pragma unroll
   for (int t = 0; t < 4; ++t) taps[t] = *reinterpret_cast<const float4*>(ly.conv_w + (size_t)(c4 + t) * 4);
   bias = *reinterpret_cast<const float4*>(ly.conv_b + c4);
 
-  for (int j0 = 0; j0 < nt; j0 += kTS) {
+  // conv inputs, gate inputs, step and decay of positions j0 .. j0 + kTS - 1 into LDS buffer `buf`
+  auto stage = [&](int j0, int buf) {
     const int tc = min(kTS, nt - j0);
-    if (tid < NGBC + NGX) {
+    if (conv_thread) {
 #pragma unroll
       for (int hp = 0; hp < 2; ++hp) {
         const int jb = j0 + hp * HP;                           // first position of the half chunk (relative)
@@ -287,11 +306,11 @@ __global__ __launch_bounds__(kRows * kSub) void ssm_chunk_kernel(const Dims d, c
           }
           const float4 ov = make_float4(o[0], o[1], o[2], o[3]);
           if (!is_x) {
-            if (tid < NGBC / 2) *reinterpret_cast<float4*>(&Bs[jj][4 * tid]) = ov;
-            else *reinterpret_cast<float4*>(&Cs[jj][4 * tid - N]) = ov;
+            if (stid < NGBC / 2) *reinterpret_cast<float4*>(&Bs[buf][jj][4 * stid]) = ov;
+            else *reinterpret_cast<float4*>(&Cs[buf][jj][4 * stid - N]) = ov;
           } else if (active) {
-            *reinterpret_cast<float4*>(&xs[jj][4 * xg]) = ov;
-            if (a.g != nullptr) *reinterpret_cast<float4*>(&zs[jj][4 * xg]) = z[u];
+            *reinterpret_cast<float4*>(&xs[buf][jj][4 * xg]) = ov;
+            if (a.g != nullptr) *reinterpret_cast<float4*>(&zs[buf][jj][4 * xg]) = z[u];
           }
           // keep the raw inputs of these positions for later windows and for rollback
           if (a.write_ring && zx != nullptr && active && (is_x || (h == 0 && blockIdx.x == 0)))
@@ -299,28 +318,30 @@ __global__ __launch_bounds__(kRows * kSub) void ssm_chunk_kernel(const Dims d, c
         }
       }
     }
-    if (tid >= kRows * kSub - kTS && tid - (kRows * kSub - kTS) < tc) {   // the last threads: step and decay of the head
-      const int jj = tid - (kRows * kSub - kTS);
-      const float dt = softplus_f(raw_row(pos0 + j0 + jj)[d.conv_dim + h] + dtb);
-      dts[jj] = dt;
-      as[jj] = expf(negA * dt);
+    if (stager && dt_jj >= 0 && dt_jj < tc) {   // step and decay of the head
+      const float dt = softplus_f(raw_row(pos0 + j0 + dt_jj)[d.conv_dim + h] + dtb);
+      dts[buf][dt_jj] = dt;
+      as[buf][dt_jj] = expf(negA * dt);
     }
-    if (a.write_ring && zx != nullptr && h == 0 && blockIdx.x == 0) {
-      for (int it = tid; it < tc * d.Hm; it += kRows * kSub) {
+    if (stager && a.write_ring && zx != nullptr && h == 0 && blockIdx.x == 0) {
+      for (int it = stid; it < tc * d.Hm; it += NSTG) {
         const int jj = it / d.Hm, hh = it - jj * d.Hm, pos = pos0 + j0 + jj;
         ring[(size_t)(pos & rmask) * d.ring_w + d.conv_dim + hh] = raw_row(pos)[d.conv_dim + hh];
       }
     }
-    __syncthreads();
-    // ---- recurrence over the staged positions
+  };
+
+  // recurrence over the staged positions of buffer `buf`
+  auto recur = [&](int j0, int buf) {
+    const int tc = min(kTS, nt - j0);
     for (int jj = 0; jj < tc; ++jj) {
-      const float xv = xs[jj][row];
-      const float coef = dts[jj] * xv, aj = as[jj];
+      const float xv = xs[buf][jj][row];
+      const float coef = dts[buf][jj] * xv, aj = as[buf][jj];
       float part = 0.f;
 #pragma unroll
       for (int i = 0; i < NV; i += 4) {
-        const float4 Bv = *reinterpret_cast<const float4*>(&Bs[jj][i * kSub + sub * 4]);
-        const float4 Cv = *reinterpret_cast<const float4*>(&Cs[jj][i * kSub + sub * 4]);
+        const float4 Bv = *reinterpret_cast<const float4*>(&Bs[buf][jj][i * kSub + sub * 4]);
+        const float4 Cv = *reinterpret_cast<const float4*>(&Cs[buf][jj][i * kSub + sub * 4]);
         S[i] = fmaf(aj, S[i], coef * Bv.x); part = fmaf(S[i], Cv.x, part);
         S[i + 1] = fmaf(aj, S[i + 1], coef * Bv.y); part = fmaf(S[i + 1], Cv.y, part);
         S[i + 2] = fmaf(aj, S[i + 2], coef * Bv.z); part = fmaf(S[i + 2], Cv.z, part);
@@ -330,9 +351,31 @@ __global__ __launch_bounds__(kRows * kSub) void ssm_chunk_kernel(const Dims d, c
       part += dpp_perm_f<0x4E>(part);    // lane ^ 2
       part += dpp_perm_f<0x141>(part);   // the other quad of the 8 lanes that share a row
       if (a.g != nullptr && sub == 0 && prow)
-        a.g[((size_t)b * a.T + j0 + jj) * d.d_inner + h * d.P + p] = (part + dskip * xv) * silu_f(zs[jj][row]);
+        a.g[((size_t)b * a.T + j0 + jj) * d.d_inner + h * d.P + p] = (part + dskip * xv) * silu_f(zs[buf][jj][row]);
     }
+  };
+
+  if (!PIPE) {
+    for (int j0 = 0; j0 < nt; j0 += kTS) {
+      stage(j0, 0);
+      __syncthreads();
+      recur(j0, 0);
+      __syncthreads();
+    }
+  } else {
+    if (stager) stage(0, 0);
     __syncthreads();
+    int buf = 0;
+    for (int j0 = 0; j0 < nt; j0 += kTS, buf ^= 1) {
+      // the other buffer was last read by the recurrence of the chunk before this one, which
+      // ended before the barrier that closed the previous iteration
+      if (stager) {
+        if (j0 + kTS < nt) stage(j0 + kTS, buf ^ 1);
+      } else {
+        recur(j0, buf);
+      }
+      __syncthreads();
+    }
   }
 
   if (a.state_out != 0 && prow) {
@@ -619,12 +662,24 @@ static hipError_t launch_ssm_rows(const Dims& d, const SsmArgs& a, hipStream_t s
                    d.conv_dim % 4 == 0 && nv % 4 == 0 && 2 * d.N / 4 + kRows / 4 <= kRows * kSub - kTS &&
                    (a.zx == nullptr || (reinterpret_cast<uintptr_t>(a.zx) & 15) == 0);
   if (vec) {
+    // few workgroups per compute unit and several chunks: staging on wavefronts of its own
+    static const int pipe_wg = getenv("HH_SSM_PIPEWG") ? atoi(getenv("HH_SSM_PIPEWG")) : 512;
+    const bool pipe = (long long)grid.x * grid.y * grid.z <= pipe_wg && a.T > kTS;
+#define HH_CHUNK(NV_)                                                                                          \
+  case NV_:                                                                                                    \
+    if (pipe)                                                                                                  \
+      hipLaunchKernelGGL((ssm_chunk_kernel<NV_, kRows, true>), grid,                                           \
+                         dim3(kRows * kSub + chunk_stage_threads<NV_, kRows>()), 0, s, d, a);                  \
+    else                                                                                                       \
+      hipLaunchKernelGGL((ssm_chunk_kernel<NV_, kRows, false>), grid, block, 0, s, d, a);                      \
+    return hipGetLastError();
     switch (nv) {
-      case 4: hipLaunchKernelGGL((ssm_chunk_kernel<4, kRows>), grid, block, 0, s, d, a); return hipGetLastError();
-      case 8: hipLaunchKernelGGL((ssm_chunk_kernel<8, kRows>), grid, block, 0, s, d, a); return hipGetLastError();
-      case 16: hipLaunchKernelGGL((ssm_chunk_kernel<16, kRows>), grid, block, 0, s, d, a); return hipGetLastError();
-      case 32: hipLaunchKernelGGL((ssm_chunk_kernel<32, kRows>), grid, block, 0, s, d, a); return hipGetLastError();
+      HH_CHUNK(4)
+      HH_CHUNK(8)
+      HH_CHUNK(16)
+      HH_CHUNK(32)
     }
+#undef HH_CHUNK
   }
   switch (d.N / kSub) {
     case 1: hipLaunchKernelGGL((ssm_kernel<1, kRows>), grid, block, 0, s, d, a); break;

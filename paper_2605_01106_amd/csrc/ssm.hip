@@ -189,10 +189,12 @@ __global__ __launch_bounds__(kRows * kSub) void ssm_kernel(const Dims d, const S
 // flight together, taps and bias loaded once - instead of one scalar item per channel and position,
 // and the gate inputs z are staged with x, so the recurrence loop touches no global memory but
 // its output.  (Prefill chunks: the scalar staging made the pass latency-bound.)
-// Threads of the staging role of ssm_chunk_kernel: one per group of 4 conv channels (B | C | the
-// workgroup's x rows) plus one per staged position (step and decay), rounded up to whole wavefronts.
+// Threads of the staging role of ssm_chunk_kernel when it has wavefronts of its own: two sets (one
+// per half chunk, so that the loads of both halves are in flight together) of one thread per group
+// of 4 conv channels (B | C | the workgroup's x rows), plus one per staged position (step and
+// decay), rounded up to whole wavefronts.
 template <int NV, int kRows>
-constexpr int chunk_stage_threads() { return ((2 * NV * kSub / 4 + kRows / 4 + kTS + 63) / 64) * 64; }
+constexpr int chunk_stage_threads() { return ((2 * (2 * NV * kSub / 4 + kRows / 4) + kTS + 63) / 64) * 64; }
 
 // PIPE: the staging role gets wavefronts of its own (behind the kRows * kSub recurrence threads) and
 // stages chunk c+1 into the other LDS buffer while the recurrence runs over chunk c, so the global
@@ -205,7 +207,8 @@ __global__ __launch_bounds__(kRows * kSub + (PIPE ? chunk_stage_threads<NV, kRow
   constexpr int NREC = kRows * kSub;                               // recurrence threads
   constexpr int NSTG = PIPE ? chunk_stage_threads<NV, kRows>() : NREC;   // threads that can take the staging role
   constexpr int NBUF = PIPE ? 2 : 1;
-  static_assert(NGBC + NGX + kTS <= NSTG, "one thread per channel group and per staged position");
+  constexpr int NSETS = PIPE ? 2 : 1;                              // conv thread sets (one half chunk each when 2)
+  static_assert(NSETS * (NGBC + NGX) + kTS <= NSTG, "one thread per channel group and per staged position");
   __shared__ __align__(16) float xs[NBUF][kTS][kRows];
   __shared__ __align__(16) float zs[NBUF][kTS][kRows];
   __shared__ __align__(16) float Bs[NBUF][kTS][N];
@@ -255,11 +258,13 @@ __global__ __launch_bounds__(kRows * kSub + (PIPE ? chunk_stage_threads<NV, kRow
   const float dtb = ly.dt_bias[h];
   const float negA = -expf(ly.a_log[h]);
   // this thread's channel group: B|C groups first, then the x rows of the workgroup
-  const bool conv_thread = stager && stid >= 0 && stid < NGBC + NGX;
-  const bool is_x = stid >= NGBC;
-  const int xg = stid - NGBC;                                // x group (is_x)
+  const bool conv_thread = stager && stid >= 0 && stid < NSETS * (NGBC + NGX);
+  const int cset = max(stid, 0) / (NGBC + NGX);              // which half chunk this thread stages (two sets)
+  const int cid = max(stid, 0) % (NGBC + NGX);               // channel group
+  const bool is_x = cid >= NGBC;
+  const int xg = cid - NGBC;                                 // x group (is_x)
   const bool active = conv_thread && (!is_x || p0 + 4 * xg < d.P);
-  const int c4 = is_x ? h * d.P + min(p0 + 4 * max(xg, 0), d.P - 4) : d.d_inner + 4 * min(max(stid, 0), NGBC - 1);
+  const int c4 = is_x ? h * d.P + min(p0 + 4 * xg, d.P - 4) : d.d_inner + 4 * cid;
   // the step-and-decay threads: the last kTS of the staging role
   const int dt_jj = stid - (NSTG - kTS);
   float4 taps[4], bias;
@@ -271,8 +276,7 @@ __global__ __launch_bounds__(kRows * kSub + (PIPE ? chunk_stage_threads<NV, kRow
   auto stage = [&](int j0, int buf) {
     const int tc = min(kTS, nt - j0);
     if (conv_thread) {
-#pragma unroll
-      for (int hp = 0; hp < 2; ++hp) {
+      for (int hp = (NSETS == 2 ? cset : 0); hp < (NSETS == 2 ? cset + 1 : 2); ++hp) {
         const int jb = j0 + hp * HP;                           // first position of the half chunk (relative)
         if (jb >= j0 + tc) break;
         // raw rows of positions jb-3 .. jb+HP-1 (clamped to the last valid one), z of jb .. jb+HP-1
@@ -306,8 +310,8 @@ __global__ __launch_bounds__(kRows * kSub + (PIPE ? chunk_stage_threads<NV, kRow
           }
           const float4 ov = make_float4(o[0], o[1], o[2], o[3]);
           if (!is_x) {
-            if (stid < NGBC / 2) *reinterpret_cast<float4*>(&Bs[buf][jj][4 * stid]) = ov;
-            else *reinterpret_cast<float4*>(&Cs[buf][jj][4 * stid - N]) = ov;
+            if (cid < NGBC / 2) *reinterpret_cast<float4*>(&Bs[buf][jj][4 * cid]) = ov;
+            else *reinterpret_cast<float4*>(&Cs[buf][jj][4 * cid - N]) = ov;
           } else if (active) {
             *reinterpret_cast<float4*>(&xs[buf][jj][4 * xg]) = ov;
             if (a.g != nullptr) *reinterpret_cast<float4*>(&zs[buf][jj][4 * xg]) = z[u];

@@ -189,12 +189,13 @@ __global__ __launch_bounds__(kRows * kSub) void ssm_kernel(const Dims d, const S
 // flight together, taps and bias loaded once - instead of one scalar item per channel and position,
 // and the gate inputs z are staged with x, so the recurrence loop touches no global memory but
 // its output.  (Prefill chunks: the scalar staging made the pass latency-bound.)
-// Threads of the staging role of ssm_chunk_kernel when it has wavefronts of its own: two sets (one
-// per half chunk, so that the loads of both halves are in flight together) of one thread per group
-// of 4 conv channels (B | C | the workgroup's x rows), plus one per staged position (step and
-// decay), rounded up to whole wavefronts.
+// Threads of the staging role of ssm_chunk_kernel when it has wavefronts of its own: kPipeSets sets
+// (one per part of a chunk, so that the loads of all parts are in flight together) of one thread
+// per group of 4 conv channels (B | C | the workgroup's x rows), plus one per staged position (step
+// and decay), rounded up to whole wavefronts.
+static constexpr int kPipeSets = 4;
 template <int NV, int kRows>
-constexpr int chunk_stage_threads() { return ((2 * (2 * NV * kSub / 4 + kRows / 4) + kTS + 63) / 64) * 64; }
+constexpr int chunk_stage_threads() { return ((kPipeSets * (2 * NV * kSub / 4 + kRows / 4) + kTS + 63) / 64) * 64; }
 
 // PIPE: the staging role gets wavefronts of its own (behind the kRows * kSub recurrence threads) and
 // stages chunk c+1 into the other LDS buffer while the recurrence runs over chunk c, so the global
@@ -203,11 +204,12 @@ constexpr int chunk_stage_threads() { return ((2 * (2 * NV * kSub / 4 + kRows / 
 template <int NV, int kRows, bool PIPE>
 __global__ __launch_bounds__(kRows * kSub + (PIPE ? chunk_stage_threads<NV, kRows>() : 0)) void ssm_chunk_kernel(const Dims d, const SsmArgs a) {
   constexpr int N = NV * kSub;
-  constexpr int NGBC = 2 * N / 4, NGX = kRows / 4, HP = kTS / 2;
+  constexpr int NSETS = PIPE ? kPipeSets : 1;                      // conv thread sets (one part of a chunk each)
+  constexpr int NPARTS = PIPE ? kPipeSets : 2;                     // parts a chunk is staged in
+  constexpr int NGBC = 2 * N / 4, NGX = kRows / 4, HP = kTS / NPARTS;
   constexpr int NREC = kRows * kSub;                               // recurrence threads
   constexpr int NSTG = PIPE ? chunk_stage_threads<NV, kRows>() : NREC;   // threads that can take the staging role
   constexpr int NBUF = PIPE ? 2 : 1;
-  constexpr int NSETS = PIPE ? 2 : 1;                              // conv thread sets (one half chunk each when 2)
   static_assert(NSETS * (NGBC + NGX) + kTS <= NSTG, "one thread per channel group and per staged position");
   __shared__ __align__(16) float xs[NBUF][kTS][kRows];
   __shared__ __align__(16) float zs[NBUF][kTS][kRows];
@@ -259,7 +261,7 @@ __global__ __launch_bounds__(kRows * kSub + (PIPE ? chunk_stage_threads<NV, kRow
   const float negA = -expf(ly.a_log[h]);
   // this thread's channel group: B|C groups first, then the x rows of the workgroup
   const bool conv_thread = stager && stid >= 0 && stid < NSETS * (NGBC + NGX);
-  const int cset = max(stid, 0) / (NGBC + NGX);              // which half chunk this thread stages (two sets)
+  const int cset = max(stid, 0) / (NGBC + NGX);              // which part of a chunk this thread stages (several sets)
   const int cid = max(stid, 0) % (NGBC + NGX);               // channel group
   const bool is_x = cid >= NGBC;
   const int xg = cid - NGBC;                                 // x group (is_x)
@@ -276,8 +278,8 @@ __global__ __launch_bounds__(kRows * kSub + (PIPE ? chunk_stage_threads<NV, kRow
   auto stage = [&](int j0, int buf) {
     const int tc = min(kTS, nt - j0);
     if (conv_thread) {
-      for (int hp = (NSETS == 2 ? cset : 0); hp < (NSETS == 2 ? cset + 1 : 2); ++hp) {
-        const int jb = j0 + hp * HP;                           // first position of the half chunk (relative)
+      for (int hp = (NSETS > 1 ? cset : 0); hp < (NSETS > 1 ? cset + 1 : NPARTS); ++hp) {
+        const int jb = j0 + hp * HP;                           // first position of the part (relative)
         if (jb >= j0 + tc) break;
         // raw rows of positions jb-3 .. jb+HP-1 (clamped to the last valid one), z of jb .. jb+HP-1
         float4 r[HP + 3], z[HP];

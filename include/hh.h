@@ -200,7 +200,8 @@ HH_API hh_status hh_commit(hh_ctx* ctx, const int32_t* n_accepted, void* stream)
 HH_API hh_status hh_get_tokens(hh_ctx* ctx, int32_t seq, int32_t* out, int32_t cap, int32_t* n_out, void* stream);
 /* Per sequence: cache length, committed count, accepted count of the last commit.  Any pointer may be NULL. */
 HH_API hh_status hh_get_lengths(hh_ctx* ctx, int32_t* kv_len, int32_t* committed, int32_t* last_n, void* stream);
-/* Tokens of the current round: drafts [batch][k] and targets g [batch][k+1].  Either may be NULL. */
+/* Tokens of the current round: drafts [batch][k] and targets g [batch][k+1] (M_H's argmaxes; at
+ * temperature > 0 the kept drafts, the emitted token and -1 behind it).  Either may be NULL. */
 HH_API hh_status hh_get_round(hh_ctx* ctx, int32_t* drafts, int32_t* targets, void* stream);
 /* Logits (needs cfg.keep_logits): which = 0 draft rows [batch][k][vocab], 1 verify rows
  * [batch][k+1][vocab], 2 prefill last-position rows [batch][vocab]. */

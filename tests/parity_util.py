@@ -44,6 +44,7 @@ def run_lockstep(ctx, weights: W.Weights, prompts, lens, G: int, k: int, forced:
     `layers`: layers whose state and cache are read back (default all).  `oracle_rows`: batch
     rows the oracle runs (default all); the library always runs the whole batch, rows are
     independent, so the remaining rows are covered by the batch-invariance of the kernels.
+    `k`: the draft length, or a sequence of draft lengths used round after round (cyclically).
     `temperature` > 0: both sides draw tokens and apply the rejection test with the uniforms of
     `sample_seed`; `min_margin` is the seed audit of those decisions (the analogue of `min_gap`).
     Returns a dict of the worst errors seen."""
@@ -54,7 +55,8 @@ def run_lockstep(ctx, weights: W.Weights, prompts, lens, G: int, k: int, forced:
     B = len(rows)
     layer_list = list(range(cfg.n_layers)) if layers is None else list(layers)
     lm = HybridLM(cfg, weights.values)
-    cap = int(max(lens)) + G + 2 * k + 4
+    ks = [int(k)] if np.isscalar(k) else [int(v) for v in k]
+    cap = int(max(lens)) + G + 2 * max(ks) + 4
     dec = SpecDecoder(lm, cap, engine=engine, chunk=chunk, temperature=temperature, seed=sample_seed)
     plist = [np.asarray(prompts[b][:lens[b]]) for b in rows]
     dec.prefill(plist, G)
@@ -99,6 +101,7 @@ def run_lockstep(ctx, weights: W.Weights, prompts, lens, G: int, k: int, forced:
     while not dec.all_finished() and r < max_rounds:
         active = [not dec.finished(b) for b in range(B)]
         ov = None if override is None else override[r]
+        k = ks[r % len(ks)]
         dec.draft(k, None if ov is None else ov[rows])
         ctx.hh_draft(k)
         if k > 0:

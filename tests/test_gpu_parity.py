@@ -201,6 +201,21 @@ def test_stochastic_call_rules(B):
             assert g[b][n] != d[b][n]
 
 
+def test_draft_length_changes_every_round(B):
+    """A different k every round on one context (the choice of k per round is the caller's: the
+    adaptive draft length the paper names as future work needs nothing else from the library).
+    Every round matches the oracle, and the committed stream equals that of a fixed k."""
+    cfg = W.scaled_config("lively", n_layers=3, d_model=72, vocab=200, m_heads=3, m_head_dim=40, d_state=16,
+                          n_q_heads=6, n_kv_heads=2, head_dim=24, d_ff=104, w_dtype=W.BF16)
+    wts = W.make_lively_weights(cfg, 7)
+    lens = [37, 5, 70, 18]
+    prompts = W.make_prompts(cfg.vocab, 4, lens, 3)
+    ctx = _ctx(B, wts, 4, 160, 4, 24, kv_page_tokens=16, prefill_chunk=16)
+    w = run_lockstep(ctx, wts, prompts, lens, 24, [3, 0, 1, 4, 2], engine="pass", report=_say("k-schedule"))
+    w2 = run_lockstep(ctx, wts, prompts, lens, 24, 3, engine="pass", report=_say("k-fixed"))
+    assert w["tokens"] == w2["tokens"]
+
+
 def test_forced_acceptance_and_arbitrary_drafts(B):
     """Forced accepted counts (drafts committed as drafted) and caller-supplied draft tokens."""
     cfg = W.scaled_config("forced", n_layers=2, d_model=64, vocab=96, m_heads=4, m_head_dim=16, d_state=8,

@@ -160,7 +160,8 @@ HH_API hh_status hh_set_sampling(hh_ctx* ctx, float temperature, uint64_t seed, 
  * draft_logits [batch][k][vocab] and verify_logits [batch][k+1][vocab] and the token emitted after
  * the n kept drafts; positions[b] is the stream position of the first draft (uniforms: purpose 1 at
  * positions[b] + i for test i, purpose 2 at positions[b] + n for the emitted token).  Writes
- * targets [batch][k+1]: drafts[b][i] for i < n, the emitted token at n, -1 behind it.
+ * targets [batch][k+1]: drafts[b][i] for i < n, the emitted token at n, -1 behind it.  A draft id
+ * outside [0, vocab) counts as rejected.
  * scratch: batch * (2k+1) * 2 floats. */
 HH_API hh_status hh_draw_tokens(const float* logits, int64_t row_stride, int32_t vocab, int32_t rows, float temperature,
                                 uint64_t seed, const int32_t* positions, int32_t position_offset, int32_t purpose,

@@ -267,6 +267,7 @@ __global__ __launch_bounds__(kDrawThreads) void spec_targets_kernel(const float*
     int n = k;
     for (int i = 0; i < k; ++i) {
       const int di = d[i];
+      if (di < 0 || di >= V) { n = i; break; }   // not a token: rejected, never used as an index
       const float ps = prob(rows_d[static_cast<size_t>(i) * V + di], st[2 * i], inv_t, 1.0f / st[2 * i + 1]);
       const float ph = prob(rows_v[static_cast<size_t>(i) * V + di], st[2 * (kmax + i)], inv_t, 1.0f / st[2 * (kmax + i) + 1]);
       const float u = uniform24(seed, b, base + i, 1);

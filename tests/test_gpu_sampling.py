@@ -104,6 +104,12 @@ def test_stand_alone_argument_checks(B):
         B.hh_draw_tokens(logits, float("inf"), 1)
     with pytest.raises(B.HHError):
         B.hh_draw_tokens(logits, 0.5, 1, purpose=7)
+    # a draft id that is no token is rejected where it stands, and the emitted token is a valid one
+    v = torch.zeros((1, 3, 16), dtype=torch.float32, device=dev)
+    dl = torch.zeros((1, 2, 16), dtype=torch.float32, device=dev)
+    bad = torch.tensor([[3, 99]], dtype=torch.int32, device=dev)
+    g = B.hh_accept_tokens(dl, v, bad, torch.zeros(1, dtype=torch.int32, device=dev), 1.0, 2).cpu().numpy()[0]
+    assert g[0] == 3 and 0 <= g[1] < 16 and g[2] == -1          # equal distributions keep draft 0 (ratio 1)
     # all-equal logits: the draw is floor(u * vocab)
     got = B.hh_draw_tokens(logits, 0.5, 5).cpu().numpy()
     assert [int(v) for v in got] == [int(S.uniform(5, b, 0, 2) * 16) for b in range(2)]

@@ -122,7 +122,8 @@ HH_API hh_status hh_destroy(hh_ctx* ctx);
 /* Run M_H over the prompts (Section 3.3: the prefix x_{1:t}), fill the KV cache
  * and the recurrent state, and take the first generated token as each
  * sequence's pending token (emitted, not yet consumed by the caches).
- *   tokens      DEVICE int32 [batch][row_stride], ids in [0, vocab)
+ *   tokens      DEVICE int32 [batch][row_stride], ids in [0, vocab) (the library cannot check device
+ *               data: an id outside the range is read as the nearest valid one)
  *   lens        HOST   int32 [batch], 1 <= lens[b] <= row_stride
  *   max_new     generation budget per sequence (1 .. cfg.max_new_tokens)
  * Resets every sequence slot.  HH_ECAPACITY if lens[b] + max_new + 2*max_draft + 2

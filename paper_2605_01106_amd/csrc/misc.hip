@@ -7,9 +7,9 @@
 namespace hh {
 
 // h[m][:] = E[tok[m]][:]
-__global__ void embed_kernel(const void* embed, int bf16, const int* tok, int D, float* h) {
+__global__ void embed_kernel(const void* embed, int bf16, const int* tok, int D, int V, float* h) {
   const int m = blockIdx.x;
-  const size_t src = (size_t)tok[m] * D;
+  const size_t src = (size_t)min(max(tok[m], 0), V - 1) * D;   // an id that is no token reads a valid row, never out of bounds
   for (int k = threadIdx.x; k < D; k += blockDim.x) {
     float v;
     if (bf16) v = __uint_as_float((uint32_t) static_cast<const uint16_t*>(embed)[src + k] << 16);
@@ -19,7 +19,7 @@ __global__ void embed_kernel(const void* embed, int bf16, const int* tok, int D,
 }
 
 hipError_t launch_embed(const Dims& d, const void* embed, const int* tok, int M, float* h, hipStream_t s) {
-  hipLaunchKernelGGL(embed_kernel, dim3(M), dim3(256), 0, s, embed, d.bf16, tok, d.D, h);
+  hipLaunchKernelGGL(embed_kernel, dim3(M), dim3(256), 0, s, embed, d.bf16, tok, d.D, d.V, h);
   return hipGetLastError();
 }
 

@@ -75,3 +75,29 @@ def test_create_needs_workspace_and_weights(B):
     assert "workspace" in B.hh_last_error(None)
     assert B.lib.hh_destroy(None) == B.HH_EINVAL
     assert B.lib.hh_draft(None, 1, None) == B.HH_EINVAL
+
+
+def test_stand_alone_token_choice_rejects_bad_arguments(B):
+    """hh_draw_tokens / hh_accept_tokens validate on the host before any launch: NULL pointers, a
+    row stride below the vocabulary, an unknown purpose, and temperatures that are not finite
+    and > 0 (temperature 0 is the greedy path of the context calls, not a draw)."""
+    fake = C.c_void_p(256)          # never dereferenced: every call below fails validation first
+    def draw(logits=fake, stride=16, vocab=16, rows=1, t=0.5, purpose=2, out=fake):
+        return B.lib.hh_draw_tokens(logits, stride, vocab, rows, C.c_float(t), C.c_uint64(1), None, 0, purpose, out, None)
+    assert draw(logits=None) == B.HH_EINVAL
+    assert draw(out=None) == B.HH_EINVAL
+    assert draw(stride=8) == B.HH_EINVAL
+    assert draw(vocab=0) == B.HH_EINVAL
+    assert draw(purpose=9) == B.HH_EINVAL
+    for t in (0.0, -1.0, float("inf"), float("nan")):
+        assert draw(t=t) == B.HH_EINVAL
+    def accept(dl=fake, vl=fake, k=2, drafts=fake, pos=fake, t=0.5, scratch=fake, targets=fake):
+        return B.lib.hh_accept_tokens(dl, vl, 16, 1, k, drafts, pos, C.c_float(t), C.c_uint64(1), scratch, targets, None)
+    assert accept(vl=None) == B.HH_EINVAL
+    assert accept(dl=None) == B.HH_EINVAL            # k > 0 needs the draft rows and the drafts
+    assert accept(drafts=None) == B.HH_EINVAL
+    assert accept(pos=None) == B.HH_EINVAL
+    assert accept(scratch=None) == B.HH_EINVAL
+    assert accept(targets=None) == B.HH_EINVAL
+    assert accept(k=-1) == B.HH_EINVAL
+    assert accept(t=0.0) == B.HH_EINVAL

@@ -55,6 +55,16 @@ typedef enum {
 
 typedef enum { HH_F32 = 0, HH_BF16 = 1 } hh_dtype;
 
+/* hh_cfg.kernel_flags: each bit routes a family of launches to the slower kernel that computes the
+ * same thing, so that tests can compare the two (results agree to float32 rounding order). */
+enum {
+  HH_KF_ATTN_SCALAR = 1,   /* bf16 cache: attention on the vector ALU instead of the matrix cores */
+  HH_KF_SSM_GENERAL = 2,   /* the any-length scan kernel also for passes of at most 9 positions */
+  HH_KF_MID_OFF = 4,       /* 17..96 activation rows through the many-row GEMM */
+  HH_KF_SKINNY_OFF = 8,    /* 4..16 activation rows through the FMA kernel (4..8) and the many-row GEMM (9..16) */
+  HH_KF_SSM_SCALAR_CONV = 16 /* prefill scan: element-wise staging of the convolution inputs */
+};
+
 /* Model shape and capacities.  Plain data; set struct_size = sizeof(hh_cfg). */
 typedef struct hh_cfg {
   uint32_t struct_size;
@@ -74,8 +84,22 @@ typedef struct hh_cfg {
   int32_t kv_page_tokens;               /* tokens per KV page: 16, 32, 64, 128 or 256; 0 = default */
   int32_t prefill_chunk;                /* prompt positions per sequence per prefill pass, 1..1024; 0 = default:
                                            4096 / max_batch rounded down to a multiple of 64, within 64..512 */
-  int32_t keep_logits;                  /* 1: materialise float32 logits of draft and verify rows for hh_get_logits */
-  int32_t use_graphs;                   /* 1: replay draft/verify/commit as HIP graphs after their first call */
+  int32_t keep_logits;                  /* 1: float32 logits of the draft, verification and last prefill rows are kept for
+                                           hh_get_logits.  0: greedy rounds (temperature 0) keep only the argmax of every
+                                           row - the LM head of a pass with more than 16 rows then writes no logits at
+                                           all - and hh_get_logits returns HH_ESTATE; at temperature > 0 the rows are
+                                           written regardless (Eq. 6 reads them) */
+  int32_t use_graphs;                   /* 1: the launch sequences of hh_draft and hh_verify are replayed as HIP graphs from
+                                           their second use on (non-NULL stream only); hh_commit is always enqueued directly */
+  /* Tunables: results must not depend on them beyond float32 rounding order (0 = the library's default). */
+  int32_t overlap_mode;                 /* attention branch of a full pass on a side stream beside the SSM branch:
+                                           0 automatic (prefill passes; verification from 512k cached tokens in the batch),
+                                           1 never, 2 prefill passes only, 3 always */
+  int32_t attn_max_splits;              /* most key slices (workgroups along the cache) per sequence and KV head: 1..32; 0 = 16 */
+  int32_t attn_single_slice_steps;      /* matrix-core attention: caches of at most this many 32-key steps use one slice;
+                                           0 = 28, -1 = split from the first step on */
+  int32_t kernel_flags;                 /* HH_KF_* bits: kernel selection for cross-checks, all 0 by default */
+  int32_t prefill_progress;             /* n > 0: hh_prefill waits for every n-th pass and reports it on stderr */
   void* workspace;                      /* DEVICE, 256-byte aligned */
   size_t workspace_bytes;
 } hh_cfg;
@@ -234,8 +258,8 @@ HH_API hh_status hh_profile_read(hh_ctx* ctx, int32_t n_tags, int32_t* launches,
 HH_API hh_status hh_time_kind(hh_ctx* ctx, int32_t phase, int32_t kind, int32_t k, int32_t reps, float* total_ms,
                               int32_t* launches, void* stream);
 
-/* Human-readable description of the last error on this context (or of the last
- * failed hh_create when ctx is NULL).  Never NULL. */
+/* Human-readable description of the last error on this context (or, when ctx is NULL, of the
+ * last failed context-free call: hh_create, hh_workspace_bytes, ...).  Never NULL. */
 HH_API const char* hh_last_error(const hh_ctx* ctx);
 
 #ifdef __cplusplus

@@ -86,6 +86,9 @@ def stochastic_round(p_s: Sequence[np.ndarray], p_h: Sequence[np.ndarray], draft
     n = k
     for i in range(k):
         d = int(drafts[i])
+        if not 0 <= d < len(p_h[i]):          # not a token: rejected where it stands
+            n = i
+            break
         ratio = p_h[i][d] / p_s[i][d]
         margin = min(margin, abs(u_accept[i] - ratio))
         if not u_accept[i] < ratio:           # keep with probability min(1, ratio)
@@ -93,9 +96,17 @@ def stochastic_round(p_s: Sequence[np.ndarray], p_h: Sequence[np.ndarray], draft
             break
     if n < k:
         r = residual(p_h[n], p_s[n])
-        if r.sum() <= 0.0:                    # identical distributions: nothing to correct towards
-            r = np.asarray(p_h[n], np.float64)
-        tok, m = draw(r, u_correct_at(n))
+        if r.sum() > 0.0:
+            tok, m = draw(r, u_correct_at(n))
+        else:
+            # Eq. 6 leaves this case open: the residual has no mass (in exact arithmetic a rejection
+            # implies mass elsewhere, so it only arises from rounding, or from a draft id that is no
+            # token).  Reading: draw from P_H with the same uniform; should that be the rejected
+            # draft itself, take its successor in index order, so that the targets row (entry n
+            # differs from the draft) still encodes n.
+            tok, m = draw(np.asarray(p_h[n], np.float64), u_correct_at(n))
+            if tok == int(drafts[n]):
+                tok = (tok + 1) % len(p_h[n])
     else:
         tok, m = draw(p_h[k], u_correct_at(k))
     return n, tok, min(margin, m)

@@ -25,6 +25,7 @@ lib = C.CDLL(_LIB_PATH)
 
 HH_OK, HH_EINVAL, HH_ESTATE, HH_ECAPACITY, HH_EWORKSPACE, HH_EDEVICE = 0, -1, -2, -3, -4, -5
 HH_F32, HH_BF16 = 0, 1
+HH_KF_ATTN_SCALAR, HH_KF_SSM_GENERAL, HH_KF_MID_OFF, HH_KF_SKINNY_OFF, HH_KF_SSM_SCALAR_CONV = 1, 2, 4, 8, 16
 STATUS_NAMES = {0: "HH_OK", -1: "HH_EINVAL", -2: "HH_ESTATE", -3: "HH_ECAPACITY", -4: "HH_EWORKSPACE",
                 -5: "HH_EDEVICE"}
 
@@ -39,6 +40,8 @@ class hh_cfg(C.Structure):
                 ("w_dtype", C.c_int32), ("max_batch", C.c_int32), ("max_seq_len", C.c_int32),
                 ("max_draft", C.c_int32), ("max_new_tokens", C.c_int32), ("kv_page_tokens", C.c_int32),
                 ("prefill_chunk", C.c_int32), ("keep_logits", C.c_int32), ("use_graphs", C.c_int32),
+                ("overlap_mode", C.c_int32), ("attn_max_splits", C.c_int32), ("attn_single_slice_steps", C.c_int32),
+                ("kernel_flags", C.c_int32), ("prefill_progress", C.c_int32),
                 ("workspace", C.c_void_p), ("workspace_bytes", C.c_size_t)]
 
 
@@ -96,7 +99,9 @@ class HHError(RuntimeError):
 
 
 def make_cfg(cfg: W.HybridConfig, max_batch: int, max_seq_len: int, max_draft: int, max_new_tokens: int,
-             kv_page_tokens: int = 0, prefill_chunk: int = 0, keep_logits: int = 1, use_graphs: int = 0) -> hh_cfg:
+             kv_page_tokens: int = 0, prefill_chunk: int = 0, keep_logits: int = 1, use_graphs: int = 0,
+             overlap_mode: int = 0, attn_max_splits: int = 0, attn_single_slice_steps: int = 0, kernel_flags: int = 0,
+             prefill_progress: int = 0) -> hh_cfg:
     c = hh_cfg()
     c.struct_size = C.sizeof(hh_cfg)
     c.n_layers, c.d_model, c.vocab = cfg.n_layers, cfg.d_model, cfg.vocab
@@ -107,6 +112,8 @@ def make_cfg(cfg: W.HybridConfig, max_batch: int, max_seq_len: int, max_draft: i
     c.w_dtype = HH_BF16 if cfg.w_dtype == W.BF16 else HH_F32
     c.max_batch, c.max_seq_len, c.max_draft, c.max_new_tokens = max_batch, max_seq_len, max_draft, max_new_tokens
     c.kv_page_tokens, c.prefill_chunk, c.keep_logits, c.use_graphs = kv_page_tokens, prefill_chunk, keep_logits, use_graphs
+    c.overlap_mode, c.attn_max_splits, c.attn_single_slice_steps = overlap_mode, attn_max_splits, attn_single_slice_steps
+    c.kernel_flags, c.prefill_progress = kernel_flags, prefill_progress
     c.workspace, c.workspace_bytes = None, 0
     return c
 

@@ -463,10 +463,9 @@ __global__ __launch_bounds__(256) void kv_append_kernel(const Dims d, const Attn
   }
 }
 
-// bf16 cache: matrix-core kernel (HH_ATTN_SCALAR=1 selects the float32-FMA kernel instead, for cross-checks)
+// bf16 cache: matrix-core kernel (HH_KF_ATTN_SCALAR selects the float32-FMA kernel instead, for cross-checks)
 bool attention_uses_mfma(const Dims& d) {
-  static const bool force_scalar = getenv("HH_ATTN_SCALAR") != nullptr && atoi(getenv("HH_ATTN_SCALAR")) != 0;
-  return d.bf16 && !force_scalar && d.page_tokens % 32 == 0;   // a 32-key step of that kernel lies in one page
+  return d.bf16 && !(d.flags & HH_KF_ATTN_SCALAR) && d.page_tokens % 32 == 0;   // a 32-key step of that kernel lies in one page
 }
 
 hipError_t launch_attention(const Dims& d, const AttnArgs& a, hipStream_t s) {

@@ -27,15 +27,11 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
 // bf16 terms an activation is split into for this kernel (planes per row tile and step): three
-// (exact).  HH_GEMM_TERMS=2 keeps 16 mantissa bits only: the kernel is then about twice as fast
-// (fewer MFMAs, fewer plane re-reads) and the benign random-weight workloads still match the
-// float64 reference, but models with order-one activations and recurrences amplify the 2^-17
-// relative error beyond the logit tolerance (seen on the test initialisation with 160 prefill
-// rows), so it is an option, not the default.
-static int gemm_terms(int M) {
-  static const int t = getenv("HH_GEMM_TERMS") != nullptr && atoi(getenv("HH_GEMM_TERMS")) == 2 ? 2 : 3;
-  return M <= 96 ? 3 : t;   // up to 96 rows (only with the mid-row kernel switched off) always exact
-}
+// (exact).  Two terms (16 mantissa bits) would be about twice as fast, and the benign
+// random-weight workloads would still match the float64 reference, but models with order-one
+// activations and recurrences amplify the 2^-17 relative error beyond the logit tolerance (seen
+// on the test initialisation with 160 prefill rows).
+static int gemm_terms(int) { return 3; }
 
 // split activations in MFMA operand order (see below); rows >= M and columns >= K are zero.
 // One workgroup per row; a thread handles groups of 8 consecutive columns (two float4 loads,
@@ -349,12 +345,11 @@ hipError_t launch_gemm_mfma(const GemvArgs& g, uint16_t* planes, float* partial,
   const int steps = Kp / 32, tiles = (N + 15) / 16, m_tiles = Mp / 16;
   a.strip_groups = (tiles + nt - 1) / nt;
   // row tiles per unit: 5 with two terms; 4 with three (5 would spill under the two-workgroups-per-CU register cap)
-  static const int mtw_cap3 = getenv("HH_GEMM_MTW3") ? atoi(getenv("HH_GEMM_MTW3")) : 4;
-  const int mtw_cap = a.terms == 3 ? (mtw_cap3 >= 1 && mtw_cap3 <= 5 ? mtw_cap3 : 4) : 5;
+  const int mtw_cap = a.terms == 3 ? 4 : 5;
   a.m_groups = (m_tiles + mtw_cap - 1) / mtw_cap;
   const int mtw = (m_tiles + a.m_groups - 1) / a.m_groups;
   // K split: enough units (wavefronts) to cover the chip, at least 4 steps each, partial buffer permitting
-  static const int unit_target = getenv("HH_GEMM_UNITS") ? atoi(getenv("HH_GEMM_UNITS")) : 2048;
+  constexpr int unit_target = 2048;
   int ksplit = 1;
   while (a.strip_groups * a.m_groups * ksplit * 2 <= unit_target && steps / (ksplit * 2) >= 4 &&
          (size_t)(ksplit * 2) * nf * M * N <= gemm_partial_elems())

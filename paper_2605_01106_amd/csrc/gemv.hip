@@ -44,13 +44,12 @@ static bool make_plan(const GemvArgs& a, int MT, GemvPlan& p) {
   p.R = rmax;
   const int rgb = kGemvWaves / p.KS;
   // R must divide N; use fewer rows per wavefront while that is needed to cover the CUs
-  static const int min_blocks = getenv("HH_GEMV_MINBLK") ? atoi(getenv("HH_GEMV_MINBLK")) : 256;
+  constexpr int min_blocks = 256;
   while (p.R > 1 && (N % p.R || N / p.R / rgb < min_blocks)) p.R >>= 1;
   const int nrg = N / p.R;
   // several row groups per workgroup, so that staging the activations (MT * K floats per
   // workgroup, from L2) stays small next to the weights it meets
-  static const int tb1 = getenv("HH_GEMV_TB1") ? atoi(getenv("HH_GEMV_TB1")) : 1024;
-  static const int tbm = getenv("HH_GEMV_TBM") ? atoi(getenv("HH_GEMV_TBM")) : 1024;
+  constexpr int tb1 = 1024, tbm = 1024;
   const int per = (nrg + rgb - 1) / rgb;
   const int target = MT == 1 ? tb1 : tbm;
   p.iters = (per + target - 1) / target;

@@ -140,6 +140,15 @@ bool derive_dims(const hh_cfg& c, Dims& d, std::string& why) {
   d.n_pages = d.pages_per_seq * d.Bmax;
   d.bf16 = c.w_dtype == HH_BF16;
   d.eps = c.rms_eps; d.rope_base = c.rope_base;
+  if (c.overlap_mode < 0 || c.overlap_mode > 3) return bad("overlap_mode must be in 0..3");
+  if (c.attn_max_splits < 0 || c.attn_max_splits > kMaxSplits) return bad("attn_max_splits must be in 0..32");
+  if (c.attn_single_slice_steps < -1) return bad("attn_single_slice_steps must be -1, 0 or a step count");
+  if (c.kernel_flags & ~(HH_KF_ATTN_SCALAR | HH_KF_SSM_GENERAL | HH_KF_MID_OFF | HH_KF_SKINNY_OFF | HH_KF_SSM_SCALAR_CONV))
+    return bad("unknown bit in kernel_flags");
+  if (c.prefill_progress < 0) return bad("prefill_progress must not be negative");
+  if (c.keep_logits != 0 && c.keep_logits != 1) return bad("keep_logits must be 0 or 1");
+  if (c.use_graphs != 0 && c.use_graphs != 1) return bad("use_graphs must be 0 or 1");
+  d.flags = c.kernel_flags;
   return true;
 }
 
@@ -253,13 +262,10 @@ hh_status fail(hh_ctx* x, hh_status st, const std::string& msg) {
 // matrix-core GEMM over pre-split activations for 9 rows and more otherwise.  float32 weights:
 // the FMA kernel.
 constexpr int kMfmaMinRows = 9;
-int skinny_min_rows() {
-  static const int v = getenv("HH_SKINNY_MINROWS") ? atoi(getenv("HH_SKINNY_MINROWS")) : 4;
-  return v;
-}
+constexpr int kSkinnyMinRows = 4;
 // the arguments with the packed weights in place of the row-major ones, if this product can take the skinny kernel
 bool skinny_args(const GemvArgs& a, GemvArgs& b) {
-  if (!a.bf16 || a.M < skinny_min_rows() || a.M > 16 || a.seg[0].P == nullptr) return false;
+  if (!a.bf16 || (a.flags & HH_KF_SKINNY_OFF) || a.M < kSkinnyMinRows || a.M > 16 || a.seg[0].P == nullptr) return false;
   b = a;
   b.seg[0].W = a.seg[0].P; b.seg[0].W2 = a.seg[0].P2;
   return skinny_mfma_fits(b);
@@ -278,27 +284,27 @@ hipError_t product(hh_ctx* x, const GemvArgs& a, hipStream_t s, bool side = fals
 // Prefill passes always do (both branches are long).  In a verification pass the fork makes the
 // captured graph a two-queue graph, and measured on this machine every launch of the following
 // (single-stream) draft graphs then takes about 0.9 us longer; that only pays once the attention
-// branch is long: from 512k cached tokens in the batch.  HH_OVERLAP_MODE: 0 never, 1 prefill
-// only, 2 always, default automatic.
-bool branch_overlap(const hh_ctx* x, int B, int T) {
-  static const int mode = getenv("HH_OVERLAP_MODE") != nullptr ? atoi(getenv("HH_OVERLAP_MODE")) : 3;
-  if (mode == 0) return false;
-  if (T > x->d.Kmax + 1) return true;            // prefill chunk
+// branch is long: from 512k cached tokens in the batch.  cfg.overlap_mode: 0 automatic, 1 never,
+// 2 prefill passes only, 3 always.
+bool branch_overlap(const hh_ctx* x, int B, int T, bool prefill) {
+  const int mode = x->cfg.overlap_mode;
   if (mode == 1) return false;
-  if (mode == 2) return true;
+  if (mode == 3) return true;
+  if (prefill) return true;
+  if (mode == 2) return false;
   return (long long)B * x->len_upper >= (512LL << 10);
 }
 
 // ---- one pass of the block stack over M = B*T rows.  full: M_H (both branches); !full: M_S.
 hh_status run_layers(hh_ctx* x, bool full, int B, int T, const int* n_tok, int state_in, int state_out,
-                     int n_splits, hipStream_t s) {
+                     int n_splits, bool prefill, hipStream_t s) {
   const Dims& d = x->d;
   const int M = B * T;
   for (int l = 0; l < d.L; ++l) {
     const LayerDev& w = x->layers_host[l];
     {  // shared input norm, Mamba-2 input projection (+ q, k, v of the attention branch)
       GemvArgs a{};
-      a.X = x->h; a.ldx = d.D; a.M = M; a.K = d.D; a.norm_w = w.norm1; a.eps = d.eps; a.epi = EPI_STORE; a.bf16 = d.bf16;
+      a.X = x->h; a.ldx = d.D; a.M = M; a.K = d.D; a.norm_w = w.norm1; a.eps = d.eps; a.epi = EPI_STORE; a.bf16 = d.bf16; a.flags = d.flags;
       a.seg[0] = {w.w_inqkv, nullptr, w.p_inqkv, nullptr, x->zx, full ? d.ldzx : d.d_in_proj, d.ldzx};
       a.n_seg = 1;
       HH_LAUNCH(HH_K_IN_PROJ, product(x, a, s));
@@ -307,7 +313,7 @@ hh_status run_layers(hh_ctx* x, bool full, int B, int T, const int* n_tok, int s
     // (attention, then its output projection into a buffer of its own) is enqueued on a side
     // stream beside the SSM branch (scan, then out projection into the residual stream); the
     // branches meet at the MLP, whose input is h + ho and whose down projection adds both.
-    const bool overlap = full && !x->prof_on && x->side != nullptr && branch_overlap(x, B, T);
+    const bool overlap = full && !x->prof_on && x->side != nullptr && branch_overlap(x, B, T, prefill);
     hipStream_t sa = s;
     if (overlap) {
       sa = x->side;
@@ -321,7 +327,7 @@ hh_status run_layers(hh_ctx* x, bool full, int B, int T, const int* n_tok, int s
       a.counters = x->attn_counters;
       a.T = T; a.B = B; a.n_splits = n_splits;
       GemvArgs b{};
-      b.X = x->o; b.ldx = d.dq; b.M = M; b.K = d.dq; b.norm_w = nullptr; b.epi = EPI_STORE; b.bf16 = d.bf16;
+      b.X = x->o; b.ldx = d.dq; b.M = M; b.K = d.dq; b.norm_w = nullptr; b.epi = EPI_STORE; b.bf16 = d.bf16; b.flags = d.flags;
       b.seg[0] = {w.w_o, nullptr, w.p_o, nullptr, x->ho, d.D, d.D}; b.n_seg = 1;
       if (overlap) {
         HH_HIP(launch_attention(d, a, sa));
@@ -341,7 +347,7 @@ hh_status run_layers(hh_ctx* x, bool full, int B, int T, const int* n_tok, int s
     }
     {  // h += W_out * gated_norm(g)
       GemvArgs a{};
-      a.X = x->g; a.ldx = d.d_inner; a.M = M; a.K = d.d_inner; a.norm_w = w.gnorm; a.eps = d.eps; a.epi = EPI_ADD; a.bf16 = d.bf16;
+      a.X = x->g; a.ldx = d.d_inner; a.M = M; a.K = d.d_inner; a.norm_w = w.gnorm; a.eps = d.eps; a.epi = EPI_ADD; a.bf16 = d.bf16; a.flags = d.flags;
       a.seg[0] = {w.w_out, nullptr, w.p_out, nullptr, x->h, d.D, d.D}; a.n_seg = 1;
       HH_LAUNCH(HH_K_OUT_PROJ, product(x, a, s));
     }
@@ -349,11 +355,11 @@ hh_status run_layers(hh_ctx* x, bool full, int B, int T, const int* n_tok, int s
     {  // SwiGLU MLP on r = rmsnorm(h + ho); h += ho + W_d(...)   (ho: full mode only)
       const float* ho = full ? x->ho : nullptr;
       GemvArgs a{};
-      a.X = x->h; a.X2 = ho; a.ldx = d.D; a.M = M; a.K = d.D; a.norm_w = w.norm2; a.eps = d.eps; a.epi = EPI_SWIGLU; a.bf16 = d.bf16;
+      a.X = x->h; a.X2 = ho; a.ldx = d.D; a.M = M; a.K = d.D; a.norm_w = w.norm2; a.eps = d.eps; a.epi = EPI_SWIGLU; a.bf16 = d.bf16; a.flags = d.flags;
       a.seg[0] = {w.w_gate, w.w_up, w.p_gate, w.p_up, x->act, d.F, d.F}; a.n_seg = 1;
       HH_LAUNCH(HH_K_MLP_UP, product(x, a, s));
       GemvArgs b{};
-      b.X = x->act; b.ldx = d.F; b.M = M; b.K = d.F; b.norm_w = nullptr; b.epi = EPI_ADD; b.bf16 = d.bf16; b.R2 = ho;
+      b.X = x->act; b.ldx = d.F; b.M = M; b.K = d.F; b.norm_w = nullptr; b.epi = EPI_ADD; b.bf16 = d.bf16; b.flags = d.flags; b.R2 = ho;
       b.seg[0] = {w.w_down, nullptr, w.p_down, nullptr, x->h, d.D, d.D}; b.n_seg = 1;
       HH_LAUNCH(HH_K_MLP_DOWN, product(x, b, s));
     }
@@ -367,7 +373,7 @@ hh_status run_head(hh_ctx* x, const float* X, int M, int T, float* logits, int l
   const Dims& d = x->d;
   GemvArgs a{};
   a.X = X; a.ldx = d.D; a.M = M; a.K = d.D; a.norm_w = static_cast<const float*>(x->final_norm); a.eps = d.eps;
-  a.epi = EPI_STORE; a.bf16 = d.bf16; a.best = x->best;
+  a.epi = EPI_STORE; a.bf16 = d.bf16; a.flags = d.flags; a.best = x->best;
   a.seg[0] = {x->lm_head, nullptr, x->p_lm_head, nullptr, logits, d.V, ld_logits}; a.n_seg = 1;
   GemvArgs sk;
   if (skinny_args(a, sk)) {
@@ -421,8 +427,9 @@ hh_status run_graphed(hh_ctx* x, long long key, hipStream_t s, F enqueue) {
 
 // Key slices per (sequence, KV head, row chunk) of a verification pass: enough workgroups to
 // cover the chip, but no slice smaller than the unit of work of the kernel.
-int pick_splits(const Dims& d, int B, int T, int len_upper) {
-  static const int cap = getenv("HH_ATTN_MAXSPLIT") ? atoi(getenv("HH_ATTN_MAXSPLIT")) : 16;
+int pick_splits(const hh_cfg& c, const Dims& d, int B, int T, int len_upper) {
+  const int cap = c.attn_max_splits > 0 ? c.attn_max_splits : 16;
+  const int single = c.attn_single_slice_steps == 0 ? 28 : c.attn_single_slice_steps;   // -1: never a single slice by this rule
   int s;
   if (attention_uses_mfma(d)) {
     const int blocks = attention_mfma_row_chunks(d, T) * d.Hkv * B;
@@ -431,7 +438,7 @@ int pick_splits(const Dims& d, int B, int T, int len_upper) {
     if (s > (steps + 3) / 4) s = (steps + 3) / 4;
     // short caches: the ticket and the merge across workgroups (about 4 us) cost more than the
     // few extra steps per wavefront of a single slice
-    if (steps <= 28) s = 1;
+    if (steps <= single) s = 1;
   } else {
     const int G = d.Hq / d.Hkv;
     const int row_chunks = (T * G + 15) / 16;
@@ -628,11 +635,11 @@ hh_status hh_prefill(hh_ctx* x, const int32_t* tokens, int32_t row_stride, const
     const int* nt = x->plan_ntok + (size_t)p * B;
     HH_HIP(launch_gather_prompt(tokens, row_stride, p * chunk, nt, B, T, x->tok, x->kv_len, x->pos0, s));
     HH_HIP(launch_embed(d, x->embed, x->tok, B * T, x->h, s));
-    hh_status st = run_layers(x, true, B, T, nt, p == 0 ? 2 : 0, 1, 1, s);
+    hh_status st = run_layers(x, true, B, T, nt, p == 0 ? 2 : 0, 1, 1, true, s);
     if (st != HH_OK) return st;
     HH_HIP(launch_prefill_tail(x->h, T, d.D, nt, x->plan_last + (size_t)p * B, x->lasth, x->kv_len, B, s));
-    // HH_PROGRESS=n: wait for every n-th pass and report it (long prompts; otherwise the call only enqueues)
-    static const int progress = getenv("HH_PROGRESS") ? atoi(getenv("HH_PROGRESS")) : 0;
+    // cfg.prefill_progress = n: wait for every n-th pass and report it (long prompts; otherwise the call only enqueues)
+    const int progress = x->cfg.prefill_progress;
     if (progress > 0 && (p + 1) % progress == 0) {
       HH_HIP(hipStreamSynchronize(s));
       fprintf(stderr, "[hh] prefill pass %d of %d done\n", p + 1, n_pass);
@@ -712,7 +719,7 @@ hh_status hh_draft(hh_ctx* x, int32_t k, void* stream) {
     for (int i = 0; i < k; ++i) {
       HH_HIP(launch_gather_tokens(x->pending, x->drafts, d.Kmax, B, 1, 0, i, x->tok, x->kv_len, x->pos0, s));
       HH_HIP(launch_embed(d, x->embed, x->tok, B, x->h, s));
-      hh_status st = run_layers(x, false, B, 1, nullptr, i == 0 ? 0 : 1, 2, 1, s);
+      hh_status st = run_layers(x, false, B, 1, nullptr, i == 0 ? 0 : 1, 2, 1, false, s);
       if (st != HH_OK) return st;
       st = run_head(x, x->h, B, 1, x->logits_d + (size_t)i * d.V, d.Kmax * d.V, x->drafts, d.Kmax, i, s);
       if (st != HH_OK) return st;
@@ -752,11 +759,11 @@ hh_status hh_verify(hh_ctx* x, void* stream) {
   const int B = x->B, T = x->k + 1;
   const bool stochastic = x->temperature > 0.f;
   x->prof_phase = HH_PHASE_VERIFY;
-  const int splits = pick_splits(d, B, T, x->len_upper);
+  const int splits = pick_splits(x->cfg, d, B, T, x->len_upper);
   auto enqueue = [&]() -> hh_status {
     HH_HIP(launch_gather_tokens(x->pending, x->drafts, d.Kmax, B, T, 1, 0, x->tok, x->kv_len, x->pos0, s));
     HH_HIP(launch_embed(d, x->embed, x->tok, B * T, x->h, s));
-    hh_status st = run_layers(x, true, B, T, nullptr, 0, 0, splits, s);
+    hh_status st = run_layers(x, true, B, T, nullptr, 0, 0, splits, false, s);
     if (st != HH_OK) return st;
     st = run_head(x, x->h, B * T, T, x->logits_v, d.V, x->targets, d.Kmax + 1, 0, s);
     if (st != HH_OK) return st;
@@ -765,7 +772,7 @@ hh_status hh_verify(hh_ctx* x, void* stream) {
                                  x->committed, x->targets, s));
     return HH_OK;
   };
-  const hh_status st = run_graphed(x, (2LL << 40) | ((long long)branch_overlap(x, B, T) << 39) | ((long long)stochastic << 38) | ((long long)B << 20) | ((long long)splits << 8) | T, s, enqueue);
+  const hh_status st = run_graphed(x, (2LL << 40) | ((long long)branch_overlap(x, B, T, false) << 39) | ((long long)stochastic << 38) | ((long long)B << 20) | ((long long)splits << 8) | T, s, enqueue);
   if (st != HH_OK) return st;
   x->phase = PH_VERIFIED;
   return HH_OK;
@@ -851,6 +858,7 @@ hh_status hh_get_logits(hh_ctx* x, int32_t which, float* out, void* stream) {
   if (!x) return HH_EINVAL;
   if (x->phase == PH_CREATED) return fail(x, HH_ESTATE, "hh_get_logits: nothing prefilled");
   if (!out || which < 0 || which > 2) return fail(x, HH_EINVAL, "hh_get_logits: bad argument");
+  if (!x->cfg.keep_logits) return fail(x, HH_ESTATE, "hh_get_logits: the context was created with keep_logits = 0");
   hh_status st = sync_stream(x, stream);
   if (st != HH_OK) return st;
   const Dims& d = x->d;
@@ -942,7 +950,7 @@ hh_status hh_time_kind(hh_ctx* x, int32_t phase, int32_t kind, int32_t k, int32_
                       full ? x->targets : x->drafts, full ? d.Kmax + 1 : d.Kmax, 0, s);
         n += 1;
       } else {
-        st = run_layers(x, full, B, T, nullptr, 0, full ? 0 : 2, pick_splits(d, B, T, x->len_upper), s);
+        st = run_layers(x, full, B, T, nullptr, 0, full ? 0 : 2, pick_splits(x->cfg, d, B, T, x->len_upper), false, s);
         n += d.L;
       }
     }

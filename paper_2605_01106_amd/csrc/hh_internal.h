@@ -19,6 +19,7 @@ struct Dims {
   int Bmax, Tmax, Gmax, Kmax, max_seq;
   int bf16;         // storage type of matrices and KV
   float eps, rope_base;
+  int flags;        // hh_cfg.kernel_flags (HH_KF_* bits)
 };
 
 // ---- per-layer device pointers (an array of these lives in the workspace)
@@ -54,6 +55,7 @@ struct GemvArgs {
   int epi;
   unsigned long long* best;                // optional per-block argmax partials [M][gridDim.x]
   int bf16;
+  int flags;                               // hh_cfg.kernel_flags (HH_KF_* bits)
 };
 hipError_t launch_gemv(const GemvArgs& a, int* n_blocks_out, hipStream_t s);
 int gemv_max_blocks();   // upper bound on gridDim.x of launch_gemv (size of the argmax partial rows)

@@ -247,7 +247,7 @@ static bool mid_plan(const GemvArgs& g, MidPlan& p) {
   p.units = nf == 2 ? tiles : (tiles + 1) / 2;
   // K-loop kernel: 8 units per workgroup, windows of 128 columns, K chunks so that the launch
   // has at most one workgroup per compute unit (its LDS and registers allow no second one)
-  static const int target = getenv("HH_MID_BLOCKS") ? atoi(getenv("HH_MID_BLOCKS")) : 256;
+  constexpr int target = 256;
   const int n_win = (g.K + 127) / 128;
   p.blocks = (p.units + 7) / 8;
   int ks = target / p.blocks;
@@ -261,9 +261,8 @@ static bool mid_plan(const GemvArgs& g, MidPlan& p) {
 }
 
 bool mid_mfma_fits(const GemvArgs& g) {
-  static const bool off = getenv("HH_MID_OFF") != nullptr && atoi(getenv("HH_MID_OFF")) != 0;
   MidPlan p;
-  return !off && mid_plan(g, p);
+  return !(g.flags & HH_KF_MID_OFF) && mid_plan(g, p);
 }
 
 template <int NF, int MT>

@@ -103,7 +103,8 @@ __device__ void row_stats(const float* __restrict__ row, int V, float inv_t, flo
 // masses (>= 0) of indices jj .. jj+3, zero past `end`.
 // Wavefront w owns the contiguous segment [w * seg, (w + 1) * seg); the segment sums give the
 // segment that holds u * total, and that wavefront alone scans its segment in index order.
-// red: kDrawWaves floats, res: one int (both in LDS).  Every thread returns the drawn index.
+// red: kDrawWaves floats, res: one int (both in LDS).  Every thread returns the drawn index, or -1
+// when no entry has mass.
 template <typename F>
 __device__ int block_draw(F val, int V, float u, float* red, int* res) {
   const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
@@ -121,6 +122,10 @@ __device__ int block_draw(F val, int V, float u, float* red, int* res) {
   __syncthreads();
   float total = 0.f;
   for (int i = 0; i < kDrawWaves; ++i) total += red[i];
+  if (!(total > 0.f)) {          // uniform over the workgroup: every thread summed the same values
+    __syncthreads();
+    return -1;
+  }
   const float target = u * total;
   int ws = -1;
   float carry = 0.f, c = 0.f;
@@ -293,7 +298,20 @@ __global__ __launch_bounds__(kDrawThreads) void spec_targets_kernel(const float*
           for (int e = 0; e < 4; ++e) v[e] = fmaxf(0.f, prob(a[e], mh, inv_t, rsh) - prob(c[e], ms, inv_t, rss));
         },
         V, u, red, &res);
-    if (tok == d[n]) tok = tok + 1 < V ? tok + 1 : 0;   // only if rounding left the residual without mass
+    if (tok < 0) {
+      // The residual has no mass (the two distributions agree to rounding; in exact arithmetic a
+      // rejection implies mass elsewhere): the token is drawn from P_H with the same uniform, and
+      // should that be the rejected draft itself, its successor in index order is taken, so that
+      // the targets row still encodes n.
+      tok = block_draw(
+          [&](int jj, int end, float (&v)[4]) {
+            float l[4];
+            load_group(lh, jj, end, row_is_vec(lh), l);
+            for (int e = 0; e < 4; ++e) v[e] = expf((l[e] - mh) * inv_t);
+          },
+          V, u, red, &res);
+      if (tok == d[n]) tok = tok + 1 < V ? tok + 1 : 0;
+    }
   } else {
     const bool vec = row_is_vec(lh);
     tok = block_draw(

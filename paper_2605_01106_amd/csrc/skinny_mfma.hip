@@ -319,7 +319,7 @@ struct SkinnyPlan { int nwaves, ksteps, rounds, blocks, windows; size_t lds; };
 // plan for a window of K columns of the product (the whole row, or a part when the staged
 // activations of the whole row would not fit in LDS)
 static bool skinny_plan_k(const GemvArgs& g, int K, SkinnyPlan& p) {
-  static const int blk_target = getenv("HH_SKINNY_BLOCKS") ? atoi(getenv("HH_SKINNY_BLOCKS")) : 768;
+  constexpr int blk_target = 768;
   const int M = g.M, N = g.seg[0].n_rows, nf = g.epi == EPI_SWIGLU ? 2 : 1;
   const int steps = (K + 31) / 32, tiles = (N + 15) / 16;
   // K split: 8 wavefronts, 16 for long rows; a slice is at most 8 steps (the fragments of two
@@ -347,7 +347,7 @@ static bool skinny_plan_k(const GemvArgs& g, int K, SkinnyPlan& p) {
 // product has too few weight tiles to occupy the chip (N small, K long): the windows run side
 // by side as gridDim.y and a reduction kernel adds them.
 static int skinny_windows(const GemvArgs& g, SkinnyPlan& p) {
-  static const int min_blocks = getenv("HH_SKINNY_WINBLK") ? atoi(getenv("HH_SKINNY_WINBLK")) : 192;
+  constexpr int min_blocks = 192;
   const int tiles = (g.seg[0].n_rows + 15) / 16;
   // the reduction handles store / residual add and the norm scale; not SwiGLU or argmax partials
   const bool can_split = g.epi != EPI_SWIGLU && g.best == nullptr &&

@@ -628,7 +628,7 @@ static hipError_t launch_ssm_small_t(const Dims& d, const SsmArgs& a, int tmax, 
   // Several row groups per workgroup pay off only in the rebuild from the ring (commit: all layers
   // in one launch, every load of a workgroup besides the state is fixed cost); measured, the
   // draft step and the verification pass are no faster with them.
-  static const int min_wg = getenv("HH_SSM_MINWG") ? atoi(getenv("HH_SSM_MINWG")) : 1024;
+  constexpr int min_wg = 1024;
   const int groups = (d.P + 64 / SUBS - 1) / (64 / SUBS);
   const long wgs = (long)groups * d.Hm * a.n_layers_z * a.B;
   if (a.zx == nullptr && NV <= 16) {            // (32 values per lane and row group: registers; four wavefronts instead)
@@ -636,15 +636,14 @@ static hipError_t launch_ssm_small_t(const Dims& d, const SsmArgs& a, int tmax, 
     if (groups % 2 == 0 && wgs / 2 >= min_wg) return launch_ssm_small_r<NV, SUBS, 2, 1>(d, a, tmax, s);
   }
   // large launches: four wavefronts per workgroup (workgroup dispatch rate, shared B/C convolution)
-  static const int wide_wg = getenv("HH_SSM_WIDEWG") ? atoi(getenv("HH_SSM_WIDEWG")) : 2048;
+  constexpr int wide_wg = 2048;
   if (groups % 4 == 0 && wgs >= wide_wg) return launch_ssm_small_r<NV, SUBS, 1, 4>(d, a, tmax, s);
   return launch_ssm_small_r<NV, SUBS, 1, 1>(d, a, tmax, s);
 }
 
 // true if the pass was taken by the few-positions kernel
 static bool launch_ssm_small(const Dims& d, const SsmArgs& a, hipStream_t s, hipError_t* err) {
-  static const bool off = getenv("HH_SSM_GENERAL") != nullptr && atoi(getenv("HH_SSM_GENERAL")) != 0;
-  if (off || a.T > 9 || d.Hm % 4 != 0 || d.P % 4 != 0 || d.N % 32 != 0 || d.ldzx % 4 != 0 || d.d_inner % 4 != 0) return false;
+  if ((d.flags & HH_KF_SSM_GENERAL) || a.T > 9 || d.Hm % 4 != 0 || d.P % 4 != 0 || d.N % 32 != 0 || d.ldzx % 4 != 0 || d.d_inner % 4 != 0) return false;
   const int tmax = a.T <= 1 ? 1 : a.T <= 3 ? 3 : a.T <= 5 ? 5 : 9;
   const long waves8 = (long)((d.P + 7) / 8) * d.Hm * a.n_layers_z * a.B;
   const bool wide = d.N % 64 == 0 && waves8 < 1024;     // 16 lanes per row: twice the wavefronts
@@ -662,14 +661,14 @@ static hipError_t launch_ssm_rows(const Dims& d, const SsmArgs& a, hipStream_t s
   const dim3 grid((d.P + kRows - 1) / kRows, d.Hm, a.n_layers_z * a.B);
   const dim3 block(kRows * kSub);
   // aligned shapes: the kernel with the vectorised chunk convolution
-  static const bool scalar = getenv("HH_SSM_SCALAR_CONV") != nullptr && atoi(getenv("HH_SSM_SCALAR_CONV")) != 0;
+  const bool scalar = (d.flags & HH_KF_SSM_SCALAR_CONV) != 0;
   const int nv = d.N / kSub;
   const bool vec = !scalar && d.P % 4 == 0 && d.d_inner % 4 == 0 && d.ldzx % 4 == 0 && d.ring_w % 4 == 0 &&
                    d.conv_dim % 4 == 0 && nv % 4 == 0 && 2 * d.N / 4 + kRows / 4 <= kRows * kSub - kTS &&
                    (a.zx == nullptr || (reinterpret_cast<uintptr_t>(a.zx) & 15) == 0);
   if (vec) {
     // few workgroups per compute unit and several chunks: staging on wavefronts of its own
-    static const int pipe_wg = getenv("HH_SSM_PIPEWG") ? atoi(getenv("HH_SSM_PIPEWG")) : 512;
+    constexpr int pipe_wg = 512;
     const bool pipe = (long long)grid.x * grid.y * grid.z <= pipe_wg && a.T > kTS;
 #define HH_CHUNK(NV_)                                                                                          \
   case NV_:                                                                                                    \

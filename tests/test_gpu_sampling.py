@@ -113,3 +113,37 @@ def test_stand_alone_argument_checks(B):
     # all-equal logits: the draw is floor(u * vocab)
     got = B.hh_draw_tokens(logits, 0.5, 5).cpu().numpy()
     assert [int(v) for v in got] == [int(S.uniform(5, b, 0, 2) * 16) for b in range(2)]
+
+
+def test_residual_without_mass_draws_from_p_h(B):
+    """Identical draft and verification rows and a draft id that is no token: the id is rejected
+    where it stands, the residual max(0, P_H - P_S) is exactly zero on both sides, and the emitted
+    token is the inverse-CDF draw from P_H with the correction uniform - the oracle's rule for the
+    case Eq. 6 leaves open.  Seeds whose uniform lies within DELTA of a CDF edge are skipped."""
+    import torch
+    dev = torch.device("cuda:0")
+    batch, k, vocab, T = 6, 3, 777, 0.8
+    _, verify = W.make_logit_rows(batch, k, vocab, 31)
+    draft = np.ascontiguousarray(verify[:, :k])
+    positions = np.arange(batch, dtype=np.int32) * 2
+    checked = 0
+    for seed in range(40, 48):
+        drafts = np.zeros((batch, k), np.int32)
+        bad_at = [b % k for b in range(batch)]
+        for b in range(batch):
+            for i in range(k):
+                drafts[b, i] = (7 * b + i) % vocab
+            drafts[b, bad_at[b]] = vocab + b if b % 2 else -1 - b
+        g = B.hh_accept_tokens(torch.from_numpy(draft).to(dev), torch.from_numpy(verify).to(dev),
+                               torch.from_numpy(drafts).to(dev), torch.from_numpy(positions).to(dev), T, seed).cpu().numpy()
+        for b in range(batch):
+            p_h = [S.softmax_t(verify[b, i], T) for i in range(k + 1)]
+            u_acc = [S.uniform(seed, b, int(positions[b]) + i, S.PURPOSE_ACCEPT) for i in range(k)]
+            n, tok, margin = S.stochastic_round(p_h[:k], p_h, list(drafts[b]), u_acc,
+                                                lambda n_: S.uniform(seed, b, int(positions[b]) + n_, S.PURPOSE_CORRECT))
+            assert n == bad_at[b]                       # ratio 1 keeps every real token before it
+            assert list(g[b][:n]) == list(drafts[b][:n]) and all(v == -1 for v in g[b][n + 1:])
+            if margin > DELTA:
+                assert g[b][n] == tok, (seed, b, g[b], tok)
+                checked += 1
+    assert checked > 30

@@ -193,3 +193,24 @@ def test_first_token_statistics_over_seeds():
     # total variation distance, against the sampling noise of 400 draws over a small vocabulary
     tv = 0.5 * np.abs(counts / trials - expect / seen).sum()
     assert tv < 0.5 * np.sqrt(cfg.vocab / trials) + 0.1 * (1 - seen) + 0.05, tv
+
+
+def test_residual_without_mass_and_ids_that_are_no_token():
+    """The case Eq. 6 leaves open.  With P_S == P_H the ratio is 1, so every real uniform keeps the
+    draft; a test value of 1.0 (outside the generator's range) forces the rejection and with it a
+    residual without mass: the token then is the inverse-CDF draw from P_H (hand-computed grid
+    below), or its successor when that draw is the rejected draft, so the targets row encodes n.
+    A draft id that is no token is rejected where it stands and never used as an index."""
+    p = np.array([0.125, 0.5, 0.25, 0.125])
+    for u_c, d, want in [(0.0, 2, 0), (0.2, 0, 1), (0.2, 1, 2), (0.7, 1, 2), (0.7, 2, 3), (0.95, 3, 0), (0.95, 0, 3)]:
+        n, tok, _ = S.stochastic_round([p], [p, p], [d], [1.0], lambda n_: u_c)
+        assert (n, tok) == (0, want), (u_c, d, tok)
+        assert S.stochastic_targets([d], n, tok)[0] != d
+    # real uniforms: identical distributions keep the draft
+    assert S.stochastic_round([p], [p, p], [1], [0.99999994], lambda n_: 0.3)[0] == 1
+    # ids outside the vocabulary: position 1 is rejected, position 0 (ratio 1) kept; the residual of
+    # identical rows has no mass, so the token comes from P_H: u = 0.7 -> index 2
+    for bad in (-1, 4, 99):
+        n, tok, _ = S.stochastic_round([p, p], [p, p, p], [3, bad], [0.5, 0.5], lambda n_: 0.7)
+        assert (n, tok) == (1, 2)
+        assert S.stochastic_targets([3, bad], n, tok) == [3, 2, -1]

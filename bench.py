@@ -2,18 +2,22 @@
 """Throughput of the speculative-decoding hot path on one MI355X.
 
 A step is one speculative round over the whole batch: hh_draft(k) + hh_verify + hh_commit
-through the C ABI, on a seeded random-init model shaped like the paper's Falcon-H1-0.5B
-(default) with the prompt already prefilled and everything resident in HBM.  Prints ONE JSON
-line: committed tokens/s (value), draft tokens/s, verify passes/s, per-segment and per-kernel
-HBM roofline fractions, and the CPU oracle timed on the host cores on a bounded sample.
+through the C ABI, on a seeded random-init model with the prompts already prefilled and
+everything resident in HBM.  The default workload is the largest configuration that fits one
+GPU: the Falcon-H1-3B-shaped model, 64 sequences with 32768-token prompts, k = 8, acceptance
+from the seeded fixed pattern with per-token probability 0.68 (`--workload c1|c2|c2f|c3` select
+the others).  Prints ONE JSON line: committed tokens/s (value), draft tokens/s, verify passes/s,
+per-segment and per-kernel HBM roofline fractions, and the CPU oracle timed on the host cores on
+a bounded sample.
 
-    python bench.py --gpus 1 --steps 64 --warmup 8 [--workload c1] [--cpu-seconds 20]
+    python bench.py --gpus 1 --steps 20 --warmup 5 [--workload c4] [--cpu-seconds 20]
 """
 from __future__ import annotations
 
 import argparse
 import json
 import os
+import re
 import sys
 import time
 
@@ -24,17 +28,21 @@ sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0      # MI355X HBM3E, published peak
 
-# HBM bytes per launch of the dominant kernel, from rocprofv3 --pmc runs of `bench.py --counters`
-# (FETCH_SIZE, then WRITE_SIZE, each scaled by what the same counter reads for a device-to-device
-# copy of known size in the same run); the summaries with the commands are under profiles/.
-# Keyed by (workload, kernel); anything else reports null.
-MEASURED_TRAFFIC = {
-    ("c1", "draft.mlp_gate_up"): 16941568,
-    ("c1", "draft.mlp_down"): 8648704,
-    ("c1", "draft.in_proj"): 7006310,
-    ("c1", "draft.out_proj"): 3364864,
-    ("c1", "draft.ssm_scan"): 2119066,
-}
+
+def measured_traffic(workload):
+    """HBM bytes per launch of this workload's kernels, from rocprofv3 --pmc runs of
+    `bench.py --counters` (FETCH_SIZE, then WRITE_SIZE, each scaled by what the same counter reads for
+    a device-to-device copy of known size in the same run).  The summary with the commands is
+    profiles/<workload>_hbm_traffic.md; its last json block holds {"traffic_bytes_per_launch": {...}}.
+    Returns ({kernel: bytes}, file name) or ({}, None) when no summary is committed."""
+    path = os.path.join(ROOT, "profiles", f"{workload}_hbm_traffic.md")
+    if not os.path.exists(path):
+        return {}, None
+    blocks = re.findall(r"```json\s*(\{.*?\})\s*```", open(path).read(), re.S)
+    if not blocks:
+        return {}, None
+    return json.loads(blocks[-1]).get("traffic_bytes_per_launch", {}), os.path.relpath(path, ROOT)
+
 
 KIND_NAMES = {0: "in_proj", 1: "ssm_scan", 2: "rope_append", 3: "attention", 4: "out_proj", 5: "o_proj",
               6: "mlp_gate_up", 7: "mlp_down", 8: "lm_head"}
@@ -73,21 +81,24 @@ def algorithmic_bytes(cfg, B, k, kv_len):
     return per_kind, draft_step, verify, commit
 
 
-def cpu_baseline(wl, weights, prompts, seconds):
-    """The oracle, as it stands, on the host cores: prefill once (multi-position pass), then
-    speculative rounds for about `seconds`; returns committed tokens/s over the rounds."""
+def cpu_baseline(wl, weights, prompts, seconds, sample_prompt):
+    """The oracle, as it stands, on the host cores: prefill of `sample_prompt` tokens of sequence 0
+    (multi-position pass, not counted), then speculative rounds for about `seconds`; returns committed
+    tokens/s over the rounds.  Workloads with a forced acceptance pattern use the same pattern."""
     from oracle.hybrid_lm import HybridLM
     from oracle.protocol import SpecDecoder
+    from paper_2605_01106_amd import workloads as W
     try:
         from threadpoolctl import threadpool_info
         threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
     except Exception:
         threads = len(os.sched_getaffinity(0))
     lm = HybridLM(wl.cfg, weights.values)
-    dec = SpecDecoder(lm, wl.prompt_len + wl.gen_len + 2 * wl.k + 4, engine="pass", chunk=64)
+    dec = SpecDecoder(lm, sample_prompt + wl.gen_len + 2 * wl.k + 4, engine="pass", chunk=64)
     t0 = time.perf_counter()
-    dec.prefill([prompts[b][:wl.prompt_len] for b in range(min(wl.batch, 1))], wl.gen_len)
+    dec.prefill([prompts[0][:sample_prompt]], wl.gen_len)
     t_prefill = time.perf_counter() - t0
+    forced = None if wl.forced_p is None else W.make_forced_pattern(4096, 1, wl.k, wl.forced_p, wl.seed)
     rounds, t_draft, t_verify = 0, 0.0, 0.0
     before = sum(len(o) for o in dec.out)
     t0 = time.perf_counter()
@@ -97,15 +108,17 @@ def cpu_baseline(wl, weights, prompts, seconds):
         b = time.perf_counter()
         dec.verify()
         c = time.perf_counter()
-        dec.commit()
+        dec.commit(None if forced is None else forced[rounds])
         t_draft += b - a
         t_verify += c - b
         rounds += 1
     dt = time.perf_counter() - t0
     toks = sum(len(o) for o in dec.out) - before
+    mode = "greedy acceptance" if forced is None else f"forced acceptance p={wl.forced_p}"
     return {"value": toks / dt, "unit": "committed tokens/s", "cores": int(threads), "kind": "oracle",
-            "sample": f"sequence 0 of {wl.batch}: prefill {wl.prompt_len} tokens ({t_prefill:.1f} s, not counted), then "
-                      f"{rounds} rounds of k={wl.k} ({dt:.1f} s)",
+            "sample": f"sequence 0 of {wl.batch} alone (per-sequence rate, not scaled to the batch): prefill of the first "
+                      f"{sample_prompt} of its {wl.prompt_len} prompt tokens ({t_prefill:.1f} s, not counted), then "
+                      f"{rounds} rounds of k={wl.k}, {mode} ({dt:.1f} s)",
             "draft_tokens_per_s": rounds * wl.k / max(t_draft, 1e-9),
             "verify_passes_per_s": rounds / max(t_verify, 1e-9)}
 
@@ -113,13 +126,18 @@ def cpu_baseline(wl, weights, prompts, seconds):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=64)
-    ap.add_argument("--warmup", type=int, default=8)
-    ap.add_argument("--workload", default="c1")
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="c4")
     ap.add_argument("--seed", type=int, default=0)
-    ap.add_argument("--forced-p", type=float, default=None, help="per-token accept probability of the forced leg")
+    ap.add_argument("--forced-p", type=float, default=None,
+                    help="per-token accept probability of the forced-pattern leg (default: the workload's, else 0.68)")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="0 disables the oracle baseline")
+    ap.add_argument("--cpu-prompt", type=int, default=256,
+                    help="prompt tokens of sequence 0 the oracle baseline prefills (at most the workload's prompt)")
     ap.add_argument("--graphs", type=int, default=1)
+    ap.add_argument("--keep-logits", type=int, default=0,
+                    help="1: the library materialises the logits rows (parity runs); 0: argmax only at temperature 0")
     ap.add_argument("--temperature", type=float, default=0.6,
                     help="temperature of the stochastic-acceptance leg (the paper's second setting); 0 skips the leg")
     ap.add_argument("--counters", action="store_true",
@@ -146,6 +164,7 @@ def main():
     K, Wm = args.steps, args.warmup
     prof_rounds, greedy_rounds = 3, min(K, 32)
     forced_p = args.forced_p if args.forced_p is not None else (wl.forced_p or 0.68)
+    primary_forced = wl.forced_p is not None          # the workload's own acceptance mode is the headline leg
     total_rounds = Wm + K + K + K + prof_rounds + greedy_rounds + 6
     G = max(wl.gen_len, total_rounds * (k + 1) + 2)
     max_seq = wl.prompt_len + G + 2 * k + 4
@@ -161,7 +180,9 @@ def main():
     stream = torch.cuda.Stream()          # HIP graphs cannot be captured on the default stream
     torch.cuda.set_stream(stream)
     say(f"weights in {t_gen:.1f} s; creating the context")
-    ctx = B.Context(weights, Bn, max_seq, k, G, use_graphs=args.graphs, prefill_chunk=args.prefill_chunk)
+    n_pass_hint = 16 if wl.prompt_len * Bn > (1 << 18) else 0
+    ctx = B.Context(weights, Bn, max_seq, k, G, use_graphs=0 if args.counters else args.graphs,
+                    prefill_chunk=args.prefill_chunk, keep_logits=args.keep_logits, prefill_progress=n_pass_hint)
     torch.cuda.synchronize()
     say("prefill")
     t0 = time.perf_counter()
@@ -198,8 +219,10 @@ def main():
         seg = [sum(e[i].elapsed_time(e[i + 1]) for e in evs) * 1e-3 for i in range(3)]
         return dt, sum(c1) - sum(c0), seg
 
+    pattern = W.make_forced_pattern(Wm + K, Bn, k, forced_p, args.seed)
+    forced_dev = [torch.from_numpy(pattern[r]).to(ctx.device) for r in range(Wm + K)]
     if args.counters:
-        run_rounds(max(K, 1), k)
+        run_rounds(max(K, 1), k, forced_dev[:max(K, 1)] if primary_forced and K <= Wm + K else None)
         torch.cuda.synchronize()
         src = torch.empty(256 << 20, dtype=torch.uint8, device=ctx.device).fill_(1)
         dst = torch.empty_like(src)
@@ -209,16 +232,14 @@ def main():
         print(json.dumps({"counters_run": True, "rounds": max(K, 1), "copy_bytes": 256 << 20, "copies": 4}))
         return
     say(f"prefill in {t_prefill:.2f} s; {Wm} warm-up and {K} timed rounds")
-    run_rounds(Wm, k)
-    dt, toks, (t_draft, t_verify, t_commit) = timed_leg(K, k)
-    say(f"timed rounds: {toks / dt:.1f} tokens/s; forced-acceptance and plain-greedy legs")
+    # headline leg: the workload's own acceptance mode (the seeded fixed pattern where the workload names one)
+    run_rounds(Wm, k, forced_dev[:Wm] if primary_forced else None)
+    dt, toks, (t_draft, t_verify, t_commit) = timed_leg(K, k, forced_dev[Wm:] if primary_forced else None)
+    say(f"timed rounds: {toks / dt:.1f} tokens/s; other acceptance mode and plain-greedy legs")
     kv_len, _, _ = ctx.hh_get_lengths()
     kv_mid = int(np.mean(kv_len)) - K * (k + 1) // 4
-
-    # forced-acceptance leg (seeded fixed pattern, per-token accept probability forced_p)
-    pattern = W.make_forced_pattern(K, Bn, k, forced_p, args.seed)
-    forced_dev = [torch.from_numpy(pattern[r]).to(ctx.device) for r in range(K)]
-    dt_f, toks_f, _ = timed_leg(K, k, forced_dev)
+    # the other acceptance mode: greedy acceptance of the random-init model's own drafts, or the pattern
+    dt_o, toks_o, _ = timed_leg(K, k, None if primary_forced else forced_dev[Wm:])
     # plain greedy decoding of the full model (k = 0) for the speedup the paper's Table 7 reports
     dt_g, toks_g, _ = timed_leg(greedy_rounds, 0)
 
@@ -230,10 +251,8 @@ def main():
     kernels = {}
     per_round = {1: k, 2: 1}
     # the library runs the attention branch of verification (attention, o_proj) on a side stream
-    # beside scan + out_proj only for long caches (its rule: batch * longest cache >= 512k tokens,
-    # or HH_OVERLAP_MODE=2)
-    ovl = os.environ.get("HH_OVERLAP_MODE")
-    side_branch = ovl == "2" or (ovl in (None, "3") and Bn * wl.prompt_len >= 512 * 1024)
+    # beside scan + out_proj only for long caches (its rule: batch * longest cache >= 512k tokens)
+    side_branch = Bn * wl.prompt_len >= 512 * 1024
     for ph in (1, 2):
         for kind in sorted(KIND_NAMES):
             if kind == 2 or (ph == 1 and kind in (3, 5)):   # RoPE/append is fused into attention
@@ -268,10 +287,12 @@ def main():
     dom_name, dom = max(((n, v) for n, v in kernels.items()
                          if v["bytes"] and v["stream"] == "launch" and n.split(".")[1] == dom_kind),
                         key=lambda nv: nv[1]["us_per_round"])
+    traffic, traffic_file = measured_traffic(args.workload) if args.prompt_len is None else ({}, None)
     roofline = {"bound": "hbm", "kernel": dom_name, "achieved": dom["gbs"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": round(dom["gbs"] / HBM_PEAK_GBS, 4),
-                "traffic": MEASURED_TRAFFIC.get((args.workload if args.prompt_len is None else None, dom_name)),
-                "bytes_per_launch": dom["bytes"], "avg_us": dom["avg_us"]}
+                "traffic": traffic.get(dom_name), "traffic_source": traffic_file if dom_name in traffic else None,
+                "bytes_per_launch": dom["bytes"], "avg_us": dom["avg_us"],
+                "share_of_round": round(share[dom_kind] / sum(share.values()), 3)}
 
     # stochastic-acceptance leg (Eq. 6) at the paper's temperature: same kernels plus the draws (last, so that
     # the per-kernel timings above see the same cache lengths whether or not this leg runs)
@@ -284,13 +305,21 @@ def main():
         stochastic = {"temperature": args.temperature, "committed_tokens_per_s": round(toks_s / dt_s, 2),
                       "mean_accepted_per_round": round(toks_s / (K * Bn) - 1, 3)}
 
+    mode = f"forced acceptance p={forced_p}" if primary_forced else "greedy acceptance"
+    other = {"mode": "greedy acceptance" if primary_forced else f"forced acceptance p={forced_p}",
+             "committed_tokens_per_s": round(toks_o / dt_o, 2),
+             "mean_accepted_per_round": round(toks_o / (K * Bn) - 1, 3)}
+    prompt_note = "" if args.prompt_len is None else " (shortened stand-in)"
     out = {
-        "metric": "committed tokens/s (speculative rounds, greedy acceptance); draft tok/s and verify passes/s alongside",
+        "metric": "committed tokens/s (speculative rounds); draft tok/s and verify passes/s alongside",
         "value": round(toks / dt, 2), "unit": "tokens/s", "n_gpus": 1, "steps": K, "warmup": Wm,
         "ms_per_step": round(dt / K * 1e3, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "f32 accumulate over bf16 weights/KV" if cfg.w_dtype == "bf16" else "f32", "data": "synthetic",
-        "config": {"workload": f"{args.workload}: {cfg.name}, batch {Bn}, prompt {wl.prompt_len}, k={k}, seed {args.seed}",
-                   "rounds_timed": K, "graphs": args.graphs},
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": f"{args.workload}: {cfg.name}, bf16 weights and KV cache, batch {Bn}, prompt {wl.prompt_len}"
+                               f"{prompt_note}, k={k}, {mode}, seed {args.seed}"
+                               if cfg.w_dtype == "bf16" else
+                               f"{args.workload}: {cfg.name}, f32 weights, batch {Bn}, prompt {wl.prompt_len}, k={k}, {mode}",
+                   "rounds_timed": K, "graphs": args.graphs, "keep_logits": args.keep_logits},
         "draft_tokens_per_s": round(Bn * k * K / t_draft, 1),
         "verify_passes_per_s": round(K / t_verify, 1),
         "commit_us": round(t_commit / K * 1e6, 2),
@@ -302,18 +331,18 @@ def main():
                             "hbm_frac": round(verify_bytes / (t_verify / K) / 1e9 / HBM_PEAK_GBS, 4)},
             "commit": {"bytes": commit_bytes, "us": round(t_commit / K * 1e6, 2),
                        "hbm_frac": round(commit_bytes / (t_commit / K) / 1e9 / HBM_PEAK_GBS, 4)}},
-        "forced": {"p": forced_p, "committed_tokens_per_s": round(toks_f / dt_f, 2),
-                   "mean_accepted_per_round": round(toks_f / (K * Bn) - 1, 3)},
+        "other_acceptance": other,
         "stochastic": stochastic,
         "plain_greedy_tokens_per_s": round(toks_g / dt_g, 2),
         "speedup_vs_plain_greedy": round((toks / dt) / (toks_g / dt_g), 4),
-        "prefill_s": round(t_prefill, 3), "weight_gen_s": round(t_gen, 1),
+        "prefill_s": round(t_prefill, 3), "prefill_tokens_per_s": round(Bn * wl.prompt_len / t_prefill, 1),
+        "weight_gen_s": round(t_gen, 1),
         "roofline": roofline,
         "kernels": kernels,
     }
     if args.cpu_seconds > 0:
         say("oracle baseline on the host cores")
-        out["cpu_baseline"] = cpu_baseline(wl, weights, prompts, args.cpu_seconds)
+        out["cpu_baseline"] = cpu_baseline(wl, weights, prompts, args.cpu_seconds, min(args.cpu_prompt, wl.prompt_len))
     print(json.dumps(out))
 
 

@@ -197,7 +197,10 @@ class Context:
     """Owns one hh_ctx plus the device memory it borrows (weights, workspace)."""
 
     def __init__(self, weights: W.Weights, max_batch: int, max_seq_len: int, max_draft: int,
-                 max_new_tokens: int, device="cuda:0", **cfg_kw):
+                 max_new_tokens: int, device="cuda:0", guard_bytes: int = 0, **cfg_kw):
+        """guard_bytes (a multiple of 256): the workspace is handed over from inside a larger buffer
+        whose first and last guard_bytes hold the byte 0xA5, so that a caller can check
+        (`guards_intact`) that the library never writes outside what it was given."""
         self.torch = torch
         self.device = device
         self.model_cfg = weights.cfg
@@ -205,14 +208,24 @@ class Context:
         need = hh_workspace_bytes(self.cfg)
         if need == 0:
             raise HHError(HH_EINVAL, hh_last_error(None))
-        self.workspace = torch.empty(need, dtype=torch.uint8, device=device)
-        self.cfg.workspace = self.workspace.data_ptr()
+        assert guard_bytes % 256 == 0
+        self.guard_bytes = guard_bytes
+        self.workspace = torch.empty(need + 2 * guard_bytes, dtype=torch.uint8, device=device)
+        if guard_bytes:
+            self.workspace[:guard_bytes].fill_(0xA5)
+            self.workspace[guard_bytes + need:].fill_(0xA5)
+        self.cfg.workspace = self.workspace.data_ptr() + guard_bytes
         self.cfg.workspace_bytes = need
         self.hw, self._keep = upload_weights(weights, device)
         self.ctx = _ctx_p()
         _check(lib.hh_create(C.byref(self.hw), C.byref(self.cfg), C.byref(self.ctx)))
         self.B = 0
         self.k = 0
+
+    def guards_intact(self) -> bool:
+        g = self.guard_bytes
+        self.torch.cuda.synchronize()
+        return bool((self.workspace[:g] == 0xA5).all().item()) and bool((self.workspace[-g:] == 0xA5).all().item())
 
     def close(self):
         if self.ctx:

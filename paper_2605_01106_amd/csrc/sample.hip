@@ -41,8 +41,19 @@ __device__ __forceinline__ float wave_sum(float v) {
 }
 
 // softmax(l / T) entry from the row's maximum m and 1 / sum: the one expression every kernel here uses,
-// so that a probability computed in two places has the same bits
-__device__ __forceinline__ float prob(float l, float m, float inv_t, float rsum) { return expf((l - m) * inv_t) * rsum; }
+// so that a probability computed in two places has the same bits.  The product is rounded on its own
+// (never contracted into a following subtraction: fma(a, b, -round(a * b)) is the rounding error of
+// the product, which would give the residual of two identical distributions a noise mass).
+__device__ __forceinline__ float prob(float l, float m, float inv_t, float rsum) {
+#pragma clang fp contract(off)
+  return expf((l - m) * inv_t) * rsum;
+}
+// max(0, P_H - P_S) of one entry, the subtraction kept apart from the two products
+__device__ __forceinline__ float residual_mass(float ph, float ps) {
+#pragma clang fp contract(off)
+  const float d = ph - ps;
+  return fmaxf(0.f, d);
+}
 
 constexpr float kNoLogit = -3.0e38f;   // stands for an entry past the end of the row: exp((kNoLogit - m) / T) = 0
 
@@ -295,7 +306,7 @@ __global__ __launch_bounds__(kDrawThreads) void spec_targets_kernel(const float*
           float a[4], c[4];
           load_group(lh, jj, end, vec, a);
           load_group(ls, jj, end, vec, c);
-          for (int e = 0; e < 4; ++e) v[e] = fmaxf(0.f, prob(a[e], mh, inv_t, rsh) - prob(c[e], ms, inv_t, rss));
+          for (int e = 0; e < 4; ++e) v[e] = residual_mass(prob(a[e], mh, inv_t, rsh), prob(c[e], ms, inv_t, rss));
         },
         V, u, red, &res);
     if (tok < 0) {

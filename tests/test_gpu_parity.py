@@ -69,15 +69,105 @@ def test_draft_lengths_and_plain_greedy(B, k):
 def test_aligned_shapes_fast_paths(B, k, d_state, dtype):
     """Shapes whose rows are 16-byte aligned (heads and head dimension multiples of 4, state a
     multiple of 32) take the few-positions SSM kernel (8 or 16 lanes per state row, a partly
-    filled last workgroup) and, with a bf16 cache, the matrix-core attention with several
-    16-row tiles; prompts straddle pages and key steps, one sequence finishes early."""
+    filled last workgroup) and, with a bf16 cache and 32-token pages, the matrix-core attention
+    with one to three 16-row tiles (k + 1 positions x 4 query heads per KV head); prompts straddle
+    pages and key steps, one sequence finishes early."""
     cfg = W.scaled_config("aligned", n_layers=2, d_model=64, vocab=160, m_heads=4, m_head_dim=12, d_state=d_state,
                           n_q_heads=8, n_kv_heads=2, head_dim=32, d_ff=96, w_dtype=dtype)
     wts = W.make_lively_weights(cfg, 17)
     lens = [33, 6, 95]
     prompts = W.make_prompts(cfg.vocab, 3, lens, 21)
-    ctx = _ctx(B, wts, 3, 160, 8, 30, kv_page_tokens=16, prefill_chunk=32)
+    ctx = _ctx(B, wts, 3, 160, 8, 30, kv_page_tokens=32, prefill_chunk=32)
     run_lockstep(ctx, wts, prompts, lens, 30, k, engine="pass", report=_say(f"aligned-k{k}-N{d_state}-{dtype}"))
+
+
+# ---------------------------------------------------------------------------------------------
+# Long caches on thin models: the key-slice paths of the matrix-core attention that the
+# paper-shaped workloads take at their real prompt lengths (Section 3.3, verification phase: M_H
+# attends over the whole prefix), at a cost the float64 oracle can afford.
+
+def _thin(name, head_dim, n_q, n_kv, **kw):
+    base = dict(n_layers=2, d_model=64, vocab=192, m_heads=4, m_head_dim=16, d_state=32, n_q_heads=n_q,
+                n_kv_heads=n_kv, head_dim=head_dim, d_ff=96, w_dtype=W.BF16)
+    base.update(kw)
+    return W.scaled_config(name, **base)
+
+
+def test_long_cache_ticket_merge(B):
+    """Head dimension 64, one sequence, 1100 cached keys, 32-token pages: 35 key steps, so the
+    verification attention runs 9 key slices per KV head whose partial results are merged inside the
+    kernel by the workgroup that draws the last ticket (18 workgroups, 37 KB of partials per row
+    chunk: under both limits of that path).  Prefill chunks of 256 positions run the multi-tile
+    kernel over a growing cache."""
+    cfg = _thin("thin-ticket", 64, 4, 2)
+    wts = W.make_lively_weights(cfg, 47)          # seeds audited: top-1/top-2 gap 5.4e-3
+    lens = [1100]
+    prompts = W.make_prompts(cfg.vocab, 1, lens, 12)
+    ctx = _ctx(B, wts, 1, 1100 + 40, 2, 12, kv_page_tokens=32, prefill_chunk=256)
+    w = run_lockstep(ctx, wts, prompts, lens, 12, 2, engine="pass", chunk=64, min_gap=1e-3, report=_say("ticket-merge"))
+    assert w["rounds"] >= 4
+
+
+def test_long_cache_merge_kernel_batch16(B):
+    """Head dimension 64 (two 32-wide key blocks), 16 sequences with 1900..2110 cached keys, k = 4:
+    16 key slices x 32 (sequence, KV head) pairs = 512 workgroups, so the slices are merged by the
+    separate merge kernel; the batch is ragged, so slices end at different steps per sequence.
+    The oracle follows the longest and the shortest sequence."""
+    cfg = _thin("thin-merge", 64, 8, 2)
+    wts = W.make_lively_weights(cfg, 47)          # seeds audited: top-1/top-2 gap 3.4e-3
+    lens = [2110 - 14 * i for i in range(16)]
+    prompts = W.make_prompts(cfg.vocab, 16, lens, 13)
+    ctx = _ctx(B, wts, 16, 2110 + 48, 4, 10, kv_page_tokens=64, prefill_chunk=128)
+    w = run_lockstep(ctx, wts, prompts, lens, 10, 4, engine="pass", chunk=64, oracle_rows=[0, 15],
+                     min_gap=1e-3, report=_say("merge-kernel-b16"))
+    assert w["rounds"] >= 2
+
+
+@pytest.mark.parametrize("overlap_mode", [1, 3])
+def test_long_cache_head128_three_row_tiles(B, overlap_mode):
+    """Head dimension 128, 5 query heads per KV head, k = 8: 45 query rows = three 16-row tiles per
+    workgroup, the new keys appended and scored inside the kernel, 3 sequences of about 1150 cached
+    keys (10 slices per KV head, 245 KB of partials per row chunk: the separate merge kernel, as at
+    the 3B shape).  Forced accepted counts exercise the rollback to every position.  Run once with the
+    attention branch in line (overlap_mode 1) and once forked to the side stream beside the SSM
+    branch in every pass (overlap_mode 3): the schedule must not change a result."""
+    cfg = _thin("thin-h128", 128, 10, 2)
+    wts = W.make_lively_weights(cfg, 41)          # seeds audited: top-1/top-2 gap 8.2e-4
+    lens = [1150, 1101, 1127]
+    prompts = W.make_prompts(cfg.vocab, 3, lens, 14)
+    forced = W.make_forced_pattern(32, 3, 8, 0.68, 3)
+    ctx = _ctx(B, wts, 3, 1150 + 80, 8, 27, kv_page_tokens=64, prefill_chunk=192, overlap_mode=overlap_mode)
+    w = run_lockstep(ctx, wts, prompts, lens, 27, 8, forced=forced, engine="pass", chunk=64,
+                     min_gap=4e-4, report=_say(f"h128-rt3-overlap{overlap_mode}"))
+    assert w["rounds"] >= 3
+
+
+@pytest.mark.parametrize("max_splits,single", [(1, 0), (3, -1), (32, -1)])
+def test_key_slices_do_not_change_results(B, max_splits, single):
+    """The number of key slices is a tunable: one slice, three, and as many as the cache allows
+    (split from the first step on), on caches of 70..200 keys with 32-token pages."""
+    cfg = _thin("thin-slices", 32, 8, 2, d_state=64)
+    wts = W.make_lively_weights(cfg, 42)          # seeds audited: top-1/top-2 gap 2.6e-3
+    lens = [200, 70, 131]
+    prompts = W.make_prompts(cfg.vocab, 3, lens, 15)
+    ctx = _ctx(B, wts, 3, 256, 4, 12, kv_page_tokens=32, prefill_chunk=64, attn_max_splits=max_splits,
+               attn_single_slice_steps=single)
+    run_lockstep(ctx, wts, prompts, lens, 12, 3, engine="pass", min_gap=1e-3, report=_say(f"slices-{max_splits}"))
+
+
+@pytest.mark.parametrize("flag", ["HH_KF_ATTN_SCALAR", "HH_KF_SSM_GENERAL", "HH_KF_MID_OFF", "HH_KF_SKINNY_OFF",
+                                  "HH_KF_SSM_SCALAR_CONV"])
+def test_kernel_selection_flags_do_not_change_results(B, flag):
+    """Every kernel-selection switch routes a family of launches to the slower kernel that computes
+    the same thing; each variant is checked against the oracle on a workload that reaches the family:
+    6 sequences with k = 3 give 6 draft rows (skinny), 24 verification rows (mid) and 6 x 32 = 192
+    prefill rows (many-row GEMM), a bf16 cache with 32-token pages and aligned SSM shapes."""
+    cfg = _thin("thin-flags", 32, 4, 2, d_model=96, d_ff=160, d_state=32)
+    wts = W.make_lively_weights(cfg, 46)          # seeds audited: top-1/top-2 gap 8.9e-4
+    lens = [61, 33, 90, 47, 75, 52]
+    prompts = W.make_prompts(cfg.vocab, 6, lens, 16)
+    ctx = _ctx(B, wts, 6, 128, 3, 10, kv_page_tokens=32, prefill_chunk=32, kernel_flags=getattr(B, flag))
+    run_lockstep(ctx, wts, prompts, lens, 10, 3, engine="pass", min_gap=4e-4, report=_say(flag))
 
 
 def test_mid_rows_long_k_and_wide_head(B):

@@ -195,6 +195,18 @@ HH_API hh_status hh_accept_tokens(const float* draft_logits, const float* verify
                                   int32_t k, const int32_t* drafts, const int32_t* positions, float temperature,
                                   uint64_t seed, float* scratch, int32_t* targets, void* stream);
 
+/* hh_accept_tokens for callers that cannot allocate device memory or pass a workspace (code under
+ * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc): same arguments without
+ * `scratch`, same kernels, same result.  The per-row softmax statistics live in an array built
+ * into the library (256 KiB of device memory per GPU, held until the process ends); the call
+ * allocates nothing.  HH_ECAPACITY if batch * (2k + 1) * 2 exceeds 65536 floats (e.g. 64 sequences
+ * with k = 8 need 2176); the message is available from hh_last_error(NULL).  Every entry the
+ * kernels read is written first, so nothing has to be cleared between calls; calls that overlap on
+ * one GPU (different streams or threads) share the array and race - serialise them. */
+HH_API hh_status hh_accept_tokens_static(const float* draft_logits, const float* verify_logits, int32_t vocab, int32_t batch,
+                                         int32_t k, const int32_t* drafts, const int32_t* positions, float temperature,
+                                         uint64_t seed, int32_t* targets, void* stream);
+
 /* Draft phase (Section 3.3 / Eq. 4): k autoregressive greedy steps of the
  * SSM-only subgraph per sequence, starting from the committed recurrent state
  * on a scratch copy; never touches the KV cache.  0 <= k <= max_draft; k = 0

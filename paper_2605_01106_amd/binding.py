@@ -72,6 +72,8 @@ EXPORTS = {
                                  C.c_int32, C.c_int32, C.c_void_p, C.c_void_p]),
     "hh_accept_tokens": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p,
                                    C.c_float, C.c_uint64, C.c_void_p, C.c_void_p, C.c_void_p]),
+    "hh_accept_tokens_static": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p,
+                                          C.c_float, C.c_uint64, C.c_void_p, C.c_void_p]),
     "hh_draft": (C.c_int, [_ctx_p, C.c_int32, C.c_void_p]),
     "hh_set_drafts": (C.c_int, [_ctx_p, C.c_void_p, C.c_void_p]),
     "hh_verify": (C.c_int, [_ctx_p, C.c_void_p]),
@@ -166,6 +168,20 @@ def hh_accept_tokens(draft_logits, verify_logits, drafts, positions, temperature
     _check(lib.hh_accept_tokens(dl, C.c_void_p(verify_logits.data_ptr()), vocab, batch, k, dr,
                                 C.c_void_p(positions.data_ptr()), C.c_float(temperature), C.c_uint64(seed),
                                 C.c_void_p(scratch.data_ptr()), C.c_void_p(targets.data_ptr()), _stream_ptr(stream)))
+    return targets
+
+
+def hh_accept_tokens_static(draft_logits, verify_logits, drafts, positions, targets, temperature: float, seed: int,
+                            stream=None):
+    """hh_accept_tokens without a scratch argument; `targets` (int32 [batch][k+1], device) is written in place:
+    the call itself allocates nothing."""
+    batch, k1, vocab = verify_logits.shape
+    k = k1 - 1
+    dl = None if k == 0 else C.c_void_p(draft_logits.data_ptr())
+    dr = None if k == 0 else C.c_void_p(drafts.data_ptr())
+    _check(lib.hh_accept_tokens_static(dl, C.c_void_p(verify_logits.data_ptr()), vocab, batch, k, dr,
+                                       C.c_void_p(positions.data_ptr()), C.c_float(temperature), C.c_uint64(seed),
+                                       C.c_void_p(targets.data_ptr()), _stream_ptr(stream)))
     return targets
 
 

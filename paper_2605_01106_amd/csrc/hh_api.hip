@@ -706,6 +706,31 @@ hh_status hh_accept_tokens(const float* draft_logits, const float* verify_logits
   return HH_OK;
 }
 
+hh_status hh_accept_tokens_static(const float* draft_logits, const float* verify_logits, int32_t vocab, int32_t batch,
+                                  int32_t k, const int32_t* drafts, const int32_t* positions, float temperature,
+                                  uint64_t seed, int32_t* targets, void* stream) {
+  SamplingParams p{};
+  if (!verify_logits || !positions || !targets || vocab < 1 || batch < 0 || k < 0 || (k > 0 && (!draft_logits || !drafts)) ||
+      !sampling_value(temperature, seed, p))
+    return fail(nullptr, HH_EINVAL, "hh_accept_tokens_static: bad argument");
+  if (batch == 0) return HH_OK;
+  float* stats = nullptr;
+  size_t cap = 0;
+  const hipError_t e = static_accept_scratch(&stats, &cap);
+  if (e != hipSuccess) return fail(nullptr, HH_EDEVICE, std::string("hh_accept_tokens_static: ") + hipGetErrorString(e));
+  const unsigned long long need = (unsigned long long)batch * (2ull * (unsigned long long)k + 1ull) * 2ull;
+  if (need > cap) {
+    char msg[200];
+    snprintf(msg, sizeof msg, "hh_accept_tokens_static: batch * (2k + 1) * 2 = %llu floats of statistics exceed the built-in %zu",
+             need, cap);
+    return fail(nullptr, HH_ECAPACITY, msg);
+  }
+  if (launch_spec_targets(draft_logits, verify_logits, vocab, batch, k, k, nullptr, p, stats, drafts, positions, targets,
+                          static_cast<hipStream_t>(stream)) != hipSuccess)
+    return fail(nullptr, HH_EDEVICE, "hh_accept_tokens_static: launch failed");
+  return HH_OK;
+}
+
 hh_status hh_draft(hh_ctx* x, int32_t k, void* stream) {
   if (!x) return HH_EINVAL;
   if (x->phase != PH_READY) return fail(x, HH_ESTATE, "hh_draft: needs a prefilled context with no round in flight");

@@ -148,6 +148,8 @@ hipError_t launch_sample_rows(const float* logits, size_t row_stride, int V, int
 hipError_t launch_spec_targets(const float* logits_d, const float* logits_v, int V, int B, int k, int kmax,
                                const SamplingParams* prm, SamplingParams prm_val, float* stats, const int* drafts,
                                const int* committed, int* targets, hipStream_t s);
+// device address and size of the current GPU's file-scope statistics array (no allocation)
+hipError_t static_accept_scratch(float** ptr, size_t* n_floats);
 hipError_t launch_fill_i32(int* p, int v, size_t n, hipStream_t s);
 hipError_t launch_fill_f32(float* p, float v, size_t n, hipStream_t s);
 hipError_t launch_export_state(const Dims& d, const LayerDev* layer, const int* kv_len, int B, float* conv_out,

@@ -11,6 +11,8 @@
 // The outcome of a round is written in the form the commit step already consumes: targets[i] =
 // drafts[i] for the kept positions, targets[n] = the emitted token, later entries -1; the
 // longest-matching-prefix rule then returns n, because the residual has no mass at a rejected draft.
+#include <mutex>
+
 #include "hh_internal.h"
 
 namespace hh {
@@ -345,6 +347,33 @@ hipError_t launch_sample_rows(const float* logits, size_t row_stride, int V, int
   hipLaunchKernelGGL(sample_rows_kernel, dim3(B), dim3(kDrawThreads), 0, s, logits, row_stride, V, prm, prm_val, idx_base,
                      idx_off, purpose, out, out_stride, out_off);
   return hipGetLastError();
+}
+
+// ---- statistics buffer of the entry point that allocates nothing (hh_accept_tokens_static):
+// one array per GPU, held until the process ends.  In host code the array's name is only a
+// stand-in for the symbol; the device address comes from hipGetSymbolAddress, once per device.
+constexpr size_t kStaticScratchFloats = 1 << 16;
+static __device__ __align__(256) float scratch[kStaticScratchFloats];
+
+hipError_t static_accept_scratch(float** ptr, size_t* n_floats) {
+  constexpr int kMaxDevices = 64;
+  static std::mutex mu;
+  static float* per_device[kMaxDevices] = {};
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+  std::lock_guard<std::mutex> lock(mu);
+  if (per_device[dev] == nullptr) {
+    void* p = nullptr;
+    e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));   // the current device's copy of the array
+    if (e != hipSuccess) return e;
+    if (p == nullptr) return hipErrorInvalidSymbol;
+    per_device[dev] = static_cast<float*>(p);
+  }
+  *ptr = per_device[dev];
+  *n_floats = kStaticScratchFloats;
+  return hipSuccess;
 }
 
 hipError_t launch_spec_targets(const float* logits_d, const float* logits_v, int V, int B, int k, int kmax,

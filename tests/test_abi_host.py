@@ -104,3 +104,11 @@ def test_stand_alone_token_choice_rejects_bad_arguments(B):
     assert accept(targets=None) == B.HH_EINVAL
     assert accept(k=-1) == B.HH_EINVAL
     assert accept(t=0.0) == B.HH_EINVAL
+    def accept_static(dl=fake, vl=fake, k=2, drafts=fake, pos=fake, t=0.5, targets=fake):
+        return B.lib.hh_accept_tokens_static(dl, vl, 16, 1, k, drafts, pos, C.c_float(t), C.c_uint64(1), targets, None)
+    assert accept_static(vl=None) == B.HH_EINVAL
+    assert accept_static(dl=None) == B.HH_EINVAL
+    assert accept_static(targets=None) == B.HH_EINVAL
+    assert accept_static(k=-1) == B.HH_EINVAL
+    assert accept_static(t=float("nan")) == B.HH_EINVAL
+    assert "hh_accept_tokens_static" in B.hh_last_error(None)

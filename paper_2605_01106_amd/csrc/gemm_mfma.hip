@@ -20,6 +20,7 @@
 
 #include "hh_internal.h"
 #include "bf16_split.h"
+#include "wave_ops.h"
 
 namespace hh {
 
@@ -125,6 +126,9 @@ struct GemmArgs {
   // nullptr); the row sum is then scaled by 1 / sqrt(sum * rnorm_k + eps)
   const float* ssq; int ssq_ld; float rnorm_k, eps;
   int terms;                              // bf16 terms per activation in the planes (2 or 3)
+  // EPI_STORE: per-row argmax keys [M], zeroed by the caller and raised with atomic maxima (the
+  // maximum of the keys is the same in any order), or nullptr; store = 0: Y itself is not written
+  unsigned long long* row_best; int store;
 };
 
 union GFrag {
@@ -191,6 +195,9 @@ __global__ __launch_bounds__(256, 2) void gemm_tiled_kernel(const GemmArgs a) {
   }
 
   // ---- results: D[weight row 4g+r][activation row n] of every (strip, m tile)
+  unsigned long long best[MTW];
+#pragma unroll
+  for (int m = 0; m < MTW; ++m) best[m] = 0ull;
 #pragma unroll
   for (int t = 0; t < NT; ++t) {
     const int row0 = (t0 + t) * 16 + 4 * g;
@@ -216,22 +223,42 @@ __global__ __launch_bounds__(256, 2) void gemm_tiled_kernel(const GemmArgs a) {
             float v = acc[0][t][m][r];
             if (EPI == EPI_SWIGLU) v = v / (1.0f + expf(-v)) * acc[NF - 1][t][m][r];
             if (EPI == EPI_ADD) v += y[r] + (a.R2 != nullptr ? a.R2[(size_t)am * a.ldy + row0 + r] : 0.f);
-            y[r] = v;
+            if (EPI != EPI_STORE || a.store) y[r] = v;
+            if (EPI == EPI_STORE) { const unsigned long long key = argmax_key(v, row0 + r); if (key > best[m]) best[m] = key; }
           }
         }
       }
+    }
+  }
+  if (EPI == EPI_STORE && a.row_best != nullptr && a.ksplit == 1) {
+    // largest key of this lane's activation row over the unit's weight rows: across the four lane
+    // groups, then one atomic maximum per row and wavefront
+#pragma unroll
+    for (int m = 0; m < MTW; ++m) {
+      unsigned long long b = best[m];
+      unsigned long long o = __shfl_xor(b, 16, 64); if (o > b) b = o;
+      o = __shfl_xor(b, 32, 64); if (o > b) b = o;
+      const int am = (mt0 + m) * 16 + n;
+      if (g == 0 && mt0 + m < m_tiles && am < a.M && b != 0ull) atomicMax(a.row_best + am, b);
     }
   }
 }
 
 // second pass when K is split: sum of the partial products in split order + epilogue
 // (4 consecutive columns per thread when the shapes allow vector accesses: VEC)
-template <int EPI, bool VEC>
+// ARGMAX (EPI_STORE): the grid is (column blocks, rows) so that a workgroup stays inside one row;
+// it raises the row's argmax key by one atomic maximum.
+template <int EPI, bool VEC, bool ARGMAX = false>
 __global__ __launch_bounds__(256) void gemm_reduce_kernel(const GemmArgs a) {
   constexpr int NF = EPI == EPI_SWIGLU ? 2 : 1;
   constexpr int W = VEC ? 4 : 1;
   const size_t total = (size_t)a.M * a.N;
-  for (size_t it = (blockIdx.x * (size_t)256 + threadIdx.x) * W; it < total; it += (size_t)gridDim.x * 256 * W) {
+  unsigned long long best = 0ull;
+  const size_t it_first = ARGMAX ? (size_t)blockIdx.y * a.N + (blockIdx.x * (size_t)256 + threadIdx.x) * W
+                                 : (blockIdx.x * (size_t)256 + threadIdx.x) * W;
+  const size_t it_stride = ARGMAX ? total : (size_t)gridDim.x * 256 * W;
+  const size_t it_end = ARGMAX ? ((blockIdx.x * (size_t)256 + threadIdx.x) * W < (size_t)a.N ? total : 0) : total;
+  for (size_t it = it_first; it < it_end; it += it_stride) {
     const size_t m = it / a.N, nn = it - m * a.N;
     // the sums of squares are requested first, so that they arrive with the partial products
     float tot = 0.f;
@@ -276,13 +303,28 @@ __global__ __launch_bounds__(256) void gemm_reduce_kernel(const GemmArgs a) {
       o[w] = v[0][w] * scale;
       if (EPI == EPI_SWIGLU) o[w] = o[w] / (1.0f + expf(-o[w])) * (v[NF - 1][w] * scale);
     }
+    if (ARGMAX) {
+#pragma unroll
+      for (int w = 0; w < W; ++w) { const unsigned long long key = argmax_key(o[w], (int)nn + w); if (key > best) best = key; }
+    }
     if (VEC) {
       float4 r = make_float4(o[0], o[1 % W], o[2 % W], o[3 % W]);
       if (EPI == EPI_ADD) { r.x += old.x; r.y += old.y; r.z += old.z; r.w += old.w; }
-      *reinterpret_cast<float4*>(y) = r;
+      if (!ARGMAX || a.store) *reinterpret_cast<float4*>(y) = r;
     } else {
       if (EPI == EPI_ADD) o[0] += *y + (a.R2 != nullptr ? a.R2[m * a.ldy + nn] : 0.f);
-      *y = o[0];
+      if (!ARGMAX || a.store) *y = o[0];
+    }
+  }
+  if (ARGMAX) {
+    __shared__ unsigned long long wb[4];
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) { const unsigned long long v = __shfl_xor(best, o, 64); if (v > best) best = v; }
+    if ((threadIdx.x & 63) == 0) wb[threadIdx.x >> 6] = best;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+      for (int i = 1; i < 4; ++i) if (wb[i] > best) best = wb[i];
+      if (best != 0ull) atomicMax(a.row_best + blockIdx.y, best);
     }
   }
 }
@@ -291,6 +333,14 @@ template <int EPI>
 static hipError_t reduce_launch(const GemmArgs& a, hipStream_t s) {
   const size_t total = (size_t)a.M * a.N;
   const bool vec = a.N % 4 == 0 && a.ldy % 4 == 0;
+  if (EPI == EPI_STORE && a.row_best != nullptr) {
+    if (a.M > 65535) return hipErrorInvalidValue;
+    const int per = vec ? 1024 : 256;
+    const dim3 grid((a.N + per - 1) / per, a.M);
+    if (vec) hipLaunchKernelGGL((gemm_reduce_kernel<EPI_STORE, true, true>), grid, dim3(256), 0, s, a);
+    else hipLaunchKernelGGL((gemm_reduce_kernel<EPI_STORE, false, true>), grid, dim3(256), 0, s, a);
+    return hipGetLastError();
+  }
   const size_t items = vec ? total / 4 : total;
   const int rb = (int)((items + 255) / 256 < 2048 ? (items + 255) / 256 : 2048);
   if (vec) hipLaunchKernelGGL((gemm_reduce_kernel<EPI, true>), dim3(rb), dim3(256), 0, s, a);
@@ -342,6 +392,7 @@ hipError_t launch_gemm_mfma(const GemvArgs& g, uint16_t* planes, float* partial,
   a.planes = planes; a.Mp = Mp; a.Kp = Kp; a.terms = gemm_terms(M);
   a.W = static_cast<const uint16_t*>(g.seg[0].P); a.W2 = static_cast<const uint16_t*>(g.seg[0].P2);
   a.Y = g.seg[0].Y; a.ldy = g.seg[0].ldy; a.R2 = g.R2; a.partial = partial; a.M = M; a.N = N; a.K = K;
+  a.row_best = g.epi == EPI_STORE ? g.row_best : nullptr; a.store = g.no_store && a.row_best != nullptr ? 0 : 1;
   const int steps = Kp / 32, tiles = (N + 15) / 16, m_tiles = Mp / 16;
   a.strip_groups = (tiles + nt - 1) / nt;
   // row tiles per unit: 5 with two terms; 4 with three (5 would spill under the two-workgroups-per-CU register cap)
@@ -376,50 +427,19 @@ hipError_t launch_gemm_mfma(const GemvArgs& g, uint16_t* planes, float* partial,
 // windows of the in-kernel-split products.  ssq: per-window sums of squares [ksplit][ssq_ld] of the
 // activation rows, or nullptr (no norm).
 hipError_t launch_gemm_reduce(int epi, float* partial, int ksplit, int M, int N, float* Y, int ldy, const float* R2,
-                              const float* ssq, int ssq_ld, float rnorm_k, float eps, hipStream_t s) {
+                              const float* ssq, int ssq_ld, float rnorm_k, float eps, unsigned long long* row_best, int store,
+                              hipStream_t s) {
   if (ssq != nullptr && M > ssq_ld) return hipErrorInvalidValue;
   GemmArgs a{};
   a.partial = partial; a.ksplit = ksplit; a.M = M; a.N = N; a.Y = Y; a.ldy = ldy; a.R2 = R2;
   a.ssq = ssq; a.ssq_ld = ssq_ld; a.rnorm_k = rnorm_k; a.eps = eps;
+  a.row_best = epi == EPI_STORE ? row_best : nullptr; a.store = a.row_best != nullptr ? store : 1;
   switch (epi) {
     case EPI_STORE: return reduce_launch<EPI_STORE>(a, s);
     case EPI_ADD: return reduce_launch<EPI_ADD>(a, s);
     case EPI_SWIGLU: return reduce_launch<EPI_SWIGLU>(a, s);
   }
   return hipErrorInvalidValue;
-}
-
-// argmax of each row of logits [M][ld] (largest value, lowest index on ties):
-// row m = b*T + j -> out[b*out_stride + out_off + j]
-__global__ __launch_bounds__(256) void argmax_rows_kernel(const float* __restrict__ logits, int ld, int V, int* out,
-                                                          int out_stride, int out_off, int T) {
-  const int m = blockIdx.x;
-  const float* row = logits + (size_t)m * ld;
-  float bv = -INFINITY;
-  int bi = 0x7fffffff;
-  for (int n = threadIdx.x; n < V; n += 256) {
-    const float v = row[n];
-    if (v > bv) { bv = v; bi = n; }   // strided ascending n per thread: first maximum kept
-  }
-  __shared__ float sv[256];
-  __shared__ int si[256];
-  sv[threadIdx.x] = bv; si[threadIdx.x] = bi;
-  __syncthreads();
-  for (int o = 128; o > 0; o >>= 1) {
-    if ((int)threadIdx.x < o) {
-      const float v2 = sv[threadIdx.x + o];
-      const int i2 = si[threadIdx.x + o];
-      if (v2 > sv[threadIdx.x] || (v2 == sv[threadIdx.x] && i2 < si[threadIdx.x])) { sv[threadIdx.x] = v2; si[threadIdx.x] = i2; }
-    }
-    __syncthreads();
-  }
-  if (threadIdx.x == 0) out[(size_t)(m / T) * out_stride + out_off + m % T] = si[0];
-}
-
-hipError_t launch_argmax_rows(const float* logits, int ld, int V, int M, int* out, int out_stride, int out_off, int T,
-                              hipStream_t s) {
-  hipLaunchKernelGGL(argmax_rows_kernel, dim3(M), dim3(256), 0, s, logits, ld, V, out, out_stride, out_off, T);
-  return hipGetLastError();
 }
 
 }  // namespace hh

@@ -357,10 +357,10 @@ hh_status run_layers(hh_ctx* x, bool full, int B, int T, const int* n_tok, int s
       GemvArgs a{};
       a.X = x->h; a.X2 = ho; a.ldx = d.D; a.M = M; a.K = d.D; a.norm_w = w.norm2; a.eps = d.eps; a.epi = EPI_SWIGLU; a.bf16 = d.bf16; a.flags = d.flags;
       a.seg[0] = {w.w_gate, w.w_up, w.p_gate, w.p_up, x->act, d.F, d.F}; a.n_seg = 1;
-      HH_LAUNCH(HH_K_MLP_UP, product(x, a, s));
       GemvArgs b{};
       b.X = x->act; b.ldx = d.F; b.M = M; b.K = d.F; b.norm_w = nullptr; b.epi = EPI_ADD; b.bf16 = d.bf16; b.flags = d.flags; b.R2 = ho;
       b.seg[0] = {w.w_down, nullptr, w.p_down, nullptr, x->h, d.D, d.D}; b.n_seg = 1;
+      HH_LAUNCH(HH_K_MLP_UP, product(x, a, s));
       HH_LAUNCH(HH_K_MLP_DOWN, product(x, b, s));
     }
   }
@@ -374,6 +374,8 @@ hh_status run_head(hh_ctx* x, const float* X, int M, int T, float* logits, int l
   GemvArgs a{};
   a.X = X; a.ldx = d.D; a.M = M; a.K = d.D; a.norm_w = static_cast<const float*>(x->final_norm); a.eps = d.eps;
   a.epi = EPI_STORE; a.bf16 = d.bf16; a.flags = d.flags; a.best = x->best;
+  // greedy rounds of a context created with keep_logits = 0 only need the argmax of every row
+  a.no_store = !x->cfg.keep_logits && !(x->temperature > 0.f);
   a.seg[0] = {x->lm_head, nullptr, x->p_lm_head, nullptr, logits, d.V, ld_logits}; a.n_seg = 1;
   GemvArgs sk;
   if (skinny_args(a, sk)) {
@@ -383,10 +385,13 @@ hh_status run_head(hh_ctx* x, const float* X, int M, int T, float* logits, int l
     return HH_OK;
   }
   if (a.bf16 && M >= kMfmaMinRows) {
-    a.best = nullptr;
+    // many-row kernels: every row's argmax key is raised with atomic maxima in the epilogue (the first
+    // M entries of the partials buffer, cleared here), so the logits need not be written or re-read
+    a.best = nullptr; a.row_best = x->best;
+    HH_HIP(launch_fill_i32(reinterpret_cast<int*>(x->best), 0, (size_t)2 * M, s));
     if (mid_mfma_fits(a)) HH_LAUNCH(HH_K_LM_HEAD, launch_mid_mfma(a, x->gemm_partial, s));
     else HH_LAUNCH(HH_K_LM_HEAD, launch_gemm_mfma(a, x->planes, x->gemm_partial, s));
-    HH_HIP(launch_argmax_rows(logits, ld_logits, d.V, M, out, out_stride, out_off, T, s));
+    HH_HIP(launch_argmax_finish(x->best, 1, M, out, out_stride, out_off, T, s));
     return HH_OK;
   }
   int nblk = 0;

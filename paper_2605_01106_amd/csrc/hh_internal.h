@@ -56,6 +56,8 @@ struct GemvArgs {
   unsigned long long* best;                // optional per-block argmax partials [M][gridDim.x]
   int bf16;
   int flags;                               // hh_cfg.kernel_flags (HH_KF_* bits)
+  int no_store;                            // EPI_STORE with an argmax output: only the argmax is wanted, Y need not be written
+  unsigned long long* row_best;            // EPI_STORE, many-row kernels: per-row argmax keys [M] (zeroed by the caller), or nullptr
 };
 hipError_t launch_gemv(const GemvArgs& a, int* n_blocks_out, hipStream_t s);
 int gemv_max_blocks();   // upper bound on gridDim.x of launch_gemv (size of the argmax partial rows)
@@ -66,8 +68,10 @@ __host__ __device__ size_t packed_weight_elems(int N, int K);
 hipError_t launch_pack_weights(const void* W, int N, int K, size_t ldw, void* P, hipStream_t s);
 bool skinny_mfma_fits(const GemvArgs& a);
 hipError_t launch_skinny_mfma(const GemvArgs& a, float* partial, int* n_blocks_out, hipStream_t s);
+// row_best (EPI_STORE only): per-row argmax keys [M], zeroed by the caller, raised with atomic maxima; store = 0: Y is not written
 hipError_t launch_gemm_reduce(int epi, float* partial, int ksplit, int M, int N, float* Y, int ldy, const float* R2,
-                              const float* ssq, int ssq_ld, float rnorm_k, float eps, hipStream_t s);
+                              const float* ssq, int ssq_ld, float rnorm_k, float eps, unsigned long long* row_best, int store,
+                              hipStream_t s);
 
 // ---- the same product for 17..96 activation rows on the matrix cores (bf16 weights from seg[0].P / P2,
 // activations split in-kernel per K window; partial: scratch of gemm_partial_elems() floats)
@@ -78,8 +82,6 @@ hipError_t launch_mid_mfma(const GemvArgs& a, float* partial, hipStream_t s);
 size_t gemm_planes_elems(int M, int K);   // bf16 elements of scratch for the split activations
 size_t gemm_partial_elems();              // float elements of scratch for split-K partial products
 hipError_t launch_gemm_mfma(const GemvArgs& a, uint16_t* planes, float* partial, hipStream_t s);
-hipError_t launch_argmax_rows(const float* logits, int ld, int V, int M, int* out, int out_stride, int out_off, int T,
-                              hipStream_t s);
 
 // ---- SSM branch: causal conv + selective scan over up to T positions per sequence
 struct SsmArgs {

@@ -239,7 +239,7 @@ __global__ __launch_bounds__(512) void mid_loop_kernel(const MidArgs a) {
 struct MidPlan { int mt, windows, units, blocks, wpb; size_t lds, partial_elems; };   // windows: K chunks = partial products
 
 static bool mid_plan(const GemvArgs& g, MidPlan& p) {
-  if (!g.bf16 || g.n_seg != 1 || g.seg[0].P == nullptr || g.best != nullptr) return false;
+  if (!g.bf16 || g.n_seg != 1 || g.seg[0].P == nullptr || g.best != nullptr) return false;   // (argmax: through g.row_best)
   if (g.M <= 16 || g.M > 96 || g.K % 8 != 0 || g.K < 32 || g.ldx % 4 != 0) return false;
   if (g.epi == EPI_SWIGLU && g.seg[0].P2 == nullptr) return false;
   const int nf = g.epi == EPI_SWIGLU ? 2 : 1, N = g.seg[0].n_rows, tiles = (N + 15) / 16;
@@ -305,7 +305,7 @@ hipError_t launch_mid_mfma(const GemvArgs& g, float* partial, hipStream_t s) {
   hipError_t e = nf == 2 ? mid_dispatch<2>(a, p, s) : mid_dispatch<1>(a, p, s);
   if (e != hipSuccess) return e;
   return launch_gemm_reduce(g.epi, partial, p.windows, g.M, N, g.seg[0].Y, g.seg[0].ldy, g.R2, a.ssq, a.ssq_ld,
-                            1.0f / (float)g.K, g.eps, s);
+                            1.0f / (float)g.K, g.eps, g.row_best, g.no_store ? 0 : 1, s);
 }
 
 }  // namespace hh

@@ -454,7 +454,7 @@ hipError_t launch_skinny_mfma(const GemvArgs& g, float* partial, int* n_blocks_o
     case EPI_SWIGLU: e = skinny_dispatch<EPI_SWIGLU>(a, p, s); break;
   }
   if (e != hipSuccess || windows == 1) return e;
-  return launch_gemm_reduce(g.epi, partial, windows, g.M, a.N, g.seg[0].Y, g.seg[0].ldy, g.R2, a.ssq, 16, a.rnorm_k, g.eps, s);
+  return launch_gemm_reduce(g.epi, partial, windows, g.M, a.N, g.seg[0].Y, g.seg[0].ldy, g.R2, a.ssq, 16, a.rnorm_k, g.eps, nullptr, 1, s);
 }
 
 }  // namespace hh

@@ -185,6 +185,27 @@ def test_mid_rows_long_k_and_wide_head(B):
     run_lockstep(ctx, wts, prompts, lens, 16, 4, engine="pass", report=_say("midk"))
 
 
+@pytest.mark.parametrize("keep_logits", [1, 0])
+def test_row_block_kernel_chunks_planes_and_argmax(B, keep_logits):
+    """17..96 activation rows with a long, thin model (d_inner = d_ff = 2048 against d_model 64):
+    the out and down projections have few weight tiles and a long K (many K chunks per product, norm
+    scale from the chunks' sums of squares), 25 verification rows and 80-row prefill passes (two and
+    five row tiles).  The LM head's argmax is raised with atomic maxima in the chunk reduction; with
+    keep_logits = 0 no logits are written at all: tokens, counts, state and cache must still match."""
+    cfg = W.scaled_config("rowblock", n_layers=2, d_model=64, vocab=200, m_heads=32, m_head_dim=64, d_state=16,
+                          n_q_heads=4, n_kv_heads=2, head_dim=32, d_ff=2048, w_dtype=W.BF16)
+    wts = W.make_lively_weights(cfg, 50)          # seeds audited: top-1/top-2 gap 7.3e-4
+    lens = [40, 9, 70, 23, 33]
+    prompts = W.make_prompts(cfg.vocab, 5, lens, 7)
+    ctx = _ctx(B, wts, 5, 128, 4, 12, kv_page_tokens=32, prefill_chunk=16, keep_logits=keep_logits)
+    run_lockstep(ctx, wts, prompts, lens, 12, 4, engine="pass", min_gap=4e-4, compare_logits=bool(keep_logits),
+                 report=_say(f"rowblock-keep{keep_logits}"))
+    if not keep_logits:
+        with pytest.raises(B.HHError) as ei:
+            ctx.hh_get_logits(1)
+        assert ei.value.status == B.HH_ESTATE
+
+
 def test_many_rows_lively(B):
     """More than 96 activation rows (10 sequences x 16-position prefill chunks = 160 rows: the
     tiled matrix-core GEMM over pre-split activations) on the initialisation with order-one

@@ -21,6 +21,7 @@
 #include "hh_internal.h"
 #include "bf16_split.h"
 #include "wave_ops.h"
+#include "gemm_lds.h"
 
 namespace hh {
 
@@ -355,6 +356,20 @@ size_t gemm_planes_elems(int M, int K) {
 // float elements of scratch for the partial products of split-K launches
 size_t gemm_partial_elems() { return (size_t)24 << 20; }
 
+// The LDS-staged kernel: more than six row tiles (96 rows)
+template <int EPI>
+static hipError_t lds_launch(const LdsGemmArgs& a, hipStream_t s) {
+  auto kern = gemm_lds_kernel<EPI>;
+  static bool enabled = false;
+  if (!enabled) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, 3 * kLdsStageBytes);
+    if (e != hipSuccess) return e;
+    enabled = true;
+  }
+  hipLaunchKernelGGL(kern, dim3(a.n_blocks * a.m_blocks * a.ksplit), dim3(64 * kLdsWaves), 3 * kLdsStageBytes, s, a);
+  return hipGetLastError();
+}
+
 template <int EPI, int NT, int MTW>
 static hipError_t gemm_launch(const GemmArgs& a, int units, hipStream_t s) {
   if (a.terms == 3) hipLaunchKernelGGL((gemm_tiled_kernel<EPI, NT, MTW, 3>), dim3((units + 3) / 4), dim3(256), 0, s, a);
@@ -394,6 +409,38 @@ hipError_t launch_gemm_mfma(const GemvArgs& g, uint16_t* planes, float* partial,
   a.Y = g.seg[0].Y; a.ldy = g.seg[0].ldy; a.R2 = g.R2; a.partial = partial; a.M = M; a.N = N; a.K = K;
   a.row_best = g.epi == EPI_STORE ? g.row_best : nullptr; a.store = g.no_store && a.row_best != nullptr ? 0 : 1;
   const int steps = Kp / 32, tiles = (N + 15) / 16, m_tiles = Mp / 16;
+  if (m_tiles > 6 && a.terms == 3) {
+    LdsGemmArgs l{};
+    l.planes = planes; l.m_tiles = m_tiles; l.KST = steps;
+    l.W = a.W; l.W2 = a.W2; l.Y = a.Y; l.ldy = a.ldy; l.R2 = a.R2; l.partial = partial;
+    l.M = M; l.N = N; l.n_tiles = tiles; l.row_best = a.row_best; l.store = a.store;
+    l.n_blocks = (tiles + kLdsA / nf - 1) / (kLdsA / nf);
+    l.m_blocks = (m_tiles + kLdsRowTiles - 1) / kLdsRowTiles;
+    // K split only where the tiles alone leave most of the chip idle: the partial products cost
+    // ks * M * N floats written and read again.  At least 8 steps per workgroup, partial buffer permitting.
+    const int blocks = l.n_blocks * l.m_blocks;
+    int ks = 1;
+    if (blocks < 128) {
+      ks = (224 + blocks - 1) / blocks;
+      while (ks > 1 && (steps / ks < 8 || (size_t)ks * nf * M * N > gemm_partial_elems())) --ks;
+    }
+    l.ksteps = (steps + ks - 1) / ks;
+    l.ksplit = (steps + l.ksteps - 1) / l.ksteps;
+    switch (g.epi) {
+      case EPI_STORE: e = lds_launch<EPI_STORE>(l, s); break;
+      case EPI_ADD: e = lds_launch<EPI_ADD>(l, s); break;
+      case EPI_SWIGLU: e = lds_launch<EPI_SWIGLU>(l, s); break;
+      default: return hipErrorInvalidValue;
+    }
+    if (e != hipSuccess || l.ksplit == 1) return e;
+    a.ksplit = l.ksplit;
+    switch (g.epi) {
+      case EPI_STORE: return reduce_launch<EPI_STORE>(a, s);
+      case EPI_ADD: return reduce_launch<EPI_ADD>(a, s);
+      case EPI_SWIGLU: return reduce_launch<EPI_SWIGLU>(a, s);
+    }
+    return hipErrorInvalidValue;
+  }
   a.strip_groups = (tiles + nt - 1) / nt;
   // row tiles per unit: 5 with two terms; 4 with three (5 would spill under the two-workgroups-per-CU register cap)
   const int mtw_cap = a.terms == 3 ? 4 : 5;

@@ -128,12 +128,27 @@ class HybridLM:
             kv_len=0)
 
     # -- one token
-    def step(self, st: SeqState, tok: int, mode: str = "full") -> np.ndarray:
+    def step(self, st: SeqState, tok: int, mode="full") -> np.ndarray:
         """Consume token `tok` at position st.kv_len (full) or on the recurrent
         state only (draft); returns logits[V].  Full mode appends to the KV cache
-        and advances kv_len; draft mode never touches the cache."""
-        assert mode in ("full", "draft")
+        and advances kv_len; draft mode never touches the cache.
+
+        `mode` may also be a sequence of one entry per layer, "full" | "ssm" | "skip"
+        (a masked draft): a "full" layer computes both branches of Eq. 2 at position
+        st.kv_len and writes its K/V there, an "ssm" layer suppresses its attention
+        output (Eq. 4), a "skip" layer passes the stream through unchanged and leaves
+        its state alone (the identity pass-through of Eq. 5 applied to a whole block,
+        and the layer skipping of the generic drafts of Section 4.2).  A masked step
+        advances st.kv_len, so it is run on a scratch state."""
         c = self.cfg
+        if isinstance(mode, str):
+            assert mode in ("full", "draft")
+            layer_modes = ["full" if mode == "full" else "ssm"] * c.n_layers
+            advance = mode == "full"
+        else:
+            layer_modes = list(mode)
+            assert len(layer_modes) == c.n_layers and all(m in ("full", "ssm", "skip") for m in layer_modes)
+            advance = True
         Hm, P, N = c.m_heads, c.m_head_dim, c.d_state
         d_inner = Hm * P
         conv_dim = d_inner + 2 * N
@@ -142,6 +157,8 @@ class HybridLM:
 
         h = self.embed[tok].copy()
         for l, w in enumerate(self.layers):
+            if layer_modes[l] == "skip":
+                continue
             # shared input norm and the Mamba-2 input projection
             u = rmsnorm(h, w["norm1"], c.rms_eps)
             zxbcdt = w["w_in"] @ u
@@ -164,7 +181,7 @@ class HybridLM:
             # gate, normalise over all of d_inner, project out
             m = w["w_out"] @ rmsnorm(y.reshape(-1) * silu(z), w["gnorm"], c.rms_eps)
             # attention branch (Eq. 2); suppressed in the draft (Eq. 4)
-            if mode == "full":
+            if layer_modes[l] == "full":
                 q = rope((w["w_q"] @ u).reshape(Hq, Dh), pos, c.rope_base)
                 kk = rope((w["w_k"] @ u).reshape(Hkv, Dh), pos, c.rope_base)
                 vv = (w["w_v"] @ u).reshape(Hkv, Dh)
@@ -184,6 +201,6 @@ class HybridLM:
             # SwiGLU MLP
             r = rmsnorm(h, w["norm2"], c.rms_eps)
             h = h + w["w_down"] @ (silu(w["w_gate"] @ r) * (w["w_up"] @ r))
-        if mode == "full":
+        if advance:
             st.kv_len = pos + 1
         return self.lm_head @ rmsnorm(h, self.final_norm, c.rms_eps)

@@ -42,6 +42,18 @@ def speedup_model(alpha: float, k: int, cost_ratio: float) -> float:
     return expected_tokens_per_round(alpha, k) / (1.0 + k * cost_ratio)
 
 
+def optimal_draft_length(alpha: float, cost_ratio: float, candidates: Sequence[int]) -> int:
+    """The draft length among `candidates` that maximises Eq. 1 for per-token
+    acceptance probability alpha and cost ratio c_draft / c_verify (the choice the
+    paper's Section 7 "Optimal draft length" describes); the smallest on ties."""
+    best, best_s = None, -1.0
+    for k in sorted(int(v) for v in candidates):
+        s = speedup_model(alpha, k, cost_ratio)
+        if s > best_s + 1e-15:
+            best, best_s = k, s
+    return best
+
+
 def accepted_prefix(drafts: Sequence[int], targets: Sequence[int]) -> int:
     """Greedy acceptance (Section 3.3): the number n of leading draft tokens with
     drafts[i] == targets[i], where targets[i] is M_H's argmax given the prefix
@@ -77,11 +89,27 @@ class SpecDecoder:
     engine="pass" uses the multi-position pass for prefill and verification."""
 
     def __init__(self, lm: HybridLM, capacity: int, engine: str = "step", chunk: int = 64,
-                 temperature: float = 0.0, seed: int = 0):
+                 temperature: float = 0.0, seed: int = 0, draft_state: str = "shared",
+                 draft_mask: Optional[Sequence[str]] = None):
         """temperature 0: greedy acceptance.  temperature > 0: tokens are drawn from
         softmax(logits / T) and drafts pass the rejection test of Eq. 6, with the
-        counter-based uniforms of `sampling.uniform(seed, ...)`."""
+        counter-based uniforms of `sampling.uniform(seed, ...)`.
+
+        draft_state "shared" (default): every round the draft starts from the committed
+        recurrent state of the full model.  "strict": the draft model M_S is its own
+        model over the whole prefix (Eq. 4 applied at every position, Section 3.3
+        "Draft phase": P_S(. | x_{1:t+i-1})): it keeps a recurrent state of its own,
+        advanced with attention suppressed over the prompt and over every committed
+        token.  Either way the committed stream is the full model's; only the accepted
+        counts differ.
+
+        draft_mask: one entry per layer, "full" | "ssm" | "skip": the draft steps run
+        the masked model of `HybridLM.step` (all "ssm" is Eq. 4, the default)."""
         assert engine in ("step", "pass")
+        assert draft_state in ("shared", "strict")
+        assert draft_mask is None or draft_state == "shared", "the strict state is defined for the SSM-only draft"
+        self.draft_state = draft_state
+        self.draft_mask = None if draft_mask is None else list(draft_mask)
         self.lm, self.capacity, self.engine, self.chunk = lm, capacity, engine, chunk
         self.T, self.seed = float(temperature), int(seed)
         self.gaps: List[float] = []          # top-1/top-2 gap of every greedy decision taken
@@ -105,7 +133,13 @@ class SpecDecoder:
         self.pending: List[int] = []
         self.last_n = [0] * self.B
         self.prefill_logits = []
+        self.ms: List[SeqState] = []             # strict mode: M_S's own recurrent state per sequence
         for b, p in enumerate(prompts):
+            if self.draft_state == "strict":
+                ms = self.lm.new_state(1)
+                for t in p:
+                    self.lm.step(ms, int(t), "draft")
+                self.ms.append(ms)
             st = self.lm.new_state(self.capacity)
             if self.engine == "pass":
                 logits = full_pass(self.lm, st, p, self.chunk, last_only=True)[0][0]
@@ -138,12 +172,14 @@ class SpecDecoder:
             if self.finished(b):
                 continue
             st = self.st[b]
-            S, conv = st.recurrent_copy()
+            S, conv = (self.ms[b] if self.draft_state == "strict" else st).recurrent_copy()
+            # (a masked draft with "full" layers writes K/V at the positions it drafts: slots at and
+            # behind kv_len are dead until verification rewrites them)
             scratch = SeqState(S=S, conv=conv, K=st.K, V=st.V, kv_len=st.kv_len)
             t = self.pending[b]
             ds, ls = [], []
             for i in range(k):
-                logits = self.lm.step(scratch, t, "draft")
+                logits = self.lm.step(scratch, t, "draft" if self.draft_mask is None else self.draft_mask)
                 t = self._pick(logits, b, len(self.out[b]) + i, sampling.PURPOSE_DRAFT)
                 ds.append(t)
                 ls.append(logits)
@@ -208,6 +244,9 @@ class SpecDecoder:
             n = accepted_prefix(d, g) if forced_n is None else int(forced_n[b])
             assert 0 <= n <= len(d)
             self.gaps.extend(gaps_v[:n + 1])     # only positions that decided a token
+            if self.draft_state == "strict":     # M_S consumes what the caches consumed: pending, d_1 .. d_n
+                for t in [self.pending[b]] + list(d[:n]):
+                    self.lm.step(self.ms[b], int(t), "draft")
             emit = list(d[:n]) + [g[n]]
             room = self.G - len(self.out[b])
             self.out[b].extend(emit[:room])

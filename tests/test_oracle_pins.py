@@ -489,3 +489,144 @@ def test_parameter_count_ratio():
     assert c1.params_per_layer(True) == 17600840 and c1.params_per_layer(False) == 18911560
     c3 = W.WORKLOADS["c3"].cfg
     assert c3.params_per_layer(True) == 74181240 and c3.params_per_layer(False) == 82045560
+
+
+# ------------------------------------------------------------------ masked drafts, strict draft state, draft length
+
+def test_layer_modes_reduce_to_the_full_model_the_ssm_draft_and_a_layerless_model():
+    """Per-layer draft modes (Eq. 4 / Eq. 5 generalised): all "full" is the full step bit for bit
+    (logits, state, K/V), all "ssm" the Eq. 4 draft step, all "skip" leaves nothing but the
+    embedding, the final norm and the LM head (written out by hand here), and a single skipped
+    layer is the model whose output, attention-output and down projections of that layer are zero
+    (the block then adds nothing to the stream)."""
+    cfg = tiny_cfg(n_layers=3)
+    wts = W.make_lively_weights(cfg, 4)
+    lm = HybridLM(cfg, wts.values)
+    toks = [3, 9, 1, 4, 7]
+    a, b = lm.new_state(16), lm.new_state(16)
+    for t in toks:
+        la = lm.step(a, t, "full")
+        lb = lm.step(b, t, ["full"] * 3)
+        assert np.array_equal(la, lb)
+    assert a.kv_len == b.kv_len == 5
+    for l in range(3):
+        assert np.array_equal(a.S[l], b.S[l]) and np.array_equal(a.K[l], b.K[l]) and np.array_equal(a.V[l], b.V[l])
+    c, d = lm.new_state(16), lm.new_state(16)
+    for t in toks:
+        assert np.array_equal(lm.step(c, t, "draft"), lm.step(d, t, ["ssm"] * 3))
+    assert c.kv_len == 0 and d.kv_len == 5 and not d.K[0].any()          # the SSM-only layers write no K/V
+    e = lm.new_state(16)
+    got = lm.step(e, 6, ["skip"] * 3)
+    x = np.asarray(wts.values["embed"], np.float64)[6]
+    want = np.asarray(wts.values["lm_head"], np.float64) @ (x / np.sqrt((x * x).mean() + cfg.rms_eps) * wts.values["final_norm"])
+    np.testing.assert_allclose(got, want, rtol=1e-13, atol=1e-15)
+    assert not any(s.any() for s in e.S)                                  # skipped layers keep their state
+    # one skipped layer == that layer's three output projections zeroed
+    vals = dict(wts.values)
+    for n in ("w_out", "w_o", "w_down"):
+        vals[f"L1.{n}"] = np.zeros_like(vals[f"L1.{n}"])
+    lm0 = HybridLM(cfg, vals)
+    f, g = lm.new_state(16), lm0.new_state(16)
+    for t in toks:
+        np.testing.assert_allclose(lm.step(f, t, ["full", "skip", "ssm"]), lm0.step(g, t, ["full", "full", "ssm"]),
+                                   rtol=1e-12, atol=1e-14)
+
+
+@pytest.mark.parametrize("mask", [("full", "full"), ("ssm", "skip"), ("skip", "full"), ("full", "ssm")])
+@pytest.mark.parametrize("k", [1, 3])
+def test_masked_drafts_are_lossless_and_the_full_mask_is_always_accepted(mask, k):
+    """Losslessness does not depend on the draft (Section 3.3), so it holds for every layer
+    mask; the all-"full" mask drafts with M_H itself and has all k drafts accepted every round.
+    After every commit the committed state equals plain consumption (a masked draft writes K/V
+    only into dead slots)."""
+    cfg = tiny_cfg(n_layers=2)
+    lm = lively(cfg, 6)
+    G = 12
+    prompt = W.make_prompts(cfg.vocab, 1, 6, 11)[0]
+    ref = greedy_generate(lm, prompt, G + k + 2)
+    dec = SpecDecoder(lm, capacity=64, engine="step", draft_mask=mask)
+    dec.prefill([prompt], G)
+    while not dec.all_finished():
+        have = len(dec.out[0])
+        dec.draft(k)
+        dec.verify()
+        dec.commit()
+        if mask == ("full", "full"):
+            assert dec.last_n[0] == k
+        shadow = lm.new_state(64)
+        for t in list(prompt) + ref[:have + dec.last_n[0]]:
+            lm.step(shadow, int(t), "full")
+        assert dec.st[0].kv_len == shadow.kv_len
+        for l in range(cfg.n_layers):
+            np.testing.assert_allclose(dec.st[0].S[l], shadow.S[l], rtol=1e-9, atol=1e-12)
+            np.testing.assert_allclose(dec.st[0].K[l][:shadow.kv_len], shadow.K[l][:shadow.kv_len], rtol=1e-9, atol=1e-12)
+    assert dec.out[0] == ref[:G]
+
+
+def test_strict_draft_state_is_m_s_over_the_whole_prefix():
+    """Strict reading of Eq. 4 / Section 3.3 "Draft phase": the draft model's own recurrent state
+    equals M_S run from scratch over the prompt and every token the caches have consumed; the
+    committed stream is still plain greedy decoding; and when the attention output projection is
+    zero (M_H == M_S) the strict and the shared state coincide, every draft is accepted, in both."""
+    cfg = tiny_cfg(n_layers=2)
+    lm = lively(cfg, 6)
+    G, k = 12, 3
+    prompt = W.make_prompts(cfg.vocab, 1, 7, 5)[0]
+    ref = greedy_generate(lm, prompt, G)
+    dec = SpecDecoder(lm, 64, engine="step", draft_state="strict")
+    dec.prefill([prompt], G)
+    shared = SpecDecoder(lm, 64, engine="step")
+    shared.prefill([prompt], G)
+    n_strict, n_shared = [], []
+    while not dec.all_finished():
+        consumed_before = list(prompt) + dec.out[0][:-1]
+        dec.draft(k); dec.verify(); dec.commit()
+        n_strict.append(dec.last_n[0])
+        brute = lm.new_state(1)
+        for t in list(prompt) + dec.out[0][:-1]:                         # everything but the pending token
+            lm.step(brute, int(t), "draft")
+        assert len(dec.out[0]) - 1 - (len(consumed_before) - len(prompt)) == dec.last_n[0] + 1 or dec.finished(0)
+        if not dec.finished(0) or len(dec.out[0]) == G:
+            for l in range(cfg.n_layers):
+                np.testing.assert_allclose(dec.ms[0].S[l], brute.S[l], rtol=1e-10, atol=1e-13)
+                np.testing.assert_allclose(dec.ms[0].conv[l], brute.conv[l], rtol=1e-10, atol=1e-13)
+    while not shared.all_finished():
+        shared.draft(k); shared.verify(); shared.commit()
+        n_shared.append(shared.last_n[0])
+    assert dec.out[0] == ref == shared.out[0]
+    assert n_strict != n_shared                                            # the two readings differ in what they accept
+    # M_H == M_S: zero attention output projection
+    vals = dict(W.make_lively_weights(cfg, 6).values)
+    for l in range(cfg.n_layers):
+        vals[f"L{l}.w_o"] = np.zeros_like(vals[f"L{l}.w_o"])
+    lm0 = HybridLM(cfg, vals)
+    for mode in ("strict", "shared"):
+        d0 = SpecDecoder(lm0, 64, engine="step", draft_state=mode)
+        d0.prefill([prompt], G)
+        while not d0.all_finished():
+            d0.draft(k); d0.verify(); d0.commit()
+            assert d0.last_n[0] == k
+        assert d0.out[0] == greedy_generate(lm0, prompt, G)
+
+
+def test_optimal_draft_length_follows_eq1():
+    """The draft length that maximises Eq. 1: brute force over the candidates; the paper's own
+    conclusion (Section 7: k* = 2 among the evaluated lengths at the high cost ratios, for both
+    readings of the printed acceptance rate); and its remark that a lower effective cost ratio
+    makes larger k optimal (k* never shrinks as the ratio falls)."""
+    from oracle.protocol import optimal_draft_length, speedup_model
+    golden = json.load(open(os.path.join(os.path.dirname(__file__), "golden", "paper_values.json")))
+    c = golden["section_3_4_cost_ratio_falcon_h1_0p5b"]
+    for alpha_k2 in (golden["table_3_alpha_greedy"]["falcon_h1_0p5b"]["k2"], golden["table_3_alpha_greedy"]["falcon_h1_3b"]["k2"]):
+        for alpha in (alpha_k2, alpha_k2 ** 0.5):                        # per-token reading, and the all-token rate's root
+            assert optimal_draft_length(alpha, c, [2, 4, 8]) == 2
+    for alpha in (0.3, 0.68, 0.9, 0.97):
+        prev = 0
+        for ratio in (1.0, 0.784, 0.5, 0.2, 0.05, 0.01):
+            ks = list(range(1, 17))
+            best = optimal_draft_length(alpha, ratio, ks)
+            assert all(speedup_model(alpha, best, ratio) >= speedup_model(alpha, k, ratio) - 1e-12 for k in ks)
+            assert best >= prev
+            prev = best
+    assert optimal_draft_length(0.9, 0.05, range(1, 17)) > 2
+    assert optimal_draft_length(0.0, 0.5, [1, 2, 3]) == 1                # nothing is ever accepted: shortest draft

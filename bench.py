@@ -146,6 +146,11 @@ def main():
                     help="prompt positions per sequence per prefill pass (0: the library's default)")
     ap.add_argument("--prompt-len", type=int, default=None,
                     help="override the workload's prompt length (a shorter stand-in; named in config.workload)")
+    ap.add_argument("--k", type=int, default=None, help="draft length (default: the workload's)")
+    ap.add_argument("--draft-state", choices=("shared", "strict"), default="shared",
+                    help="strict: the draft model keeps its own recurrent state over the whole prefix")
+    ap.add_argument("--draft-mask", default=None,
+                    help="draft model by layers, comma-separated ssm|full|skip, each optionally *count (e.g. ssm*30,full*2)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build measures one GPU only (the path shards by sequence with no exchange step); "
@@ -160,7 +165,19 @@ def main():
     if args.prompt_len is not None:
         import dataclasses
         wl = dataclasses.replace(wl, prompt_len=args.prompt_len)
-    cfg, k, Bn = wl.cfg, wl.k, wl.batch
+    cfg, k, Bn = wl.cfg, (wl.k if args.k is None else args.k), wl.batch
+    if k < 1 or k > 64:
+        print("bench.py: the draft length must be in 1..64", file=sys.stderr)
+        sys.exit(2)
+    draft_mask = None
+    if args.draft_mask:
+        draft_mask = []
+        for item in args.draft_mask.split(","):
+            mode, _, count = item.partition("*")
+            draft_mask += [mode.strip()] * (int(count) if count else 1)
+        if len(draft_mask) != cfg.n_layers or any(m not in B.DRAFT_MODES for m in draft_mask):
+            print(f"bench.py: --draft-mask needs {cfg.n_layers} entries of ssm|full|skip", file=sys.stderr)
+            sys.exit(2)
     K, Wm = args.steps, args.warmup
     prof_rounds, greedy_rounds = 3, min(K, 32)
     forced_p = args.forced_p if args.forced_p is not None else (wl.forced_p or 0.68)
@@ -182,7 +199,9 @@ def main():
     say(f"weights in {t_gen:.1f} s; creating the context")
     n_pass_hint = 16 if wl.prompt_len * Bn > (1 << 18) else 0
     ctx = B.Context(weights, Bn, max_seq, k, G, use_graphs=0 if args.counters else args.graphs,
-                    prefill_chunk=args.prefill_chunk, keep_logits=args.keep_logits, prefill_progress=n_pass_hint)
+                    prefill_chunk=args.prefill_chunk, keep_logits=args.keep_logits, prefill_progress=n_pass_hint,
+                    draft_state_mode=1 if args.draft_state == "strict" else 0)
+    ctx.hh_set_draft_mask(draft_mask)
     torch.cuda.synchronize()
     say("prefill")
     t0 = time.perf_counter()
@@ -310,6 +329,7 @@ def main():
              "committed_tokens_per_s": round(toks_o / dt_o, 2),
              "mean_accepted_per_round": round(toks_o / (K * Bn) - 1, 3)}
     prompt_note = "" if args.prompt_len is None else " (shortened stand-in)"
+    cost_ratio = (t_draft / (K * max(k, 1))) / (t_verify / K) if k > 0 else 0.0
     out = {
         "metric": "committed tokens/s (speculative rounds); draft tok/s and verify passes/s alongside",
         "value": round(toks / dt, 2), "unit": "tokens/s", "n_gpus": 1, "steps": K, "warmup": Wm,
@@ -319,7 +339,8 @@ def main():
                                f"{prompt_note}, k={k}, {mode}, seed {args.seed}"
                                if cfg.w_dtype == "bf16" else
                                f"{args.workload}: {cfg.name}, f32 weights, batch {Bn}, prompt {wl.prompt_len}, k={k}, {mode}",
-                   "rounds_timed": K, "graphs": args.graphs, "keep_logits": args.keep_logits},
+                   "rounds_timed": K, "graphs": args.graphs, "keep_logits": args.keep_logits,
+                   "draft_state": args.draft_state, "draft_mask": args.draft_mask},
         "draft_tokens_per_s": round(Bn * k * K / t_draft, 1),
         "verify_passes_per_s": round(K / t_verify, 1),
         "commit_us": round(t_commit / K * 1e6, 2),
@@ -331,6 +352,11 @@ def main():
                             "hbm_frac": round(verify_bytes / (t_verify / K) / 1e9 / HBM_PEAK_GBS, 4)},
             "commit": {"bytes": commit_bytes, "us": round(t_commit / K * 1e6, 2),
                        "hbm_frac": round(commit_bytes / (t_commit / K) / 1e9 / HBM_PEAK_GBS, 4)}},
+        # Eq. 1 with the measured costs of this run: c = one draft step / one verification pass
+        "draft_length_model": {
+            "alpha": forced_p, "cost_ratio": round(cost_ratio, 4),
+            "k_star": B.hh_optimal_draft_length(forced_p, cost_ratio, list(range(1, max(k, 8) + 1))),
+            "k_star_of_2_4_8": B.hh_optimal_draft_length(forced_p, cost_ratio, [2, 4, 8])},
         "other_acceptance": other,
         "stochastic": stochastic,
         "plain_greedy_tokens_per_s": round(toks_g / dt_g, 2),

@@ -100,6 +100,13 @@ typedef struct hh_cfg {
                                            0 = 28, -1 = split from the first step on */
   int32_t kernel_flags;                 /* HH_KF_* bits: kernel selection for cross-checks, all 0 by default */
   int32_t prefill_progress;             /* n > 0: hh_prefill waits for every n-th pass and reports it on stderr */
+  int32_t draft_state_mode;             /* recurrent state the draft model M_S runs on (Eq. 4, Section 3.3 draft phase):
+                                           0 shared: every round's draft starts from the full model's committed state;
+                                           1 strict: M_S is a model of its own over the whole prefix - a second committed
+                                             state and ring per layer, advanced with attention suppressed over the prompt
+                                             (one more SSM-only pass per prefill chunk) and over every committed token
+                                             (hh_draft runs k+1 SSM-only steps, the last without LM head; hh_commit
+                                             rebuilds both states).  The committed stream is the same; accepted counts differ */
   void* workspace;                      /* DEVICE, 256-byte aligned */
   size_t workspace_bytes;
 } hh_cfg;
@@ -215,8 +222,28 @@ HH_API hh_status hh_draft(hh_ctx* ctx, int32_t k, void* stream);
 
 /* Replace the drafted tokens of the current round by caller-chosen ones
  * (DEVICE int32 [batch][k]); valid between hh_draft and hh_verify.  The
- * committed stream does not depend on the draft source (losslessness). */
+ * committed stream does not depend on the draft source (losslessness).
+ * With draft_state_mode = 1 the call also runs M_S (no LM head) over the
+ * replaced tokens, so that its state follows what is committed. */
 HH_API hh_status hh_set_drafts(hh_ctx* ctx, const int32_t* drafts, void* stream);
+
+/* Draft model by layers (Section 4.2: layer-skipping and early-exit drafts; Eq. 5 applied to whole
+ * blocks).  modes: HOST int32 [n_layers], one of
+ *   HH_DRAFT_SSM   only the SSM branch of the block runs (Eq. 4; the default for every layer),
+ *   HH_DRAFT_FULL  both branches run as in M_H: the draft step attends over the cache and writes its
+ *                  K/V at the position it drafts (a slot behind the cache length, rewritten by hh_verify),
+ *   HH_DRAFT_SKIP  the block is the identity on the residual stream; its state is not touched.
+ * NULL restores the default.  Copied; applies to the following hh_draft calls.  The committed stream
+ * never depends on the mask.  HH_ESTATE inside a round, or for a mask other than all-SSM on a context
+ * with draft_state_mode = 1; HH_EINVAL for an unknown mode. */
+enum { HH_DRAFT_SSM = 0, HH_DRAFT_FULL = 1, HH_DRAFT_SKIP = 2 };
+HH_API hh_status hh_set_draft_mask(hh_ctx* ctx, const int32_t* modes);
+
+/* The draft length among candidates[0..n_candidates) (HOST, each >= 0) that maximises the speedup
+ * model of Eq. 1, (1 - alpha^(k+1)) / ((1 - alpha) (1 + k * cost_ratio)), for per-token acceptance
+ * probability alpha in [0, 1] and cost_ratio = c_draft / c_verify >= 0 (Section 7, optimal draft
+ * length); the shortest of equally good lengths.  Host arithmetic only.  -1 for bad arguments. */
+HH_API int32_t hh_optimal_draft_length(double alpha, double cost_ratio, const int32_t* candidates, int32_t n_candidates);
 
 /* Verification phase (Section 3.3): one pass of M_H over pending, d_1..d_k at
  * positions len..len+k of every sequence: chunked SSM scan from the committed
@@ -247,6 +274,8 @@ HH_API hh_status hh_get_logits(hh_ctx* ctx, int32_t which, float* out, void* str
 /* Committed recurrent state of one layer: ssm [batch][m_heads][m_head_dim][d_state],
  * conv [batch][conv_dim][d_conv-1] (oldest first).  Either may be NULL. */
 HH_API hh_status hh_get_state(hh_ctx* ctx, int32_t layer, float* ssm, float* conv, void* stream);
+/* The same for the draft model's own committed state (draft_state_mode = 1; HH_ESTATE otherwise). */
+HH_API hh_status hh_get_draft_state(hh_ctx* ctx, int32_t layer, float* ssm, float* conv, void* stream);
 /* First n_tokens cache entries of one sequence and layer as float32 [n_tokens][n_kv_heads][head_dim]. */
 HH_API hh_status hh_get_kv(hh_ctx* ctx, int32_t layer, int32_t seq, int32_t n_tokens, float* k, float* v, void* stream);
 

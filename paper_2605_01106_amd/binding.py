@@ -26,6 +26,8 @@ lib = C.CDLL(_LIB_PATH)
 HH_OK, HH_EINVAL, HH_ESTATE, HH_ECAPACITY, HH_EWORKSPACE, HH_EDEVICE = 0, -1, -2, -3, -4, -5
 HH_F32, HH_BF16 = 0, 1
 HH_KF_ATTN_SCALAR, HH_KF_SSM_GENERAL, HH_KF_MID_OFF, HH_KF_SKINNY_OFF, HH_KF_SSM_SCALAR_CONV = 1, 2, 4, 8, 16
+HH_DRAFT_SSM, HH_DRAFT_FULL, HH_DRAFT_SKIP = 0, 1, 2
+DRAFT_MODES = {"ssm": HH_DRAFT_SSM, "full": HH_DRAFT_FULL, "skip": HH_DRAFT_SKIP}
 STATUS_NAMES = {0: "HH_OK", -1: "HH_EINVAL", -2: "HH_ESTATE", -3: "HH_ECAPACITY", -4: "HH_EWORKSPACE",
                 -5: "HH_EDEVICE"}
 
@@ -41,7 +43,7 @@ class hh_cfg(C.Structure):
                 ("max_draft", C.c_int32), ("max_new_tokens", C.c_int32), ("kv_page_tokens", C.c_int32),
                 ("prefill_chunk", C.c_int32), ("keep_logits", C.c_int32), ("use_graphs", C.c_int32),
                 ("overlap_mode", C.c_int32), ("attn_max_splits", C.c_int32), ("attn_single_slice_steps", C.c_int32),
-                ("kernel_flags", C.c_int32), ("prefill_progress", C.c_int32),
+                ("kernel_flags", C.c_int32), ("prefill_progress", C.c_int32), ("draft_state_mode", C.c_int32),
                 ("workspace", C.c_void_p), ("workspace_bytes", C.c_size_t)]
 
 
@@ -76,6 +78,8 @@ EXPORTS = {
                                           C.c_float, C.c_uint64, C.c_void_p, C.c_void_p]),
     "hh_draft": (C.c_int, [_ctx_p, C.c_int32, C.c_void_p]),
     "hh_set_drafts": (C.c_int, [_ctx_p, C.c_void_p, C.c_void_p]),
+    "hh_set_draft_mask": (C.c_int, [_ctx_p, _i32p]),
+    "hh_optimal_draft_length": (C.c_int32, [C.c_double, C.c_double, _i32p, C.c_int32]),
     "hh_verify": (C.c_int, [_ctx_p, C.c_void_p]),
     "hh_commit": (C.c_int, [_ctx_p, C.c_void_p, C.c_void_p]),
     "hh_get_tokens": (C.c_int, [_ctx_p, C.c_int32, _i32p, C.c_int32, _i32p, C.c_void_p]),
@@ -83,6 +87,7 @@ EXPORTS = {
     "hh_get_round": (C.c_int, [_ctx_p, _i32p, _i32p, C.c_void_p]),
     "hh_get_logits": (C.c_int, [_ctx_p, C.c_int32, _f32p, C.c_void_p]),
     "hh_get_state": (C.c_int, [_ctx_p, C.c_int32, _f32p, _f32p, C.c_void_p]),
+    "hh_get_draft_state": (C.c_int, [_ctx_p, C.c_int32, _f32p, _f32p, C.c_void_p]),
     "hh_get_kv": (C.c_int, [_ctx_p, C.c_int32, C.c_int32, C.c_int32, _f32p, _f32p, C.c_void_p]),
     "hh_profile": (C.c_int, [_ctx_p, C.c_int32]),
     "hh_profile_read": (C.c_int, [_ctx_p, C.c_int32, _i32p, _f32p, C.c_void_p]),
@@ -103,7 +108,7 @@ class HHError(RuntimeError):
 def make_cfg(cfg: W.HybridConfig, max_batch: int, max_seq_len: int, max_draft: int, max_new_tokens: int,
              kv_page_tokens: int = 0, prefill_chunk: int = 0, keep_logits: int = 1, use_graphs: int = 0,
              overlap_mode: int = 0, attn_max_splits: int = 0, attn_single_slice_steps: int = 0, kernel_flags: int = 0,
-             prefill_progress: int = 0) -> hh_cfg:
+             prefill_progress: int = 0, draft_state_mode: int = 0) -> hh_cfg:
     c = hh_cfg()
     c.struct_size = C.sizeof(hh_cfg)
     c.n_layers, c.d_model, c.vocab = cfg.n_layers, cfg.d_model, cfg.vocab
@@ -115,7 +120,7 @@ def make_cfg(cfg: W.HybridConfig, max_batch: int, max_seq_len: int, max_draft: i
     c.max_batch, c.max_seq_len, c.max_draft, c.max_new_tokens = max_batch, max_seq_len, max_draft, max_new_tokens
     c.kv_page_tokens, c.prefill_chunk, c.keep_logits, c.use_graphs = kv_page_tokens, prefill_chunk, keep_logits, use_graphs
     c.overlap_mode, c.attn_max_splits, c.attn_single_slice_steps = overlap_mode, attn_max_splits, attn_single_slice_steps
-    c.kernel_flags, c.prefill_progress = kernel_flags, prefill_progress
+    c.kernel_flags, c.prefill_progress, c.draft_state_mode = kernel_flags, prefill_progress, draft_state_mode
     c.workspace, c.workspace_bytes = None, 0
     return c
 
@@ -137,6 +142,12 @@ def _stream_ptr(stream) -> Optional[int]:
     if stream is None:
         stream = torch.cuda.current_stream()
     return C.c_void_p(getattr(stream, "cuda_stream", stream))
+
+
+def hh_optimal_draft_length(alpha: float, cost_ratio: float, candidates: Sequence[int]) -> int:
+    """The candidate draft length that maximises Eq. 1 (-1 for bad arguments)."""
+    ks = (C.c_int32 * len(candidates))(*[int(k) for k in candidates])
+    return int(lib.hh_optimal_draft_length(float(alpha), float(cost_ratio), ks, len(candidates)))
 
 
 def hh_draw_tokens(logits, temperature: float, seed: int, positions=None, position_offset: int = 0, purpose: int = 2,
@@ -278,6 +289,15 @@ class Context:
         self._drafts_keep = t
         _check(lib.hh_set_drafts(self.ctx, C.c_void_p(t.data_ptr()), _stream_ptr(stream)), self.ctx)
 
+    def hh_set_draft_mask(self, modes):
+        """modes: None (every layer SSM-only) or one of "ssm" | "full" | "skip" (or HH_DRAFT_*) per layer."""
+        if modes is None:
+            _check(lib.hh_set_draft_mask(self.ctx, None), self.ctx)
+            return
+        assert len(modes) == self.model_cfg.n_layers
+        arr = (C.c_int32 * len(modes))(*[DRAFT_MODES.get(m, m) for m in modes])
+        _check(lib.hh_set_draft_mask(self.ctx, arr), self.ctx)
+
     def hh_verify(self, stream=None):
         _check(lib.hh_verify(self.ctx, _stream_ptr(stream)), self.ctx)
 
@@ -322,6 +342,14 @@ class Context:
         conv = np.zeros((self.B, c.conv_dim, c.d_conv - 1), np.float32)
         _check(lib.hh_get_state(self.ctx, layer, ssm.ctypes.data_as(_f32p), conv.ctypes.data_as(_f32p),
                                 _stream_ptr(stream)), self.ctx)
+        return ssm, conv
+
+    def hh_get_draft_state(self, layer: int, stream=None):
+        c = self.model_cfg
+        ssm = np.zeros((self.B, c.m_heads, c.m_head_dim, c.d_state), np.float32)
+        conv = np.zeros((self.B, c.conv_dim, c.d_conv - 1), np.float32)
+        _check(lib.hh_get_draft_state(self.ctx, layer, ssm.ctypes.data_as(_f32p), conv.ctypes.data_as(_f32p),
+                                      _stream_ptr(stream)), self.ctx)
         return ssm, conv
 
     def hh_profile(self, enable: bool):

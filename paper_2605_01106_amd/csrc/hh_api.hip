@@ -8,6 +8,7 @@
 #include <stdlib.h>
 #include <string.h>
 
+#include <algorithm>
 #include <map>
 #include <string>
 #include <vector>
@@ -46,6 +47,13 @@ struct hh_ctx {
   const void *embed, *final_norm, *lm_head;
   std::vector<LayerDev> layers_host;
   LayerDev* layers_dev;
+  // strict draft state (cfg.draft_state_mode = 1): the same layers with M_S's own committed
+  // recurrent state and ring of raw convolution inputs in place of the full model's
+  std::vector<LayerDev> layers_ms_host;
+  LayerDev* layers_ms_dev = nullptr;
+  bool strict = false;
+  std::vector<int> draft_modes;   // per layer HH_DRAFT_*; empty: every layer SSM-only (Eq. 4)
+  bool draft_has_full = false;
   // device int state
   int *kv_len, *committed, *last_n, *pending, *n_acc, *skip, *adv, *drafts, *targets, *tok, *pos0, *out_tok,
       *page_table, *plan_ntok, *plan_last, *first_tok;
@@ -146,6 +154,7 @@ bool derive_dims(const hh_cfg& c, Dims& d, std::string& why) {
   if (c.kernel_flags & ~(HH_KF_ATTN_SCALAR | HH_KF_SSM_GENERAL | HH_KF_MID_OFF | HH_KF_SKINNY_OFF | HH_KF_SSM_SCALAR_CONV))
     return bad("unknown bit in kernel_flags");
   if (c.prefill_progress < 0) return bad("prefill_progress must not be negative");
+  if (c.draft_state_mode != 0 && c.draft_state_mode != 1) return bad("draft_state_mode must be 0 (shared) or 1 (strict)");
   if (c.keep_logits != 0 && c.keep_logits != 1) return bad("keep_logits must be 0 or 1");
   if (c.use_graphs != 0 && c.use_graphs != 1) return bad("use_graphs must be 0 or 1");
   d.flags = c.kernel_flags;
@@ -159,6 +168,8 @@ size_t carve(hh_ctx* x, char* base) {
   const size_t B = d.Bmax, Mmax = B * d.Tmax, Mv = B * (d.Kmax + 1);
   const size_t esz = d.bf16 ? 2 : 4;
   x->layers_dev = c.take<LayerDev>(d.L);
+  const bool strict = x->cfg.draft_state_mode == 1;
+  x->layers_ms_dev = strict ? c.take<LayerDev>(d.L) : nullptr;
   x->kv_len = c.take<int>(B); x->committed = c.take<int>(B); x->last_n = c.take<int>(B);
   x->pending = c.take<int>(B); x->n_acc = c.take<int>(B); x->skip = c.take<int>(B); x->adv = c.take<int>(B);
   x->first_tok = c.take<int>(B);
@@ -203,10 +214,13 @@ size_t carve(hh_ctx* x, char* base) {
   const size_t ring = B * d.ring_slots * d.ring_w;
   const size_t pool = (size_t)d.n_pages * d.Hkv * d.page_tokens * d.Dh * esz;
   if (base) x->layers_host.resize(d.L);
+  if (base && strict) x->layers_ms_host.resize(d.L);
   for (int l = 0; l < d.L; ++l) {
     float* S = c.take<float>(state);
     float* Sd = c.take<float>(state);
     float* rg = c.take<float>(ring);
+    float* S_ms = strict ? c.take<float>(state) : nullptr;
+    float* rg_ms = strict ? c.take<float>(ring) : nullptr;
     char* kp = c.take<char>(pool);
     char* vp = c.take<char>(pool);
     char* wf = c.take<char>((size_t)d.ldzx * d.D * esz);
@@ -223,6 +237,10 @@ size_t carve(hh_ctx* x, char* base) {
       LayerDev& ld = x->layers_host[l];
       ld.S = S; ld.S_draft = Sd; ld.ring = rg; ld.kpool = kp; ld.vpool = vp; ld.w_inqkv = wf;
       ld.p_inqkv = pi; ld.p_out = po; ld.p_o = poo; ld.p_gate = pg; ld.p_up = pu; ld.p_down = pd;
+      if (strict) {   // completed in hh_create, once the weight pointers are in place
+        x->layers_ms_host[l].S = S_ms;
+        x->layers_ms_host[l].ring = rg_ms;
+      }
     }
   }
   x->p_lm_head = d.bf16 ? c.take<uint16_t>(packed_weight_elems(d.V, d.D)) : nullptr;
@@ -295,13 +313,20 @@ bool branch_overlap(const hh_ctx* x, int B, int T, bool prefill) {
   return (long long)B * x->len_upper >= (512LL << 10);
 }
 
-// ---- one pass of the block stack over M = B*T rows.  full: M_H (both branches); !full: M_S.
-hh_status run_layers(hh_ctx* x, bool full, int B, int T, const int* n_tok, int state_in, int state_out,
-                     int n_splits, bool prefill, hipStream_t s) {
+// ---- one pass of the block stack over M = B*T rows.  all_full: M_H (both branches of every
+// block, Eq. 2); otherwise M_S (Eq. 4), or, with `modes` (one HH_DRAFT_* per layer), the draft
+// model in which a layer keeps both branches, only its SSM branch, or is passed over whole
+// (identity on the residual stream, Eq. 5 applied to the block).  table: the layers with the
+// recurrent state and ring this pass works on.
+hh_status run_layers(hh_ctx* x, const std::vector<LayerDev>& table, bool all_full, const int* modes, int B, int T,
+                     const int* n_tok, int state_in, int state_out, int n_splits, bool prefill, hipStream_t s) {
   const Dims& d = x->d;
   const int M = B * T;
   for (int l = 0; l < d.L; ++l) {
-    const LayerDev& w = x->layers_host[l];
+    const int mode = all_full ? HH_DRAFT_FULL : (modes ? modes[l] : HH_DRAFT_SSM);
+    if (mode == HH_DRAFT_SKIP) continue;
+    const bool full = mode == HH_DRAFT_FULL;
+    const LayerDev& w = table[l];
     {  // shared input norm, Mamba-2 input projection (+ q, k, v of the attention branch)
       GemvArgs a{};
       a.X = x->h; a.ldx = d.D; a.M = M; a.K = d.D; a.norm_w = w.norm1; a.eps = d.eps; a.epi = EPI_STORE; a.bf16 = d.bf16; a.flags = d.flags;
@@ -457,6 +482,20 @@ int pick_splits(const hh_cfg& c, const Dims& d, int B, int T, int len_upper) {
   return s < 1 ? 1 : s;
 }
 
+// Strict draft state: M_S (no head) over positions first..last of the round (position 0 consumes
+// the pending token, position i draft i), continuing from the draft scratch state (from M_S's
+// committed state at position 0); leaves the raw inputs of those positions in M_S's ring.
+hh_status ms_consume(hh_ctx* x, int B, int first, int last, hipStream_t s) {
+  const Dims& d = x->d;
+  for (int i = first; i <= last; ++i) {
+    HH_HIP(launch_gather_tokens(x->pending, x->drafts, d.Kmax, B, 1, 0, i, x->tok, x->kv_len, x->pos0, s));
+    HH_HIP(launch_embed(d, x->embed, x->tok, B, x->h, s));
+    const hh_status st = run_layers(x, x->layers_ms_host, false, nullptr, B, 1, nullptr, i == 0 ? 0 : 1, 2, 1, false, s);
+    if (st != HH_OK) return st;
+  }
+  return HH_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -545,6 +584,17 @@ hh_status hh_create(const hh_weights* weights, const hh_cfg* cfg, hh_ctx** out) 
   }
   hipError_t e = hipMemcpy(ctx->layers_dev, ctx->layers_host.data(), sizeof(LayerDev) * d.L, hipMemcpyHostToDevice);
   if (e != hipSuccess) return bail(e, "hh_create: upload of layer table");
+  ctx->strict = cfg->draft_state_mode == 1;
+  if (ctx->strict) {
+    for (int l = 0; l < d.L; ++l) {
+      LayerDev ms = ctx->layers_host[l];
+      ms.S = ctx->layers_ms_host[l].S;
+      ms.ring = ctx->layers_ms_host[l].ring;
+      ctx->layers_ms_host[l] = ms;
+    }
+    e = hipMemcpy(ctx->layers_ms_dev, ctx->layers_ms_host.data(), sizeof(LayerDev) * d.L, hipMemcpyHostToDevice);
+    if (e != hipSuccess) return bail(e, "hh_create: upload of the draft model's layer table");
+  }
   e = hipMemset(ctx->attn_counters, 0, sizeof(int) * (size_t)d.Bmax * d.Hkv * attention_row_chunks(d, d.Tmax));
   if (e != hipSuccess) return bail(e, "hh_create: clearing the attention tickets");
   // rotary table: angle pos * base^(-2i/Dh) evaluated in double, stored as float (cos, sin)
@@ -640,7 +690,13 @@ hh_status hh_prefill(hh_ctx* x, const int32_t* tokens, int32_t row_stride, const
     const int* nt = x->plan_ntok + (size_t)p * B;
     HH_HIP(launch_gather_prompt(tokens, row_stride, p * chunk, nt, B, T, x->tok, x->kv_len, x->pos0, s));
     HH_HIP(launch_embed(d, x->embed, x->tok, B * T, x->h, s));
-    hh_status st = run_layers(x, true, B, T, nt, p == 0 ? 2 : 0, 1, 1, true, s);
+    hh_status st = HH_OK;
+    if (x->strict) {   // M_S over the same positions first, into its own state and ring (Eq. 4 at every prefix position)
+      st = run_layers(x, x->layers_ms_host, false, nullptr, B, T, nt, p == 0 ? 2 : 0, 1, 1, true, s);
+      if (st != HH_OK) return st;
+      HH_HIP(launch_embed(d, x->embed, x->tok, B * T, x->h, s));
+    }
+    st = run_layers(x, x->layers_host, true, nullptr, B, T, nt, p == 0 ? 2 : 0, 1, 1, true, s);
     if (st != HH_OK) return st;
     HH_HIP(launch_prefill_tail(x->h, T, d.D, nt, x->plan_last + (size_t)p * B, x->lasth, x->kv_len, B, s));
     // cfg.prefill_progress = n: wait for every n-th pass and report it (long prompts; otherwise the call only enqueues)
@@ -745,11 +801,14 @@ hh_status hh_draft(hh_ctx* x, int32_t k, void* stream) {
   const int B = x->B;
   const bool stochastic = x->temperature > 0.f;
   x->prof_phase = HH_PHASE_DRAFT;
+  const std::vector<LayerDev>& table = x->strict ? x->layers_ms_host : x->layers_host;
+  const int* modes = x->draft_modes.empty() ? nullptr : x->draft_modes.data();
+  const int splits = x->draft_has_full ? pick_splits(x->cfg, d, B, 1, x->len_upper) : 1;
   auto enqueue = [&]() -> hh_status {
     for (int i = 0; i < k; ++i) {
       HH_HIP(launch_gather_tokens(x->pending, x->drafts, d.Kmax, B, 1, 0, i, x->tok, x->kv_len, x->pos0, s));
       HH_HIP(launch_embed(d, x->embed, x->tok, B, x->h, s));
-      hh_status st = run_layers(x, false, B, 1, nullptr, i == 0 ? 0 : 1, 2, 1, false, s);
+      hh_status st = run_layers(x, table, false, modes, B, 1, nullptr, i == 0 ? 0 : 1, 2, splits, false, s);
       if (st != HH_OK) return st;
       st = run_head(x, x->h, B, 1, x->logits_d + (size_t)i * d.V, d.Kmax * d.V, x->drafts, d.Kmax, i, s);
       if (st != HH_OK) return st;
@@ -757,10 +816,13 @@ hh_status hh_draft(hh_ctx* x, int32_t k, void* stream) {
         HH_HIP(launch_sample_rows(x->logits_d + (size_t)i * d.V, (size_t)d.Kmax * d.V, d.V, B, x->sampling, SamplingParams{},
                                   x->committed, i, 0, x->drafts, d.Kmax, i, s));
     }
+    // strict state: M_S also consumes d_k (no head), so that its ring holds the raw inputs of all
+    // k+1 positions a commit may keep
+    if (x->strict) return ms_consume(x, B, k, k, s);
     return HH_OK;
   };
-  if (k > 0) {
-    const hh_status st = run_graphed(x, (1LL << 40) | ((long long)stochastic << 38) | ((long long)B << 20) | k, s, enqueue);
+  if (k > 0 || x->strict) {
+    const hh_status st = run_graphed(x, (1LL << 40) | ((long long)stochastic << 38) | ((long long)B << 20) | ((long long)splits << 8) | k, s, enqueue);
     if (st != HH_OK) return st;
   }
   x->k = k;
@@ -778,7 +840,62 @@ hh_status hh_set_drafts(hh_ctx* x, const int32_t* drafts, void* stream) {
   if (x->k > 0)
     HH_HIP(hipMemcpy2DAsync(x->drafts, (size_t)x->d.Kmax * sizeof(int), drafts, (size_t)x->k * sizeof(int),
                             (size_t)x->k * sizeof(int), x->B, hipMemcpyDeviceToDevice, s));
+  // strict state: M_S's ring must hold the raw inputs of the tokens that may be committed
+  if (x->strict) return ms_consume(x, x->B, 0, x->k, s);
   return HH_OK;
+}
+
+hh_status hh_set_draft_mask(hh_ctx* x, const int32_t* modes) {
+  if (!x) return HH_EINVAL;
+  if (x->phase != PH_CREATED && x->phase != PH_READY)
+    return fail(x, HH_ESTATE, "hh_set_draft_mask: not while a round is in flight");
+  const Dims& d = x->d;
+  std::vector<int> m;
+  bool any = false, has_full = false;
+  if (modes) {
+    m.assign(modes, modes + d.L);
+    for (int v : m) {
+      if (v != HH_DRAFT_SSM && v != HH_DRAFT_FULL && v != HH_DRAFT_SKIP)
+        return fail(x, HH_EINVAL, "hh_set_draft_mask: modes must be HH_DRAFT_SSM, HH_DRAFT_FULL or HH_DRAFT_SKIP");
+      any |= v != HH_DRAFT_SSM;
+      has_full |= v == HH_DRAFT_FULL;
+    }
+  }
+  if (any && x->strict)
+    return fail(x, HH_ESTATE, "hh_set_draft_mask: the strict draft state is defined for the SSM-only draft (all HH_DRAFT_SSM)");
+  if (!any) m.clear();
+  if (m != x->draft_modes) {
+    // captured draft sequences belong to the old mask
+    for (auto it = x->graphs.begin(); it != x->graphs.end();) {
+      if ((it->first >> 40) == 1) {
+        if (it->second.exec) (void)hipGraphExecDestroy(it->second.exec);
+        it = x->graphs.erase(it);
+      } else {
+        ++it;
+      }
+    }
+  }
+  x->draft_modes = m;
+  x->draft_has_full = has_full;
+  return HH_OK;
+}
+
+int32_t hh_optimal_draft_length(double alpha, double cost_ratio, const int32_t* candidates, int32_t n_candidates) {
+  if (!candidates || n_candidates < 1 || !(alpha >= 0.0) || !(alpha <= 1.0) || !(cost_ratio >= 0.0) || !(cost_ratio < 1e30))
+    return -1;
+  std::vector<int32_t> ks(candidates, candidates + n_candidates);
+  std::sort(ks.begin(), ks.end());
+  if (ks.front() < 0) return -1;
+  int32_t best = -1;
+  double best_s = -1.0;
+  for (int32_t k : ks) {   // ascending, so that the shortest of equally good lengths wins
+    // Eq. 1: expected tokens per round 1 + alpha + .. + alpha^k over the round's cost 1 + k * c
+    double tokens = 0.0, pw = 1.0;
+    for (int32_t j = 0; j <= k; ++j) { tokens += pw; pw *= alpha; }
+    const double sp = tokens / (1.0 + (double)k * cost_ratio);
+    if (sp > best_s + 1e-15) { best = k; best_s = sp; }
+  }
+  return best;
 }
 
 hh_status hh_verify(hh_ctx* x, void* stream) {
@@ -793,7 +910,7 @@ hh_status hh_verify(hh_ctx* x, void* stream) {
   auto enqueue = [&]() -> hh_status {
     HH_HIP(launch_gather_tokens(x->pending, x->drafts, d.Kmax, B, T, 1, 0, x->tok, x->kv_len, x->pos0, s));
     HH_HIP(launch_embed(d, x->embed, x->tok, B * T, x->h, s));
-    hh_status st = run_layers(x, true, B, T, nullptr, 0, 0, splits, false, s);
+    hh_status st = run_layers(x, x->layers_host, true, nullptr, B, T, nullptr, 0, 0, splits, false, s);
     if (st != HH_OK) return st;
     st = run_head(x, x->h, B * T, T, x->logits_v, d.V, x->targets, d.Kmax + 1, 0, s);
     if (st != HH_OK) return st;
@@ -829,6 +946,10 @@ hh_status hh_commit(hh_ctx* x, const int32_t* n_accepted, void* stream) {
   a.zx = nullptr; a.g = nullptr; a.pos0 = x->kv_len; a.n_tok = nullptr; a.n_acc = x->n_acc; a.skip = x->skip;
   a.T = x->k + 1; a.B = B; a.state_in = 0; a.state_out = 1; a.write_ring = 0;
   HH_LAUNCH(HH_K_SSM, launch_ssm(d, a, s));
+  if (x->strict) {   // M_S has consumed the same n+1 tokens: its state after position n, from its own ring
+    a.layers = x->layers_ms_dev;
+    HH_LAUNCH(HH_K_SSM, launch_ssm(d, a, s));
+  }
   HH_HIP(launch_advance(x->kv_len, x->adv, B, s));
   x->len_upper += x->k + 1;
   if (x->len_upper > d.max_seq) x->len_upper = d.max_seq;
@@ -920,6 +1041,22 @@ hh_status hh_get_state(hh_ctx* x, int32_t layer, float* ssm, float* conv, void* 
   return HH_OK;
 }
 
+hh_status hh_get_draft_state(hh_ctx* x, int32_t layer, float* ssm, float* conv, void* stream) {
+  if (!x) return HH_EINVAL;
+  if (x->phase == PH_CREATED) return fail(x, HH_ESTATE, "hh_get_draft_state: nothing prefilled");
+  if (!x->strict) return fail(x, HH_ESTATE, "hh_get_draft_state: needs cfg.draft_state_mode = 1");
+  const Dims& d = x->d;
+  if (layer < 0 || layer >= d.L) return fail(x, HH_EINVAL, "hh_get_draft_state: layer out of range");
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  if (conv) HH_HIP(launch_export_state(d, x->layers_ms_dev + layer, x->kv_len, x->B, x->export_buf, s));
+  hh_status st = sync_stream(x, stream);
+  if (st != HH_OK) return st;
+  if (ssm)
+    HH_HIP(hipMemcpy(ssm, x->layers_ms_host[layer].S, (size_t)x->B * d.Hm * d.P * d.N * 4, hipMemcpyDeviceToHost));
+  if (conv) HH_HIP(hipMemcpy(conv, x->export_buf, (size_t)x->B * d.conv_dim * 3 * 4, hipMemcpyDeviceToHost));
+  return HH_OK;
+}
+
 hh_status hh_get_kv(hh_ctx* x, int32_t layer, int32_t seq, int32_t n_tokens, float* k, float* v, void* stream) {
   if (!x) return HH_EINVAL;
   if (x->phase == PH_CREATED) return fail(x, HH_ESTATE, "hh_get_kv: nothing prefilled");
@@ -980,7 +1117,7 @@ hh_status hh_time_kind(hh_ctx* x, int32_t phase, int32_t kind, int32_t k, int32_
                       full ? x->targets : x->drafts, full ? d.Kmax + 1 : d.Kmax, 0, s);
         n += 1;
       } else {
-        st = run_layers(x, full, B, T, nullptr, 0, full ? 0 : 2, pick_splits(x->cfg, d, B, T, x->len_upper), false, s);
+        st = run_layers(x, x->layers_host, full, nullptr, B, T, nullptr, 0, full ? 0 : 2, pick_splits(x->cfg, d, B, T, x->len_upper), false, s);
         n += d.L;
       }
     }

@@ -6,7 +6,7 @@ from typing import Optional
 import numpy as np
 
 from oracle.hybrid_lm import HybridLM
-from oracle.protocol import SpecDecoder
+from oracle.protocol import SpecDecoder, accepted_prefix
 from paper_2605_01106_amd import workloads as W
 
 
@@ -37,7 +37,7 @@ def run_lockstep(ctx, weights: W.Weights, prompts, lens, G: int, k: int, forced:
                  override: Optional[np.ndarray] = None, engine: str = "pass", max_rounds: int = 10 ** 9,
                  check_state_every: int = 1, check_kv: bool = True, min_gap: float = 0.0, report=None,
                  layers=None, oracle_rows=None, chunk: int = 5, temperature: float = 0.0, sample_seed: int = 0,
-                 min_margin: float = 0.0, compare_logits: bool = True):
+                 min_margin: float = 0.0, compare_logits: bool = True, draft_state: str = "shared", draft_mask=None):
     """Runs prefill and rounds on both sides, comparing after every call:
     tokens, accepted counts, cache lengths and committed counts bit-exactly;
     logits, SSM state, conv window and KV entries within tolerance.
@@ -49,6 +49,9 @@ def run_lockstep(ctx, weights: W.Weights, prompts, lens, G: int, k: int, forced:
     `sample_seed`; `min_margin` is the seed audit of those decisions (the analogue of `min_gap`).
     `compare_logits` False: the context keeps no logits (keep_logits = 0); tokens, counts, lengths,
     state and cache are still compared.
+    `draft_state` "strict": the context was created with draft_state_mode = 1; the oracle keeps M_S's
+    own state, which is compared as well.  `draft_mask`: per-layer "full" | "ssm" | "skip" of the draft
+    model, set on both sides.
     Returns a dict of the worst errors seen."""
     import torch
     cfg = weights.cfg
@@ -59,14 +62,16 @@ def run_lockstep(ctx, weights: W.Weights, prompts, lens, G: int, k: int, forced:
     lm = HybridLM(cfg, weights.values)
     ks = [int(k)] if np.isscalar(k) else [int(v) for v in k]
     cap = int(max(lens)) + G + 2 * max(ks) + 4
-    dec = SpecDecoder(lm, cap, engine=engine, chunk=chunk, temperature=temperature, seed=sample_seed)
+    dec = SpecDecoder(lm, cap, engine=engine, chunk=chunk, temperature=temperature, seed=sample_seed,
+                      draft_state=draft_state, draft_mask=draft_mask)
+    ctx.hh_set_draft_mask(draft_mask)
     plist = [np.asarray(prompts[b][:lens[b]]) for b in rows]
     dec.prefill(plist, G)
     if temperature > 0:
         assert oracle_rows is None, "the uniforms are keyed by the batch row"
     ctx.hh_set_sampling(temperature, sample_seed)
     ctx.hh_prefill(prompts, lens, G)
-    worst = {"logits": 0.0, "ssm": 0.0, "conv": 0.0, "kv": 0.0}
+    worst = {"logits": 0.0, "ssm": 0.0, "conv": 0.0, "kv": 0.0, "ms_ssm": 0.0, "ms_conv": 0.0}
     if compare_logits:
         worst["logits"] = max(worst["logits"], assert_close(
             "prefill logits", ctx.hh_get_logits(2)[rows], np.array(dec.prefill_logits), atol, rtol))
@@ -85,6 +90,12 @@ def run_lockstep(ctx, weights: W.Weights, prompts, lens, G: int, k: int, forced:
                 f"{tag} ssm L{l}", ssm, np.array([s.S[l] for s in dec.st]), atol, rtol, scale_to_ref=True))
             worst["conv"] = max(worst["conv"], assert_close(
                 f"{tag} conv L{l}", conv, np.array([s.conv[l] for s in dec.st]), atol, rtol, scale_to_ref=True))
+            if draft_state == "strict":
+                ssm, conv = ctx.hh_get_draft_state(l)
+                worst["ms_ssm"] = max(worst["ms_ssm"], assert_close(
+                    f"{tag} M_S ssm L{l}", ssm[rows], np.array([s.S[l] for s in dec.ms]), atol, rtol, scale_to_ref=True))
+                worst["ms_conv"] = max(worst["ms_conv"], assert_close(
+                    f"{tag} M_S conv L{l}", conv[rows], np.array([s.conv[l] for s in dec.ms]), atol, rtol, scale_to_ref=True))
             if check_kv:
                 for b in range(B):
                     n = dec.st[b].kv_len
@@ -130,7 +141,23 @@ def run_lockstep(ctx, weights: W.Weights, prompts, lens, G: int, k: int, forced:
                 if compare_logits:
                     worst["logits"] = max(worst["logits"], assert_close(
                         f"round {r} verify logits b{b}", vl[b], dec.verify_logits[b], atol, rtol))
-                assert list(g_gpu[b]) == list(dec.targets[b]), (r, b, list(g_gpu[b]), dec.targets[b])
+                # targets up to the first mismatch decide tokens and must agree exactly (their top-2 gaps
+                # are audited by min_gap); behind it they are never used: there a near-tie of M_H's logits on
+                # junk input may fall either way, and the library's choice only has to be a maximum within
+                # the logit tolerance
+                if temperature > 0:
+                    n_dec = len(dec.targets[b])
+                elif forced is not None:
+                    n_dec = int(forced[r][rows[b]]) + 1
+                else:
+                    n_dec = accepted_prefix(dec.drafts[b], dec.targets[b]) + 1
+                assert list(g_gpu[b][:n_dec]) == list(dec.targets[b][:n_dec]), (r, b, list(g_gpu[b]), dec.targets[b])
+                for j in range(n_dec, len(dec.targets[b])):
+                    if int(g_gpu[b][j]) != int(dec.targets[b][j]):
+                        row = dec.verify_logits[b][j]
+                        top = float(np.max(row))
+                        assert 0 <= g_gpu[b][j] < len(row) and row[g_gpu[b][j]] >= top - 2 * (atol + rtol * abs(top)), \
+                            (r, b, j, list(g_gpu[b]), dec.targets[b], float(row[g_gpu[b][j]]), top)
         if forced is None:
             dec.commit()
             ctx.hh_commit()

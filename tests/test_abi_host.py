@@ -112,3 +112,15 @@ def test_stand_alone_token_choice_rejects_bad_arguments(B):
     assert accept_static(k=-1) == B.HH_EINVAL
     assert accept_static(t=float("nan")) == B.HH_EINVAL
     assert "hh_accept_tokens_static" in B.hh_last_error(None)
+
+
+def test_optimal_draft_length_matches_the_oracle(B):
+    """hh_optimal_draft_length against the oracle's maximiser of Eq. 1 on a grid; bad arguments give -1."""
+    from oracle.protocol import optimal_draft_length
+    for alpha in (0.0, 0.3, 0.68, 0.9, 0.97, 1.0):
+        for c in (0.0, 0.05, 0.2, 0.5, 0.784, 1.0):
+            for cand in ([2, 4, 8], list(range(0, 17)), [8, 1, 3]):
+                assert B.hh_optimal_draft_length(alpha, c, cand) == optimal_draft_length(alpha, c, cand), (alpha, c, cand)
+    assert B.hh_optimal_draft_length(1.5, 0.5, [1, 2]) == -1
+    assert B.hh_optimal_draft_length(0.5, -1.0, [1, 2]) == -1
+    assert B.hh_optimal_draft_length(0.5, 0.5, [1, -2]) == -1

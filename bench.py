@@ -146,6 +146,7 @@ def main():
                     help="prompt positions per sequence per prefill pass (0: the library's default)")
     ap.add_argument("--prompt-len", type=int, default=None,
                     help="override the workload's prompt length (a shorter stand-in; named in config.workload)")
+    ap.add_argument("--kernel-flags", type=int, default=0, help="hh_cfg.kernel_flags (HH_KF_* bits: kernel selection)")
     ap.add_argument("--k", type=int, default=None, help="draft length (default: the workload's)")
     ap.add_argument("--draft-state", choices=("shared", "strict"), default="shared",
                     help="strict: the draft model keeps its own recurrent state over the whole prefix")
@@ -200,7 +201,7 @@ def main():
     n_pass_hint = 16 if wl.prompt_len * Bn > (1 << 18) else 0
     ctx = B.Context(weights, Bn, max_seq, k, G, use_graphs=0 if args.counters else args.graphs,
                     prefill_chunk=args.prefill_chunk, keep_logits=args.keep_logits, prefill_progress=n_pass_hint,
-                    draft_state_mode=1 if args.draft_state == "strict" else 0)
+                    draft_state_mode=1 if args.draft_state == "strict" else 0, kernel_flags=args.kernel_flags)
     ctx.hh_set_draft_mask(draft_mask)
     torch.cuda.synchronize()
     say("prefill")

@@ -32,11 +32,12 @@ union LFrag {
 
 constexpr int kLdsWaves = 8;                  // 4 along the weight rows x 2 along the activation rows
 constexpr int kLdsA = 16;                     // weight fragments per workgroup and step
-constexpr int kLdsRowTiles = 12;              // activation row tiles per workgroup
-constexpr int kLdsP = kLdsRowTiles * 3;       // plane fragments per workgroup and step
-constexpr int kLdsFrags = kLdsA + kLdsP;      // 52
-constexpr int kLdsStageBytes = kLdsFrags * 1024;
-constexpr int kLdsItems = (kLdsFrags * 64 + 64 * kLdsWaves - 1) / (64 * kLdsWaves);   // 16-byte copies per thread and step: 7
+// MTW = activation row tiles per wavefront (6, or 1..3 for passes of at most 96 rows): the
+// workgroup covers 2 MTW row tiles, 6 MTW plane fragments per step
+constexpr int lds_row_tiles(int mtw) { return 2 * mtw; }
+constexpr int lds_frags(int mtw) { return kLdsA + 6 * mtw; }
+constexpr int lds_stage_bytes(int mtw) { return lds_frags(mtw) * 1024; }
+constexpr int lds_items(int mtw) { return (lds_frags(mtw) + kLdsWaves - 1) / kLdsWaves; }   // 16-byte copies per thread and step
 
 struct LdsGemmArgs {
   const uint16_t* planes; int m_tiles, KST;    // split activations: block (row tile, step, term) of 512 elements
@@ -48,12 +49,13 @@ struct LdsGemmArgs {
   unsigned long long* row_best; int store;     // EPI_STORE: per-row argmax keys (atomic maxima); store = 0: Y not written
 };
 
-template <int EPI>
+template <int EPI, int MTW>
 __global__ __launch_bounds__(64 * kLdsWaves) void gemm_lds_kernel(const LdsGemmArgs a) {
   constexpr int NF = EPI == EPI_SWIGLU ? 2 : 1;
   constexpr int NS = 4 / NF;                   // strips (strip pairs) per wavefront
-  constexpr int MTW = 6;                       // row tiles per wavefront
   constexpr int SPB = kLdsA / NF;              // strips (pairs) per workgroup
+  constexpr int ROW_TILES = lds_row_tiles(MTW), FRAGS = lds_frags(MTW), STAGE = lds_stage_bytes(MTW), ITEMS = lds_items(MTW);
+  static_assert(ITEMS >= 3 && ITEMS <= 7 && kLdsA == 2 * kLdsWaves, "two weight fragments and one to five plane fragments per wavefront and step");
   extern __shared__ __align__(16) unsigned char smem_raw[];
   const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int wn = wave & 3, wm = wave >> 2;
@@ -64,51 +66,57 @@ __global__ __launch_bounds__(64 * kLdsWaves) void gemm_lds_kernel(const LdsGemmA
   const int n_steps = k_end - k_begin;
 
   // ---- the copies of this thread: wavefront w copies the fragments w, w + 8, ... (a fragment is
-  // 1 KB: one 16-byte copy per lane); the first two are weight fragments, the rest plane fragments
-  // (the seventh only exists for the wavefronts 0..3)
-  const uint16_t* src[kLdsItems];
+  // 1 KB: one 16-byte copy per lane); the first two are weight fragments, the rest plane
+  // fragments.  Every wavefront issues exactly ITEMS copies per step (a wavefront without a
+  // fragment of its own in the last round repeats its previous one), so that "at most ITEMS
+  // copies outstanding" means for each of them: the copies of the step before the newest one
+  // have landed.
+  const uint16_t* src[ITEMS];
+  unsigned dst[ITEMS];      // byte offset of the fragment within a stage
+  int stride[ITEMS];        // elements from one step's fragment to the next step's
 #pragma unroll
-  for (int j = 0; j < kLdsItems; ++j) {
-    // (the seventh copy of the wavefronts 4..7 repeats their sixth fragment)
-    const int frag = wave + kLdsWaves * j < kLdsFrags ? wave + kLdsWaves * j : wave + kLdsWaves * (j - 1);
-    if (j < 2) {
+  for (int j = 0; j < ITEMS; ++j) {
+    const int frag = wave + kLdsWaves * j < FRAGS ? wave + kLdsWaves * j : wave + kLdsWaves * (j - 1);
+    dst[j] = (unsigned)frag * 1024;
+    if (frag < kLdsA) {
       // fragment wn' * 4 + i of the workgroup: NF == 1: strip wn' * 4 + i; NF == 2: pair wn' * 2 + i % 2 of matrix i / 2
       const int w4 = frag >> 2, i = frag & 3;
       const int strip = nb * SPB + (NF == 2 ? w4 * 2 + (i & 1) : frag);
       const uint16_t* base = (NF == 2 && i >= 2) ? a.W2 : a.W;
       src[j] = base + ((size_t)min(strip, a.n_tiles - 1) * a.KST + k_begin) * 512 + lane * 8;
+      stride[j] = 512;
     } else {
       const int pf = frag - kLdsA, rt = pf / 3, term = pf - rt * 3;
-      const int mt = min(mb * kLdsRowTiles + rt, a.m_tiles - 1);
+      const int mt = min(mb * ROW_TILES + rt, a.m_tiles - 1);
       src[j] = a.planes + (((size_t)mt * a.KST + k_begin) * 3 + term) * 512 + lane * 8;
+      stride[j] = 1536;
     }
   }
-  // Every wavefront issues exactly seven copies per step (the wavefronts 4..7, which have six
-  // fragments, repeat their last one), so that "at most seven copies outstanding" means for each
-  // of them: the copies of the step before the newest one have landed.
   // The copies are issued through inline assembly (M0 = LDS byte address of the wavefront's 1 KB
   // slot): issued through the compiler's builtin, every LDS read after them is made to wait for
   // ALL outstanding copies, which would serialise the pipeline.  The waits are explicit below.
   typedef __attribute__((address_space(3))) void* lptr_t;
-  static_assert(kLdsItems == 7 && kLdsA == 2 * kLdsWaves, "seven copies per wavefront and step: 2 weight and 5 plane fragments");
-  const int last_frag = wave + kLdsWaves * 6 < kLdsFrags ? wave + kLdsWaves * 6 : wave + kLdsWaves * 5;
   const unsigned lds0 = (unsigned)(size_t)(lptr_t)smem_raw;
   auto copy16 = [](const void* gsrc, unsigned lds_byte_address) {
     asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(gsrc), "s"(lds_byte_address) : "memory", "m0");
   };
+#define HH_LDS_COPY1(j, s_, b_) \
+  if (ITEMS > (j)) copy16(src[(j) < ITEMS ? (j) : 0] + s_ * (size_t)stride[(j) < ITEMS ? (j) : 0], b_ + dst[(j) < ITEMS ? (j) : 0])
 #define HH_LDS_COPY(step, stage)                                                                       \
   do {                                                                                                 \
     const size_t s_ = (size_t)min((step), n_steps - 1);   /* past the end: the last step again */      \
-    const unsigned b_ = lds0 + (unsigned)(stage) * kLdsStageBytes + (unsigned)wave * 1024;             \
-    copy16(src[0] + s_ * 512, b_);                                                                     \
-    copy16(src[1] + s_ * 512, b_ + 8192);                                                              \
-    copy16(src[2] + s_ * 1536, b_ + 2 * 8192);                                                         \
-    copy16(src[3] + s_ * 1536, b_ + 3 * 8192);                                                         \
-    copy16(src[4] + s_ * 1536, b_ + 4 * 8192);                                                         \
-    copy16(src[5] + s_ * 1536, b_ + 5 * 8192);                                                         \
-    copy16(src[6] + s_ * 1536, lds0 + (unsigned)(stage) * kLdsStageBytes + (unsigned)last_frag * 1024); \
+    const unsigned b_ = lds0 + (unsigned)(stage) * STAGE;                                              \
+    HH_LDS_COPY1(0, s_, b_); HH_LDS_COPY1(1, s_, b_); HH_LDS_COPY1(2, s_, b_); HH_LDS_COPY1(3, s_, b_); \
+    HH_LDS_COPY1(4, s_, b_); HH_LDS_COPY1(5, s_, b_); HH_LDS_COPY1(6, s_, b_);                         \
   } while (0)
-#define HH_LDS_WAIT_PREVIOUS() asm volatile("s_waitcnt vmcnt(7)" ::: "memory")
+#define HH_LDS_WAIT_PREVIOUS()                                                 \
+  do {                                                                         \
+    if (ITEMS == 7) asm volatile("s_waitcnt vmcnt(7)" ::: "memory");           \
+    else if (ITEMS == 6) asm volatile("s_waitcnt vmcnt(6)" ::: "memory");      \
+    else if (ITEMS == 5) asm volatile("s_waitcnt vmcnt(5)" ::: "memory");      \
+    else if (ITEMS == 4) asm volatile("s_waitcnt vmcnt(4)" ::: "memory");      \
+    else asm volatile("s_waitcnt vmcnt(3)" ::: "memory");                      \
+  } while (0)
 
   lds_f32x4 acc[NF][NS][MTW];
 #pragma unroll
@@ -122,7 +130,7 @@ __global__ __launch_bounds__(64 * kLdsWaves) void gemm_lds_kernel(const LdsGemmA
   // one step: this wavefront's 4 weight fragments, then row tile by row tile three plane fragments
   // (the next row tile's are read while this one is multiplied)
   auto compute = [&](int stage) {
-    const unsigned char* base = smem_raw + (size_t)stage * kLdsStageBytes + lane * 16;
+    const unsigned char* base = smem_raw + (size_t)stage * STAGE + lane * 16;
     LFrag wf[4];
 #pragma unroll
     for (int i = 0; i < 4; ++i) wf[i].u = *reinterpret_cast<const uint4*>(base + (wn * 4 + i) * 1024);
@@ -168,6 +176,7 @@ __global__ __launch_bounds__(64 * kLdsWaves) void gemm_lds_kernel(const LdsGemmA
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");     // the copies issued past the end land before the workgroup leaves
 #undef HH_LDS_FENCE
 #undef HH_LDS_COPY
+#undef HH_LDS_COPY1
 #undef HH_LDS_WAIT_PREVIOUS
 
   // ---- results: lane (g, n) holds D[weight row 4g+r][activation row n] of every (strip, row tile).
@@ -179,7 +188,7 @@ __global__ __launch_bounds__(64 * kLdsWaves) void gemm_lds_kernel(const LdsGemmA
   unsigned long long best[MTW];
 #pragma unroll
   for (int m = 0; m < MTW; ++m) best[m] = 0ull;
-  const int mt0 = mb_e * kLdsRowTiles + wm * MTW;
+  const int mt0 = mb_e * ROW_TILES + wm * MTW;
 #pragma unroll
   for (int t = 0; t < NS; ++t) {
     const int strip = nb_e * SPB + wn * NS + t;

@@ -262,9 +262,18 @@ __global__ __launch_bounds__(256) void gemm_reduce_kernel(const GemmArgs a) {
   for (size_t it = it_first; it < it_end; it += it_stride) {
     const size_t m = it / a.N, nn = it - m * a.N;
     // the sums of squares are requested first, so that they arrive with the partial products
+    // (in batches of 8 independent loads: one load per loop pass would cost a cache round trip per split)
     float tot = 0.f;
-    if (a.ssq != nullptr)
-      for (int s = 0; s < a.ksplit; ++s) tot += a.ssq[(size_t)s * a.ssq_ld + m];
+    if (a.ssq != nullptr) {
+      for (int s0 = 0; s0 < a.ksplit; s0 += 8) {
+        float q[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) q[u] = a.ssq[(size_t)min(s0 + u, a.ksplit - 1) * a.ssq_ld + m];
+#pragma unroll
+        for (int u = 0; u < 8; ++u)
+          if (s0 + u < a.ksplit) tot += q[u];
+      }
+    }
     float* y = a.Y + m * a.ldy + nn;
     float4 old = make_float4(0.f, 0.f, 0.f, 0.f);          // residual(s), requested with them
     if (EPI == EPI_ADD && VEC) {
@@ -356,18 +365,28 @@ size_t gemm_planes_elems(int M, int K) {
 // float elements of scratch for the partial products of split-K launches
 size_t gemm_partial_elems() { return (size_t)24 << 20; }
 
-// The LDS-staged kernel: more than six row tiles (96 rows)
-template <int EPI>
-static hipError_t lds_launch(const LdsGemmArgs& a, hipStream_t s) {
-  auto kern = gemm_lds_kernel<EPI>;
+// The LDS-staged kernel with MTW row tiles per wavefront (2 MTW per workgroup)
+template <int EPI, int MTW>
+static hipError_t lds_launch_m(const LdsGemmArgs& a, hipStream_t s) {
+  auto kern = gemm_lds_kernel<EPI, MTW>;
   static bool enabled = false;
   if (!enabled) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, 3 * kLdsStageBytes);
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, 3 * lds_stage_bytes(MTW));
     if (e != hipSuccess) return e;
     enabled = true;
   }
-  hipLaunchKernelGGL(kern, dim3(a.n_blocks * a.m_blocks * a.ksplit), dim3(64 * kLdsWaves), 3 * kLdsStageBytes, s, a);
+  hipLaunchKernelGGL(kern, dim3(a.n_blocks * a.m_blocks * a.ksplit), dim3(64 * kLdsWaves), 3 * lds_stage_bytes(MTW), s, a);
   return hipGetLastError();
+}
+template <int EPI>
+static hipError_t lds_launch(const LdsGemmArgs& a, int mtw, hipStream_t s) {
+  switch (mtw) {
+    case 1: return lds_launch_m<EPI, 1>(a, s);
+    case 2: return lds_launch_m<EPI, 2>(a, s);
+    case 3: return lds_launch_m<EPI, 3>(a, s);
+    case 6: return lds_launch_m<EPI, 6>(a, s);
+  }
+  return hipErrorInvalidValue;
 }
 
 template <int EPI, int NT, int MTW>
@@ -409,27 +428,31 @@ hipError_t launch_gemm_mfma(const GemvArgs& g, uint16_t* planes, float* partial,
   a.Y = g.seg[0].Y; a.ldy = g.seg[0].ldy; a.R2 = g.R2; a.partial = partial; a.M = M; a.N = N; a.K = K;
   a.row_best = g.epi == EPI_STORE ? g.row_best : nullptr; a.store = g.no_store && a.row_best != nullptr ? 0 : 1;
   const int steps = Kp / 32, tiles = (N + 15) / 16, m_tiles = Mp / 16;
-  if (m_tiles > 6 && a.terms == 3) {
+  if ((m_tiles > 6 || (g.flags & HH_KF_ROWS_LDS)) && a.terms == 3) {
+    // row tiles per wavefront: 6 (192-row workgroups) for many rows; up to 96 rows one workgroup holds them all
+    const int mtw = m_tiles > 6 ? 6 : (m_tiles + 1) / 2;
     LdsGemmArgs l{};
     l.planes = planes; l.m_tiles = m_tiles; l.KST = steps;
     l.W = a.W; l.W2 = a.W2; l.Y = a.Y; l.ldy = a.ldy; l.R2 = a.R2; l.partial = partial;
     l.M = M; l.N = N; l.n_tiles = tiles; l.row_best = a.row_best; l.store = a.store;
     l.n_blocks = (tiles + kLdsA / nf - 1) / (kLdsA / nf);
-    l.m_blocks = (m_tiles + kLdsRowTiles - 1) / kLdsRowTiles;
+    l.m_blocks = (m_tiles + lds_row_tiles(mtw) - 1) / lds_row_tiles(mtw);
     // K split only where the tiles alone leave most of the chip idle: the partial products cost
-    // ks * M * N floats written and read again.  At least 8 steps per workgroup, partial buffer permitting.
+    // ks * M * N floats written and read again.  At least 8 steps per workgroup (3 with few rows,
+    // where the products are short and latency-bound), partial buffer permitting.
     const int blocks = l.n_blocks * l.m_blocks;
+    const int min_steps = m_tiles > 6 ? 8 : 3;
     int ks = 1;
     if (blocks < 128) {
-      ks = (224 + blocks - 1) / blocks;
-      while (ks > 1 && (steps / ks < 8 || (size_t)ks * nf * M * N > gemm_partial_elems())) --ks;
+      ks = ((m_tiles > 6 ? 224 : 256) + blocks - 1) / blocks;
+      while (ks > 1 && (steps / ks < min_steps || (size_t)ks * nf * M * N > gemm_partial_elems())) --ks;
     }
     l.ksteps = (steps + ks - 1) / ks;
     l.ksplit = (steps + l.ksteps - 1) / l.ksteps;
     switch (g.epi) {
-      case EPI_STORE: e = lds_launch<EPI_STORE>(l, s); break;
-      case EPI_ADD: e = lds_launch<EPI_ADD>(l, s); break;
-      case EPI_SWIGLU: e = lds_launch<EPI_SWIGLU>(l, s); break;
+      case EPI_STORE: e = lds_launch<EPI_STORE>(l, mtw, s); break;
+      case EPI_ADD: e = lds_launch<EPI_ADD>(l, mtw, s); break;
+      case EPI_SWIGLU: e = lds_launch<EPI_SWIGLU>(l, mtw, s); break;
       default: return hipErrorInvalidValue;
     }
     if (e != hipSuccess || l.ksplit == 1) return e;

@@ -151,7 +151,7 @@ bool derive_dims(const hh_cfg& c, Dims& d, std::string& why) {
   if (c.overlap_mode < 0 || c.overlap_mode > 3) return bad("overlap_mode must be in 0..3");
   if (c.attn_max_splits < 0 || c.attn_max_splits > kMaxSplits) return bad("attn_max_splits must be in 0..32");
   if (c.attn_single_slice_steps < -1) return bad("attn_single_slice_steps must be -1, 0 or a step count");
-  if (c.kernel_flags & ~(HH_KF_ATTN_SCALAR | HH_KF_SSM_GENERAL | HH_KF_MID_OFF | HH_KF_SKINNY_OFF | HH_KF_SSM_SCALAR_CONV))
+  if (c.kernel_flags & ~(HH_KF_ATTN_SCALAR | HH_KF_SSM_GENERAL | HH_KF_MID_OFF | HH_KF_SKINNY_OFF | HH_KF_SSM_SCALAR_CONV | HH_KF_ROWS_LDS))
     return bad("unknown bit in kernel_flags");
   if (c.prefill_progress < 0) return bad("prefill_progress must not be negative");
   if (c.draft_state_mode != 0 && c.draft_state_mode != 1) return bad("draft_state_mode must be 0 (shared) or 1 (strict)");
@@ -484,13 +484,14 @@ int pick_splits(const hh_cfg& c, const Dims& d, int B, int T, int len_upper) {
 
 // Strict draft state: M_S (no head) over positions first..last of the round (position 0 consumes
 // the pending token, position i draft i), continuing from the draft scratch state (from M_S's
-// committed state at position 0); leaves the raw inputs of those positions in M_S's ring.
+// committed state at position 0); leaves the raw inputs of those positions in M_S's ring (the
+// scratch state after the last of them is not needed and not written).
 hh_status ms_consume(hh_ctx* x, int B, int first, int last, hipStream_t s) {
   const Dims& d = x->d;
   for (int i = first; i <= last; ++i) {
     HH_HIP(launch_gather_tokens(x->pending, x->drafts, d.Kmax, B, 1, 0, i, x->tok, x->kv_len, x->pos0, s));
     HH_HIP(launch_embed(d, x->embed, x->tok, B, x->h, s));
-    const hh_status st = run_layers(x, x->layers_ms_host, false, nullptr, B, 1, nullptr, i == 0 ? 0 : 1, 2, 1, false, s);
+    const hh_status st = run_layers(x, x->layers_ms_host, false, nullptr, B, 1, nullptr, i == 0 ? 0 : 1, i == last ? 0 : 2, 1, false, s);
     if (st != HH_OK) return st;
   }
   return HH_OK;
@@ -808,7 +809,9 @@ hh_status hh_draft(hh_ctx* x, int32_t k, void* stream) {
     for (int i = 0; i < k; ++i) {
       HH_HIP(launch_gather_tokens(x->pending, x->drafts, d.Kmax, B, 1, 0, i, x->tok, x->kv_len, x->pos0, s));
       HH_HIP(launch_embed(d, x->embed, x->tok, B, x->h, s));
-      hh_status st = run_layers(x, table, false, modes, B, 1, nullptr, i == 0 ? 0 : 1, 2, splits, false, s);
+      // the scratch state after the last step is never read (unless M_S goes on to consume d_k): not written
+      const int state_out = (i == k - 1 && !x->strict) ? 0 : 2;
+      hh_status st = run_layers(x, table, false, modes, B, 1, nullptr, i == 0 ? 0 : 1, state_out, splits, false, s);
       if (st != HH_OK) return st;
       st = run_head(x, x->h, B, 1, x->logits_d + (size_t)i * d.V, d.Kmax * d.V, x->drafts, d.Kmax, i, s);
       if (st != HH_OK) return st;

@@ -233,6 +233,7 @@ __global__ __launch_bounds__(512) void mid_loop_kernel(const MidArgs a) {
       }
     }
   }
+  TR(5);
 }
 
 

@@ -156,7 +156,7 @@ def test_key_slices_do_not_change_results(B, max_splits, single):
 
 
 @pytest.mark.parametrize("flag", ["HH_KF_ATTN_SCALAR", "HH_KF_SSM_GENERAL", "HH_KF_MID_OFF", "HH_KF_SKINNY_OFF",
-                                  "HH_KF_SSM_SCALAR_CONV"])
+                                  "HH_KF_SSM_SCALAR_CONV", "HH_KF_MID_OFF|HH_KF_ROWS_LDS"])
 def test_kernel_selection_flags_do_not_change_results(B, flag):
     """Every kernel-selection switch routes a family of launches to the slower kernel that computes
     the same thing; each variant is checked against the oracle on a workload that reaches the family:
@@ -166,7 +166,10 @@ def test_kernel_selection_flags_do_not_change_results(B, flag):
     wts = W.make_lively_weights(cfg, 46)          # seeds audited: top-1/top-2 gap 8.9e-4
     lens = [61, 33, 90, 47, 75, 52]
     prompts = W.make_prompts(cfg.vocab, 6, lens, 16)
-    ctx = _ctx(B, wts, 6, 128, 3, 10, kv_page_tokens=32, prefill_chunk=32, kernel_flags=getattr(B, flag))
+    bits = 0
+    for name in flag.split("|"):
+        bits |= getattr(B, name)
+    ctx = _ctx(B, wts, 6, 128, 3, 10, kv_page_tokens=32, prefill_chunk=32, kernel_flags=bits)
     run_lockstep(ctx, wts, prompts, lens, 10, 3, engine="pass", min_gap=4e-4, report=_say(flag))
 
 

@@ -147,6 +147,9 @@ def main():
     ap.add_argument("--prompt-len", type=int, default=None,
                     help="override the workload's prompt length (a shorter stand-in; named in config.workload)")
     ap.add_argument("--kernel-flags", type=int, default=0, help="hh_cfg.kernel_flags (HH_KF_* bits: kernel selection)")
+    ap.add_argument("--adaptive-rounds", type=int, default=0,
+                    help="extra leg of this many rounds in which k is re-chosen every 4 rounds from the library's acceptance "
+                         "statistics and the measured cost ratio (Eq. 1); forced acceptance pattern cut off at k")
     ap.add_argument("--k", type=int, default=None, help="draft length (default: the workload's)")
     ap.add_argument("--draft-state", choices=("shared", "strict"), default="shared",
                     help="strict: the draft model keeps its own recurrent state over the whole prefix")
@@ -183,7 +186,7 @@ def main():
     prof_rounds, greedy_rounds = 3, min(K, 32)
     forced_p = args.forced_p if args.forced_p is not None else (wl.forced_p or 0.68)
     primary_forced = wl.forced_p is not None          # the workload's own acceptance mode is the headline leg
-    total_rounds = Wm + K + K + K + prof_rounds + greedy_rounds + 6
+    total_rounds = Wm + K + K + K + prof_rounds + greedy_rounds + 6 + args.adaptive_rounds
     G = max(wl.gen_len, total_rounds * (k + 1) + 2)
     max_seq = wl.prompt_len + G + 2 * k + 4
 
@@ -325,6 +328,35 @@ def main():
         stochastic = {"temperature": args.temperature, "committed_tokens_per_s": round(toks_s / dt_s, 2),
                       "mean_accepted_per_round": round(toks_s / (K * Bn) - 1, 3)}
 
+    # adaptive draft length (Section 7): k re-chosen every 4 rounds as the maximiser of Eq. 1 for the acceptance rate
+    # the library has counted in this leg and the cost ratio measured above
+    adaptive = None
+    if args.adaptive_rounds > 0:
+        ratio = (t_draft / (K * k)) / (t_verify / K)
+        pat = W.make_forced_pattern(args.adaptive_rounds, Bn, k, forced_p, args.seed + 1)
+        a0, t0_ = ctx.hh_get_acceptance()
+        _, c0, _ = ctx.hh_get_lengths()
+        torch.cuda.synchronize()
+        ts = time.perf_counter()
+        kk, ks_used = k, []
+        for r in range(args.adaptive_rounds):
+            if r and r % 4 == 0:
+                a1, t1_ = ctx.hh_get_acceptance()
+                if t1_ > t0_:
+                    kk = B.hh_optimal_draft_length((a1 - a0) / (t1_ - t0_), ratio, list(range(1, k + 1)))
+            ks_used.append(kk)
+            ctx.hh_draft(kk)
+            ctx.hh_verify()
+            ctx.hh_commit(torch.from_numpy(np.minimum(pat[r], kk).astype(np.int32)).to(ctx.device))
+        torch.cuda.synchronize()
+        dt_a = time.perf_counter() - ts
+        _, c1, _ = ctx.hh_get_lengths()
+        a1, t1_ = ctx.hh_get_acceptance()
+        adaptive = {"rounds": args.adaptive_rounds, "cost_ratio": round(ratio, 4), "alpha_measured": round((a1 - a0) / max(t1_ - t0_, 1), 4),
+                    "k_last": kk, "k_mean": round(float(np.mean(ks_used)), 2),
+                    "committed_tokens_per_s": round((sum(c1) - sum(c0)) / dt_a, 2),
+                    "note": "includes the eager first use and graph capture of every new k"}
+
     mode = f"forced acceptance p={forced_p}" if primary_forced else "greedy acceptance"
     other = {"mode": "greedy acceptance" if primary_forced else f"forced acceptance p={forced_p}",
              "committed_tokens_per_s": round(toks_o / dt_o, 2),
@@ -360,6 +392,7 @@ def main():
             "k_star_of_2_4_8": B.hh_optimal_draft_length(forced_p, cost_ratio, [2, 4, 8])},
         "other_acceptance": other,
         "stochastic": stochastic,
+        "adaptive_k": adaptive,
         "plain_greedy_tokens_per_s": round(toks_g / dt_g, 2),
         "speedup_vs_plain_greedy": round((toks / dt) / (toks_g / dt_g), 4),
         "prefill_s": round(t_prefill, 3), "prefill_tokens_per_s": round(Bn * wl.prompt_len / t_prefill, 1),

@@ -266,6 +266,13 @@ HH_API hh_status hh_commit(hh_ctx* ctx, const int32_t* n_accepted, void* stream)
 HH_API hh_status hh_get_tokens(hh_ctx* ctx, int32_t seq, int32_t* out, int32_t cap, int32_t* n_out, void* stream);
 /* Per sequence: cache length, committed count, accepted count of the last commit.  Any pointer may be NULL. */
 HH_API hh_status hh_get_lengths(hh_ctx* ctx, int32_t* kv_len, int32_t* committed, int32_t* last_n, void* stream);
+/* Acceptance statistics since the last hh_prefill, summed over rounds and unfinished sequences:
+ * *accepted = drafts that passed their test (sum of n), *tested = drafts that were tested (in a round
+ * with k drafts and n accepted: min(n + 1, k) - the first rejected draft is the last one tested).
+ * accepted / tested is the maximum-likelihood estimate of the per-token acceptance probability alpha
+ * of Eq. 1, the input of hh_optimal_draft_length for choosing k round by round (Section 7: adaptive
+ * draft length).  Forced counts are counted as given. */
+HH_API hh_status hh_get_acceptance(hh_ctx* ctx, uint64_t* accepted, uint64_t* tested, void* stream);
 /* Tokens of the current round: drafts [batch][k] and targets g [batch][k+1] (M_H's argmaxes; at
  * temperature > 0 the kept drafts, the emitted token and -1 behind it).  Either may be NULL. */
 HH_API hh_status hh_get_round(hh_ctx* ctx, int32_t* drafts, int32_t* targets, void* stream);

@@ -54,6 +54,16 @@ def optimal_draft_length(alpha: float, cost_ratio: float, candidates: Sequence[i
     return best
 
 
+def acceptance_counts(n_accepted: Sequence[int], k: int):
+    """(accepted, tested) drafts of rounds with k drafts each: a round that accepts n drafts tested
+    min(n + 1, k) of them (drafts 1..n passed, draft n+1 - if it exists - failed).  Under the model
+    behind Eq. 1 (each test passes independently with probability alpha) accepted / tested is the
+    maximum-likelihood estimate of alpha."""
+    acc = sum(int(n) for n in n_accepted)
+    tested = sum(min(int(n) + 1, k) for n in n_accepted) if k > 0 else 0
+    return acc, tested
+
+
 def accepted_prefix(drafts: Sequence[int], targets: Sequence[int]) -> int:
     """Greedy acceptance (Section 3.3): the number n of leading draft tokens with
     drafts[i] == targets[i], where targets[i] is M_H's argmax given the prefix
@@ -132,6 +142,8 @@ class SpecDecoder:
         self.out: List[List[int]] = []
         self.pending: List[int] = []
         self.last_n = [0] * self.B
+        self.accepted = 0            # running acceptance statistics (see acceptance_counts)
+        self.tested = 0
         self.prefill_logits = []
         self.ms: List[SeqState] = []             # strict mode: M_S's own recurrent state per sequence
         for b, p in enumerate(prompts):
@@ -243,6 +255,9 @@ class SpecDecoder:
             assert forced_n is None or self.T == 0.0, "a forced count has no correction token at T > 0"
             n = accepted_prefix(d, g) if forced_n is None else int(forced_n[b])
             assert 0 <= n <= len(d)
+            a_, t_ = acceptance_counts([n], len(d))
+            self.accepted += a_
+            self.tested += t_
             self.gaps.extend(gaps_v[:n + 1])     # only positions that decided a token
             if self.draft_state == "strict":     # M_S consumes what the caches consumed: pending, d_1 .. d_n
                 for t in [self.pending[b]] + list(d[:n]):

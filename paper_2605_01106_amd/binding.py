@@ -84,6 +84,7 @@ EXPORTS = {
     "hh_commit": (C.c_int, [_ctx_p, C.c_void_p, C.c_void_p]),
     "hh_get_tokens": (C.c_int, [_ctx_p, C.c_int32, _i32p, C.c_int32, _i32p, C.c_void_p]),
     "hh_get_lengths": (C.c_int, [_ctx_p, _i32p, _i32p, _i32p, C.c_void_p]),
+    "hh_get_acceptance": (C.c_int, [_ctx_p, C.POINTER(C.c_uint64), C.POINTER(C.c_uint64), C.c_void_p]),
     "hh_get_round": (C.c_int, [_ctx_p, _i32p, _i32p, C.c_void_p]),
     "hh_get_logits": (C.c_int, [_ctx_p, C.c_int32, _f32p, C.c_void_p]),
     "hh_get_state": (C.c_int, [_ctx_p, C.c_int32, _f32p, _f32p, C.c_void_p]),
@@ -319,6 +320,12 @@ class Context:
         a, b, c = (C.c_int32 * B)(), (C.c_int32 * B)(), (C.c_int32 * B)()
         _check(lib.hh_get_lengths(self.ctx, a, b, c, _stream_ptr(stream)), self.ctx)
         return list(a), list(b), list(c)
+
+    def hh_get_acceptance(self, stream=None):
+        """(accepted, tested) draft counts since the last prefill; accepted / tested estimates alpha of Eq. 1."""
+        a, t = C.c_uint64(0), C.c_uint64(0)
+        _check(lib.hh_get_acceptance(self.ctx, C.byref(a), C.byref(t), _stream_ptr(stream)), self.ctx)
+        return int(a.value), int(t.value)
 
     def hh_get_round(self, stream=None):
         B, k = self.B, self.k

@@ -14,12 +14,13 @@
 // compute unit takes in well under 30 bytes per cycle this way (the register-tiled kernel, where
 // every wavefront loads its own operands, asks for 85 and is bound by exactly that).  The copies
 // are LDS-direct loads (global_load_lds_dwordx4: lane l's 16 bytes land at the wavefront's LDS
-// base + 16 l, no registers in between) into three stages of LDS: the copies of step s+2 are
-// issued before step s is multiplied, so two steps of copies are in flight behind the MFMAs; one
-// workgroup barrier per step.
+// base + 16 l, no registers in between) into three to six stages of LDS (what fits 160 KB): the
+// copies of step s + stages - 1 are issued before step s is multiplied, so that many steps of
+// copies are in flight behind the MFMAs; one workgroup barrier per step.
 #pragma once
 #include "hh_internal.h"
 #include "wave_ops.h"
+#include "trace.h"
 
 namespace hh {
 
@@ -49,8 +50,12 @@ struct LdsGemmArgs {
   unsigned long long* row_best; int store;     // EPI_STORE: per-row argmax keys (atomic maxima); store = 0: Y not written
 };
 
+// LDS stages of the copy pipeline: as many as fit 160 KB, at most 6 (three for 192-row workgroups)
+constexpr int lds_stages(int mtw) { return 160 * 1024 / lds_stage_bytes(mtw) > 6 ? 6 : 160 * 1024 / lds_stage_bytes(mtw); }
+
 template <int EPI, int MTW>
 __global__ __launch_bounds__(64 * kLdsWaves) void gemm_lds_kernel(const LdsGemmArgs a) {
+  constexpr int NSTAGE = lds_stages(MTW);
   constexpr int NF = EPI == EPI_SWIGLU ? 2 : 1;
   constexpr int NS = 4 / NF;                   // strips (strip pairs) per wavefront
   constexpr int SPB = kLdsA / NF;              // strips (pairs) per workgroup
@@ -109,14 +114,9 @@ __global__ __launch_bounds__(64 * kLdsWaves) void gemm_lds_kernel(const LdsGemmA
     HH_LDS_COPY1(0, s_, b_); HH_LDS_COPY1(1, s_, b_); HH_LDS_COPY1(2, s_, b_); HH_LDS_COPY1(3, s_, b_); \
     HH_LDS_COPY1(4, s_, b_); HH_LDS_COPY1(5, s_, b_); HH_LDS_COPY1(6, s_, b_);                         \
   } while (0)
-#define HH_LDS_WAIT_PREVIOUS()                                                 \
-  do {                                                                         \
-    if (ITEMS == 7) asm volatile("s_waitcnt vmcnt(7)" ::: "memory");           \
-    else if (ITEMS == 6) asm volatile("s_waitcnt vmcnt(6)" ::: "memory");      \
-    else if (ITEMS == 5) asm volatile("s_waitcnt vmcnt(5)" ::: "memory");      \
-    else if (ITEMS == 4) asm volatile("s_waitcnt vmcnt(4)" ::: "memory");      \
-    else asm volatile("s_waitcnt vmcnt(3)" ::: "memory");                      \
-  } while (0)
+  // the copies of the NSTAGE - 2 newest steps may still be in flight; everything older has landed
+#define HH_LDS_WAIT_PREVIOUS() asm volatile("s_waitcnt vmcnt(%0)" ::"n"((NSTAGE - 2) * ITEMS) : "memory")
+  static_assert((NSTAGE - 2) * ITEMS <= 63, "vmcnt is a 6-bit counter");
 
   lds_f32x4 acc[NF][NS][MTW];
 #pragma unroll
@@ -157,22 +157,26 @@ __global__ __launch_bounds__(64 * kLdsWaves) void gemm_lds_kernel(const LdsGemmA
     }
   };
 
-  // ---- pipeline: LDS stage s % 3 holds step s.  Before step s is multiplied its copies are
-  // waited for, a barrier makes them (and the end of step s-1 everywhere) known to all
-  // wavefronts, and the copies of step s+2 are issued into the stage step s-1 has just left.
-  HH_LDS_COPY(0, 0);
-  HH_LDS_COPY(1, 1);
+  // ---- pipeline: LDS stage s % NSTAGE holds step s.  Before step s is multiplied its copies
+  // are waited for, a barrier makes them (and the end of step s-1 everywhere) known to all
+  // wavefronts, and the copies of step s + NSTAGE - 1 are issued into the stage step s-1 has just
+  // left: NSTAGE - 1 steps of copies are in flight behind the MFMAs.
+  TR(0);
+#pragma unroll
+  for (int p = 0; p < NSTAGE - 1; ++p) HH_LDS_COPY(p, p);
+  TR(1);
   int st = 0;                                    // stage of step s
 #pragma unroll 1
   for (int s = 0; s < n_steps; ++s) {
     HH_LDS_WAIT_PREVIOUS();
     __syncthreads();
-    const int st2 = st == 0 ? 2 : st - 1;        // (s + 2) % 3: the stage step s-1 has just left
-    HH_LDS_COPY(s + 2, st2);
+    const int st2 = st == 0 ? NSTAGE - 1 : st - 1;   // (s + NSTAGE - 1) % NSTAGE: the stage step s-1 has just left
+    HH_LDS_COPY(s + NSTAGE - 1, st2);
     compute(st);
     HH_LDS_FENCE();
-    st = st == 2 ? 0 : st + 1;
+    st = st == NSTAGE - 1 ? 0 : st + 1;
   }
+  TR(2);
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");     // the copies issued past the end land before the workgroup leaves
 #undef HH_LDS_FENCE
 #undef HH_LDS_COPY
@@ -255,6 +259,7 @@ __global__ __launch_bounds__(64 * kLdsWaves) void gemm_lds_kernel(const LdsGemmA
       if (g_e == 0 && mt0 + m < a.m_tiles && am < a.M && b != 0ull) atomicMax(a.row_best + am, b);
     }
   }
+  TR(3);
 }
 
 }  // namespace hh

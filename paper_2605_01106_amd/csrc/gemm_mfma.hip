@@ -371,11 +371,11 @@ static hipError_t lds_launch_m(const LdsGemmArgs& a, hipStream_t s) {
   auto kern = gemm_lds_kernel<EPI, MTW>;
   static bool enabled = false;
   if (!enabled) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, 3 * lds_stage_bytes(MTW));
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, lds_stages(MTW) * lds_stage_bytes(MTW));
     if (e != hipSuccess) return e;
     enabled = true;
   }
-  hipLaunchKernelGGL(kern, dim3(a.n_blocks * a.m_blocks * a.ksplit), dim3(64 * kLdsWaves), 3 * lds_stage_bytes(MTW), s, a);
+  hipLaunchKernelGGL(kern, dim3(a.n_blocks * a.m_blocks * a.ksplit), dim3(64 * kLdsWaves), lds_stages(MTW) * lds_stage_bytes(MTW), s, a);
   return hipGetLastError();
 }
 template <int EPI>
@@ -429,24 +429,36 @@ hipError_t launch_gemm_mfma(const GemvArgs& g, uint16_t* planes, float* partial,
   a.row_best = g.epi == EPI_STORE ? g.row_best : nullptr; a.store = g.no_store && a.row_best != nullptr ? 0 : 1;
   const int steps = Kp / 32, tiles = (N + 15) / 16, m_tiles = Mp / 16;
   if ((m_tiles > 6 || (g.flags & HH_KF_ROWS_LDS)) && a.terms == 3) {
-    // row tiles per wavefront: 6 (192-row workgroups) for many rows; up to 96 rows one workgroup holds them all
-    const int mtw = m_tiles > 6 ? 6 : (m_tiles + 1) / 2;
     LdsGemmArgs l{};
     l.planes = planes; l.m_tiles = m_tiles; l.KST = steps;
     l.W = a.W; l.W2 = a.W2; l.Y = a.Y; l.ldy = a.ldy; l.R2 = a.R2; l.partial = partial;
     l.M = M; l.N = N; l.n_tiles = tiles; l.row_best = a.row_best; l.store = a.store;
     l.n_blocks = (tiles + kLdsA / nf - 1) / (kLdsA / nf);
-    l.m_blocks = (m_tiles + lds_row_tiles(mtw) - 1) / lds_row_tiles(mtw);
-    // K split only where the tiles alone leave most of the chip idle: the partial products cost
-    // ks * M * N floats written and read again.  At least 8 steps per workgroup (3 with few rows,
-    // where the products are short and latency-bound), partial buffer permitting.
-    const int blocks = l.n_blocks * l.m_blocks;
-    const int min_steps = m_tiles > 6 ? 8 : 3;
-    int ks = 1;
-    if (blocks < 128) {
-      ks = ((m_tiles > 6 ? 224 : 256) + blocks - 1) / blocks;
-      while (ks > 1 && (steps / ks < min_steps || (size_t)ks * nf * M * N > gemm_partial_elems())) --ks;
+    // Row tiles per wavefront (workgroup = 256 weight rows x 32 MTW activation rows) and K split, by a
+    // cost model in microseconds: a workgroup step takes the longer of its MFMAs (384 MTW cycles
+    // per SIMD) and its copies ((16 + 6 MTW) KB at 28 bytes per cycle and compute unit); the
+    // workgroups run in rounds of one per compute unit; a K split adds the reduction kernel and
+    // ks * M * N floats of partial products written and read again (about 4 TB/s).  Up to 96 rows one
+    // workgroup holds all rows; many rows choose between 192-row and 96-row workgroups.
+    int mtw = 0, ks = 1;
+    double best = 1e30;
+    const int mtw_lo = m_tiles > 6 ? 3 : (m_tiles + 1) / 2, mtw_hi = m_tiles > 6 ? 6 : (m_tiles + 1) / 2;
+    for (int cand = mtw_lo; cand <= mtw_hi; cand += 3) {
+      const int m_blocks = (m_tiles + lds_row_tiles(cand) - 1) / lds_row_tiles(cand);
+      const double mfma = 384.0 * cand, copy = (16.0 + 6.0 * cand) * 1024.0 / 28.0;
+      const double step_us = (mfma > copy ? mfma : copy) / 2400.0;
+      const int min_steps = m_tiles > 6 ? 8 : 3;
+      for (int k = 1; k <= 32; ++k) {
+        if (k > 1 && (steps / k < min_steps || (size_t)k * nf * M * N > gemm_partial_elems())) break;
+        const int ksteps = (steps + k - 1) / k, kk = (steps + ksteps - 1) / ksteps;
+        const long wgs = (long)l.n_blocks * m_blocks * kk;
+        const double rounds = (double)((wgs + 255) / 256);
+        double t = rounds * (ksteps + 3) * step_us;
+        if (kk > 1) t += 3.0 + (double)kk * nf * M * N * 8.0 / 4e6;
+        if (t < best) { best = t; mtw = cand; ks = kk; }
+      }
     }
+    l.m_blocks = (m_tiles + lds_row_tiles(mtw) - 1) / lds_row_tiles(mtw);
     l.ksteps = (steps + ks - 1) / ks;
     l.ksplit = (steps + l.ksteps - 1) / l.ksteps;
     switch (g.epi) {

@@ -58,6 +58,7 @@ struct hh_ctx {
   int *kv_len, *committed, *last_n, *pending, *n_acc, *skip, *adv, *drafts, *targets, *tok, *pos0, *out_tok,
       *page_table, *plan_ntok, *plan_last, *first_tok;
   unsigned long long* best;
+  unsigned long long* acc_stats;   // accepted / tested drafts since the last prefill
   SamplingParams* sampling;   // temperature and seed read by the drawing kernels
   float* softmax_stats;       // (max, sum) of the round's logit rows
   float temperature = 0.f;    // 0: greedy
@@ -183,6 +184,7 @@ size_t carve(hh_ctx* x, char* base) {
   x->plan_ntok = c.take<int>((size_t)x->max_passes * B);
   x->plan_last = c.take<int>((size_t)x->max_passes * B);
   x->best = c.take<unsigned long long>(Mv * gemv_max_blocks());
+  x->acc_stats = c.take<unsigned long long>(2);
   x->sampling = c.take<SamplingParams>(1);
   x->softmax_stats = c.take<float>(B * (2 * d.Kmax + 1) * 2);
   x->attn_counters = c.take<int>(B * d.Hkv * attention_row_chunks(d, d.Tmax));
@@ -685,6 +687,7 @@ hh_status hh_prefill(hh_ctx* x, const int32_t* tokens, int32_t row_stride, const
   HH_HIP(hipMemcpyAsync(x->plan_last, x->h_plan.data() + (size_t)n_pass * B, (size_t)n_pass * B * sizeof(int), hipMemcpyHostToDevice, s));
   HH_HIP(launch_fill_i32(x->kv_len, 0, B, s));
   HH_HIP(launch_fill_i32(x->committed, 0, B, s));
+  HH_HIP(launch_fill_i32(reinterpret_cast<int*>(x->acc_stats), 0, 4, s));
 
   for (int p = 0; p < n_pass; ++p) {
     const int T = maxlen - p * chunk < chunk ? maxlen - p * chunk : chunk;
@@ -940,7 +943,7 @@ hh_status hh_commit(hh_ctx* x, const int32_t* n_accepted, void* stream) {
   CommitArgs c{};
   c.drafts = x->drafts; c.targets = x->targets; c.forced = n_accepted;
   c.committed = x->committed; c.last_n = x->last_n; c.pending = x->pending; c.out_tok = x->out_tok;
-  c.n_acc = x->n_acc; c.skip = x->skip; c.adv = x->adv;
+  c.n_acc = x->n_acc; c.skip = x->skip; c.adv = x->adv; c.acc_stats = x->acc_stats;
   c.B = B; c.k = x->k; c.kmax = d.Kmax; c.G = x->G; c.out_stride = d.Gmax;
   HH_HIP(launch_accept(c, s));
   // rollback: rebuild the state after position n from the committed state and the ring
@@ -990,6 +993,18 @@ hh_status hh_get_lengths(hh_ctx* x, int32_t* kv_len, int32_t* committed, int32_t
   if (kv_len) HH_HIP(hipMemcpy(kv_len, x->kv_len, n, hipMemcpyDeviceToHost));
   if (committed) HH_HIP(hipMemcpy(committed, x->committed, n, hipMemcpyDeviceToHost));
   if (last_n) HH_HIP(hipMemcpy(last_n, x->last_n, n, hipMemcpyDeviceToHost));
+  return HH_OK;
+}
+
+hh_status hh_get_acceptance(hh_ctx* x, uint64_t* accepted, uint64_t* tested, void* stream) {
+  if (!x) return HH_EINVAL;
+  if (x->phase == PH_CREATED) return fail(x, HH_ESTATE, "hh_get_acceptance: nothing prefilled");
+  if (!accepted || !tested) return fail(x, HH_EINVAL, "hh_get_acceptance: NULL argument");
+  hh_status st = sync_stream(x, stream);
+  if (st != HH_OK) return st;
+  unsigned long long v[2] = {0, 0};
+  HH_HIP(hipMemcpy(v, x->acc_stats, sizeof v, hipMemcpyDeviceToHost));
+  *accepted = v[0]; *tested = v[1];
   return HH_OK;
 }
 

@@ -128,6 +128,7 @@ hipError_t launch_argmax_finish(const unsigned long long* best, int n_part, int 
 struct CommitArgs {
   const int* drafts; const int* targets; const int* forced;  // [B][kmax], [B][kmax+1], [B] or nullptr
   int *committed, *last_n, *pending, *out_tok, *n_acc, *skip, *adv;
+  unsigned long long* acc_stats;   // [2] running sums over rounds and active sequences: accepted drafts, tested drafts
   int B, k, kmax, G, out_stride;
 };
 hipError_t launch_accept(const CommitArgs& a, hipStream_t s);

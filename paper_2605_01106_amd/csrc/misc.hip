@@ -115,6 +115,11 @@ __global__ void accept_kernel(const CommitArgs a) {
   a.last_n[b] = n;
   a.n_acc[b] = n;
   a.adv[b] = n + 1;
+  // acceptance statistics: drafts 1..n passed their test, draft n+1 (if there is one) failed it
+  if (a.acc_stats != nullptr && a.k > 0) {
+    atomicAdd(a.acc_stats, (unsigned long long)n);
+    atomicAdd(a.acc_stats + 1, (unsigned long long)min(n + 1, a.k));
+  }
 }
 
 hipError_t launch_accept(const CommitArgs& a, hipStream_t s) {

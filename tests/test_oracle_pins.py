@@ -630,3 +630,28 @@ def test_optimal_draft_length_follows_eq1():
             prev = best
     assert optimal_draft_length(0.9, 0.05, range(1, 17)) > 2
     assert optimal_draft_length(0.0, 0.5, [1, 2, 3]) == 1                # nothing is ever accepted: shortest draft
+
+
+def test_acceptance_counts_estimate_alpha():
+    """The acceptance statistics behind the choice of k (Eq. 1's alpha, Section 7): by hand on a few
+    rounds; with k = 1 it is the plain success rate; and on simulated rounds in which every test passes
+    independently with probability alpha (the model of Eq. 1) accepted / tested recovers alpha although
+    the rounds are cut off at k - unlike the naive mean(n) / k."""
+    from oracle.protocol import acceptance_counts
+    assert acceptance_counts([0, 2, 3, 1], 3) == (6, 1 + 3 + 3 + 2)
+    assert acceptance_counts([1, 0, 1, 1], 1) == (3, 4)
+    assert acceptance_counts([0, 0], 0) == (0, 0)
+    rng = np.random.default_rng(5)
+    for alpha in (0.37, 0.68, 0.9):
+        for k in (2, 8):
+            ns = []
+            for _ in range(20000):
+                n = 0
+                while n < k and rng.random() < alpha:
+                    n += 1
+                ns.append(n)
+            acc, tested = acceptance_counts(ns, k)
+            assert abs(acc / tested - alpha) < 0.01, (alpha, k, acc / tested)
+            # mean tokens per round matches Eq. 1's numerator
+            assert abs(np.mean(ns) + 1 - expected_tokens_per_round(alpha, k)) < 0.05
+    assert abs(np.mean(ns) / 8 - 0.9) > 0.15            # the naive estimate is biased by the cut-off

@@ -16,6 +16,7 @@
 // accumulates output dimension d.  With several key slices every workgroup stores its partial
 // result; the last one to finish (a counter per row chunk) merges them, so no second launch.
 #include <stdlib.h>
+#include "wave_ops.h"
 
 #include "attn_common.h"
 
@@ -28,24 +29,20 @@ static constexpr int kMaxDh = 256;
 
 // Reductions over the 64 lanes without LDS traffic: DPP butterflies inside each row of 16
 // lanes, then the four row results are read out and combined.  All lanes must be active.
-template <int CTRL>
-__device__ __forceinline__ float dpp_perm_a(float v) {
-  return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xf, 0xf, false));
-}
 __device__ __forceinline__ float wave_max(float v) {
-  v = fmaxf(v, dpp_perm_a<0xB1>(v));
-  v = fmaxf(v, dpp_perm_a<0x4E>(v));
-  v = fmaxf(v, dpp_perm_a<0x141>(v));
-  v = fmaxf(v, dpp_perm_a<0x140>(v));
+  v = fmaxf(v, dpp_move<0xB1>(v));
+  v = fmaxf(v, dpp_move<0x4E>(v));
+  v = fmaxf(v, dpp_move<0x141>(v));
+  v = fmaxf(v, dpp_move<0x140>(v));
   const int iv = __float_as_int(v);
   return fmaxf(fmaxf(__int_as_float(__builtin_amdgcn_readlane(iv, 0)), __int_as_float(__builtin_amdgcn_readlane(iv, 16))),
                fmaxf(__int_as_float(__builtin_amdgcn_readlane(iv, 32)), __int_as_float(__builtin_amdgcn_readlane(iv, 48))));
 }
 __device__ __forceinline__ float wave_add(float v) {
-  v += dpp_perm_a<0xB1>(v);
-  v += dpp_perm_a<0x4E>(v);
-  v += dpp_perm_a<0x141>(v);
-  v += dpp_perm_a<0x140>(v);
+  v += dpp_move<0xB1>(v);
+  v += dpp_move<0x4E>(v);
+  v += dpp_move<0x141>(v);
+  v += dpp_move<0x140>(v);
   const int iv = __float_as_int(v);
   return (__int_as_float(__builtin_amdgcn_readlane(iv, 0)) + __int_as_float(__builtin_amdgcn_readlane(iv, 16))) +
          (__int_as_float(__builtin_amdgcn_readlane(iv, 32)) + __int_as_float(__builtin_amdgcn_readlane(iv, 48)));

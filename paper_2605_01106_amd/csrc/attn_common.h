@@ -8,16 +8,9 @@
 #pragma once
 #include "hh_internal.h"
 #include "trace.h"
+#include "wave_ops.h"
 
 namespace hh {
-
-
-__device__ __forceinline__ uint16_t f32_to_bf16_rne(float f) {
-  uint32_t u = __float_as_uint(f);
-  u += 0x7FFFu + ((u >> 16) & 1u);
-  return (uint16_t)(u >> 16);
-}
-__device__ __forceinline__ float bf16_bits_to_f32(uint16_t h) { return __uint_as_float((uint32_t)h << 16); }
 
 // element index of K[pos][0] of one KV head
 __device__ __forceinline__ size_t k_index(const Dims& d, const int* pt_row, int kvh, int pos) {

@@ -2,6 +2,7 @@
 // unit per epilogue so that the instantiations compile in parallel.
 #pragma once
 #include "hh_internal.h"
+#include "wave_ops.h"
 
 namespace hh {
 
@@ -44,27 +45,17 @@ template <> struct W8<0> {
 // Sum over the 64 lanes of a wavefront without LDS traffic: butterfly inside each row of 16
 // lanes with DPP lane permutations, then the four row totals are read out and added.
 // Every lane returns the total.  Must be called with all 64 lanes active.
-template <int CTRL>
-__device__ __forceinline__ float dpp_perm(float v) {
-  return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xf, 0xf, false));
-}
 __device__ __forceinline__ float wave_sum(float v) {
-  v += dpp_perm<0xB1>(v);    // quad_perm [1,0,3,2]: lane ^ 1
-  v += dpp_perm<0x4E>(v);    // quad_perm [2,3,0,1]: lane ^ 2
-  v += dpp_perm<0x141>(v);   // row_half_mirror: lane i <-> 7 - i inside each 8
-  v += dpp_perm<0x140>(v);   // row_mirror: lane i <-> 15 - i inside each 16
+  v += dpp_move<0xB1>(v);    // quad_perm [1,0,3,2]: lane ^ 1
+  v += dpp_move<0x4E>(v);    // quad_perm [2,3,0,1]: lane ^ 2
+  v += dpp_move<0x141>(v);   // row_half_mirror: lane i <-> 7 - i inside each 8
+  v += dpp_move<0x140>(v);   // row_mirror: lane i <-> 15 - i inside each 16
   const int iv = __float_as_int(v);
   const float r0 = __int_as_float(__builtin_amdgcn_readlane(iv, 0));
   const float r1 = __int_as_float(__builtin_amdgcn_readlane(iv, 16));
   const float r2 = __int_as_float(__builtin_amdgcn_readlane(iv, 32));
   const float r3 = __int_as_float(__builtin_amdgcn_readlane(iv, 48));
   return (r0 + r1) + (r2 + r3);
-}
-
-__device__ __forceinline__ unsigned long long argmax_key(float v, int n) {
-  uint32_t u = __float_as_uint(v);
-  u = (u & 0x80000000u) ? ~u : (u | 0x80000000u);
-  return (static_cast<unsigned long long>(u) << 32) | static_cast<unsigned long long>(0xFFFFFFFFu - (uint32_t)n);
 }
 
 // LDS layout of one activation row: the 8 floats a lane multiplies in chunk c

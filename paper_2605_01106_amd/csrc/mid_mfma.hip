@@ -17,6 +17,7 @@
 #include <stdlib.h>
 
 #include "hh_internal.h"
+#include "wave_ops.h"
 #include "bf16_split.h"
 #include "trace.h"
 
@@ -47,10 +48,6 @@ struct MidArgs {
   int wpb;                                 // K-loop kernel: windows per workgroup (K chunk)
 };
 
-template <int CTRL>
-__device__ __forceinline__ float mid_dpp(float v) {
-  return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xf, 0xf, false));
-}
 // The K loop: the staged activations are double-buffered in LDS and the weight fragments
 // triple-buffered in registers: while window i is multiplied, the activations of window i+1 are
 // loaded, split and written to the other buffer and the weights of window i+2 are requested;
@@ -202,7 +199,7 @@ __global__ __launch_bounds__(512) void mid_loop_kernel(const MidArgs a) {
 #pragma unroll
     for (int u = 0; u < NP; ++u) {
       float t = sq[u];
-      t += mid_dpp<0xB1>(t); t += mid_dpp<0x4E>(t); t += mid_dpp<0x141>(t); t += mid_dpp<0x140>(t);
+      t += dpp_move<0xB1>(t); t += dpp_move<0x4E>(t); t += dpp_move<0x141>(t); t += dpp_move<0x140>(t);
       const int iv = __float_as_int(t);
       const float lo = __int_as_float(__builtin_amdgcn_readlane(iv, 0)) + __int_as_float(__builtin_amdgcn_readlane(iv, 16));
       const float hi = __int_as_float(__builtin_amdgcn_readlane(iv, 32)) + __int_as_float(__builtin_amdgcn_readlane(iv, 48));

@@ -17,6 +17,7 @@
 #include <stdlib.h>
 
 #include "hh_internal.h"
+#include "wave_ops.h"
 #include "trace.h"
 #include "bf16_split.h"
 
@@ -30,25 +31,11 @@ union SFrag {
   bf16x8 v;
 };
 
-__device__ __forceinline__ uint32_t sk_bf16_rne(float f) {
-  uint32_t u = __float_as_uint(f);
-  u += 0x7FFFu + ((u >> 16) & 1u);
-  return u >> 16;
-}
 __device__ __forceinline__ void sk_split3(float x, uint32_t& t0, uint32_t& t1, uint32_t& t2) { split3_bf16(x, t0, t1, t2); }
-__device__ __forceinline__ unsigned long long sk_argmax_key(float v, int n) {
-  uint32_t u = __float_as_uint(v);
-  u = (u & 0x80000000u) ? ~u : (u | 0x80000000u);
-  return (static_cast<unsigned long long>(u) << 32) | static_cast<unsigned long long>(0xFFFFFFFFu - (uint32_t)n);
-}
 
 // sum over the 64 lanes: DPP butterflies inside each row of 16 lanes, then the four row totals
-template <int CTRL>
-__device__ __forceinline__ float sk_dpp(float v) {
-  return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xf, 0xf, false));
-}
 __device__ __forceinline__ float sk_wave_sum(float v) {
-  v += sk_dpp<0xB1>(v); v += sk_dpp<0x4E>(v); v += sk_dpp<0x141>(v); v += sk_dpp<0x140>(v);
+  v += dpp_move<0xB1>(v); v += dpp_move<0x4E>(v); v += dpp_move<0x141>(v); v += dpp_move<0x140>(v);
   const int iv = __float_as_int(v);
   return (__int_as_float(__builtin_amdgcn_readlane(iv, 0)) + __int_as_float(__builtin_amdgcn_readlane(iv, 16))) +
          (__int_as_float(__builtin_amdgcn_readlane(iv, 32)) + __int_as_float(__builtin_amdgcn_readlane(iv, 48)));
@@ -255,7 +242,7 @@ __global__ __launch_bounds__(64 * NWAVES) void skinny_mfma_kernel(const SkinnyAr
         if (a.best != nullptr) {
 #pragma unroll
           for (int r = 0; r < 4; ++r)
-            if (row0 + r < N) { const unsigned long long key = sk_argmax_key(v[r], row0 + r); if (key > best) best = key; }
+            if (row0 + r < N) { const unsigned long long key = argmax_key(v[r], row0 + r); if (key > best) best = key; }
         }
       }
     }

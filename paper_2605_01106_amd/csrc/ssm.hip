@@ -17,6 +17,7 @@
 #include <stdlib.h>
 
 #include "hh_internal.h"
+#include "wave_ops.h"
 #include "trace.h"
 
 namespace hh {
@@ -30,10 +31,6 @@ static constexpr int kTS = 16;     // positions staged per pass through LDS
 __device__ __forceinline__ float silu_f(float v) { return v * __frcp_rn(1.0f + __expf(-v)); }
 __device__ __forceinline__ float softplus_f(float v) { return v > 20.0f ? v : log1pf(expf(v)); }
 
-template <int CTRL>
-__device__ __forceinline__ float dpp_perm_f(float v) {
-  return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xf, 0xf, false));
-}
 
 // kRows = 8: one wavefront per workgroup, many small workgroups (latency-bound small batches);
 // kRows = 32: four wavefronts, the conv of B and C is shared by four times as many state rows.
@@ -153,9 +150,9 @@ __global__ __launch_bounds__(kRows * kSub) void ssm_kernel(const Dims d, const S
         S[i] = fmaf(aj, S[i], coef * Bs[jj][sub * NV + i]);
         part = fmaf(S[i], Cs[jj][sub * NV + i], part);
       }
-      part += dpp_perm_f<0xB1>(part);    // lane ^ 1
-      part += dpp_perm_f<0x4E>(part);    // lane ^ 2
-      part += dpp_perm_f<0x141>(part);   // the other quad of the 8 lanes that share a row
+      part += dpp_move<0xB1>(part);    // lane ^ 1
+      part += dpp_move<0x4E>(part);    // lane ^ 2
+      part += dpp_move<0x141>(part);   // the other quad of the 8 lanes that share a row
       if (a.g != nullptr && sub == 0 && prow) {
         const size_t m = (size_t)b * a.T + j0 + jj;
         const float z = a.zx[m * d.ldzx + h * d.P + p];
@@ -353,9 +350,9 @@ __global__ __launch_bounds__(kRows * kSub + (PIPE ? chunk_stage_threads<NV, kRow
         S[i + 2] = fmaf(aj, S[i + 2], coef * Bv.z); part = fmaf(S[i + 2], Cv.z, part);
         S[i + 3] = fmaf(aj, S[i + 3], coef * Bv.w); part = fmaf(S[i + 3], Cv.w, part);
       }
-      part += dpp_perm_f<0xB1>(part);    // lane ^ 1
-      part += dpp_perm_f<0x4E>(part);    // lane ^ 2
-      part += dpp_perm_f<0x141>(part);   // the other quad of the 8 lanes that share a row
+      part += dpp_move<0xB1>(part);    // lane ^ 1
+      part += dpp_move<0x4E>(part);    // lane ^ 2
+      part += dpp_move<0x141>(part);   // the other quad of the 8 lanes that share a row
       if (a.g != nullptr && sub == 0 && prow)
         a.g[((size_t)b * a.T + j0 + jj) * d.d_inner + h * d.P + p] = (part + dskip * xv) * silu_f(zs[buf][jj][row]);
     }
@@ -589,10 +586,10 @@ __global__ __launch_bounds__(64 * NWV) void ssm_small_kernel(const Dims d, const
         S[rg][i + 2] = fmaf(aj[j], S[rg][i + 2], coef * Bv.z); part = fmaf(S[rg][i + 2], Cv.z, part);
         S[rg][i + 3] = fmaf(aj[j], S[rg][i + 3], coef * Bv.w); part = fmaf(S[rg][i + 3], Cv.w, part);
       }
-      part += dpp_perm_f<0xB1>(part);    // lane ^ 1
-      part += dpp_perm_f<0x4E>(part);    // lane ^ 2
-      part += dpp_perm_f<0x141>(part);   // the other quad of 8 lanes
-      if (SUBS == 16) part += dpp_perm_f<0x140>(part);   // the other half of 16 lanes
+      part += dpp_move<0xB1>(part);    // lane ^ 1
+      part += dpp_move<0x4E>(part);    // lane ^ 2
+      part += dpp_move<0x141>(part);   // the other quad of 8 lanes
+      if (SUBS == 16) part += dpp_move<0x140>(part);   // the other half of 16 lanes
       y[j] = (part + dskip * xv) * gate;
     }
     if (a.g != nullptr && sub == 0 && prow[rg]) {

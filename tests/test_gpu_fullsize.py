@@ -14,7 +14,8 @@ pytestmark = pytest.mark.gpu
 from parity_util import run_lockstep  # noqa: E402
 
 
-def _run(name, seed, G, rounds, batch=None, lens=None, rows=None, layers=None, forced_p=None, min_gap=0.0):
+def _run(name, seed, G, rounds, batch=None, lens=None, rows=None, layers=None, forced_p=None, min_gap=0.0,
+         invariance_rows=None):
     import torch
     from paper_2605_01106_amd import binding as B
     wl = W.WORKLOADS[name]
@@ -31,15 +32,46 @@ def _run(name, seed, G, rounds, batch=None, lens=None, rows=None, layers=None, f
         w = run_lockstep(ctx, wts, prompts, lens, G, wl.k, forced=forced, engine="pass", chunk=64,
                          max_rounds=rounds, check_state_every=max(rounds // 2, 1), oracle_rows=rows, layers=layers,
                          min_gap=min_gap)
+        if invariance_rows is not None:
+            w["invariance"] = _batch_invariance(B, torch, ctx, wts, prompts, lens, G, wl.k, forced, rounds, invariance_rows)
     stream.synchronize()
     print(f"[{name}] {time.time() - t0:.1f}s rounds={w['rounds']} mean_n={w['mean_n']:.2f} min_gap={w['min_gap']:.2e} "
           f"err: logits={w['logits']:.2e} ssm={w['ssm']:.2e} conv={w['conv']:.2e} kv={w['kv']:.2e}", flush=True)
     return w
 
 
+def _batch_invariance(B, torch, big, wts, prompts, lens, G, k, forced, rounds, rows):
+    """The sequences `rows` of the batch again, as a batch of their own on a second context (other
+    kernels: fewer activation rows pick the weight-streaming and skinny products instead of the
+    many-row ones): same committed tokens, verification logits of the last round within the logit
+    tolerance of each other.  This is what lets the oracle follow a few rows of a large batch."""
+    from parity_util import assert_close, tolerances
+    atol, rtol = tolerances(wts.cfg.w_dtype)
+    sub_lens = [lens[b] for b in rows]
+    sub_prompts = np.stack([prompts[b] for b in rows])
+    small = B.Context(wts, len(rows), max(lens) + G + 2 * k + 4, k, G, use_graphs=1)
+    out = {}
+    for name, ctx, pr, ln, sel in (("big", big, prompts, lens, rows), ("small", small, sub_prompts, sub_lens, list(range(len(rows))))):
+        ctx.hh_prefill(pr, ln, G)
+        for r in range(rounds):
+            ctx.hh_draft(k)
+            ctx.hh_verify()
+            f = None
+            if forced is not None:
+                fr = forced[r] if name == "big" else forced[r][rows]
+                f = torch.from_numpy(np.ascontiguousarray(fr, np.int32)).to(ctx.device)
+            ctx.hh_commit(f)
+        out[name] = ([ctx.hh_get_tokens(b) for b in sel], ctx.hh_get_logits(1)[sel], [ctx.hh_get_state(0)[0][b] for b in sel])
+    assert out["big"][0] == out["small"][0], "committed tokens depend on the batch a sequence is in"
+    e1 = assert_close("batch invariance: verification logits", out["small"][1], out["big"][1], 2 * atol, 2 * rtol)
+    e2 = assert_close("batch invariance: SSM state", np.array(out["small"][2]), np.array(out["big"][2]), 2 * atol, 2 * rtol, scale_to_ref=True)
+    print(f"[batch invariance] rows {rows}: tokens equal, logits differ by at most {e1:.2e}, state by {e2:.2e} (relative)", flush=True)
+    return e1
+
+
 def test_c1_falcon_h1_0p5b_shape():
     """36 layers, d_model 1024, vocab 32768, bf16, batch 1, prompt 512, k = 2."""
-    w = _run("c1", seed=0, G=40, rounds=12, layers=[0, 17, 35])
+    w = _run("c1", seed=0, G=40, rounds=12, layers=[0, 17, 35], min_gap=4e-4)      # seed audited: smallest gap 1.9e-3
     assert w["rounds"] == 12
 
 
@@ -48,7 +80,8 @@ def test_c2_batch16_ragged_forced():
     p = 0.37; oracle on rows 0 and 15 (a ragged batch: slices and passes end at different places
     per sequence)."""
     lens = [600 - 13 * i for i in range(16)]
-    w = _run("c2f", seed=0, G=24, rounds=6, lens=lens, rows=[0, 15], layers=[0, 35], forced_p=0.37)
+    w = _run("c2f", seed=0, G=24, rounds=6, lens=lens, rows=[0, 15], layers=[0, 35], forced_p=0.37,
+             min_gap=1e-4)                                                           # seed audited: smallest gap 5.6e-4
     assert w["rounds"] == 6
 
 
@@ -58,14 +91,14 @@ def test_c2_batch16_full_prompts():
     16 key slices per KV head merged by the merge kernel in verification).  The float64 oracle's
     prefill of 2048 tokens at this shape takes minutes per sequence on the host cores, so it follows
     sequence 0 only; the other rows run the same kernels on the same shapes."""
-    w = _run("c2", seed=0, G=16, rounds=3, rows=[0], layers=[0, 35])
+    w = _run("c2", seed=0, G=16, rounds=3, rows=[0], layers=[0, 35], min_gap=5e-3)   # seed audited: smallest gap 2.4e-2
     assert w["rounds"] == 3
 
 
 def test_c3_falcon_h1_3b_shape():
     """32 layers, d_model 2560, vocab 65536, head_dim 128, d_state 256, bf16, batch 1, k = 4.
     Prompt 1024 here (the oracle's float64 prefill of 4096 tokens takes minutes)."""
-    w = _run("c3", seed=0, G=16, rounds=4, lens=[1024], layers=[0, 31])
+    w = _run("c3", seed=0, G=16, rounds=4, lens=[1024], layers=[0, 31], min_gap=2e-3)   # seed audited: smallest gap 7.4e-3
     assert w["rounds"] == 4
 
 
@@ -73,7 +106,9 @@ def test_c4_batch64_k8_forced():
     """3B shape, batch 64, k = 8, forced acceptance p = 0.68 (the paper's per-token rate): the
     9-position verification runs 576 rows per pass.  Ragged prompts of 71..260 tokens stand in
     for the 32768-token prompts, which neither the float64 oracle nor a test-sized prefill can
-    afford; the oracle follows the longest and the shortest sequence."""
+    afford; the oracle follows the longest and the shortest sequence, and three sequences are run
+    again as a batch of their own (batch invariance: what the other 61 rows rest on)."""
     lens = [260 - 3 * i for i in range(64)]
-    w = _run("c4", seed=0, G=30, rounds=3, lens=lens, rows=[0, 63], layers=[0, 31], forced_p=0.68)
+    w = _run("c4", seed=0, G=30, rounds=3, lens=lens, rows=[0, 63], layers=[0, 31], forced_p=0.68,
+             min_gap=2e-3, invariance_rows=[0, 31, 63])                              # seed audited: smallest gap 7.6e-3
     assert w["rounds"] == 3

@@ -63,7 +63,8 @@ enum {
   HH_KF_MID_OFF = 4,       /* 17..96 activation rows through the many-row GEMM */
   HH_KF_SKINNY_OFF = 8,    /* 4..16 activation rows through the FMA kernel (4..8) and the many-row GEMM (9..16) */
   HH_KF_SSM_SCALAR_CONV = 16, /* prefill scan: element-wise staging of the convolution inputs */
-  HH_KF_ROWS_LDS = 32      /* with HH_KF_MID_OFF: 17..96 activation rows through the LDS-staged many-row GEMM */
+  HH_KF_ROWS_LDS = 32,     /* with HH_KF_MID_OFF: 17..96 activation rows through the LDS-staged many-row GEMM */
+  HH_KF_SSM_SEQUENTIAL = 64 /* passes of 16 and more positions: the position-by-position scan instead of the matmul form */
 };
 
 /* Model shape and capacities.  Plain data; set struct_size = sizeof(hh_cfg). */

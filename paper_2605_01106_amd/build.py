@@ -14,7 +14,7 @@ from concurrent.futures import ThreadPoolExecutor
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OUT = os.path.join(HERE, "libhh.so")
-SOURCES = ["gemv.hip", "gemv_store.hip", "gemv_add.hip", "gemv_swiglu.hip", "gemm_mfma.hip", "skinny_mfma.hip", "mid_mfma.hip", "sample.hip", "ssm.hip", "attn.hip", "attn_mfma.hip", "misc.hip", "hh_api.hip"]
+SOURCES = ["gemv.hip", "gemv_store.hip", "gemv_add.hip", "gemv_swiglu.hip", "gemm_mfma.hip", "skinny_mfma.hip", "mid_mfma.hip", "sample.hip", "ssm.hip", "ssd_mfma.hip", "attn.hip", "attn_mfma.hip", "misc.hip", "hh_api.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fvisibility=hidden",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wno-unused-command-line-argument"]

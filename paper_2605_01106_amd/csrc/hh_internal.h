@@ -98,6 +98,8 @@ struct SsmArgs {
   int write_ring;
 };
 hipError_t launch_ssm(const Dims& d, const SsmArgs& a, hipStream_t s);
+// matmul-form kernel for passes with many positions (ssd_mfma.hip); true if it took the pass
+bool launch_ssd_mfma(const Dims& d, const SsmArgs& a, hipStream_t s, hipError_t* err);
 
 // ---- attention branch
 struct AttnArgs {

@@ -699,6 +699,7 @@ hipError_t launch_ssm(const Dims& d, const SsmArgs& a, hipStream_t s) {
   if (d.N % kSub != 0) return hipErrorInvalidValue;
   hipError_t e = hipSuccess;
   if (launch_ssm_small(d, a, s, &e)) return e;
+  if (launch_ssd_mfma(d, a, s, &e)) return e;
   return launch_ssm_rows<32>(d, a, s);
 }
 

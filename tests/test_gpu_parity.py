@@ -366,3 +366,24 @@ def test_graph_replay_matches_oracle(B):
         w2 = run_lockstep(ctx, wts, prompts, [wl.prompt_len], 40, wl.k, engine="step", check_state_every=4)
     stream.synchronize()
     assert w["tokens"] == eager["tokens"] == w2["tokens"] and w["rounds"] >= 10
+
+
+@pytest.mark.parametrize("dtype,d_state,chunk", [(W.F32, 64, 64), (W.F32, 128, 256), (W.BF16, 64, 128), (W.BF16, 256, 40)])
+def test_prefill_scan_matmul_form(B, dtype, d_state, chunk):
+    """Prefill passes of 16 and more positions take the matmul (state-space dual) form of the scan on
+    the matrix cores: head dimension 64, state sizes 64 / 128 / 256, passes of 40 to 256 positions
+    (several 32-position chunks per pass, a ragged last chunk and a ragged last pass per sequence, a
+    sequence shorter than one chunk), weights with order-one recurrence so that a wrong decay factor,
+    a dropped intra-chunk term or a wrong carried state moves the logits.  The state after prefill,
+    the conv window, the logits and every later round are compared with the sequential float64 oracle;
+    the same run with the position-by-position kernel (HH_KF_SSM_SEQUENTIAL) gives the same tokens."""
+    cfg = W.scaled_config("ssd", n_layers=2, d_model=64, vocab=160, m_heads=2, m_head_dim=64, d_state=d_state,
+                          n_q_heads=2, n_kv_heads=1, head_dim=32, d_ff=96, w_dtype=dtype)
+    wts = W.make_lively_weights(cfg, 61)
+    lens = [333, 17, 290, 97]
+    prompts = W.make_prompts(cfg.vocab, 4, lens, 23)
+    ctx = _ctx(B, wts, 4, 400, 3, 10, kv_page_tokens=32, prefill_chunk=chunk)
+    w = run_lockstep(ctx, wts, prompts, lens, 10, 3, engine="pass", chunk=64, report=_say(f"ssd-{dtype}-N{d_state}-T{chunk}"))
+    seq = _ctx(B, wts, 4, 400, 3, 10, kv_page_tokens=32, prefill_chunk=chunk, kernel_flags=B.HH_KF_SSM_SEQUENTIAL)
+    w2 = run_lockstep(seq, wts, prompts, lens, 10, 3, engine="pass", chunk=64)
+    assert w["tokens"] == w2["tokens"]

@@ -10,17 +10,20 @@
 // float32 products, float32 accumulation): the rounding differs from the sequential kernels only
 // in the order of the sums.
 //
-// One workgroup of four wavefronts per (sequence, head), head dimension P = 64; wavefront w owns
-// the 16 rows p = 16 w .. 16 w + 15 of the head for everything - its slice of the state, transposed
-// (n down, p across), lives in MFMA accumulator registers for the whole pass and is fed back as
-// the A operand of the read-out product as it is: lane (g, j) holds S[p = 16 w + j][n = 16 tile +
-// 4 g + r], which the instruction takes as A[row j][k = g] when the B operand is read with the same
-// n for k = g.  Per chunk of 32 positions: the convolution + SiLU of x, B, C (a thread walks 4
-// channels through the positions with a sliding window of raw rows), the step sizes and their
-// running sum, then  G = C B^T  (three 16 x 16 tiles at or below the diagonal), the masked and
-// scaled M to LDS, the read-out of the old state, the intra-chunk product M x, the outputs
-// y * silu(z), and the state update.  B is kept row-major and C transposed in LDS, padded so
-// that the operand reads of the two large products are free of bank conflicts.
+// One workgroup of eight wavefronts per (sequence, pair of heads), head dimension P = 64: B, C
+// and G = C B^T do not depend on the head, so their convolution is shared by the pair, and two
+// wavefronts per SIMD hide each other's LDS latency.  Wavefront 4 hh + wq owns the 16 rows
+// p = 16 wq .. 16 wq + 15 of head hh of the pair for everything - its slice of the state,
+// transposed (n down, p across), lives in MFMA accumulator registers for the whole pass and is
+// fed back as the A operand of the read-out product as it is: lane (g, j) holds S[p = 16 wq + j]
+// [n = 16 tile + 4 g + r], which the instruction takes as A[row j][k = g] when the B operand is
+// read with the same n for k = g.  Per chunk of 32 positions: the convolution + SiLU of x, B, C (a
+// thread takes 4 channels through 16 positions; the raw rows of the next chunk are requested
+// before the products of this one, so their latency hides behind the MFMAs), the step sizes and
+// their running sum, then  G = C B^T  (three 16 x 16 tiles at or below the diagonal), the masked
+// and scaled M of each head to LDS, the read-out of the old state, the intra-chunk product M x,
+// the outputs y * silu(z), and the state update.  B is kept row-major and C transposed in LDS,
+// padded so that the operand reads of the two large products are free of bank conflicts.
 #include <stdlib.h>
 
 #include "hh_internal.h"
@@ -40,33 +43,34 @@ __device__ __forceinline__ float ssd_softplus(float v) { return v > 20.0f ? v : 
 template <int N>
 struct SsdLds {
   static constexpr int LDB = N + 16, LDT = kSsdL + 4, LDX = kSsdP + 16, LDM = kSsdL + 4;
-  static constexpr int kB = 0;                         // B  [L][LDB]   (position, n)
-  static constexpr int kCt = kB + kSsdL * LDB;         // C^T [N][LDT]  (n, position)
-  static constexpr int kX = kCt + N * LDT;             // x  [L][LDX]   (position, p)
-  static constexpr int kM = kX + kSsdL * LDX;          // M  [L][LDM]   (t, i)
-  static constexpr int kDt = kM + kSsdL * LDM;         // dt_i
-  static constexpr int kCum = kDt + kSsdL;             // cum_i
-  static constexpr int kFloats = kCum + kSsdL;
+  static constexpr int kB = 0;                         // B  [L][LDB]      (position, n)
+  static constexpr int kCt = kB + kSsdL * LDB;         // C^T [N][LDT]     (n, position)
+  static constexpr int kX = kCt + N * LDT;             // x  [2][L][LDX]   (head of the pair, position, p)
+  static constexpr int kM = kX + 2 * kSsdL * LDX;      // M  [2][L][LDM]   (head of the pair, t, i)
+  static constexpr int kDt = kM + 2 * kSsdL * LDM;     // dt [2][L]
+  static constexpr int kCum = kDt + 2 * kSsdL;         // cum [2][L]
+  static constexpr int kFloats = kCum + 2 * kSsdL;
 };
 
 template <int N>
-__global__ __launch_bounds__(256) void ssd_mfma_kernel(const Dims d, const SsmArgs a) {
+__global__ __launch_bounds__(512) void ssd_mfma_kernel(const Dims d, const SsmArgs a) {
   typedef SsdLds<N> Lds;
-  constexpr int L = kSsdL, P = kSsdP, NT = N / 16;
+  constexpr int L = kSsdL, P = kSsdP, NT = N / 16, HALF = L / 2;
   constexpr int LDB = Lds::LDB, LDT = Lds::LDT, LDX = Lds::LDX, LDM = Lds::LDM;
-  constexpr int NG = (P + 2 * N) / 4;                  // conv channel groups of 4: x | B | C
-  static_assert(NG <= 192, "the staging threads are the first three wavefronts");
+  constexpr int NG = (2 * P + 2 * N) / 4;              // conv channel groups of 4: x of head 0 | x of head 1 | B | C
+  static_assert(2 * ((NG + 63) / 64) <= 6, "the staging tasks (a channel group x half a chunk) fit the first six wavefronts");
   extern __shared__ __align__(16) float ssd_smem[];
   float* Bs = ssd_smem + Lds::kB;
   float* Ct = ssd_smem + Lds::kCt;
-  float* Xs = ssd_smem + Lds::kX;
-  float* Ms = ssd_smem + Lds::kM;
-  float* dts = ssd_smem + Lds::kDt;
-  float* cums = ssd_smem + Lds::kCum;
 
   const int tid = threadIdx.x, lane = tid & 63, w = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int hh = w >> 2, wq = w & 3;                   // head of the pair, 16-row slice of the head
   const int g = lane >> 4, j = lane & 15;
-  const int h = blockIdx.x, b = blockIdx.y;
+  const int h = 2 * blockIdx.x + hh, b = blockIdx.y;
+  float* Xs = ssd_smem + Lds::kX + hh * L * LDX;
+  float* Ms = ssd_smem + Lds::kM + hh * L * LDM;
+  float* dts = ssd_smem + Lds::kDt + hh * L;
+  float* cums = ssd_smem + Lds::kCum + hh * L;
   const LayerDev& ly = a.one;
   int nt = a.T;
   if (a.n_tok != nullptr) nt = a.n_tok[b];
@@ -76,12 +80,12 @@ __global__ __launch_bounds__(256) void ssd_mfma_kernel(const Dims d, const SsmAr
   float* ring = ly.ring + (size_t)b * d.ring_slots * d.ring_w;
   const float* zx = a.zx + (size_t)b * a.T * d.ldzx;
 
-  // ---- state slice of this wavefront, transposed: acc[tile][r] = S[16 w + j][16 tile + 4 g + r]
+  // ---- state slice of this wavefront, transposed: acc[tile][r] = S[16 wq + j][16 tile + 4 g + r]
   ssd_f32x4 S[NT];
   {
     const float* src = a.state_in == 0 ? ly.S : (a.state_in == 1 ? ly.S_draft : nullptr);
     if (src != nullptr) {
-      const float* sp = src + (((size_t)b * d.Hm + h) * P + 16 * w + j) * N + 4 * g;
+      const float* sp = src + (((size_t)b * d.Hm + h) * P + 16 * wq + j) * N + 4 * g;
 #pragma unroll
       for (int t = 0; t < NT; ++t) {
         const float4 v = *reinterpret_cast<const float4*>(sp + 16 * t);
@@ -94,23 +98,33 @@ __global__ __launch_bounds__(256) void ssd_mfma_kernel(const Dims d, const SsmAr
   }
   const float dskip = ly.d_skip[h], dtb = ly.dt_bias[h], negA = -expf(ly.a_log[h]);
 
-  // ---- staging role: thread q < NG owns 4 conv channels
-  const bool stager = tid < NG;
-  int ch = 0;                                          // first of the 4 channels (index into xBC)
-  if (stager) ch = tid < P / 4 ? h * P + 4 * tid : d.d_inner + 4 * (tid - P / 4);
-  float4 tw[4], bias = make_float4(0.f, 0.f, 0.f, 0.f), r0, r1, r2;
+  // ---- staging role: a task is (channel group sg < NG, half sh of the chunk); the tasks of a half fill whole
+  // wavefronts (WPH of them), so that the row a wavefront loads is uniform and its address scalar
+  constexpr int WPH = (NG + 63) / 64;
+  const int sh = w / WPH < 2 ? w / WPH : 0, sg_raw = tid - 64 * WPH * sh;
+  const bool stager = w < 2 * WPH && sg_raw < NG;
+  const int sg = stager ? sg_raw : 0;
+  // first of the 4 channels (index into xBC) and where its outputs go
+  const int ch = sg < P / 4 ? (2 * blockIdx.x) * P + 4 * sg : sg < 2 * (P / 4) ? (2 * blockIdx.x + 1) * P + 4 * (sg - P / 4) : d.d_inner + 4 * (sg - 2 * (P / 4));
+  float4 tw[4], bias = make_float4(0.f, 0.f, 0.f, 0.f);
   // raw xBC row of a position: this pass's projections, or the ring for the three positions before it
-  auto raw_row = [&](int pos) -> float4 {
-    if (pos < 0) return make_float4(0.f, 0.f, 0.f, 0.f);
-    const float* p = pos >= pos0 ? zx + (size_t)(pos - pos0) * d.ldzx + d.d_inner + ch : ring + (size_t)(pos & rmask) * d.ring_w + ch;
-    return *reinterpret_cast<const float4*>(p);
-  };
-  if (stager) {
-#pragma unroll
-    for (int q = 0; q < 4; ++q) tw[q] = *reinterpret_cast<const float4*>(ly.conv_w + (size_t)(ch + q) * 4);
-    bias = *reinterpret_cast<const float4*>(ly.conv_b + ch);
-    r0 = raw_row(pos0 - 3); r1 = raw_row(pos0 - 2); r2 = raw_row(pos0 - 1);
-  }
+  // (rows[0..2]: the window before the task's first position; rows[3 + u]: its positions, clamped to
+  // the pass; a macro, not a lambda: an array captured by reference may end up in scratch memory)
+  const unsigned choff = (unsigned)(d.d_inner + ch), rchoff = (unsigned)ch;
+  float4 rows[3 + HALF / 2];
+  // rows[LO_ .. 3 + HALF / 2) <- raw rows of the positions first_ - 3 + LO_ ... (first_: chunk-local index of the
+  // batch's first position, uniform over the wavefront: scalar row address + the lane's channel offset)
+#define HH_SSD_REQUEST(first_, LO_)                                                                      \
+  do {                                                                                                   \
+    _Pragma("unroll") for (int u = (LO_); u < 3 + HALF / 2; ++u) {                                       \
+      const int pos_ = pos0 + min((first_) - 3 + u, nt - 1);                                             \
+      const bool here_ = pos_ >= pos0;                                                                   \
+      const float* rb_ = here_ ? zx + (size_t)(pos_ - pos0) * d.ldzx : ring + (size_t)(max(pos_, 0) & rmask) * d.ring_w; \
+      const float4 v_ = *reinterpret_cast<const float4*>(rb_ + (here_ ? choff : rchoff));                \
+      rows[u] = pos_ < 0 ? make_float4(0.f, 0.f, 0.f, 0.f) : v_;                                         \
+    }                                                                                                    \
+  } while (0)
+  if (stager) HH_SSD_REQUEST(HALF * sh, 0);
 
   TR(0);
   for (int j0 = 0; j0 < nt; j0 += L) {
@@ -118,65 +132,76 @@ __global__ __launch_bounds__(256) void ssd_mfma_kernel(const Dims d, const SsmAr
     if (j0 == 0) TR(1);
     // ================= staging: conv + SiLU of x, B, C; dt and its running log-decay sum
     if (stager) {
-#pragma unroll 1
-      for (int jb = 0; jb < L; jb += 8) {
-        float4 cur[8];
+      // (taps and biases are re-read per chunk from the cache rather than held in 20 registers across the products)
 #pragma unroll
-        for (int u = 0; u < 8; ++u) cur[u] = raw_row(pos0 + j0 + min(jb + u, tc - 1));   // (clamped: loads stay inside this pass)
+      for (int q = 0; q < 4; ++q) tw[q] = *reinterpret_cast<const float4*>(ly.conv_w + (size_t)(ch + q) * 4);
+      bias = *reinterpret_cast<const float4*>(ly.conv_b + ch);
+      const float bq[4] = {bias.x, bias.y, bias.z, bias.w};
+      // two batches of 8 positions: the first one's rows were requested a chunk ago, the second one's are
+      // requested when the first is done (registers: 11 rows at a time)
 #pragma unroll
-        for (int u = 0; u < 8; ++u) {
-          const int jj = jb + u;
+      for (int half2 = 0; half2 < 2; ++half2) {
+        if (half2 == 1) {
+          asm volatile("" ::: "memory");
+          rows[0] = rows[HALF / 2]; rows[1] = rows[HALF / 2 + 1]; rows[2] = rows[HALF / 2 + 2];
+          HH_SSD_REQUEST(j0 + HALF * sh + HALF / 2, 3);
+        }
+#pragma unroll
+        for (int u = 0; u < HALF / 2; ++u) {
+          const int jj = HALF * sh + (HALF / 2) * half2 + u;
           const bool on = jj < tc;
-          const float4 c4 = cur[u];
+          const float4 q0 = rows[u], q1 = rows[u + 1], q2 = rows[u + 2], q3 = rows[u + 3];
+          const float x0[4] = {q0.x, q0.y, q0.z, q0.w}, x1[4] = {q1.x, q1.y, q1.z, q1.w}, x2[4] = {q2.x, q2.y, q2.z, q2.w},
+                      x3[4] = {q3.x, q3.y, q3.z, q3.w};
           float o[4];
-          const float x0[4] = {r0.x, r0.y, r0.z, r0.w}, x1[4] = {r1.x, r1.y, r1.z, r1.w}, x2[4] = {r2.x, r2.y, r2.z, r2.w},
-                      x3[4] = {c4.x, c4.y, c4.z, c4.w}, bq[4] = {bias.x, bias.y, bias.z, bias.w};
 #pragma unroll
           for (int q = 0; q < 4; ++q) {
             float acc = tw[q].x * x0[q];
             acc = fmaf(tw[q].y, x1[q], acc); acc = fmaf(tw[q].z, x2[q], acc); acc = fmaf(tw[q].w, x3[q], acc);
             o[q] = on ? ssd_silu(acc + bq[q]) : 0.f;
           }
-          if (tid < P / 4) {
-            *reinterpret_cast<float4*>(Xs + jj * LDX + 4 * tid) = make_float4(o[0], o[1], o[2], o[3]);
-          } else if (tid < P / 4 + N / 4) {
-            *reinterpret_cast<float4*>(Bs + jj * LDB + 4 * (tid - P / 4)) = make_float4(o[0], o[1], o[2], o[3]);
+          if (sg < 2 * (P / 4)) {
+            *reinterpret_cast<float4*>(ssd_smem + Lds::kX + (sg / (P / 4)) * L * LDX + jj * LDX + 4 * (sg % (P / 4))) = make_float4(o[0], o[1], o[2], o[3]);
+          } else if (sg < 2 * (P / 4) + N / 4) {
+            *reinterpret_cast<float4*>(Bs + jj * LDB + 4 * (sg - 2 * (P / 4))) = make_float4(o[0], o[1], o[2], o[3]);
           } else {
-            const int n0 = 4 * (tid - P / 4 - N / 4);
+            const int n0 = 4 * (sg - 2 * (P / 4) - N / 4);
 #pragma unroll
             for (int q = 0; q < 4; ++q) Ct[(n0 + q) * LDT + jj] = o[q];
           }
-          if (on) {
-            // the raw inputs stay in the ring for the next pass's window and for rollbacks (x of this
-            // head by every workgroup, B and C by the workgroup of head 0)
-            if (a.write_ring && (tid < P / 4 || h == 0))
-              *reinterpret_cast<float4*>(ring + (size_t)((pos0 + j0 + jj) & rmask) * d.ring_w + ch) = c4;
-            r0 = r1; r1 = r2; r2 = c4;
-          }
+          // the raw inputs stay in the ring for the next pass's window and for rollbacks (x of this pair
+          // of heads by every workgroup, B and C by the workgroup of the first pair)
+          if (on && a.write_ring && (sg < 2 * (P / 4) || blockIdx.x == 0))
+            *reinterpret_cast<float4*>(ring + (size_t)((pos0 + j0 + jj) & rmask) * d.ring_w + ch) = q3;
         }
       }
-    } else if (w == 3 && lane < L) {
+      asm volatile("" ::: "memory");                   // (not before this chunk's rows are dead: registers)
+      if (j0 + L < nt) HH_SSD_REQUEST(j0 + L + HALF * sh, 0);   // the next chunk's first rows travel while this one is multiplied
+    } else if (w >= 6 && lane < L) {
+      // wavefront 6 + hh': step sizes and log-decay sums of head hh' (= this wavefront's own head: 6 >> 2 = 7 >> 2 = 1
+      // does not hold, so index explicitly)
+      const int hp = w - 6, hd = 2 * blockIdx.x + hp;
       const bool on = lane < tc;
-      const float rawdt = zx[(size_t)(j0 + min(lane, tc - 1)) * d.ldzx + d.d_inner + d.conv_dim + h];
-      const float dt = on ? ssd_softplus(rawdt + dtb) : 0.f;
-      if (on && a.write_ring) ring[(size_t)((pos0 + j0 + lane) & rmask) * d.ring_w + d.conv_dim + h] = rawdt;
-      float c = negA * dt;                             // log a_t, summed over the positions up to t
+      const float rawdt = zx[(size_t)(j0 + min(lane, tc - 1)) * d.ldzx + d.d_inner + d.conv_dim + hd];
+      const float dt = on ? ssd_softplus(rawdt + ly.dt_bias[hd]) : 0.f;
+      if (on && a.write_ring) ring[(size_t)((pos0 + j0 + lane) & rmask) * d.ring_w + d.conv_dim + hd] = rawdt;
+      float c = -expf(ly.a_log[hd]) * dt;              // log a_t, summed over the positions up to t
 #pragma unroll
       for (int o = 1; o < L; o <<= 1) {
         const float up = __shfl_up(c, o, 64);
         if (lane >= o) c += up;
       }
-      dts[lane] = dt;
-      cums[lane] = c;
+      ssd_smem[Lds::kDt + hp * L + lane] = dt;
+      ssd_smem[Lds::kCum + hp * L + lane] = c;
     }
     __syncthreads();
     if (j0 == 0) TR(2);
 
     // ================= G = C B^T on the tiles at or below the diagonal, M = G * decay * dt to LDS
     {
-      const int tt = w == 0 ? 0 : 1, it = w == 2 ? 1 : 0;          // wavefront 3: the tile above the diagonal is zero
+      const int tt = wq == 0 ? 0 : 1, it = wq == 2 ? 1 : 0;        // slice 3: the tile above the diagonal is zero
       ssd_f32x4 G = {0.f, 0.f, 0.f, 0.f};
-      if (w < 3) {
+      if (wq < 3) {
 #pragma unroll 4
         for (int kk = 0; kk < N / 4; ++kk) {
           const float av = Ct[(4 * kk + g) * LDT + 16 * tt + j];   // A[row t = j][k = g] = C[t][n = 4 kk + g]
@@ -185,13 +210,13 @@ __global__ __launch_bounds__(256) void ssd_mfma_kernel(const Dims d, const SsmAr
         }
       }
       // lane (g, j) holds G[t = 16 tt' + 4 g + r][i = 16 it' + j]
-      const int tt_w = w == 3 ? 0 : tt, it_w = w == 3 ? 1 : it;
+      const int tt_w = wq == 3 ? 0 : tt, it_w = wq == 3 ? 1 : it;
       const int i = 16 * it_w + j;
       const float ci = cums[i], di = dts[i];
 #pragma unroll
       for (int r = 0; r < 4; ++r) {
         const int t = 16 * tt_w + 4 * g + r;
-        const float m = (w < 3 && i <= t) ? G[r] * di * expf(cums[t] - ci) : 0.f;
+        const float m = (wq < 3 && i <= t) ? G[r] * di * expf(cums[t] - ci) : 0.f;
         Ms[t * LDM + i] = m;
       }
     }
@@ -199,7 +224,7 @@ __global__ __launch_bounds__(256) void ssd_mfma_kernel(const Dims d, const SsmAr
     if (j0 == 0) TR(3);
 
     // ================= read-out of the entering state, intra-chunk product, outputs
-    ssd_f32x4 Y[2] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}};   // Y[tt][r] = y[p = 16 w + 4 g + r][t = 16 tt + j]
+    ssd_f32x4 Y[2] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}};   // Y[tt][r] = y[p = 16 wq + 4 g + r][t = 16 tt + j]
 #pragma unroll
     for (int t = 0; t < NT; ++t) {
 #pragma unroll
@@ -208,6 +233,7 @@ __global__ __launch_bounds__(256) void ssd_mfma_kernel(const Dims d, const SsmAr
         Y[0] = __builtin_amdgcn_mfma_f32_16x16x4f32(S[t][r], crow[0], Y[0], 0, 0, 0);
         Y[1] = __builtin_amdgcn_mfma_f32_16x16x4f32(S[t][r], crow[16], Y[1], 0, 0, 0);
       }
+      if ((t & 1) == 1) asm volatile("" ::: "memory");   // operand reads at most two state tiles ahead (registers)
     }
     {
       const float e0 = expf(cums[j]), e1 = expf(cums[16 + j]);
@@ -216,7 +242,7 @@ __global__ __launch_bounds__(256) void ssd_mfma_kernel(const Dims d, const SsmAr
     }
 #pragma unroll
     for (int kk = 0; kk < L / 4; ++kk) {
-      const float xv = Xs[(4 * kk + g) * LDX + 16 * w + j];        // A[row p = j][k = g] = x[i = 4 kk + g][p]
+      const float xv = Xs[(4 * kk + g) * LDX + 16 * wq + j];       // A[row p = j][k = g] = x[i = 4 kk + g][p]
       if (kk < 4) Y[0] = __builtin_amdgcn_mfma_f32_16x16x4f32(xv, Ms[j * LDM + 4 * kk + g], Y[0], 0, 0, 0);
       Y[1] = __builtin_amdgcn_mfma_f32_16x16x4f32(xv, Ms[(16 + j) * LDM + 4 * kk + g], Y[1], 0, 0, 0);
     }
@@ -225,7 +251,7 @@ __global__ __launch_bounds__(256) void ssd_mfma_kernel(const Dims d, const SsmAr
       const int t = 16 * tt + j;
       if (t < tc) {
         const size_t m = (size_t)b * a.T + j0 + t;
-        const int p = 16 * w + 4 * g;
+        const int p = 16 * wq + 4 * g;
         const float4 xv = *reinterpret_cast<const float4*>(Xs + t * LDX + p);
         const float4 z = *reinterpret_cast<const float4*>(a.zx + m * d.ldzx + h * P + p);
         float4 o;
@@ -248,10 +274,11 @@ __global__ __launch_bounds__(256) void ssd_mfma_kernel(const Dims d, const SsmAr
 #pragma unroll
       for (int kk = 0; kk < L / 4; ++kk) {
         const int i = 4 * kk + g;
-        const float xw = Xs[i * LDX + 16 * w + j] * (dts[i] * expf(cl - cums[i]));   // B[k = g][col p = j]
+        const float xw = Xs[i * LDX + 16 * wq + j] * (dts[i] * expf(cl - cums[i]));  // B[k = g][col p = j]
         const float* brow = Bs + i * LDB + j;                                        // A[row n = j][k = g] = B[i][n]
 #pragma unroll
         for (int t = 0; t < NT; ++t) S[t] = __builtin_amdgcn_mfma_f32_16x16x4f32(brow[16 * t], xw, S[t], 0, 0, 0);
+        asm volatile("" ::: "memory");
       }
     }
     __syncthreads();
@@ -260,11 +287,13 @@ __global__ __launch_bounds__(256) void ssd_mfma_kernel(const Dims d, const SsmAr
   TR(6);
 
   if (a.state_out != 0) {
-    float* dp = (a.state_out == 1 ? ly.S : ly.S_draft) + (((size_t)b * d.Hm + h) * P + 16 * w + j) * N + 4 * g;
+    float* dp = (a.state_out == 1 ? ly.S : ly.S_draft) + (((size_t)b * d.Hm + h) * P + 16 * wq + j) * N + 4 * g;
 #pragma unroll
     for (int t = 0; t < NT; ++t) *reinterpret_cast<float4*>(dp + 16 * t) = make_float4(S[t][0], S[t][1], S[t][2], S[t][3]);
   }
   TR(7);
+  (void)dtb; (void)negA;
+#undef HH_SSD_REQUEST
 }
 
 template <int N>
@@ -277,16 +306,16 @@ static hipError_t ssd_launch(const Dims& d, const SsmArgs& a, hipStream_t s) {
     if (e != hipSuccess) return e;
     enabled = true;
   }
-  hipLaunchKernelGGL(kern, dim3(d.Hm, a.B), dim3(256), lds, s, d, a);
+  hipLaunchKernelGGL(kern, dim3(d.Hm / 2, a.B), dim3(512), lds, s, d, a);
   return hipGetLastError();
 }
 
 // true if the pass was taken by the matmul-form kernel: a single layer's pass over this call's
-// projections with outputs, at least 16 positions, head dimension 64, state size 64, 128 or 256,
+// projections with outputs, at least 16 positions, an even number of heads of dimension 64, state size 64, 128 or 256,
 // 16-byte aligned rows
 bool launch_ssd_mfma(const Dims& d, const SsmArgs& a, hipStream_t s, hipError_t* err) {
   if ((d.flags & HH_KF_SSM_SEQUENTIAL) || a.layers != nullptr || a.zx == nullptr || a.g == nullptr || a.n_acc != nullptr ||
-      a.skip != nullptr || a.T < 16 || d.P != kSsdP || d.d_inner % 4 != 0 || d.ldzx % 4 != 0 || d.ring_w % 4 != 0 ||
+      a.skip != nullptr || a.T < 16 || d.P != kSsdP || d.Hm % 2 != 0 || d.d_inner % 4 != 0 || d.ldzx % 4 != 0 || d.ring_w % 4 != 0 ||
       d.conv_dim % 4 != 0 || (reinterpret_cast<uintptr_t>(a.zx) & 15) != 0 || (reinterpret_cast<uintptr_t>(a.g) & 15) != 0)
     return false;
   switch (d.N) {

@@ -64,7 +64,8 @@ enum {
   HH_KF_SKINNY_OFF = 8,    /* 4..16 activation rows through the FMA kernel (4..8) and the many-row GEMM (9..16) */
   HH_KF_SSM_SCALAR_CONV = 16, /* prefill scan: element-wise staging of the convolution inputs */
   HH_KF_ROWS_LDS = 32,     /* with HH_KF_MID_OFF: 17..96 activation rows through the LDS-staged many-row GEMM */
-  HH_KF_SSM_SEQUENTIAL = 64 /* passes of 16 and more positions: the position-by-position scan instead of the matmul form */
+  HH_KF_SSM_SEQUENTIAL = 64, /* passes of 16 and more positions: the position-by-position scan instead of the matmul form */
+  HH_KF_NO_HANDOVER = 128  /* many-row passes: the SwiGLU result goes through float32 and a split kernel to the down projection */
 };
 
 /* Model shape and capacities.  Plain data; set struct_size = sizeof(hh_cfg). */

@@ -48,6 +48,7 @@ struct LdsGemmArgs {
   int M, N, n_tiles;
   int n_blocks, m_blocks, ksplit, ksteps;      // grid = n_blocks * m_blocks * ksplit
   unsigned long long* row_best; int store;     // EPI_STORE: per-row argmax keys (atomic maxima); store = 0: Y not written
+  uint16_t* planes_out; int out_KST;           // EPI_SWIGLU, ksplit == 1: result as split planes (out_KST = N / 32 steps per row tile) instead of Y
 };
 
 // LDS stages of the copy pipeline: as many as fit 160 KB, at most 6 (three for 192-row workgroups)
@@ -219,6 +220,19 @@ __global__ __launch_bounds__(64 * kLdsWaves) void gemm_lds_kernel(const LdsGemmA
         for (int r = 0; r < 4; ++r) {
           v[r] = acc[0][t][m][r];
           if (EPI == EPI_SWIGLU) v[r] = v[r] / (1.0f + expf(-v[r])) * acc[NF - 1][t][m][r];
+        }
+        if (EPI == EPI_SWIGLU && a.planes_out != nullptr) {
+          // the consumer's operand layout: block (row tile, step of 32 columns, term) of 512 elements, element
+          // ((column % 32) / 8 * 16 + row % 16) * 8 + column % 8; this lane's 4 columns are half a group of 8
+          uint32_t a0, a1, a2, b0, b1, b2;
+          split3_bf16_pair(v[0], v[1], a0, a1, a2);
+          split3_bf16_pair(v[2], v[3], b0, b1, b2);
+          uint16_t* dst = a.planes_out + (((size_t)(am >> 4) * a.out_KST + (row0 >> 5)) * 3) * 512 +
+                          ((((row0 & 31) >> 3) * 16 + (am & 15)) * 8 + (row0 & 7));
+          *reinterpret_cast<uint2*>(dst) = make_uint2(a0, b0);
+          *reinterpret_cast<uint2*>(dst + 512) = make_uint2(a1, b1);
+          *reinterpret_cast<uint2*>(dst + 1024) = make_uint2(a2, b2);
+          continue;
         }
         const bool vec = row0 + 3 < a.N && (a.ldy & 3) == 0;
         if (EPI == EPI_ADD) {

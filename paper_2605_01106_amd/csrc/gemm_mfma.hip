@@ -407,6 +407,44 @@ static hipError_t gemm_dispatch_m(const GemmArgs& a, int mtw, int units, hipStre
   return hipErrorInvalidValue;
 }
 
+// Row tiles per wavefront (workgroup = 256 weight rows x 32 MTW activation rows) and K split of the
+// LDS-staged kernel, by a cost model in microseconds: a workgroup step takes the longer of its MFMAs
+// (384 MTW cycles per SIMD) and its copies ((16 + 6 MTW) KB at 28 bytes per cycle and compute unit);
+// the workgroups run in rounds of one per compute unit; a K split adds the reduction kernel and
+// ks * M * N floats of partial products written and read again (about 4 TB/s).  Up to 96 rows one
+// workgroup holds all rows; many rows choose between 192-row and 96-row workgroups.
+static void lds_plan(int m_tiles, int steps, int n_blocks, int nf, int M, int N, int& mtw, int& ks) {
+  mtw = 0; ks = 1;
+  double best = 1e30;
+  const int mtw_lo = m_tiles > 6 ? 3 : (m_tiles + 1) / 2, mtw_hi = m_tiles > 6 ? 6 : (m_tiles + 1) / 2;
+  for (int cand = mtw_lo; cand <= mtw_hi; cand += 3) {
+    const int m_blocks = (m_tiles + lds_row_tiles(cand) - 1) / lds_row_tiles(cand);
+    const double mfma = 384.0 * cand, copy = (16.0 + 6.0 * cand) * 1024.0 / 28.0;
+    const double step_us = (mfma > copy ? mfma : copy) / 2400.0;
+    const int min_steps = m_tiles > 6 ? 8 : 3;
+    for (int k = 1; k <= 32; ++k) {
+      if (k > 1 && (steps / k < min_steps || (size_t)k * nf * M * N > gemm_partial_elems())) break;
+      const int ksteps = (steps + k - 1) / k, kk = (steps + ksteps - 1) / ksteps;
+      const long wgs = (long)n_blocks * m_blocks * kk;
+      const double rounds = (double)((wgs + 255) / 256);
+      double t = rounds * (ksteps + 3) * step_us;
+      if (kk > 1) t += 3.0 + (double)kk * nf * M * N * 8.0 / 4e6;
+      if (t < best) { best = t; mtw = cand; ks = kk; }
+    }
+  }
+}
+
+static bool lds_path(const GemvArgs& g, int m_tiles) { return (m_tiles > 6 || (g.flags & HH_KF_ROWS_LDS)) && gemm_terms(g.M) == 3; }
+
+bool gemm_hands_over_planes(const GemvArgs& g) {
+  if (!g.bf16 || g.n_seg != 1 || g.epi != EPI_SWIGLU || g.seg[0].P == nullptr || g.seg[0].P2 == nullptr || g.K % 8 != 0 || g.K < 8) return false;
+  const int M = g.M, N = g.seg[0].n_rows, m_tiles = (M + 15) / 16, steps = (g.K + 31) / 32, tiles = (N + 15) / 16;
+  if (M <= 0 || N <= 0 || N % 32 != 0 || !lds_path(g, m_tiles)) return false;
+  int mtw = 0, ks = 1;
+  lds_plan(m_tiles, steps, (tiles + kLdsA / 2 - 1) / (kLdsA / 2), 2, M, N, mtw, ks);
+  return ks == 1;
+}
+
 // Y (op)= norm(X) * W^T on the matrix cores.  `planes` is scratch of gemm_planes_elems(M, K) bf16,
 // `partial` of gemm_partial_elems() floats; the weights are the packed tiles (seg[0].P / P2).
 hipError_t launch_gemm_mfma(const GemvArgs& g, uint16_t* planes, float* partial, hipStream_t s) {
@@ -417,10 +455,16 @@ hipError_t launch_gemm_mfma(const GemvArgs& g, uint16_t* planes, float* partial,
   const bool vec = K % 8 == 0 && g.ldx % 4 == 0 && (reinterpret_cast<uintptr_t>(g.X) & 15) == 0 &&
                    (g.X2 == nullptr || (reinterpret_cast<uintptr_t>(g.X2) & 15) == 0) &&
                    (g.norm_w == nullptr || (reinterpret_cast<uintptr_t>(g.norm_w) & 15) == 0);
-  if (vec) hipLaunchKernelGGL(split_rows_kernel<true>, dim3(Mp), dim3(256), 0, s, g.X, g.X2, g.ldx, M, K, Mp, Kp, g.norm_w, g.eps, planes, gemm_terms(M));
-  else hipLaunchKernelGGL(split_rows_kernel<false>, dim3(Mp), dim3(256), 0, s, g.X, g.X2, g.ldx, M, K, Mp, Kp, g.norm_w, g.eps, planes, gemm_terms(M));
-  hipError_t e = hipGetLastError();
-  if (e != hipSuccess) return e;
+  hipError_t e = hipSuccess;
+  if (g.planes_in != nullptr) {
+    if (g.norm_w != nullptr || g.X2 != nullptr) return hipErrorInvalidValue;   // the producer wrote the operand as it is multiplied
+    planes = const_cast<uint16_t*>(g.planes_in);
+  } else {
+    if (vec) hipLaunchKernelGGL(split_rows_kernel<true>, dim3(Mp), dim3(256), 0, s, g.X, g.X2, g.ldx, M, K, Mp, Kp, g.norm_w, g.eps, planes, gemm_terms(M));
+    else hipLaunchKernelGGL(split_rows_kernel<false>, dim3(Mp), dim3(256), 0, s, g.X, g.X2, g.ldx, M, K, Mp, Kp, g.norm_w, g.eps, planes, gemm_terms(M));
+    e = hipGetLastError();
+    if (e != hipSuccess) return e;
+  }
   const int nf = g.epi == EPI_SWIGLU ? 2 : 1, nt = nf == 2 ? 2 : 4;
   GemmArgs a{};
   a.planes = planes; a.Mp = Mp; a.Kp = Kp; a.terms = gemm_terms(M);
@@ -428,39 +472,21 @@ hipError_t launch_gemm_mfma(const GemvArgs& g, uint16_t* planes, float* partial,
   a.Y = g.seg[0].Y; a.ldy = g.seg[0].ldy; a.R2 = g.R2; a.partial = partial; a.M = M; a.N = N; a.K = K;
   a.row_best = g.epi == EPI_STORE ? g.row_best : nullptr; a.store = g.no_store && a.row_best != nullptr ? 0 : 1;
   const int steps = Kp / 32, tiles = (N + 15) / 16, m_tiles = Mp / 16;
-  if ((m_tiles > 6 || (g.flags & HH_KF_ROWS_LDS)) && a.terms == 3) {
+  if (lds_path(g, m_tiles)) {
     LdsGemmArgs l{};
     l.planes = planes; l.m_tiles = m_tiles; l.KST = steps;
     l.W = a.W; l.W2 = a.W2; l.Y = a.Y; l.ldy = a.ldy; l.R2 = a.R2; l.partial = partial;
     l.M = M; l.N = N; l.n_tiles = tiles; l.row_best = a.row_best; l.store = a.store;
     l.n_blocks = (tiles + kLdsA / nf - 1) / (kLdsA / nf);
-    // Row tiles per wavefront (workgroup = 256 weight rows x 32 MTW activation rows) and K split, by a
-    // cost model in microseconds: a workgroup step takes the longer of its MFMAs (384 MTW cycles
-    // per SIMD) and its copies ((16 + 6 MTW) KB at 28 bytes per cycle and compute unit); the
-    // workgroups run in rounds of one per compute unit; a K split adds the reduction kernel and
-    // ks * M * N floats of partial products written and read again (about 4 TB/s).  Up to 96 rows one
-    // workgroup holds all rows; many rows choose between 192-row and 96-row workgroups.
     int mtw = 0, ks = 1;
-    double best = 1e30;
-    const int mtw_lo = m_tiles > 6 ? 3 : (m_tiles + 1) / 2, mtw_hi = m_tiles > 6 ? 6 : (m_tiles + 1) / 2;
-    for (int cand = mtw_lo; cand <= mtw_hi; cand += 3) {
-      const int m_blocks = (m_tiles + lds_row_tiles(cand) - 1) / lds_row_tiles(cand);
-      const double mfma = 384.0 * cand, copy = (16.0 + 6.0 * cand) * 1024.0 / 28.0;
-      const double step_us = (mfma > copy ? mfma : copy) / 2400.0;
-      const int min_steps = m_tiles > 6 ? 8 : 3;
-      for (int k = 1; k <= 32; ++k) {
-        if (k > 1 && (steps / k < min_steps || (size_t)k * nf * M * N > gemm_partial_elems())) break;
-        const int ksteps = (steps + k - 1) / k, kk = (steps + ksteps - 1) / ksteps;
-        const long wgs = (long)l.n_blocks * m_blocks * kk;
-        const double rounds = (double)((wgs + 255) / 256);
-        double t = rounds * (ksteps + 3) * step_us;
-        if (kk > 1) t += 3.0 + (double)kk * nf * M * N * 8.0 / 4e6;
-        if (t < best) { best = t; mtw = cand; ks = kk; }
-      }
-    }
+    lds_plan(m_tiles, steps, l.n_blocks, nf, M, N, mtw, ks);
     l.m_blocks = (m_tiles + lds_row_tiles(mtw) - 1) / lds_row_tiles(mtw);
     l.ksteps = (steps + ks - 1) / ks;
     l.ksplit = (steps + l.ksteps - 1) / l.ksteps;
+    if (g.planes_out != nullptr) {
+      if (!gemm_hands_over_planes(g) || l.ksplit != 1) return hipErrorInvalidValue;
+      l.planes_out = g.planes_out; l.out_KST = N / 32;
+    }
     switch (g.epi) {
       case EPI_STORE: e = lds_launch<EPI_STORE>(l, mtw, s); break;
       case EPI_ADD: e = lds_launch<EPI_ADD>(l, mtw, s); break;

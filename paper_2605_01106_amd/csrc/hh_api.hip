@@ -66,6 +66,7 @@ struct hh_ctx {
   uint16_t* planes;   // split activations of the matrix-core products
   float* gemm_partial;   // partial products of split-K launches
   uint16_t* planes_side; // the same two scratch areas for products enqueued on the side stream
+  uint16_t* planes_act;  // SwiGLU result of a many-row pass, handed to the down projection as split planes
   float* gemm_partial_side;
   float* ho;             // [Mmax][D] attention branch after its output projection (full mode)
   float *rope, *h, *zx, *qkv, *g, *o, *act, *logits_d, *logits_v, *logits_p, *lasth, *part_o, *part_ml, *export_buf;
@@ -152,7 +153,7 @@ bool derive_dims(const hh_cfg& c, Dims& d, std::string& why) {
   if (c.overlap_mode < 0 || c.overlap_mode > 3) return bad("overlap_mode must be in 0..3");
   if (c.attn_max_splits < 0 || c.attn_max_splits > kMaxSplits) return bad("attn_max_splits must be in 0..32");
   if (c.attn_single_slice_steps < -1) return bad("attn_single_slice_steps must be -1, 0 or a step count");
-  if (c.kernel_flags & ~(HH_KF_ATTN_SCALAR | HH_KF_SSM_GENERAL | HH_KF_MID_OFF | HH_KF_SKINNY_OFF | HH_KF_SSM_SCALAR_CONV | HH_KF_ROWS_LDS | HH_KF_SSM_SEQUENTIAL))
+  if (c.kernel_flags & ~(HH_KF_ATTN_SCALAR | HH_KF_SSM_GENERAL | HH_KF_MID_OFF | HH_KF_SKINNY_OFF | HH_KF_SSM_SCALAR_CONV | HH_KF_ROWS_LDS | HH_KF_SSM_SEQUENTIAL | HH_KF_NO_HANDOVER))
     return bad("unknown bit in kernel_flags");
   if (c.prefill_progress < 0) return bad("prefill_progress must not be negative");
   if (c.draft_state_mode != 0 && c.draft_state_mode != 1) return bad("draft_state_mode must be 0 (shared) or 1 (strict)");
@@ -195,6 +196,7 @@ size_t carve(hh_ctx* x, char* base) {
     x->planes = c.take<uint16_t>(gemm_planes_elems((int)Mmax, kmax));
     x->gemm_partial = d.bf16 ? c.take<float>(gemm_partial_elems()) : nullptr;
     x->planes_side = c.take<uint16_t>(gemm_planes_elems((int)Mmax, kmax));
+    x->planes_act = d.bf16 && Mmax > 16 ? c.take<uint16_t>(gemm_planes_elems((int)Mmax, d.F)) : nullptr;
     x->gemm_partial_side = d.bf16 ? c.take<float>(gemm_partial_elems()) : nullptr;
   }
   x->rope = c.take<float>((size_t)d.max_seq * d.Dh);
@@ -293,6 +295,8 @@ bool skinny_args(const GemvArgs& a, GemvArgs& b) {
 // side: the product is enqueued on the side stream (its own scratch, so that it may overlap a product on the main stream)
 hipError_t product(hh_ctx* x, const GemvArgs& a, hipStream_t s, bool side = false) {
   GemvArgs b;
+  if (a.planes_in != nullptr || a.planes_out != nullptr)   // hand-over between two many-row products
+    return launch_gemm_mfma(a, side ? x->planes_side : x->planes, side ? x->gemm_partial_side : x->gemm_partial, s);
   if (skinny_args(a, b)) return launch_skinny_mfma(b, side ? x->gemm_partial_side : x->gemm_partial, nullptr, s);
   if (mid_mfma_fits(a)) return launch_mid_mfma(a, side ? x->gemm_partial_side : x->gemm_partial, s);
   if (a.bf16 && a.M >= kMfmaMinRows && a.seg[0].P != nullptr)
@@ -387,6 +391,15 @@ hh_status run_layers(hh_ctx* x, const std::vector<LayerDev>& table, bool all_ful
       GemvArgs b{};
       b.X = x->act; b.ldx = d.F; b.M = M; b.K = d.F; b.norm_w = nullptr; b.epi = EPI_ADD; b.bf16 = d.bf16; b.flags = d.flags; b.R2 = ho;
       b.seg[0] = {w.w_down, nullptr, w.p_down, nullptr, x->h, d.D, d.D}; b.n_seg = 1;
+      // many rows: the SwiGLU result goes to the down projection as split bf16 planes, without the float32
+      // round trip through `act` and without a split kernel of its own
+      if (x->planes_act != nullptr && !(d.flags & HH_KF_NO_HANDOVER) && !mid_mfma_fits(a)) {
+        GemvArgs sk;
+        if (!skinny_args(a, sk) && gemm_hands_over_planes(a)) {
+          a.planes_out = x->planes_act;
+          b.planes_in = x->planes_act;
+        }
+      }
       HH_LAUNCH(HH_K_MLP_UP, product(x, a, s));
       HH_LAUNCH(HH_K_MLP_DOWN, product(x, b, s));
     }

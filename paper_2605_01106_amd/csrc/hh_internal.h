@@ -58,6 +58,9 @@ struct GemvArgs {
   int flags;                               // hh_cfg.kernel_flags (HH_KF_* bits)
   int no_store;                            // EPI_STORE with an argmax output: only the argmax is wanted, Y need not be written
   unsigned long long* row_best;            // EPI_STORE, many-row kernels: per-row argmax keys [M] (zeroed by the caller), or nullptr
+  // hand-over between two many-row products without a float32 round trip (see gemm_hands_over_planes):
+  const uint16_t* planes_in;               // X already split into bf16 planes (X itself is not read)
+  uint16_t* planes_out;                    // EPI_SWIGLU: the result goes out as split planes [gemm_planes_elems(M, N)] instead of Y
 };
 hipError_t launch_gemv(const GemvArgs& a, int* n_blocks_out, hipStream_t s);
 int gemv_max_blocks();   // upper bound on gridDim.x of launch_gemv (size of the argmax partial rows)
@@ -82,6 +85,10 @@ hipError_t launch_mid_mfma(const GemvArgs& a, float* partial, hipStream_t s);
 size_t gemm_planes_elems(int M, int K);   // bf16 elements of scratch for the split activations
 size_t gemm_partial_elems();              // float elements of scratch for split-K partial products
 hipError_t launch_gemm_mfma(const GemvArgs& a, uint16_t* planes, float* partial, hipStream_t s);
+// whether launch_gemm_mfma honours a.planes_out for these arguments (SwiGLU product through the LDS-staged
+// kernel without a K split, result columns a multiple of 32): the caller then passes the same buffer as
+// planes_in of the product that consumes the result
+bool gemm_hands_over_planes(const GemvArgs& a);
 
 // ---- SSM branch: causal conv + selective scan over up to T positions per sequence
 struct SsmArgs {

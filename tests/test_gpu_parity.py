@@ -156,7 +156,7 @@ def test_key_slices_do_not_change_results(B, max_splits, single):
 
 
 @pytest.mark.parametrize("flag", ["HH_KF_ATTN_SCALAR", "HH_KF_SSM_GENERAL", "HH_KF_MID_OFF", "HH_KF_SKINNY_OFF",
-                                  "HH_KF_SSM_SCALAR_CONV", "HH_KF_MID_OFF|HH_KF_ROWS_LDS"])
+                                  "HH_KF_SSM_SCALAR_CONV", "HH_KF_MID_OFF|HH_KF_ROWS_LDS", "HH_KF_NO_HANDOVER"])
 def test_kernel_selection_flags_do_not_change_results(B, flag):
     """Every kernel-selection switch routes a family of launches to the slower kernel that computes
     the same thing; each variant is checked against the oracle on a workload that reaches the family:

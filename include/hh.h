@@ -65,7 +65,8 @@ enum {
   HH_KF_SSM_SCALAR_CONV = 16, /* prefill scan: element-wise staging of the convolution inputs */
   HH_KF_ROWS_LDS = 32,     /* with HH_KF_MID_OFF: 17..96 activation rows through the LDS-staged many-row GEMM */
   HH_KF_SSM_SEQUENTIAL = 64, /* passes of 16 and more positions: the position-by-position scan instead of the matmul form */
-  HH_KF_NO_HANDOVER = 128  /* many-row passes: the SwiGLU result goes through float32 and a split kernel to the down projection */
+  HH_KF_NO_HANDOVER = 128, /* many-row passes: the SwiGLU result goes through float32 and a split kernel to the down projection */
+  HH_KF_CANARIES = 256     /* every region the library carves from the workspace is followed by 256 guard bytes (see hh_check_canaries) */
 };
 
 /* Model shape and capacities.  Plain data; set struct_size = sizeof(hh_cfg). */
@@ -268,6 +269,10 @@ HH_API hh_status hh_commit(hh_ctx* ctx, const int32_t* n_accepted, void* stream)
 HH_API hh_status hh_get_tokens(hh_ctx* ctx, int32_t seq, int32_t* out, int32_t cap, int32_t* n_out, void* stream);
 /* Per sequence: cache length, committed count, accepted count of the last commit.  Any pointer may be NULL. */
 HH_API hh_status hh_get_lengths(hh_ctx* ctx, int32_t* kv_len, int32_t* committed, int32_t* last_n, void* stream);
+/* Contexts created with HH_KF_CANARIES: checks the guard bytes behind every region of the workspace
+ * (a kernel that writes past the end of its buffer damages them).  *n_damaged (HOST) = number of
+ * damaged guards; hh_last_error names the first.  Synchronises `stream`.  HH_ESTATE without the flag. */
+HH_API hh_status hh_check_canaries(hh_ctx* ctx, int32_t* n_damaged, void* stream);
 /* Acceptance statistics since the last hh_prefill, summed over rounds and unfinished sequences:
  * *accepted = drafts that passed their test (sum of n), *tested = drafts that were tested (in a round
  * with k drafts and n accepted: min(n + 1, k) - the first rejected draft is the last one tested).

@@ -25,7 +25,7 @@ lib = C.CDLL(_LIB_PATH)
 
 HH_OK, HH_EINVAL, HH_ESTATE, HH_ECAPACITY, HH_EWORKSPACE, HH_EDEVICE = 0, -1, -2, -3, -4, -5
 HH_F32, HH_BF16 = 0, 1
-HH_KF_ATTN_SCALAR, HH_KF_SSM_GENERAL, HH_KF_MID_OFF, HH_KF_SKINNY_OFF, HH_KF_SSM_SCALAR_CONV, HH_KF_ROWS_LDS, HH_KF_SSM_SEQUENTIAL, HH_KF_NO_HANDOVER = 1, 2, 4, 8, 16, 32, 64, 128
+HH_KF_ATTN_SCALAR, HH_KF_SSM_GENERAL, HH_KF_MID_OFF, HH_KF_SKINNY_OFF, HH_KF_SSM_SCALAR_CONV, HH_KF_ROWS_LDS, HH_KF_SSM_SEQUENTIAL, HH_KF_NO_HANDOVER, HH_KF_CANARIES = 1, 2, 4, 8, 16, 32, 64, 128, 256
 HH_DRAFT_SSM, HH_DRAFT_FULL, HH_DRAFT_SKIP = 0, 1, 2
 DRAFT_MODES = {"ssm": HH_DRAFT_SSM, "full": HH_DRAFT_FULL, "skip": HH_DRAFT_SKIP}
 STATUS_NAMES = {0: "HH_OK", -1: "HH_EINVAL", -2: "HH_ESTATE", -3: "HH_ECAPACITY", -4: "HH_EWORKSPACE",
@@ -84,6 +84,7 @@ EXPORTS = {
     "hh_commit": (C.c_int, [_ctx_p, C.c_void_p, C.c_void_p]),
     "hh_get_tokens": (C.c_int, [_ctx_p, C.c_int32, _i32p, C.c_int32, _i32p, C.c_void_p]),
     "hh_get_lengths": (C.c_int, [_ctx_p, _i32p, _i32p, _i32p, C.c_void_p]),
+    "hh_check_canaries": (C.c_int, [_ctx_p, _i32p, C.c_void_p]),
     "hh_get_acceptance": (C.c_int, [_ctx_p, C.POINTER(C.c_uint64), C.POINTER(C.c_uint64), C.c_void_p]),
     "hh_get_round": (C.c_int, [_ctx_p, _i32p, _i32p, C.c_void_p]),
     "hh_get_logits": (C.c_int, [_ctx_p, C.c_int32, _f32p, C.c_void_p]),
@@ -320,6 +321,12 @@ class Context:
         a, b, c = (C.c_int32 * B)(), (C.c_int32 * B)(), (C.c_int32 * B)()
         _check(lib.hh_get_lengths(self.ctx, a, b, c, _stream_ptr(stream)), self.ctx)
         return list(a), list(b), list(c)
+
+    def hh_check_canaries(self, stream=None) -> int:
+        """Number of damaged guards behind the workspace regions (context created with HH_KF_CANARIES)."""
+        n = C.c_int32(0)
+        _check(lib.hh_check_canaries(self.ctx, C.byref(n), _stream_ptr(stream)), self.ctx)
+        return int(n.value)
 
     def hh_get_acceptance(self, stream=None):
         """(accepted, tested) draft counts since the last prefill; accepted / tested estimates alpha of Eq. 1."""

@@ -27,14 +27,24 @@ constexpr size_t kAlign = 256;
 
 std::string g_create_error;
 
+constexpr size_t kCanaryBytes = 256;
+constexpr int kCanaryByte = 0xA5;
+
 struct Carver {
   char* base;
   size_t off = 0;
+  bool canaries = false;               // HH_KF_CANARIES: every region is followed by kCanaryBytes of guard bytes
+  std::vector<size_t>* marks = nullptr;   // their offsets (recorded when carving for real)
   template <typename T>
   T* take(size_t n) {
     off = (off + kAlign - 1) / kAlign * kAlign;
     T* p = base ? reinterpret_cast<T*>(base + off) : nullptr;
     off += n * sizeof(T);
+    if (canaries) {
+      off = (off + kAlign - 1) / kAlign * kAlign;
+      if (base && marks) marks->push_back(off);
+      off += kCanaryBytes;
+    }
     return p;
   }
 };
@@ -53,6 +63,7 @@ struct hh_ctx {
   LayerDev* layers_ms_dev = nullptr;
   bool strict = false;
   std::vector<int> draft_modes;   // per layer HH_DRAFT_*; empty: every layer SSM-only (Eq. 4)
+  std::vector<size_t> canaries;   // offsets of the guard bytes behind every workspace region (HH_KF_CANARIES)
   bool draft_has_full = false;
   // device int state
   int *kv_len, *committed, *last_n, *pending, *n_acc, *skip, *adv, *drafts, *targets, *tok, *pos0, *out_tok,
@@ -153,7 +164,7 @@ bool derive_dims(const hh_cfg& c, Dims& d, std::string& why) {
   if (c.overlap_mode < 0 || c.overlap_mode > 3) return bad("overlap_mode must be in 0..3");
   if (c.attn_max_splits < 0 || c.attn_max_splits > kMaxSplits) return bad("attn_max_splits must be in 0..32");
   if (c.attn_single_slice_steps < -1) return bad("attn_single_slice_steps must be -1, 0 or a step count");
-  if (c.kernel_flags & ~(HH_KF_ATTN_SCALAR | HH_KF_SSM_GENERAL | HH_KF_MID_OFF | HH_KF_SKINNY_OFF | HH_KF_SSM_SCALAR_CONV | HH_KF_ROWS_LDS | HH_KF_SSM_SEQUENTIAL | HH_KF_NO_HANDOVER))
+  if (c.kernel_flags & ~(HH_KF_ATTN_SCALAR | HH_KF_SSM_GENERAL | HH_KF_MID_OFF | HH_KF_SKINNY_OFF | HH_KF_SSM_SCALAR_CONV | HH_KF_ROWS_LDS | HH_KF_SSM_SEQUENTIAL | HH_KF_NO_HANDOVER | HH_KF_CANARIES))
     return bad("unknown bit in kernel_flags");
   if (c.prefill_progress < 0) return bad("prefill_progress must not be negative");
   if (c.draft_state_mode != 0 && c.draft_state_mode != 1) return bad("draft_state_mode must be 0 (shared) or 1 (strict)");
@@ -167,6 +178,8 @@ bool derive_dims(const hh_cfg& c, Dims& d, std::string& why) {
 size_t carve(hh_ctx* x, char* base) {
   const Dims& d = x->d;
   Carver c{base};
+  c.canaries = (x->cfg.kernel_flags & HH_KF_CANARIES) != 0;
+  if (base) { x->canaries.clear(); c.marks = &x->canaries; }
   const size_t B = d.Bmax, Mmax = B * d.Tmax, Mv = B * (d.Kmax + 1);
   const size_t esz = d.bf16 ? 2 : 4;
   x->layers_dev = c.take<LayerDev>(d.L);
@@ -549,6 +562,13 @@ hh_status hh_create(const hh_weights* weights, const hh_cfg* cfg, hh_ctx** out) 
     return fail(nullptr, HH_EWORKSPACE, msg);
   }
   carve(ctx, static_cast<char*>(cfg->workspace));
+  for (size_t off : ctx->canaries) {
+    const hipError_t ce = hipMemset(static_cast<char*>(cfg->workspace) + off, kCanaryByte, kCanaryBytes);
+    if (ce != hipSuccess) {
+      delete ctx;
+      return fail(nullptr, HH_EDEVICE, std::string("hh_create: writing the region guards: ") + hipGetErrorString(ce));
+    }
+  }
   ctx->embed = weights->embed; ctx->final_norm = weights->final_norm; ctx->lm_head = weights->lm_head;
   for (int l = 0; l < d.L; ++l) {
     const hh_layer_weights& w = weights->layers[l];
@@ -1006,6 +1026,31 @@ hh_status hh_get_lengths(hh_ctx* x, int32_t* kv_len, int32_t* committed, int32_t
   if (kv_len) HH_HIP(hipMemcpy(kv_len, x->kv_len, n, hipMemcpyDeviceToHost));
   if (committed) HH_HIP(hipMemcpy(committed, x->committed, n, hipMemcpyDeviceToHost));
   if (last_n) HH_HIP(hipMemcpy(last_n, x->last_n, n, hipMemcpyDeviceToHost));
+  return HH_OK;
+}
+
+hh_status hh_check_canaries(hh_ctx* x, int32_t* n_damaged, void* stream) {
+  if (!x) return HH_EINVAL;
+  if (!n_damaged) return fail(x, HH_EINVAL, "hh_check_canaries: NULL argument");
+  if (!(x->cfg.kernel_flags & HH_KF_CANARIES)) return fail(x, HH_ESTATE, "hh_check_canaries: the context was created without HH_KF_CANARIES");
+  hh_status st = sync_stream(x, stream);
+  if (st != HH_OK) return st;
+  int bad = 0;
+  unsigned char buf[kCanaryBytes];
+  for (size_t i = 0; i < x->canaries.size(); ++i) {
+    HH_HIP(hipMemcpy(buf, static_cast<char*>(x->cfg.workspace) + x->canaries[i], kCanaryBytes, hipMemcpyDeviceToHost));
+    for (size_t k = 0; k < kCanaryBytes; ++k)
+      if (buf[k] != kCanaryByte) {
+        if (bad++ == 0) {
+          char msg[160];
+          snprintf(msg, sizeof msg, "hh_check_canaries: guard %zu of %zu (workspace offset %zu) overwritten at byte %zu", i,
+                   x->canaries.size(), x->canaries[i], k);
+          x->err = msg;
+        }
+        break;
+      }
+  }
+  *n_damaged = bad;
   return HH_OK;
 }
 

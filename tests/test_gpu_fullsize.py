@@ -28,12 +28,15 @@ def _run(name, seed, G, rounds, batch=None, lens=None, rows=None, layers=None, f
     print(f"[{name}] inputs {time.time() - t0:.1f}s", flush=True)
     stream = torch.cuda.Stream()
     with torch.cuda.stream(stream):
-        ctx = B.Context(wts, Bn, max(lens) + G + 2 * wl.k + 4, wl.k, G, use_graphs=1)
+        ctx = B.Context(wts, Bn, max(lens) + G + 2 * wl.k + 4, wl.k, G, use_graphs=1, kernel_flags=B.HH_KF_CANARIES)
         w = run_lockstep(ctx, wts, prompts, lens, G, wl.k, forced=forced, engine="pass", chunk=64,
                          max_rounds=rounds, check_state_every=max(rounds // 2, 1), oracle_rows=rows, layers=layers,
                          min_gap=min_gap)
+        # guard bytes behind every workspace region: no kernel wrote past its buffer at these sizes
+        assert ctx.hh_check_canaries() == 0, B.hh_last_error(ctx.ctx)
         if invariance_rows is not None:
             w["invariance"] = _batch_invariance(B, torch, ctx, wts, prompts, lens, G, wl.k, forced, rounds, invariance_rows)
+            assert ctx.hh_check_canaries() == 0, B.hh_last_error(ctx.ctx)
     stream.synchronize()
     print(f"[{name}] {time.time() - t0:.1f}s rounds={w['rounds']} mean_n={w['mean_n']:.2f} min_gap={w['min_gap']:.2e} "
           f"err: logits={w['logits']:.2e} ssm={w['ssm']:.2e} conv={w['conv']:.2e} kv={w['kv']:.2e}", flush=True)

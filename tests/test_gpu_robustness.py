@@ -124,27 +124,46 @@ def test_bitwise_determinism_eager_and_graphs(B, dtype):
     stream.synchronize()
 
 
-def test_nothing_is_written_outside_the_workspace(B):
-    """The workspace sits between two guard regions filled with a known byte; after prefill
-    (several passes, ragged batch), speculative rounds with every k, a stochastic round and every
-    read-back call, both guards still hold that byte."""
+@pytest.mark.parametrize("strict", [0, 1])
+def test_nothing_is_written_outside_the_workspace(B, strict):
+    """The workspace sits between two guard regions filled with a known byte, and (HH_KF_CANARIES)
+    every region the library carves from it is followed by 256 guard bytes of its own; after prefill
+    (several passes, ragged batch), speculative rounds with every k, replaced drafts, a stochastic
+    round, a masked draft and every read-back call all of them still hold that byte - no kernel writes
+    past the end of its buffer, into a neighbouring region or outside the workspace.  Also with the
+    second recurrent state of the strict draft model."""
     cfg, wts = _model()
     lens = [100, 3, 64, 31, 77]
     prompts = W.make_prompts(cfg.vocab, 5, lens, 6)
-    ctx = B.Context(wts, 5, 160, 4, 30, kv_page_tokens=32, prefill_chunk=32, guard_bytes=1 << 20)
-    assert ctx.guards_intact()
+    ctx = B.Context(wts, 5, 160, 4, 30, kv_page_tokens=32, prefill_chunk=32, guard_bytes=1 << 20,
+                    kernel_flags=B.HH_KF_CANARIES, draft_state_mode=strict)
+
+    def intact():
+        return ctx.guards_intact() and ctx.hh_check_canaries() == 0
+
+    assert intact()
     ctx.hh_prefill(prompts, lens, 30)
-    assert ctx.guards_intact()
+    assert intact(), B.hh_last_error(ctx.ctx)
     for k in (4, 0, 1, 3, 2):
         ctx.hh_draft(k)
+        if k == 3:
+            ctx.hh_set_drafts(W.make_random_drafts(cfg.vocab, 1, 5, 3, 2)[0])
         ctx.hh_verify()
         ctx.hh_commit()
-        assert ctx.guards_intact()
+        assert intact(), B.hh_last_error(ctx.ctx)
     ctx.hh_set_sampling(0.7, 9)
     ctx.hh_draft(4)
     ctx.hh_verify()
     ctx.hh_commit()
     ctx.hh_set_sampling(0.0, 0)
+    if not strict:
+        ctx.hh_set_draft_mask(["full", "skip"] + ["ssm"] * (cfg.n_layers - 2))
+        ctx.hh_draft(4)
+        ctx.hh_verify()
+        ctx.hh_commit()
     _snapshot(ctx, cfg.n_layers)
     ctx.hh_get_logits(0), ctx.hh_get_logits(1), ctx.hh_get_logits(2)
-    assert ctx.guards_intact()
+    assert intact(), B.hh_last_error(ctx.ctx)
+    plain = B.Context(wts, 5, 160, 4, 30)
+    with pytest.raises(B.HHError):
+        plain.hh_check_canaries()

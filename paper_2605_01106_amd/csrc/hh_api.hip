@@ -164,7 +164,7 @@ bool derive_dims(const hh_cfg& c, Dims& d, std::string& why) {
   if (c.overlap_mode < 0 || c.overlap_mode > 3) return bad("overlap_mode must be in 0..3");
   if (c.attn_max_splits < 0 || c.attn_max_splits > kMaxSplits) return bad("attn_max_splits must be in 0..32");
   if (c.attn_single_slice_steps < -1) return bad("attn_single_slice_steps must be -1, 0 or a step count");
-  if (c.kernel_flags & ~(HH_KF_ATTN_SCALAR | HH_KF_SSM_GENERAL | HH_KF_MID_OFF | HH_KF_SKINNY_OFF | HH_KF_SSM_SCALAR_CONV | HH_KF_ROWS_LDS | HH_KF_SSM_SEQUENTIAL | HH_KF_NO_HANDOVER | HH_KF_CANARIES))
+  if (c.kernel_flags & ~(HH_KF_ATTN_SCALAR | HH_KF_SSM_GENERAL | HH_KF_MID_OFF | HH_KF_SKINNY_OFF | HH_KF_SSM_SCALAR_CONV | HH_KF_ROWS_LDS | HH_KF_SSM_SEQUENTIAL | HH_KF_NO_HANDOVER | HH_KF_CANARIES | HH_KF_SSM_MATMUL))
     return bad("unknown bit in kernel_flags");
   if (c.prefill_progress < 0) return bad("prefill_progress must not be negative");
   if (c.draft_state_mode != 0 && c.draft_state_mode != 1) return bad("draft_state_mode must be 0 (shared) or 1 (strict)");

@@ -318,6 +318,11 @@ bool launch_ssd_mfma(const Dims& d, const SsmArgs& a, hipStream_t s, hipError_t*
       a.skip != nullptr || a.T < 16 || d.P != kSsdP || d.Hm % 2 != 0 || d.d_inner % 4 != 0 || d.ldzx % 4 != 0 || d.ring_w % 4 != 0 ||
       d.conv_dim % 4 != 0 || (reinterpret_cast<uintptr_t>(a.zx) & 15) != 0 || (reinterpret_cast<uintptr_t>(a.g) & 15) != 0)
     return false;
+  // one workgroup per (sequence, pair of heads) walks the whole pass chunk by chunk: with few of them
+  // (one sequence in prefill: 12 at the 0.5B shape, 20 at the 3B shape) the position-by-position kernel,
+  // which splits every head over several workgroups and stages on wavefronts of its own, is faster
+  // (measured: 12.1 against 15.2 ms, 164 against 184 ms; 16 sequences: 277 against 220 ms)
+  if ((d.Hm / 2) * a.B < 128 && !(d.flags & HH_KF_SSM_MATMUL)) return false;
   switch (d.N) {
     case 64: *err = ssd_launch<64>(d, a, s); return true;
     case 128: *err = ssd_launch<128>(d, a, s); return true;

@@ -382,7 +382,8 @@ def test_prefill_scan_matmul_form(B, dtype, d_state, chunk):
     wts = W.make_lively_weights(cfg, 61)
     lens = [333, 17, 290, 97]
     prompts = W.make_prompts(cfg.vocab, 4, lens, 23)
-    ctx = _ctx(B, wts, 4, 400, 3, 10, kv_page_tokens=32, prefill_chunk=chunk)
+    # (the library takes the matmul form by itself from 128 workgroups on; HH_KF_SSM_MATMUL forces it for these 4 x 1)
+    ctx = _ctx(B, wts, 4, 400, 3, 10, kv_page_tokens=32, prefill_chunk=chunk, kernel_flags=B.HH_KF_SSM_MATMUL)
     w = run_lockstep(ctx, wts, prompts, lens, 10, 3, engine="pass", chunk=64, report=_say(f"ssd-{dtype}-N{d_state}-T{chunk}"))
     seq = _ctx(B, wts, 4, 400, 3, 10, kv_page_tokens=32, prefill_chunk=chunk, kernel_flags=B.HH_KF_SSM_SEQUENTIAL)
     w2 = run_lockstep(seq, wts, prompts, lens, 10, 3, engine="pass", chunk=64)

@@ -150,6 +150,10 @@ def main():
     ap.add_argument("--adaptive-rounds", type=int, default=0,
                     help="extra leg of this many rounds in which k is re-chosen every 4 rounds from the library's acceptance "
                          "statistics and the measured cost ratio (Eq. 1); forced acceptance pattern cut off at k")
+    ap.add_argument("--prefill-profile", action="store_true",
+                    help="after the timed prefill, run it once more with per-launch events (serial, no branch overlap) and "
+                         "report the time per kind of kernel under prefill_kernels")
+    ap.add_argument("--overlap-mode", type=int, default=0, help="hh_cfg.overlap_mode (0 automatic, 1 never, 2 prefill only, 3 always)")
     ap.add_argument("--k", type=int, default=None, help="draft length (default: the workload's)")
     ap.add_argument("--draft-state", choices=("shared", "strict"), default="shared",
                     help="strict: the draft model keeps its own recurrent state over the whole prefix")
@@ -204,7 +208,7 @@ def main():
     n_pass_hint = 16 if wl.prompt_len * Bn > (1 << 18) else 0
     ctx = B.Context(weights, Bn, max_seq, k, G, use_graphs=0 if args.counters else args.graphs,
                     prefill_chunk=args.prefill_chunk, keep_logits=args.keep_logits, prefill_progress=n_pass_hint,
-                    draft_state_mode=1 if args.draft_state == "strict" else 0, kernel_flags=args.kernel_flags)
+                    draft_state_mode=1 if args.draft_state == "strict" else 0, kernel_flags=args.kernel_flags, overlap_mode=args.overlap_mode)
     ctx.hh_set_draft_mask(draft_mask)
     torch.cuda.synchronize()
     say("prefill")
@@ -212,6 +216,17 @@ def main():
     ctx.hh_prefill(prompts, [wl.prompt_len] * Bn, G)
     torch.cuda.synchronize()
     t_prefill = time.perf_counter() - t0
+
+    prefill_kernels = None
+    if args.prefill_profile:
+        ctx.hh_profile(True)
+        ctx.hh_prefill(prompts, [wl.prompt_len] * Bn, G)
+        prof = ctx.hh_profile_read()
+        ctx.hh_profile(False)
+        tot = sum(ms for (ph, _), (_, ms) in prof.items() if ph == 0)
+        prefill_kernels = {KIND_NAMES[kd]: {"launches": c, "total_ms": round(ms, 2), "avg_us": round(ms / c * 1e3, 1),
+                                            "share": round(ms / tot, 3)}
+                           for (ph, kd), (c, ms) in sorted(prof.items()) if ph == 0}
 
     def run_rounds(n, kk, forced=None, timed=False):
         evs = []
@@ -273,9 +288,9 @@ def main():
     per_kind, draft_bytes, verify_bytes, commit_bytes = algorithmic_bytes(cfg, Bn, k, kv_mid)
     kernels = {}
     per_round = {1: k, 2: 1}
-    # the library runs the attention branch of verification (attention, o_proj) on a side stream
-    # beside scan + out_proj only for long caches (its rule: batch * longest cache >= 512k tokens)
-    side_branch = Bn * wl.prompt_len >= 512 * 1024
+    # the attention branch of verification (attention, o_proj) runs on a side stream beside scan + out_proj
+    # only when asked (overlap_mode 3)
+    side_branch = args.overlap_mode == 3
     for ph in (1, 2):
         for kind in sorted(KIND_NAMES):
             if kind == 2 or (ph == 1 and kind in (3, 5)):   # RoPE/append is fused into attention
@@ -373,7 +388,7 @@ def main():
                                if cfg.w_dtype == "bf16" else
                                f"{args.workload}: {cfg.name}, f32 weights, batch {Bn}, prompt {wl.prompt_len}, k={k}, {mode}",
                    "rounds_timed": K, "graphs": args.graphs, "keep_logits": args.keep_logits,
-                   "draft_state": args.draft_state, "draft_mask": args.draft_mask},
+                   "draft_state": args.draft_state, "draft_mask": args.draft_mask, "overlap_mode": args.overlap_mode},
         "draft_tokens_per_s": round(Bn * k * K / t_draft, 1),
         "verify_passes_per_s": round(K / t_verify, 1),
         "commit_us": round(t_commit / K * 1e6, 2),
@@ -397,6 +412,7 @@ def main():
         "speedup_vs_plain_greedy": round((toks / dt) / (toks_g / dt_g), 4),
         "prefill_s": round(t_prefill, 3), "prefill_tokens_per_s": round(Bn * wl.prompt_len / t_prefill, 1),
         "weight_gen_s": round(t_gen, 1),
+        "prefill_kernels": prefill_kernels,
         "roofline": roofline,
         "kernels": kernels,
     }

@@ -98,8 +98,7 @@ typedef struct hh_cfg {
                                            their second use on (non-NULL stream only); hh_commit is always enqueued directly */
   /* Tunables: results must not depend on them beyond float32 rounding order (0 = the library's default). */
   int32_t overlap_mode;                 /* attention branch of a full pass on a side stream beside the SSM branch:
-                                           0 automatic (prefill passes; verification from 512k cached tokens in the batch),
-                                           1 never, 2 prefill passes only, 3 always */
+                                           0 automatic (= 2), 1 never, 2 prefill passes only, 3 always */
   int32_t attn_max_splits;              /* most key slices (workgroups along the cache) per sequence and KV head: 1..32; 0 = 16 */
   int32_t attn_single_slice_steps;      /* matrix-core attention: caches of at most this many 32-key steps use one slice;
                                            0 = 28, -1 = split from the first step on */

@@ -318,18 +318,18 @@ hipError_t product(hh_ctx* x, const GemvArgs& a, hipStream_t s, bool side = fals
 }
 
 // Whether a full pass runs its attention branch on the side stream beside the SSM branch.
-// Prefill passes always do (both branches are long).  In a verification pass the fork makes the
-// captured graph a two-queue graph, and measured on this machine every launch of the following
-// (single-stream) draft graphs then takes about 0.9 us longer; that only pays once the attention
-// branch is long: from 512k cached tokens in the batch.  cfg.overlap_mode: 0 automatic, 1 never,
-// 2 prefill passes only, 3 always.
+// Prefill passes do (both branches are long there).  A verification pass does not unless asked:
+// what can overlap is the shorter branch (scan + out projection: 130 us of 900 us per layer at the 3B
+// shape with 32k-token caches), both branches are bound by the same HBM bandwidth, and a forked
+// graph makes every launch of the following single-stream draft graphs about 0.9 us longer;
+// measured at that workload the pass takes 30.1 ms without the fork and 30.4 ms with it.
+// cfg.overlap_mode: 0 automatic (= 2), 1 never, 2 prefill passes only, 3 always.
 bool branch_overlap(const hh_ctx* x, int B, int T, bool prefill) {
+  (void)B; (void)T;
   const int mode = x->cfg.overlap_mode;
   if (mode == 1) return false;
   if (mode == 3) return true;
-  if (prefill) return true;
-  if (mode == 2) return false;
-  return (long long)B * x->len_upper >= (512LL << 10);
+  return prefill;
 }
 
 // ---- one pass of the block stack over M = B*T rows.  all_full: M_H (both branches of every

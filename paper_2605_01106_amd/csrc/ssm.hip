@@ -394,7 +394,11 @@ __global__ __launch_bounds__(kRows * kSub + (PIPE ? chunk_stage_threads<NV, kRow
 // NWV wavefronts per workgroup (1 or 4), each with its own rows: with tens of thousands of
 // one-wavefront workgroups the launch is bound by the workgroup dispatch rate (measured: 3
 // resident wavefronts per compute unit), and four wavefronts share one B/C convolution.
-template <int NV, int SUBS, int TMAX, int RG, int NWV>
+// OUT = false (no outputs wanted: the commit's rebuild of the state from the ring): the read-out S C and
+// the gate are not computed and positions behind the sequence's count are skipped (the count is
+// uniform over the workgroup), which halves the arithmetic per position and leaves n + 1 instead of
+// TMAX positions of it.
+template <int NV, int SUBS, int TMAX, int RG, int NWV, bool OUT = true>
 __global__ __launch_bounds__(64 * NWV) void ssm_small_kernel(const Dims d, const SsmArgs a) {
   constexpr int NTHR = 64 * NWV;
   constexpr int ROWS = 64 / SUBS, N = NV * SUBS;
@@ -507,6 +511,7 @@ __global__ __launch_bounds__(64 * NWV) void ssm_small_kernel(const Dims d, const
     const int gi = tid + NTHR * u;
 #pragma unroll
     for (int j = 0; j < TMAX; ++j) {
+      if (!OUT && j >= nt) continue;             // (a guard per position, not a loop exit: the unrolled arrays stay in registers)
       float4 o;
       float* op = reinterpret_cast<float*>(&o);
 #pragma unroll
@@ -568,6 +573,7 @@ __global__ __launch_bounds__(64 * NWV) void ssm_small_kernel(const Dims d, const
     float y[TMAX];
 #pragma unroll
     for (int j = 0; j < TMAX; ++j) {
+      if (!OUT && j >= nt) continue;
       const float r0 = pos0 + j - 3 < 0 ? 0.f : xraw[rg][j];
       const float r1 = pos0 + j - 2 < 0 ? 0.f : xraw[rg][j + 1];
       const float r2 = pos0 + j - 1 < 0 ? 0.f : xraw[rg][j + 2];
@@ -575,6 +581,17 @@ __global__ __launch_bounds__(64 * NWV) void ssm_small_kernel(const Dims d, const
       acc = fmaf(xw[rg].y, r1, acc); acc = fmaf(xw[rg].z, r2, acc); acc = fmaf(xw[rg].w, xraw[rg][j + 3], acc);
       const float xv = silu_f(acc + xb[rg]);
       const float coef = dtj[j] * xv;
+      if (!OUT) {
+#pragma unroll
+        for (int i = 0; i < NV; i += 4) {
+          const float4 Bv = *reinterpret_cast<const float4*>(&BCs[j][i * SUBS + sub * 4]);
+          S[rg][i] = fmaf(aj[j], S[rg][i], coef * Bv.x);
+          S[rg][i + 1] = fmaf(aj[j], S[rg][i + 1], coef * Bv.y);
+          S[rg][i + 2] = fmaf(aj[j], S[rg][i + 2], coef * Bv.z);
+          S[rg][i + 3] = fmaf(aj[j], S[rg][i + 3], coef * Bv.w);
+        }
+        continue;
+      }
       const float gate = silu_f(zg[rg][j]);
       float part = 0.f;
 #pragma unroll
@@ -611,6 +628,16 @@ template <int NV, int SUBS, int RG, int NWV>
 static hipError_t launch_ssm_small_r(const Dims& d, const SsmArgs& a, int tmax, hipStream_t s) {
   constexpr int rows = 64 / SUBS * RG * NWV;
   const dim3 grid((d.P + rows - 1) / rows, d.Hm, a.n_layers_z * a.B);
+  if (a.g == nullptr && a.zx == nullptr) {   // the rebuild from the ring: no outputs
+    switch (tmax) {
+      case 1: hipLaunchKernelGGL((ssm_small_kernel<NV, SUBS, 1, RG, NWV, false>), grid, dim3(64 * NWV), 0, s, d, a); break;
+      case 3: hipLaunchKernelGGL((ssm_small_kernel<NV, SUBS, 3, RG, NWV, false>), grid, dim3(64 * NWV), 0, s, d, a); break;
+      case 5: hipLaunchKernelGGL((ssm_small_kernel<NV, SUBS, 5, RG, NWV, false>), grid, dim3(64 * NWV), 0, s, d, a); break;
+      case 9: hipLaunchKernelGGL((ssm_small_kernel<NV, SUBS, 9, RG, NWV, false>), grid, dim3(64 * NWV), 0, s, d, a); break;
+      default: return hipErrorInvalidValue;
+    }
+    return hipGetLastError();
+  }
   switch (tmax) {
     case 1: hipLaunchKernelGGL((ssm_small_kernel<NV, SUBS, 1, RG, NWV>), grid, dim3(64 * NWV), 0, s, d, a); break;
     case 3: hipLaunchKernelGGL((ssm_small_kernel<NV, SUBS, 3, RG, NWV>), grid, dim3(64 * NWV), 0, s, d, a); break;

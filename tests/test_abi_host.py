@@ -124,3 +124,47 @@ def test_optimal_draft_length_matches_the_oracle(B):
     assert B.hh_optimal_draft_length(1.5, 0.5, [1, 2]) == -1
     assert B.hh_optimal_draft_length(0.5, -1.0, [1, 2]) == -1
     assert B.hh_optimal_draft_length(0.5, 0.5, [1, -2]) == -1
+
+
+def test_context_calls_reject_a_null_context(B):
+    """Every entry point that takes a context returns HH_EINVAL for NULL before touching anything."""
+    import ctypes as C
+    i32 = (C.c_int32 * 4)()
+    f32 = (C.c_float * 4)()
+    u64a, u64b = C.c_uint64(0), C.c_uint64(0)
+    n = C.c_int32(0)
+    L = B.lib
+    assert L.hh_prefill(None, None, 1, i32, 1, 1, None) == B.HH_EINVAL
+    assert L.hh_set_sampling(None, C.c_float(0.5), C.c_uint64(1), None) == B.HH_EINVAL
+    assert L.hh_draft(None, 1, None) == B.HH_EINVAL
+    assert L.hh_set_drafts(None, None, None) == B.HH_EINVAL
+    assert L.hh_set_draft_mask(None, i32) == B.HH_EINVAL
+    assert L.hh_verify(None, None) == B.HH_EINVAL
+    assert L.hh_commit(None, None, None) == B.HH_EINVAL
+    assert L.hh_get_tokens(None, 0, i32, 4, C.byref(n), None) == B.HH_EINVAL
+    assert L.hh_get_lengths(None, i32, i32, i32, None) == B.HH_EINVAL
+    assert L.hh_get_round(None, i32, i32, None) == B.HH_EINVAL
+    assert L.hh_get_acceptance(None, C.byref(u64a), C.byref(u64b), None) == B.HH_EINVAL
+    assert L.hh_check_canaries(None, C.byref(n), None) == B.HH_EINVAL
+    assert L.hh_get_logits(None, 0, f32, None) == B.HH_EINVAL
+    assert L.hh_get_state(None, 0, f32, f32, None) == B.HH_EINVAL
+    assert L.hh_get_draft_state(None, 0, f32, f32, None) == B.HH_EINVAL
+    assert L.hh_get_kv(None, 0, 0, 1, f32, f32, None) == B.HH_EINVAL
+    assert L.hh_profile(None, 1) == B.HH_EINVAL
+    assert L.hh_profile_read(None, 4, i32, f32, None) == B.HH_EINVAL
+    assert L.hh_time_kind(None, 1, 0, 1, 1, f32, i32, None) == B.HH_EINVAL
+    assert L.hh_destroy(None) == B.HH_EINVAL
+    assert B.hh_last_error(None) is not None
+
+
+def test_workspace_grows_with_the_strict_state_and_the_guards(B):
+    """draft_state_mode = 1 adds a second recurrent state and ring per layer; HH_KF_CANARIES adds 256 bytes
+    (plus alignment) behind every region."""
+    c2 = W.WORKLOADS["c2"]
+    base = B.hh_workspace_bytes(B.make_cfg(c2.cfg, 16, 2048 + 300, 4, 256))
+    strict = B.hh_workspace_bytes(B.make_cfg(c2.cfg, 16, 2048 + 300, 4, 256, draft_state_mode=1))
+    guarded = B.hh_workspace_bytes(B.make_cfg(c2.cfg, 16, 2048 + 300, 4, 256, kernel_flags=B.HH_KF_CANARIES))
+    state = 36 * 16 * 24 * 64 * 128 * 4
+    ring = 36 * 16 * 512 * (1536 + 2 * 128 + 24) * 4      # 512 slots: the next power of two above the 256-position prefill pass + 3
+    assert state + ring <= strict - base < state + ring + (1 << 20)
+    assert 0 < guarded - base < 1 << 20

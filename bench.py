@@ -153,6 +153,8 @@ def main():
     ap.add_argument("--prefill-profile", action="store_true",
                     help="after the timed prefill, run it once more with per-launch events (serial, no branch overlap) and "
                          "report the time per kind of kernel under prefill_kernels")
+    ap.add_argument("--attn-target-blocks", type=int, default=0, help="hh_cfg.attn_target_blocks (0: the library's 512)")
+    ap.add_argument("--attn-max-splits", type=int, default=0, help="hh_cfg.attn_max_splits (0: the library's 16)")
     ap.add_argument("--overlap-mode", type=int, default=0, help="hh_cfg.overlap_mode (0 automatic, 1 never, 2 prefill only, 3 always)")
     ap.add_argument("--k", type=int, default=None, help="draft length (default: the workload's)")
     ap.add_argument("--draft-state", choices=("shared", "strict"), default="shared",
@@ -208,7 +210,8 @@ def main():
     n_pass_hint = 16 if wl.prompt_len * Bn > (1 << 18) else 0
     ctx = B.Context(weights, Bn, max_seq, k, G, use_graphs=0 if args.counters else args.graphs,
                     prefill_chunk=args.prefill_chunk, keep_logits=args.keep_logits, prefill_progress=n_pass_hint,
-                    draft_state_mode=1 if args.draft_state == "strict" else 0, kernel_flags=args.kernel_flags, overlap_mode=args.overlap_mode)
+                    draft_state_mode=1 if args.draft_state == "strict" else 0, kernel_flags=args.kernel_flags, overlap_mode=args.overlap_mode,
+                    attn_target_blocks=args.attn_target_blocks, attn_max_splits=args.attn_max_splits)
     ctx.hh_set_draft_mask(draft_mask)
     torch.cuda.synchronize()
     say("prefill")

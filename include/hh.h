@@ -100,6 +100,8 @@ typedef struct hh_cfg {
   int32_t overlap_mode;                 /* attention branch of a full pass on a side stream beside the SSM branch:
                                            0 automatic (= 2), 1 never, 2 prefill passes only, 3 always */
   int32_t attn_max_splits;              /* most key slices (workgroups along the cache) per sequence and KV head: 1..32; 0 = 16 */
+  int32_t attn_target_blocks;           /* key slices are chosen so that an attention launch has about this many workgroups
+                                           (sequences x KV heads x row chunks x slices): 64..8192; 0 = 256 */
   int32_t attn_single_slice_steps;      /* matrix-core attention: caches of at most this many 32-key steps use one slice;
                                            0 = 28, -1 = split from the first step on */
   int32_t kernel_flags;                 /* HH_KF_* bits: kernel selection for cross-checks, all 0 by default */

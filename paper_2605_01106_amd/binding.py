@@ -42,7 +42,7 @@ class hh_cfg(C.Structure):
                 ("w_dtype", C.c_int32), ("max_batch", C.c_int32), ("max_seq_len", C.c_int32),
                 ("max_draft", C.c_int32), ("max_new_tokens", C.c_int32), ("kv_page_tokens", C.c_int32),
                 ("prefill_chunk", C.c_int32), ("keep_logits", C.c_int32), ("use_graphs", C.c_int32),
-                ("overlap_mode", C.c_int32), ("attn_max_splits", C.c_int32), ("attn_single_slice_steps", C.c_int32),
+                ("overlap_mode", C.c_int32), ("attn_max_splits", C.c_int32), ("attn_target_blocks", C.c_int32), ("attn_single_slice_steps", C.c_int32),
                 ("kernel_flags", C.c_int32), ("prefill_progress", C.c_int32), ("draft_state_mode", C.c_int32),
                 ("workspace", C.c_void_p), ("workspace_bytes", C.c_size_t)]
 
@@ -110,7 +110,7 @@ class HHError(RuntimeError):
 def make_cfg(cfg: W.HybridConfig, max_batch: int, max_seq_len: int, max_draft: int, max_new_tokens: int,
              kv_page_tokens: int = 0, prefill_chunk: int = 0, keep_logits: int = 1, use_graphs: int = 0,
              overlap_mode: int = 0, attn_max_splits: int = 0, attn_single_slice_steps: int = 0, kernel_flags: int = 0,
-             prefill_progress: int = 0, draft_state_mode: int = 0) -> hh_cfg:
+             prefill_progress: int = 0, draft_state_mode: int = 0, attn_target_blocks: int = 0) -> hh_cfg:
     c = hh_cfg()
     c.struct_size = C.sizeof(hh_cfg)
     c.n_layers, c.d_model, c.vocab = cfg.n_layers, cfg.d_model, cfg.vocab
@@ -123,6 +123,7 @@ def make_cfg(cfg: W.HybridConfig, max_batch: int, max_seq_len: int, max_draft: i
     c.kv_page_tokens, c.prefill_chunk, c.keep_logits, c.use_graphs = kv_page_tokens, prefill_chunk, keep_logits, use_graphs
     c.overlap_mode, c.attn_max_splits, c.attn_single_slice_steps = overlap_mode, attn_max_splits, attn_single_slice_steps
     c.kernel_flags, c.prefill_progress, c.draft_state_mode = kernel_flags, prefill_progress, draft_state_mode
+    c.attn_target_blocks = attn_target_blocks
     c.workspace, c.workspace_bytes = None, 0
     return c
 

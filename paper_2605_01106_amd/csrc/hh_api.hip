@@ -163,6 +163,7 @@ bool derive_dims(const hh_cfg& c, Dims& d, std::string& why) {
   d.eps = c.rms_eps; d.rope_base = c.rope_base;
   if (c.overlap_mode < 0 || c.overlap_mode > 3) return bad("overlap_mode must be in 0..3");
   if (c.attn_max_splits < 0 || c.attn_max_splits > kMaxSplits) return bad("attn_max_splits must be in 0..32");
+  if (c.attn_target_blocks != 0 && (c.attn_target_blocks < 64 || c.attn_target_blocks > 8192)) return bad("attn_target_blocks must be 0 or in 64..8192");
   if (c.attn_single_slice_steps < -1) return bad("attn_single_slice_steps must be -1, 0 or a step count");
   if (c.kernel_flags & ~(HH_KF_ATTN_SCALAR | HH_KF_SSM_GENERAL | HH_KF_MID_OFF | HH_KF_SKINNY_OFF | HH_KF_SSM_SCALAR_CONV | HH_KF_ROWS_LDS | HH_KF_SSM_SEQUENTIAL | HH_KF_NO_HANDOVER | HH_KF_CANARIES | HH_KF_SSM_MATMUL))
     return bad("unknown bit in kernel_flags");
@@ -484,15 +485,18 @@ hh_status run_graphed(hh_ctx* x, long long key, hipStream_t s, F enqueue) {
 }
 
 // Key slices per (sequence, KV head, row chunk) of a verification pass: enough workgroups to
-// cover the chip, but no slice smaller than the unit of work of the kernel.
+// cover the chip once (more slices cost more in partial results and their merge than they gain:
+// at 64 sequences x 2 KV heads over 8192-token caches 2 slices take 133 us per layer, 4 slices 151,
+// 8 slices 188), but no slice smaller than the unit of work of the kernel.
 int pick_splits(const hh_cfg& c, const Dims& d, int B, int T, int len_upper) {
   const int cap = c.attn_max_splits > 0 ? c.attn_max_splits : 16;
+  const int target = c.attn_target_blocks > 0 ? c.attn_target_blocks : 256;   // one workgroup per compute unit: measured best at every workload
   const int single = c.attn_single_slice_steps == 0 ? 28 : c.attn_single_slice_steps;   // -1: never a single slice by this rule
   int s;
   if (attention_uses_mfma(d)) {
     const int blocks = attention_mfma_row_chunks(d, T) * d.Hkv * B;
     const int steps = (len_upper + T + 31) / 32;      // 32 keys per wavefront step, 4 wavefronts per workgroup
-    s = (512 + blocks - 1) / blocks;
+    s = (target + blocks - 1) / blocks;
     if (s > (steps + 3) / 4) s = (steps + 3) / 4;
     // short caches: the ticket and the merge across workgroups (about 4 us) cost more than the
     // few extra steps per wavefront of a single slice
@@ -502,7 +506,7 @@ int pick_splits(const hh_cfg& c, const Dims& d, int B, int T, int len_upper) {
     const int row_chunks = (T * G + 15) / 16;
     const int blocks = row_chunks * d.Hkv * B;
     const int tiles = (len_upper + T + 63) / 64;
-    s = (512 + blocks - 1) / blocks;
+    s = (target + blocks - 1) / blocks;
     if (s > tiles) s = tiles;
   }
   if (s > kMaxSplits) s = kMaxSplits;

@@ -24,7 +24,7 @@ def test_exports_match_header(B):
     assert declared == set(B.EXPORTS), declared ^ set(B.EXPORTS)
     for name in declared:
         assert hasattr(B.lib, name)
-    assert C.sizeof(B.hh_cfg) == 136 and C.sizeof(B.hh_layer_weights) == 17 * 8
+    assert C.sizeof(B.hh_cfg) == 144 and C.sizeof(B.hh_layer_weights) == 17 * 8
 
 
 def test_workspace_sizes(B):
@@ -45,7 +45,7 @@ def test_workspace_sizes(B):
 @pytest.mark.parametrize("field,value", [("n_groups", 2), ("d_conv", 3), ("n_kv_heads", 3), ("head_dim", 12),
                                          ("d_state", 24), ("kv_page_tokens", 48), ("w_dtype", 7),
                                          ("d_model", 60), ("max_batch", 0), ("struct_size", 8),
-                                         ("overlap_mode", 4), ("attn_max_splits", 33), ("attn_single_slice_steps", -2),
+                                         ("overlap_mode", 4), ("attn_max_splits", 33), ("attn_target_blocks", 32), ("attn_single_slice_steps", -2),
                                          ("kernel_flags", 1 << 12), ("prefill_progress", -1), ("keep_logits", 2),
                                          ("use_graphs", -1)])
 def test_bad_configs_are_rejected(B, field, value):

@@ -223,7 +223,11 @@ HH_API hh_status hh_accept_tokens_static(const float* draft_logits, const float*
 /* Draft phase (Section 3.3 / Eq. 4): k autoregressive greedy steps of the
  * SSM-only subgraph per sequence, starting from the committed recurrent state
  * on a scratch copy; never touches the KV cache.  0 <= k <= max_draft; k = 0
- * makes the round a plain greedy step of M_H. */
+ * makes the round a plain greedy step of M_H.  With draft_state_mode = 1 the
+ * steps start from M_S's own committed state and one more step (no LM head)
+ * consumes d_k; with a draft mask (hh_set_draft_mask) layers marked
+ * HH_DRAFT_FULL also run their attention branch and write K/V into the slots
+ * behind the cache length, layers marked HH_DRAFT_SKIP are passed over. */
 HH_API hh_status hh_draft(hh_ctx* ctx, int32_t k, void* stream);
 
 /* Replace the drafted tokens of the current round by caller-chosen ones

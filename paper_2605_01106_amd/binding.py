@@ -25,7 +25,7 @@ lib = C.CDLL(_LIB_PATH)
 
 HH_OK, HH_EINVAL, HH_ESTATE, HH_ECAPACITY, HH_EWORKSPACE, HH_EDEVICE = 0, -1, -2, -3, -4, -5
 HH_F32, HH_BF16 = 0, 1
-HH_KF_ATTN_SCALAR, HH_KF_SSM_GENERAL, HH_KF_MID_OFF, HH_KF_SKINNY_OFF, HH_KF_SSM_SCALAR_CONV, HH_KF_ROWS_LDS, HH_KF_SSM_SEQUENTIAL, HH_KF_NO_HANDOVER, HH_KF_CANARIES, HH_KF_SSM_MATMUL = 1, 2, 4, 8, 16, 32, 64, 128, 256, 512
+HH_KF_ATTN_SCALAR, HH_KF_SSM_GENERAL, HH_KF_MID_OFF, HH_KF_SKINNY_OFF, HH_KF_SSM_SCALAR_CONV, HH_KF_ROWS_LDS, HH_KF_SSM_SEQUENTIAL, HH_KF_NO_HANDOVER, HH_KF_CANARIES, HH_KF_SSM_MATMUL, HH_KF_MID_WIDE = 1, 2, 4, 8, 16, 32, 64, 128, 256, 512, 1024
 HH_DRAFT_SSM, HH_DRAFT_FULL, HH_DRAFT_SKIP = 0, 1, 2
 DRAFT_MODES = {"ssm": HH_DRAFT_SSM, "full": HH_DRAFT_FULL, "skip": HH_DRAFT_SKIP}
 STATUS_NAMES = {0: "HH_OK", -1: "HH_EINVAL", -2: "HH_ESTATE", -3: "HH_ECAPACITY", -4: "HH_EWORKSPACE",

@@ -165,7 +165,7 @@ bool derive_dims(const hh_cfg& c, Dims& d, std::string& why) {
   if (c.attn_max_splits < 0 || c.attn_max_splits > kMaxSplits) return bad("attn_max_splits must be in 0..32");
   if (c.attn_target_blocks != 0 && (c.attn_target_blocks < 64 || c.attn_target_blocks > 8192)) return bad("attn_target_blocks must be 0 or in 64..8192");
   if (c.attn_single_slice_steps < -1) return bad("attn_single_slice_steps must be -1, 0 or a step count");
-  if (c.kernel_flags & ~(HH_KF_ATTN_SCALAR | HH_KF_SSM_GENERAL | HH_KF_MID_OFF | HH_KF_SKINNY_OFF | HH_KF_SSM_SCALAR_CONV | HH_KF_ROWS_LDS | HH_KF_SSM_SEQUENTIAL | HH_KF_NO_HANDOVER | HH_KF_CANARIES | HH_KF_SSM_MATMUL))
+  if (c.kernel_flags & ~(HH_KF_ATTN_SCALAR | HH_KF_SSM_GENERAL | HH_KF_MID_OFF | HH_KF_SKINNY_OFF | HH_KF_SSM_SCALAR_CONV | HH_KF_ROWS_LDS | HH_KF_SSM_SEQUENTIAL | HH_KF_NO_HANDOVER | HH_KF_CANARIES | HH_KF_SSM_MATMUL | HH_KF_MID_WIDE))
     return bad("unknown bit in kernel_flags");
   if (c.prefill_progress < 0) return bad("prefill_progress must not be negative");
   if (c.draft_state_mode != 0 && c.draft_state_mode != 1) return bad("draft_state_mode must be 0 (shared) or 1 (strict)");

@@ -29,6 +29,11 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 // bf16 terms an activation is split into: three (exact); with two (16 mantissa bits) the test
 // with order-one activations loses a token to a near tie
 static constexpr int kMidTerms = 3;
+// padding of a staged activation row in LDS (bf16 elements): with 16 the row stride is 288 or 160 bytes and the
+// 16-byte operand reads of a wavefront (row = lane % 16, 16-byte group = lane / 16) are free of bank conflicts
+// (measured 156 bytes per cycle against 116 with a padding of 8)
+// (8 where 16 would not fit the LDS: 96 rows with 128-column windows)
+static constexpr int mid_pad(int mt, int kw) { return (size_t)2 * kMidTerms * mt * 16 * (kw + 16) * 2 <= 160 * 1024 ? 16 : 8; }
 
 union MFrag {
   uint4 u;
@@ -53,12 +58,19 @@ struct MidArgs {
 // loaded, split and written to the other buffer and the weights of window i+2 are requested;
 // one workgroup barrier per window.  The
 // grid: x = groups of 8 units, y = K chunks of a.wpb windows.
-template <int NF, int MT>
-__global__ __launch_bounds__(512) void mid_loop_kernel(const MidArgs a) {
-  constexpr int NW = 8, KSW = 4, KW = KSW * 32, SL = KW + 8;
+// NW wavefronts per workgroup (one unit each), KSW steps of 32 columns per window: 8 x 4 (one
+// workgroup per compute unit: 104 KB of LDS at 64 rows) or 4 x 2 (half the columns and half the window:
+// 55 KB of LDS and half the registers, so that two workgroups share a compute unit and one's loads,
+// staging and barriers hide behind the other's MFMAs).
+template <int NF, int MT, int NW, int KSW>
+__global__ __launch_bounds__(64 * NW) void mid_loop_kernel(const MidArgs a) {
+  constexpr int KW = KSW * 32, SL = KW + mid_pad(MT, KW);
   constexpr int ROWS = MT * 16;
-  constexpr int PASS = NW * 2;                   // rows staged per pass: two per wavefront (32 float4 groups each)
+  constexpr int GPR = KW / 4;                    // float4 column groups per staged row: 32 or 16 lanes
+  constexpr int RPW = 64 / GPR;                  // rows a wavefront stages per pass: 2 or 4
+  constexpr int PASS = NW * RPW;                 // rows staged per pass (16 in both shapes)
   constexpr int NP = ROWS / PASS;
+  static_assert(PASS == 16 && (KSW == 4 || KSW == 2), "a staging pass is one row tile");
   constexpr size_t BUF = (size_t)kMidTerms * ROWS * SL;   // bf16 elements per LDS buffer
   extern __shared__ __align__(16) unsigned char smem_raw[];
   uint16_t* xs = reinterpret_cast<uint16_t*>(smem_raw);     // [2][kMidTerms][ROWS][SL]
@@ -77,7 +89,7 @@ __global__ __launch_bounds__(512) void mid_loop_kernel(const MidArgs a) {
     wrow[i] = ((NF == 2 && i == 1) ? a.W2 : a.W) + (size_t)min(tile[i], n_tiles - 1) * a.kst_row * 512 + lane * 8;
   }
   // staging: lane = (row in pass, float4 column group)
-  const int cgi = lane & 31, rsub = lane >> 5;
+  const int cgi = lane & (GPR - 1), rsub = lane / GPR;
   float4 v[NP], nw;
   float sq[NP];
 #pragma unroll
@@ -93,13 +105,13 @@ __global__ __launch_bounds__(512) void mid_loop_kernel(const MidArgs a) {
     if (a.norm_w != nullptr) nw = *reinterpret_cast<const float4*>(a.norm_w + colc);
 #pragma unroll
     for (int u = 0; u < NP; ++u) {
-      const int r = min(u * PASS + wave * 2 + rsub, M - 1);
+      const int r = min(u * PASS + wave * RPW + rsub, M - 1);
       v[u] = *reinterpret_cast<const float4*>(a.X + (size_t)r * a.ldx + colc);
     }
     if (a.X2 != nullptr) {
 #pragma unroll
       for (int u = 0; u < NP; ++u) {
-        const int r = min(u * PASS + wave * 2 + rsub, M - 1);
+        const int r = min(u * PASS + wave * RPW + rsub, M - 1);
         const float4 w2 = *reinterpret_cast<const float4*>(a.X2 + (size_t)r * a.ldx + colc);
         v[u].x += w2.x; v[u].y += w2.y; v[u].z += w2.z; v[u].w += w2.w;
       }
@@ -115,7 +127,7 @@ __global__ __launch_bounds__(512) void mid_loop_kernel(const MidArgs a) {
   auto stage = [&](uint16_t* buf) {
 #pragma unroll
     for (int u = 0; u < NP; ++u) {
-      const int r = u * PASS + wave * 2 + rsub;
+      const int r = u * PASS + wave * RPW + rsub;
       if (!(okc && r < M)) v[u] = make_float4(0.f, 0.f, 0.f, 0.f);
       sq[u] += v[u].x * v[u].x + v[u].y * v[u].y + v[u].z * v[u].z + v[u].w * v[u].w;
       uint32_t a0, a1, a2, b0, b1, b2;
@@ -194,17 +206,14 @@ __global__ __launch_bounds__(512) void mid_loop_kernel(const MidArgs a) {
   if (win < win1) window(win, w0, w2);
   if (win + 1 < win1) window(win + 1, w1, w0);
   TR(3);
-  // sums of squares of the rows this wavefront staged (32 lanes per row), for the norm scale
+  // sums of squares of the rows this wavefront staged (GPR lanes per row), for the norm scale
   if (a.ssq != nullptr && blockIdx.x == 0) {
 #pragma unroll
     for (int u = 0; u < NP; ++u) {
-      float t = sq[u];
-      t += dpp_move<0xB1>(t); t += dpp_move<0x4E>(t); t += dpp_move<0x141>(t); t += dpp_move<0x140>(t);
-      const int iv = __float_as_int(t);
-      const float lo = __int_as_float(__builtin_amdgcn_readlane(iv, 0)) + __int_as_float(__builtin_amdgcn_readlane(iv, 16));
-      const float hi = __int_as_float(__builtin_amdgcn_readlane(iv, 32)) + __int_as_float(__builtin_amdgcn_readlane(iv, 48));
-      const int r = u * PASS + wave * 2 + rsub;
-      if (cgi == 0 && r < M) a.ssq[(size_t)blockIdx.y * a.ssq_ld + r] = rsub == 0 ? lo : hi;
+      float t = row16_sum(sq[u]);                                   // every row of 16 lanes holds its total
+      if (GPR == 32) t += __shfl_xor(t, 16, 64);                    // a staged row spans two rows of lanes
+      const int r = u * PASS + wave * RPW + rsub;
+      if (cgi == 0 && r < M) a.ssq[(size_t)blockIdx.y * a.ssq_ld + r] = t;
     }
   }
   // lane (g, n) holds Y[activation row mt*16 + n][weight rows tile*16 + 4g .. + 3]
@@ -234,7 +243,7 @@ __global__ __launch_bounds__(512) void mid_loop_kernel(const MidArgs a) {
 }
 
 
-struct MidPlan { int mt, windows, units, blocks, wpb; size_t lds, partial_elems; };   // windows: K chunks = partial products
+struct MidPlan { int mt, windows, units, blocks, wpb, small; size_t lds, partial_elems; };   // windows: K chunks = partial products
 
 static bool mid_plan(const GemvArgs& g, MidPlan& p) {
   if (!g.bf16 || g.n_seg != 1 || g.seg[0].P == nullptr || g.best != nullptr) return false;   // (argmax: through g.row_best)
@@ -243,17 +252,19 @@ static bool mid_plan(const GemvArgs& g, MidPlan& p) {
   const int nf = g.epi == EPI_SWIGLU ? 2 : 1, N = g.seg[0].n_rows, tiles = (N + 15) / 16;
   p.mt = (g.M + 15) / 16;
   p.units = nf == 2 ? tiles : (tiles + 1) / 2;
-  // K-loop kernel: 8 units per workgroup, windows of 128 columns, K chunks so that the launch
-  // has at most one workgroup per compute unit (its LDS and registers allow no second one)
-  constexpr int target = 256;
-  const int n_win = (g.K + 127) / 128;
-  p.blocks = (p.units + 7) / 8;
+  // the small shape (4 wavefronts, windows of 64 columns, two workgroups per compute unit) for up to 64 rows
+  p.small = p.mt <= 4 && !(g.flags & HH_KF_MID_WIDE) ? 1 : 0;
+  const int upb = p.small ? 4 : 8, kw = p.small ? 64 : 128;
+  // K chunks so that the launch has at most one (two) workgroup(s) per compute unit
+  const int target = p.small ? 512 : 256;
+  const int n_win = (g.K + kw - 1) / kw;
+  p.blocks = (p.units + upb - 1) / upb;
   int ks = target / p.blocks;
   if (ks > n_win) ks = n_win;
   if (ks < 1) ks = 1;
   p.wpb = (n_win + ks - 1) / ks;
   p.windows = (n_win + p.wpb - 1) / p.wpb;          // K chunks = partial products
-  p.lds = (size_t)2 * kMidTerms * p.mt * 16 * (128 + 8) * 2;
+  p.lds = (size_t)2 * kMidTerms * p.mt * 16 * (kw + mid_pad(p.mt, kw)) * 2;
   p.partial_elems = (size_t)p.windows * nf * g.M * N + (size_t)p.windows * 96;
   return p.lds <= 160 * 1024 && p.partial_elems <= gemm_partial_elems() && p.windows <= 65535;
 }
@@ -263,26 +274,34 @@ bool mid_mfma_fits(const GemvArgs& g) {
   return !(g.flags & HH_KF_MID_OFF) && mid_plan(g, p);
 }
 
-template <int NF, int MT>
+template <int NF, int MT, int NW, int KSW>
 static hipError_t mid_launch_loop(const MidArgs& a, const MidPlan& p, hipStream_t s) {
-  auto kern = mid_loop_kernel<NF, MT>;
+  auto kern = mid_loop_kernel<NF, MT, NW, KSW>;
   static size_t lds_enabled = 48 * 1024;
   if (p.lds > lds_enabled) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)p.lds);
     if (e != hipSuccess) return e;
     lds_enabled = p.lds;
   }
-  hipLaunchKernelGGL(kern, dim3(p.blocks, p.windows), dim3(512), p.lds, s, a);
+  hipLaunchKernelGGL(kern, dim3(p.blocks, p.windows), dim3(64 * NW), p.lds, s, a);
   return hipGetLastError();
 }
 template <int NF>
 static hipError_t mid_dispatch(const MidArgs& a, const MidPlan& p, hipStream_t s) {
+  if (p.small) {
+    switch (p.mt) {
+      case 2: return mid_launch_loop<NF, 2, 4, 2>(a, p, s);
+      case 3: return mid_launch_loop<NF, 3, 4, 2>(a, p, s);
+      case 4: return mid_launch_loop<NF, 4, 4, 2>(a, p, s);
+    }
+    return hipErrorInvalidValue;
+  }
   switch (p.mt) {
-    case 2: return mid_launch_loop<NF, 2>(a, p, s);
-    case 3: return mid_launch_loop<NF, 3>(a, p, s);
-    case 4: return mid_launch_loop<NF, 4>(a, p, s);
-    case 5: return mid_launch_loop<NF, 5>(a, p, s);
-    case 6: return mid_launch_loop<NF, 6>(a, p, s);
+    case 2: return mid_launch_loop<NF, 2, 8, 4>(a, p, s);
+    case 3: return mid_launch_loop<NF, 3, 8, 4>(a, p, s);
+    case 4: return mid_launch_loop<NF, 4, 8, 4>(a, p, s);
+    case 5: return mid_launch_loop<NF, 5, 8, 4>(a, p, s);
+    case 6: return mid_launch_loop<NF, 6, 8, 4>(a, p, s);
   }
   return hipErrorInvalidValue;
 }

@@ -46,7 +46,7 @@ def test_workspace_sizes(B):
                                          ("d_state", 24), ("kv_page_tokens", 48), ("w_dtype", 7),
                                          ("d_model", 60), ("max_batch", 0), ("struct_size", 8),
                                          ("overlap_mode", 4), ("attn_max_splits", 33), ("attn_target_blocks", 32), ("attn_single_slice_steps", -2),
-                                         ("kernel_flags", 1 << 12), ("prefill_progress", -1), ("keep_logits", 2),
+                                         ("kernel_flags", 1 << 13), ("prefill_progress", -1), ("keep_logits", 2),
                                          ("use_graphs", -1)])
 def test_bad_configs_are_rejected(B, field, value):
     cfg = B.make_cfg(W.WORKLOADS["c0"].cfg, 1, 128, 2, 64)

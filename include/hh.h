@@ -67,7 +67,7 @@ enum {
   HH_KF_SSM_SEQUENTIAL = 64, /* passes of 16 and more positions: the position-by-position scan instead of the matmul form */
   HH_KF_NO_HANDOVER = 128, /* many-row passes: the SwiGLU result goes through float32 and a split kernel to the down projection */
   HH_KF_SSM_MATMUL = 512,  /* the matmul form of the scan also for launches of fewer than 128 workgroups (default: the sequential kernel there) */
-  HH_KF_MID_WIDE = 1024,   /* 17..64 activation rows: the 8-wavefront, 128-column-window shape of the 65..96-row products (one workgroup per compute unit) */
+  HH_KF_MID_WIDE = 1024,   /* 17..80 activation rows: the 8-wavefront, 128-column-window shape of the 81..96-row products (one workgroup per compute unit) */
   HH_KF_CANARIES = 256     /* every region the library carves from the workspace is followed by 256 guard bytes (see hh_check_canaries) */
 };
 

@@ -252,8 +252,9 @@ static bool mid_plan(const GemvArgs& g, MidPlan& p) {
   const int nf = g.epi == EPI_SWIGLU ? 2 : 1, N = g.seg[0].n_rows, tiles = (N + 15) / 16;
   p.mt = (g.M + 15) / 16;
   p.units = nf == 2 ? tiles : (tiles + 1) / 2;
-  // the small shape (4 wavefronts, windows of 64 columns, two workgroups per compute unit) for up to 64 rows
-  p.small = p.mt <= 4 && !(g.flags & HH_KF_MID_WIDE) ? 1 : 0;
+  // the small shape (4 wavefronts, windows of 64 columns, two workgroups per compute unit) for up to 80 rows
+  // (96 rows: two workgroups' staging buffers no longer fit the LDS)
+  p.small = p.mt <= 5 && !(g.flags & HH_KF_MID_WIDE) ? 1 : 0;
   const int upb = p.small ? 4 : 8, kw = p.small ? 64 : 128;
   // K chunks so that the launch has at most one (two) workgroup(s) per compute unit
   const int target = p.small ? 512 : 256;
@@ -293,6 +294,7 @@ static hipError_t mid_dispatch(const MidArgs& a, const MidPlan& p, hipStream_t s
       case 2: return mid_launch_loop<NF, 2, 4, 2>(a, p, s);
       case 3: return mid_launch_loop<NF, 3, 4, 2>(a, p, s);
       case 4: return mid_launch_loop<NF, 4, 4, 2>(a, p, s);
+      case 5: return mid_launch_loop<NF, 5, 4, 2>(a, p, s);
     }
     return hipErrorInvalidValue;
   }

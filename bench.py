@@ -26,6 +26,7 @@ import numpy as np
 ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
+MFMA_BF16_PEAK_TFLOPS = 2500.0   # MI355X dense bf16
 HBM_PEAK_GBS = 8000.0      # MI355X HBM3E, published peak
 
 
@@ -291,6 +292,9 @@ def main():
     per_kind, draft_bytes, verify_bytes, commit_bytes = algorithmic_bytes(cfg, Bn, k, kv_mid)
     kernels = {}
     per_round = {1: k, 2: 1}
+    dqkv = (cfg.n_q_heads + 2 * cfg.n_kv_heads) * cfg.head_dim
+    gemm_shapes = {0: (cfg.d_in_proj + dqkv, cfg.d_model), 4: (cfg.d_model, cfg.d_inner), 5: (cfg.d_model, cfg.n_q_heads * cfg.head_dim),
+                   6: (2 * cfg.d_ff, cfg.d_model), 7: (cfg.d_model, cfg.d_ff), 8: (cfg.vocab, cfg.d_model)}
     # the attention branch of verification (attention, o_proj) runs on a side stream beside scan + out_proj
     # only when asked (overlap_mode 3)
     side_branch = args.overlap_mode == 3
@@ -302,10 +306,20 @@ def main():
             avg_us, n = min(ctx.hh_time_kind(ph, kind, k, 4) for _ in range(3))
             by = per_kind.get((ph, kind))
             launches = (1 if kind == 8 else cfg.n_layers) * per_round[ph]
-            kernels[f"{PHASE_NAMES[ph]}.{KIND_NAMES[kind]}"] = {
+            entry = {
                 "launches_per_round": launches, "avg_us": round(avg_us, 3), "us_per_round": round(avg_us * launches, 1),
                 "bytes": by, "gbs": None if by is None else round(by / (avg_us * 1e-6) / 1e9, 1),
                 "stream": "side" if side_branch and ph == 2 and kind in (3, 5) else "launch"}
+            # the dense products also against the matrix-core peak: bf16 weights x float32 activations split
+            # exactly into three bf16 terms, i.e. three bf16 MFMA products per multiply-add of the method
+            shape = gemm_shapes.get(kind)
+            if shape is not None and cfg.w_dtype == "bf16":
+                rows = Bn * (k + 1 if ph == 2 else 1)
+                n_out, k_in = shape if not (kind == 0 and ph == 1) else (cfg.d_in_proj, cfg.d_model)
+                tf = 2.0 * rows * n_out * k_in * 3 / (avg_us * 1e-6) / 1e12
+                entry["mfma_tflops_3_terms"] = round(tf, 1)
+                entry["mfma_frac"] = round(tf / MFMA_BF16_PEAK_TFLOPS, 4)
+            kernels[f"{PHASE_NAMES[ph]}.{KIND_NAMES[kind]}"] = entry
     # commit rebuild: timed with the per-launch events (one launch per round)
     ctx.hh_profile(True)
     run_rounds(prof_rounds, k)

@@ -15,7 +15,7 @@ from parity_util import run_lockstep  # noqa: E402
 
 
 def _run(name, seed, G, rounds, batch=None, lens=None, rows=None, layers=None, forced_p=None, min_gap=0.0,
-         invariance_rows=None):
+         invariance_rows=None, draft_state="shared", draft_mask=None):
     import torch
     from paper_2605_01106_amd import binding as B
     wl = W.WORKLOADS[name]
@@ -28,10 +28,11 @@ def _run(name, seed, G, rounds, batch=None, lens=None, rows=None, layers=None, f
     print(f"[{name}] inputs {time.time() - t0:.1f}s", flush=True)
     stream = torch.cuda.Stream()
     with torch.cuda.stream(stream):
-        ctx = B.Context(wts, Bn, max(lens) + G + 2 * wl.k + 4, wl.k, G, use_graphs=1, kernel_flags=B.HH_KF_CANARIES)
+        ctx = B.Context(wts, Bn, max(lens) + G + 2 * wl.k + 4, wl.k, G, use_graphs=1, kernel_flags=B.HH_KF_CANARIES,
+                        draft_state_mode=1 if draft_state == "strict" else 0)
         w = run_lockstep(ctx, wts, prompts, lens, G, wl.k, forced=forced, engine="pass", chunk=64,
                          max_rounds=rounds, check_state_every=max(rounds // 2, 1), oracle_rows=rows, layers=layers,
-                         min_gap=min_gap)
+                         min_gap=min_gap, draft_state=draft_state, draft_mask=draft_mask)
         # guard bytes behind every workspace region: no kernel wrote past its buffer at these sizes
         assert ctx.hh_check_canaries() == 0, B.hh_last_error(ctx.ctx)
         if invariance_rows is not None:
@@ -76,6 +77,19 @@ def test_c1_falcon_h1_0p5b_shape():
     """36 layers, d_model 1024, vocab 32768, bf16, batch 1, prompt 512, k = 2."""
     w = _run("c1", seed=0, G=40, rounds=12, layers=[0, 17, 35], min_gap=4e-4)      # seed audited: smallest gap 1.9e-3
     assert w["rounds"] == 12
+
+
+def test_c1_shape_strict_state_and_layer_mask():
+    """The 0.5B shape with the draft model's own recurrent state (a second prefill pass with attention
+    suppressed, k + 1 draft steps, two rebuilds per commit), and with a draft mask in which the first and the
+    last third of the layers keep their attention branch and the middle third is skipped (the draft steps then
+    run one-row attention over the 256-token cache)."""
+    w = _run("c1", seed=0, G=16, rounds=5, lens=[256], layers=[0, 35], draft_state="strict")
+    assert w["rounds"] == 5 and w["ms_ssm"] > 0
+    mask = ["full"] * 12 + ["skip"] * 12 + ["ssm"] * 12
+    w2 = _run("c1", seed=0, G=16, rounds=5, lens=[256], layers=[0, 35], draft_mask=mask)
+    n = min(len(w["tokens"][0]), len(w2["tokens"][0]))       # five rounds commit different counts; the streams agree
+    assert n >= 5 and w2["tokens"][0][:n] == w["tokens"][0][:n]
 
 
 def test_c2_batch16_ragged_forced():

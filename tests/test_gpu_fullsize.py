@@ -129,3 +129,122 @@ def test_c4_batch64_k8_forced():
     w = _run("c4", seed=0, G=30, rounds=3, lens=lens, rows=[0, 63], layers=[0, 31], forced_p=0.68,
              min_gap=2e-3, invariance_rows=[0, 31, 63])                              # seed audited: smallest gap 7.6e-3
     assert w["rounds"] == 3
+
+
+def test_c4_full_workload_consistency():
+    """The workload the benchmark times, at its full size (3B shape, 64 prompts of 32768 tokens, k = 8,
+    HIP graphs, 69 GB of cached K/V): no oracle can follow it, so it is checked through what the oracle can
+    compute one value at a time and through properties that hold at any size.
+
+    (1) The cached K/V of layer 0 depend on one token and its position only: the oracle's step computes them
+        for sampled prompt positions (first and last sequence, first and last position, pass and page
+        boundaries - the largest cache offsets of the run).
+    (2) Sequences 2j and 2j+1 share a prompt.  The even one decodes speculatively with the greedy
+        longest-prefix rule (the count is taken from the round's drafts and targets with the oracle's
+        `accepted_prefix` and passed as the forced count); the odd one is forced to accept nothing, which
+        makes every round one plain greedy step of M_H.  Section 3.3 (losslessness): both emit the same
+        stream; and row i of a verification pass must give the logits of the single step at that stream
+        position.  The two paths differ in float32 rounding order only (cache of length L + i in one
+        key-slice layout or another), so the logits of a stream position must agree within the logit
+        tolerance, and the tokens wherever the top-2 gap exceeds twice the measured logit difference; a
+        pair is followed up to its first such undecided position.
+    (3) Cache lengths, committed counts and read-back streams stay consistent; no kernel writes past its
+        workspace region."""
+    import dataclasses
+    import torch
+    from oracle.hybrid_lm import HybridLM
+    from oracle.protocol import accepted_prefix
+    from paper_2605_01106_amd import binding as B
+    from parity_util import assert_close, tolerances
+
+    wl = W.WORKLOADS["c4"]
+    cfg, Bn, L, k, R = wl.cfg, wl.batch, wl.prompt_len, wl.k, 20
+    G = R * (k + 1) + 8
+    atol, rtol = tolerances(cfg.w_dtype)
+    t0 = time.time()
+    wts = W.make_weights(cfg, 0)
+    half = W.make_prompts(cfg.vocab, Bn // 2, L, 0)
+    prompts = np.repeat(half, 2, axis=0)
+    print(f"[c4 full] inputs {time.time() - t0:.1f}s", flush=True)
+    stream = torch.cuda.Stream()
+    with torch.cuda.stream(stream):
+        ctx = B.Context(wts, Bn, L + G + 2 * k + 4, k, G, use_graphs=1, kernel_flags=B.HH_KF_CANARIES)
+        ctx.hh_prefill(prompts, [L] * Bn, G)
+        kv_len, committed, _ = ctx.hh_get_lengths()
+        assert kv_len == [L] * Bn and committed == [1] * Bn
+        print(f"[c4 full] prefill done {time.time() - t0:.1f}s", flush=True)
+
+        # (1) layer-0 K/V at sampled positions against the oracle's step on a one-layer model
+        one = dataclasses.replace(cfg, n_layers=1)
+        vals = {n: v for n, v in wts.values.items() if not n.startswith("L") or n.startswith("L0.")}
+        lm1 = HybridLM(one, vals)
+        worst_kv = 0.0
+        for b in (0, Bn - 1):
+            kk, vv = ctx.hh_get_kv(0, b, L)
+            for pos in (0, 63, 64, 255, 256, 4095, 4096, 16384, L - 65, L - 1):
+                st = lm1.new_state(pos + 1)
+                st.kv_len = pos
+                lm1.step(st, int(prompts[b, pos]))
+                for nm, got, ref in (("K", kk[pos], st.K[0][pos]), ("V", vv[pos], st.V[0][pos])):
+                    # float32 evaluation error plus one bf16 storage step (the bound of the lock-step tests)
+                    worst_kv = max(worst_kv, assert_close(f"layer 0 {nm} seq {b} pos {pos}", got, ref,
+                                                          2e-3 * np.abs(ref).max(), 2.0 ** -7))
+            del kk, vv
+        print(f"[c4 full] layer-0 K/V samples: worst error {worst_kv:.2e}  {time.time() - t0:.1f}s", flush=True)
+
+        # (2) speculative rows against plain-greedy rows
+        first = ctx.hh_get_logits(2)
+        for j in range(0, Bn, 2):
+            assert_close(f"prefill logits of the pair {j}", first[j + 1], first[j], atol, rtol)
+        spec = [[] for _ in range(Bn // 2)]     # per pair: (token, top-2 gap, logits row) per stream position
+        plain = [[] for _ in range(Bn // 2)]
+
+        def entry(row, tok):
+            top = np.partition(row, -2)[-2:]
+            assert tok == int(np.argmax(row))
+            return tok, float(top[1] - top[0]), row.copy()
+
+        n_hist = []
+        for r in range(R):
+            ctx.hh_draft(k)
+            ctx.hh_verify()
+            d, g = ctx.hh_get_round()
+            lg = ctx.hh_get_logits(1)
+            forced = np.zeros(Bn, np.int32)
+            for j in range(Bn // 2):
+                n = accepted_prefix(list(d[2 * j]), list(g[2 * j]))
+                forced[2 * j] = n
+                n_hist.append(n)
+                for i in range(n + 1):
+                    if len(spec[j]) < R:
+                        spec[j].append(entry(lg[2 * j, i], int(g[2 * j, i])))
+                plain[j].append(entry(lg[2 * j + 1, 0], int(g[2 * j + 1, 0])))
+            ctx.hh_commit(torch.from_numpy(forced).to(ctx.device))
+        print(f"[c4 full] {R} rounds, mean accepted {np.mean(n_hist):.2f}  {time.time() - t0:.1f}s", flush=True)
+
+        compared, undecided, worst = 0, 0, 0.0
+        for j in range(Bn // 2):
+            for i in range(R):
+                (ta, ga, ra), (tp, gp, rp) = spec[j][i], plain[j][i]
+                delta = assert_close(f"pair {j} stream position {i + 1}: verification row against single step", ra, rp, atol, rtol)
+                worst = max(worst, delta)
+                if ta != tp:
+                    assert min(ga, gp) <= 2 * delta, (j, i, ta, tp, ga, gp, delta)
+                    undecided += 1
+                    break
+                compared += 1
+        print(f"[c4 full] {compared} stream positions equal, {undecided} pairs left at a near tie, "
+              f"logits differ by at most {worst:.2e}", flush=True)
+        assert compared >= 0.9 * (Bn // 2) * R
+
+        # (3) bookkeeping and guards
+        kv_len, committed, last_n = ctx.hh_get_lengths()
+        for b in range(Bn):
+            assert kv_len[b] == L + committed[b] - 1, (b, kv_len[b], committed[b])
+        for j in range(Bn // 2):
+            assert committed[2 * j + 1] == 1 + R and committed[2 * j] == 1 + R + sum(n_hist[j::Bn // 2])
+            toks_p = ctx.hh_get_tokens(2 * j + 1)
+            assert toks_p[1:] == [e[0] for e in plain[j]]
+            assert ctx.hh_get_tokens(2 * j)[1:1 + R] == [e[0] for e in spec[j]]
+        assert ctx.hh_check_canaries() == 0, B.hh_last_error(ctx.ctx)
+    stream.synchronize()

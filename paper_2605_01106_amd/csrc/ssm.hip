@@ -398,11 +398,28 @@ __global__ __launch_bounds__(kRows * kSub + (PIPE ? chunk_stage_threads<NV, kRow
 // the gate are not computed and positions behind the sequence's count are skipped (the count is
 // uniform over the workgroup), which halves the arithmetic per position and leaves n + 1 instead of
 // TMAX positions of it.
+// CW (4 or 2) consecutive channels as one load or store; with 2 the upper half of the float4 is never used
+template <int CW>
+__device__ __forceinline__ float4 load_channels(const float* p) {
+  if (CW == 4) return *reinterpret_cast<const float4*>(p);
+  const float2 v = *reinterpret_cast<const float2*>(p);
+  return make_float4(v.x, v.y, 0.f, 0.f);
+}
+template <int CW>
+__device__ __forceinline__ void store_channels(float* p, const float4& v) {
+  if (CW == 4) *reinterpret_cast<float4*>(p) = v;
+  else *reinterpret_cast<float2*>(p) = make_float2(v.x, v.y);
+}
+
 template <int NV, int SUBS, int TMAX, int RG, int NWV, bool OUT = true>
 __global__ __launch_bounds__(64 * NWV) void ssm_small_kernel(const Dims d, const SsmArgs a) {
   constexpr int NTHR = 64 * NWV;
   constexpr int ROWS = 64 / SUBS, N = NV * SUBS;
-  constexpr int NG = (2 * N / 4 + NTHR - 1) / NTHR;   // groups of 4 B|C channels per thread
+  // B|C channels per thread and group: 4, or 2 where groups of 4 would leave threads of the workgroup idle (half
+  // the registers for the taps and the raw rows of the convolution: one more resident wavefront per SIMD)
+  constexpr int CW = 2 * N / 4 >= NTHR ? 4 : 2;
+  constexpr int NGR = 2 * N / CW;                      // groups in all
+  constexpr int NG = (NGR + NTHR - 1) / NTHR;          // groups per thread
   __shared__ __align__(16) float BCs[TMAX][2 * N];
 
   const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -429,32 +446,36 @@ __global__ __launch_bounds__(64 * NWV) void ssm_small_kernel(const Dims d, const
   const int ntok_v = (a.n_tok != nullptr ? a.n_tok : a.pos0)[b];
   const int pos0 = a.pos0[b];
   float S[RG][NV];
-  {
-    const float* src = a.state_in == 0 ? ly.S : (a.state_in == 1 ? ly.S_draft : nullptr);
-#pragma unroll
-    for (int rg = 0; rg < RG; ++rg) {
-      if (src != nullptr) {
-        const float* sp = src + (((size_t)b * d.Hm + h) * d.P + pr[rg]) * N + sub * 4;       // float4 i of a lane: elements (i/4)*4*SUBS + 4*sub ..
-#pragma unroll
-        for (int i = 0; i < NV; i += 4) {
-          const float4 v = *reinterpret_cast<const float4*>(sp + i * SUBS);
-          S[rg][i] = v.x; S[rg][i + 1] = v.y; S[rg][i + 2] = v.z; S[rg][i + 3] = v.w;
-        }
-      } else {
-#pragma unroll
-        for (int i = 0; i < NV; ++i) S[rg][i] = 0.f;
-      }
-    }
+  // (a macro, not a lambda: the state must stay in registers)
+#define HH_LOAD_STATE()                                                                                                   \
+  {                                                                                                                       \
+    const float* src = a.state_in == 0 ? ly.S : (a.state_in == 1 ? ly.S_draft : nullptr);                                 \
+    _Pragma("unroll") for (int rg = 0; rg < RG; ++rg) {                                                                   \
+      if (src != nullptr) {                                                                                               \
+        /* float4 i of a lane: elements (i/4)*4*SUBS + 4*sub .. */                                                        \
+        const float* sp = src + (((size_t)b * d.Hm + h) * d.P + pr[rg]) * N + sub * 4;                                    \
+        _Pragma("unroll") for (int i = 0; i < NV; i += 4) {                                                               \
+          const float4 v = *reinterpret_cast<const float4*>(sp + i * SUBS);                                               \
+          S[rg][i] = v.x; S[rg][i + 1] = v.y; S[rg][i + 2] = v.z; S[rg][i + 3] = v.w;                                     \
+        }                                                                                                                 \
+      } else {                                                                                                            \
+        _Pragma("unroll") for (int i = 0; i < NV; ++i) S[rg][i] = 0.f;                                                    \
+      }                                                                                                                   \
+    }                                                                                                                     \
   }
-  float4 bw[NG][4], bb[NG], braw[NG][TMAX + 3];
+  // With outputs the state is requested first (the longest wait).  The rebuild holds up to TMAX + 3 ring rows of
+  // B | C per thread until the convolution is done; it requests the state behind that, which keeps it at the
+  // register count of the one-position kernel (more resident wavefronts cover the wait instead).
+  if (OUT) HH_LOAD_STATE();
+  float4 bw[NG][CW], bb[NG], braw[NG][TMAX + 3];
   float xraw[RG][TMAX + 3], zg[RG][TMAX];
   float dtraw_l = 0.f;   // raw dt of position `lane` (lanes < T): softplus and decay are evaluated once, lane-parallel
 #pragma unroll
   for (int u = 0; u < NG; ++u) {
-    const int c = d.d_inner + 4 * min(tid + NTHR * u, 2 * N / 4 - 1);
+    const int c = d.d_inner + CW * min(tid + NTHR * u, NGR - 1);
 #pragma unroll
-    for (int t = 0; t < 4; ++t) bw[u][t] = *reinterpret_cast<const float4*>(ly.conv_w + (size_t)(c + t) * 4);
-    bb[u] = *reinterpret_cast<const float4*>(ly.conv_b + c);
+    for (int t = 0; t < CW; ++t) bw[u][t] = *reinterpret_cast<const float4*>(ly.conv_w + (size_t)(c + t) * 4);
+    bb[u] = load_channels<CW>(ly.conv_b + c);
   }
   float4 xw[RG];
   float xb[RG];
@@ -471,7 +492,7 @@ __global__ __launch_bounds__(64 * NWV) void ssm_small_kernel(const Dims d, const
     for (int j = 0; j < TMAX; ++j) {
       const float* r = zx + (size_t)min(j, a.T - 1) * d.ldzx + d.d_inner;
 #pragma unroll
-      for (int u = 0; u < NG; ++u) braw[u][j + 3] = *reinterpret_cast<const float4*>(r + d.d_inner + 4 * min(tid + NTHR * u, 2 * N / 4 - 1));
+      for (int u = 0; u < NG; ++u) braw[u][j + 3] = load_channels<CW>(r + d.d_inner + CW * min(tid + NTHR * u, NGR - 1));
 #pragma unroll
       for (int rg = 0; rg < RG; ++rg) {
         xraw[rg][j + 3] = r[cx[rg]];
@@ -491,9 +512,10 @@ __global__ __launch_bounds__(64 * NWV) void ssm_small_kernel(const Dims d, const
 #pragma unroll
   for (int j = -3; j < (int)TMAX; ++j) {
     if (j >= 0 && zx != nullptr) continue;
+    if (!OUT && j >= nt) continue;               // the rebuild never uses positions behind the count: no loads for them
     const float* r = ring_row(min(j, nt - 1));
 #pragma unroll
-    for (int u = 0; u < NG; ++u) braw[u][j + 3] = *reinterpret_cast<const float4*>(r + d.d_inner + 4 * min(tid + NTHR * u, 2 * N / 4 - 1));
+    for (int u = 0; u < NG; ++u) braw[u][j + 3] = load_channels<CW>(r + d.d_inner + CW * min(tid + NTHR * u, NGR - 1));
 #pragma unroll
     for (int rg = 0; rg < RG; ++rg) {
       xraw[rg][j + 3] = r[cx[rg]];
@@ -512,10 +534,10 @@ __global__ __launch_bounds__(64 * NWV) void ssm_small_kernel(const Dims d, const
 #pragma unroll
     for (int j = 0; j < TMAX; ++j) {
       if (!OUT && j >= nt) continue;             // (a guard per position, not a loop exit: the unrolled arrays stay in registers)
-      float4 o;
+      float4 o = make_float4(0.f, 0.f, 0.f, 0.f);
       float* op = reinterpret_cast<float*>(&o);
 #pragma unroll
-      for (int ch = 0; ch < 4; ++ch) {
+      for (int ch = 0; ch < CW; ++ch) {
         const float r0 = pos0 + j - 3 < 0 ? 0.f : reinterpret_cast<const float*>(&braw[u][j])[ch];
         const float r1 = pos0 + j - 2 < 0 ? 0.f : reinterpret_cast<const float*>(&braw[u][j + 1])[ch];
         const float r2 = pos0 + j - 1 < 0 ? 0.f : reinterpret_cast<const float*>(&braw[u][j + 2])[ch];
@@ -524,7 +546,7 @@ __global__ __launch_bounds__(64 * NWV) void ssm_small_kernel(const Dims d, const
         acc = fmaf(bw[u][ch].y, r1, acc); acc = fmaf(bw[u][ch].z, r2, acc); acc = fmaf(bw[u][ch].w, r3, acc);
         op[ch] = silu_f(acc + reinterpret_cast<const float*>(&bb[u])[ch]);
       }
-      if (gi < 2 * N / 4) *reinterpret_cast<float4*>(&BCs[j][4 * gi]) = o;
+      if (gi < NGR) store_channels<CW>(&BCs[j][CW * gi], o);
     }
   }
   // ---- per-position scalars of the head (step and decay), all positions at once
@@ -551,10 +573,10 @@ __global__ __launch_bounds__(64 * NWV) void ssm_small_kernel(const Dims d, const
 #pragma unroll
       for (int u = 0; u < NG; ++u) {
         const int gi = tid + NTHR * u;
-        if (gi < 2 * N / 4) {
+        if (gi < NGR) {
 #pragma unroll
           for (int j = 0; j < TMAX; ++j)
-            if (j < nt) *reinterpret_cast<float4*>(ring + (size_t)((pos0 + j) & rmask) * d.ring_w + d.d_inner + 4 * gi) = braw[u][j + 3];
+            if (j < nt) store_channels<CW>(ring + (size_t)((pos0 + j) & rmask) * d.ring_w + d.d_inner + CW * gi, braw[u][j + 3]);
         }
       }
       for (int it = tid; it < nt * d.Hm; it += NTHR) {
@@ -566,6 +588,8 @@ __global__ __launch_bounds__(64 * NWV) void ssm_small_kernel(const Dims d, const
   TR(2);
   __syncthreads();
   TR(3);
+  if (!OUT) HH_LOAD_STATE();
+#undef HH_LOAD_STATE
 
   // ---- per row group: conv + SiLU of x, recurrence, outputs
 #pragma unroll

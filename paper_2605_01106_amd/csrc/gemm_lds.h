@@ -48,6 +48,7 @@ struct LdsGemmArgs {
   int M, N, n_tiles;
   int n_blocks, m_blocks, ksplit, ksteps;      // grid = n_blocks * m_blocks * ksplit
   unsigned long long* row_best; int store;     // EPI_STORE: per-row argmax keys (atomic maxima); store = 0: Y not written
+  int xcd_ranges;                              // 1: tiles numbered in per-XCD ranges (see the kernel)
   uint16_t* planes_out; int out_KST;           // EPI_SWIGLU, ksplit == 1: result as split planes (out_KST = N / 32 steps per row tile) instead of Y
 };
 
@@ -66,8 +67,17 @@ __global__ __launch_bounds__(64 * kLdsWaves) void gemm_lds_kernel(const LdsGemmA
   const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int wn = wave & 3, wm = wave >> 2;
   const int g = lane >> 4, n = lane & 15;
-  // block -> (n block, m block, k split); consecutive blocks share the K range and the weights
-  const int mb = blockIdx.x % a.m_blocks, nb = (blockIdx.x / a.m_blocks) % a.n_blocks, kp = blockIdx.x / (a.m_blocks * a.n_blocks);
+  // Workgroups are handed to the 8 XCDs (each with an L2 of its own) in turn: workgroup i runs on XCD i % 8.
+  // The tiles are numbered so that each XCD works on one contiguous range of them: XCD x takes the tiles
+  // x * q + min(x, r) ... (q, r = quotient and remainder of the grid size by 8) in the order it receives its
+  // workgroups.  Consecutive tiles share the K range and the weights (m block fastest), so the workgroups that
+  // read the same weights meet in one L2 instead of fetching them into all eight.
+  int lid = blockIdx.x;
+  if (a.xcd_ranges) {
+    const int q = gridDim.x >> 3, r = gridDim.x & 7, x = blockIdx.x & 7;
+    lid = x * q + min(x, r) + (blockIdx.x >> 3);
+  }
+  const int mb = lid % a.m_blocks, nb = (lid / a.m_blocks) % a.n_blocks, kp = lid / (a.m_blocks * a.n_blocks);
   const int k_begin = kp * a.ksteps, k_end = min(a.KST, k_begin + a.ksteps);
   const int n_steps = k_end - k_begin;
 

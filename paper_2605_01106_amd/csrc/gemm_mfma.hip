@@ -114,6 +114,74 @@ __global__ __launch_bounds__(256) void split_rows_kernel(const float* __restrict
   }
 }
 
+// The same planes for passes of many rows (three terms, K % 8 == 0, 16-byte aligned rows): one workgroup of 16
+// wavefronts per tile of 16 rows.  Thread = (row r = tid % 16, column group tid / 16 of 8 columns), so that a
+// wavefront holds the 16 rows x 32 columns of one step and each of its three stores is one whole fragment:
+// 1 KB contiguous (the row-wise kernel above writes a fragment as 64 separate 16-byte pieces from 16
+// workgroups).  Rows with a norm are read twice, as there: sums of squares first (the four lanes of a row
+// within the wavefront, then the 16 wavefronts through LDS in a fixed order), then the split.
+// grid: x = row tiles, y = column slices of `slice` columns (a multiple of 512) for passes with few row tiles:
+// every workgroup of a tile then sums the squares of the whole rows (from L2) and splits its slice.
+__global__ __launch_bounds__(1024) void split_tiles_kernel(const float* __restrict__ X, const float* __restrict__ X2, int ldx, int M, int K, int Kp,
+                                                           const float* __restrict__ norm_w, float eps, uint16_t* __restrict__ planes, int slice) {
+  __shared__ float red[16][16];
+  const int tid = threadIdx.x, r = tid & 15, kg = tid >> 4, wave = tid >> 6;
+  const int m = blockIdx.x * 16 + r;
+  const bool row_ok = m < M;
+  const float* xr = X + (size_t)min(m, M - 1) * ldx;
+  const float* xr2 = X2 != nullptr ? X2 + (size_t)min(m, M - 1) * ldx : nullptr;
+  float rstd = 1.f;
+  if (norm_w != nullptr) {
+    float ss = 0.f;
+    for (int k = kg * 8; k < K; k += 512) {
+      float4 a0 = *reinterpret_cast<const float4*>(xr + k), a1 = *reinterpret_cast<const float4*>(xr + k + 4);
+      if (xr2 != nullptr) {
+        const float4 b0 = *reinterpret_cast<const float4*>(xr2 + k), b1 = *reinterpret_cast<const float4*>(xr2 + k + 4);
+        a0.x += b0.x; a0.y += b0.y; a0.z += b0.z; a0.w += b0.w; a1.x += b1.x; a1.y += b1.y; a1.z += b1.z; a1.w += b1.w;
+      }
+      ss = fmaf(a0.x, a0.x, ss); ss = fmaf(a0.y, a0.y, ss); ss = fmaf(a0.z, a0.z, ss); ss = fmaf(a0.w, a0.w, ss);
+      ss = fmaf(a1.x, a1.x, ss); ss = fmaf(a1.y, a1.y, ss); ss = fmaf(a1.z, a1.z, ss); ss = fmaf(a1.w, a1.w, ss);
+    }
+    ss += __shfl_xor(ss, 16, 64);
+    ss += __shfl_xor(ss, 32, 64);
+    if ((tid & 63) < 16) red[wave][r] = ss;
+    __syncthreads();
+    float tot = 0.f;
+#pragma unroll
+    for (int w = 0; w < 16; ++w) tot += red[w][r];
+    rstd = 1.0f / sqrtf(tot / (float)K + eps);
+  }
+  const int KST = Kp >> 5;
+  const int k_end = min(Kp, ((int)blockIdx.y + 1) * slice);
+  for (int k = (int)blockIdx.y * slice + kg * 8; k < k_end; k += 512) {
+    float v[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) v[i] = 0.f;
+    if (row_ok && k < K) {                        // K % 8 == 0: a group is inside or outside
+      const float4 a0 = *reinterpret_cast<const float4*>(xr + k), a1 = *reinterpret_cast<const float4*>(xr + k + 4);
+      v[0] = a0.x; v[1] = a0.y; v[2] = a0.z; v[3] = a0.w; v[4] = a1.x; v[5] = a1.y; v[6] = a1.z; v[7] = a1.w;
+      if (xr2 != nullptr) {
+        const float4 b0 = *reinterpret_cast<const float4*>(xr2 + k), b1 = *reinterpret_cast<const float4*>(xr2 + k + 4);
+        v[0] += b0.x; v[1] += b0.y; v[2] += b0.z; v[3] += b0.w; v[4] += b1.x; v[5] += b1.y; v[6] += b1.z; v[7] += b1.w;
+      }
+      if (norm_w != nullptr) {
+        const float4 n0 = *reinterpret_cast<const float4*>(norm_w + k), n1 = *reinterpret_cast<const float4*>(norm_w + k + 4);
+        const float nw[8] = {n0.x, n0.y, n0.z, n0.w, n1.x, n1.y, n1.z, n1.w};
+#pragma unroll
+        for (int i = 0; i < 8; ++i) v[i] = v[i] * nw[i] * rstd;
+      }
+    }
+    uint32_t w0[4], w1[4], w2[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) split3_bf16_pair(v[2 * i], v[2 * i + 1], w0[i], w1[i], w2[i]);
+    // fragment (row tile, step k / 32): element 8 * (16 * ((k % 32) / 8) + r) = 8 * (tid % 64)
+    uint16_t* dst = planes + (((size_t)blockIdx.x * KST + (k >> 5)) * 3) * 512 + (size_t)(tid & 63) * 8;
+    *reinterpret_cast<uint4*>(dst) = make_uint4(w0[0], w0[1], w0[2], w0[3]);
+    *reinterpret_cast<uint4*>(dst + 512) = make_uint4(w1[0], w1[1], w1[2], w1[3]);
+    *reinterpret_cast<uint4*>(dst + 1024) = make_uint4(w2[0], w2[1], w2[2], w2[3]);
+  }
+}
+
 struct GemmArgs {
   const uint16_t* planes; int Mp, Kp;     // split activations [3][Mp][Kp]
   const uint16_t* W; const uint16_t* W2;  // packed tiles (W2: the "up" matrix for SwiGLU)
@@ -460,7 +528,15 @@ hipError_t launch_gemm_mfma(const GemvArgs& g, uint16_t* planes, float* partial,
     if (g.norm_w != nullptr || g.X2 != nullptr) return hipErrorInvalidValue;   // the producer wrote the operand as it is multiplied
     planes = const_cast<uint16_t*>(g.planes_in);
   } else {
-    if (vec) hipLaunchKernelGGL(split_rows_kernel<true>, dim3(Mp), dim3(256), 0, s, g.X, g.X2, g.ldx, M, K, Mp, Kp, g.norm_w, g.eps, planes, gemm_terms(M));
+    if (vec && M >= 256 && gemm_terms(M) == 3) {
+      // tile-wise; column slices so that about 256 workgroups run where the row tiles alone are fewer
+      const int tiles = Mp / 16, iters = (Kp + 511) / 512;
+      int slices = (256 + tiles - 1) / tiles;
+      if (slices > iters) slices = iters;
+      const int per = (iters + slices - 1) / slices;
+      slices = (iters + per - 1) / per;
+      hipLaunchKernelGGL(split_tiles_kernel, dim3(tiles, slices), dim3(1024), 0, s, g.X, g.X2, g.ldx, M, K, Kp, g.norm_w, g.eps, planes, per * 512);
+    } else if (vec) hipLaunchKernelGGL(split_rows_kernel<true>, dim3(Mp), dim3(256), 0, s, g.X, g.X2, g.ldx, M, K, Mp, Kp, g.norm_w, g.eps, planes, gemm_terms(M));
     else hipLaunchKernelGGL(split_rows_kernel<false>, dim3(Mp), dim3(256), 0, s, g.X, g.X2, g.ldx, M, K, Mp, Kp, g.norm_w, g.eps, planes, gemm_terms(M));
     e = hipGetLastError();
     if (e != hipSuccess) return e;

@@ -460,6 +460,51 @@ __global__ __launch_bounds__(256) void kv_append_kernel(const Dims d, const Attn
   }
 }
 
+// The same for a bf16 cache whose pages hold a multiple of 8 tokens, in groups of 8 consecutive positions
+// (aligned to 8, so a group lies in one page): the values of one dimension for the 8 tokens are 16 contiguous
+// bytes of the transposed V page and are written as one store (the kernel above writes them as 8 separate
+// 2-byte stores from 8 workgroups).  Same arithmetic and rounding.  grid: sequence x groups_per_seq.
+__global__ __launch_bounds__(256) void kv_append8_kernel(const Dims d, const AttnArgs a, int groups_per_seq) {
+  const int b = blockIdx.x / groups_per_seq, gl = blockIdx.x - b * groups_per_seq;
+  const int nt = min(a.n_tok != nullptr ? a.n_tok[b] : a.T, a.T);
+  const int pos0 = a.pos0[b];
+  const int p_first = ((pos0 >> 3) + gl) << 3;               // first position of this group
+  if (nt <= 0 || p_first >= pos0 + nt) return;
+  const int Dh = d.Dh, half = Dh >> 1;
+  const int* pt_row = a.page_table + (size_t)b * d.pages_per_seq;
+  const float* rows = a.qkv + (size_t)b * a.T * d.ldzx + d.dq;   // row j: k | v of position pos0 + j
+  const bool whole = p_first >= pos0 && p_first + 8 <= pos0 + nt;
+  uint16_t* vpool = static_cast<uint16_t*>(a.vpool);
+  for (int it = threadIdx.x; it < d.Hkv * Dh; it += 256) {
+    const int kvh = it / Dh, dd = it - kvh * Dh;
+    const size_t at = v_index(d, pt_row, kvh, p_first, dd);
+    if (whole) {
+      uint32_t h[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) h[u] = f32_to_bf16_rne(rows[(size_t)(p_first - pos0 + u) * d.ldzx + d.dkv + it]);
+      *reinterpret_cast<uint4*>(vpool + at) = make_uint4(h[0] | (h[1] << 16), h[2] | (h[3] << 16), h[4] | (h[5] << 16), h[6] | (h[7] << 16));
+    } else {
+      for (int u = 0; u < 8; ++u) {
+        const int j = p_first + u - pos0;
+        if (j >= 0 && j < nt) vpool[at + u] = f32_to_bf16_rne(rows[(size_t)j * d.ldzx + d.dkv + it]);
+      }
+    }
+  }
+  uint16_t* kpool = static_cast<uint16_t*>(a.kpool);
+  const int per = d.Hkv * half;
+  for (int it = threadIdx.x; it < 8 * per; it += 256) {
+    const int u = it / per, rem = it - u * per, kvh = rem / half, i = rem - kvh * half;
+    const int pos = p_first + u, j = pos - pos0;
+    if (j < 0 || j >= nt) continue;
+    const float2 c = reinterpret_cast<const float2*>(a.rope)[(size_t)pos * half + i];
+    const float* krow = rows + (size_t)j * d.ldzx;
+    const float x0 = krow[kvh * Dh + i], x1 = krow[kvh * Dh + i + half];
+    const float lo = x0 * c.x - x1 * c.y, hi = x1 * c.x + x0 * c.y;
+    uint16_t* kp = kpool + k_index(d, pt_row, kvh, pos);
+    kp[i] = f32_to_bf16_rne(lo); kp[i + half] = f32_to_bf16_rne(hi);
+  }
+}
+
 // bf16 cache: matrix-core kernel (HH_KF_ATTN_SCALAR selects the float32-FMA kernel instead, for cross-checks)
 bool attention_uses_mfma(const Dims& d) {
   return d.bf16 && !(d.flags & HH_KF_ATTN_SCALAR) && d.page_tokens % 32 == 0;   // a 32-key step of that kernel lies in one page
@@ -469,7 +514,12 @@ hipError_t launch_attention(const Dims& d, const AttnArgs& a, hipStream_t s) {
   if (d.Dh > kMaxDh || d.Dh % 8 != 0 || a.n_splits > 64 || a.n_splits < 1 || a.T < 1 || a.B < 1) return hipErrorInvalidValue;
   if (attention_uses_mfma(d)) {
     if (!attention_mfma_fuses_append(d, a.T)) {
-      hipLaunchKernelGGL(kv_append_kernel, dim3(a.B * a.T), dim3(256), 0, s, d, a);
+      if (a.T >= 16 && d.page_tokens % 8 == 0) {
+        const int groups = (a.T + 7) / 8 + 1;      // 8-aligned groups that T consecutive positions can touch
+        hipLaunchKernelGGL(kv_append8_kernel, dim3(a.B * groups), dim3(256), 0, s, d, a, groups);
+      } else {
+        hipLaunchKernelGGL(kv_append_kernel, dim3(a.B * a.T), dim3(256), 0, s, d, a);
+      }
       hipError_t e = hipGetLastError();
       if (e != hipSuccess) return e;
     }

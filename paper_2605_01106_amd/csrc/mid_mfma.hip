@@ -264,6 +264,26 @@ static bool mid_plan(const GemvArgs& g, MidPlan& p) {
   if (ks > n_win) ks = n_win;
   if (ks < 1) ks = 1;
   p.wpb = (n_win + ks - 1) / ks;
+  if (p.small) {
+    // The small shape picks its windows per workgroup from a cost model fitted to the 3B shape at 64 rows (us):
+    // a window costs a workgroup 0.305 us per row tile, 1.4 times that when the launch has more than one workgroup
+    // per compute unit; a K chunk costs 0.49 us per 64 x 2560 partial sums (written, then read by the reduction).
+    // Few long workgroups beat many short ones for the narrow products: out_proj 18.2 -> 14.5 us with 8 chunks of
+    // 5 windows instead of 20 of 2, in_proj 19.0 -> 17.4 us with 5 chunks of 8 instead of 10 of 4.  The longest
+    // workgroups within 3 % of the cheapest plan win (fewer partial sums).
+    const double tw = 0.305 * p.mt, cc = 0.49 * (g.M / 64.0) * nf * (N / 2560.0);
+    double t_min = 1e30;
+    for (int pass = 0; pass < 2; ++pass) {
+      for (int w = 1; w <= n_win; ++w) {
+        const int ch = (n_win + w - 1) / w;
+        const long wgs = (long)p.blocks * ch;
+        if (wgs > 512 && w < n_win) continue;            // at most two workgroups per compute unit
+        const double t = tw * w * (wgs > 256 ? 1.4 : 1.0) + cc * ch;
+        if (pass == 0) { if (t < t_min) t_min = t; }
+        else if (t <= 1.03 * t_min) p.wpb = w;
+      }
+    }
+  }
   p.windows = (n_win + p.wpb - 1) / p.wpb;          // K chunks = partial products
   p.lds = (size_t)2 * kMidTerms * p.mt * 16 * (kw + mid_pad(p.mt, kw)) * 2;
   p.partial_elems = (size_t)p.windows * nf * g.M * N + (size_t)p.windows * 96;
